@@ -1,0 +1,137 @@
+/*
+ * liquidgemm.h -- C ABI of the MI355X (gfx950) LiquidQuant W4A8 GEMM library.
+ *
+ * Problem (paper Sec. 2, "GEMM on GPUs"):  Y = X W^T  with  X [M,K] INT8 activations
+ * (per-token scale s_x[M]),  W [N,K] weights stored as UINT4 LiquidQuant codes with one
+ * (s_u8, a) pair per group of `group` consecutive k of one output channel (Sec. 4,
+ * Eq. 7 and Eq. 12) and one FP32 scale s_w[N] per output channel (level 1, Sec. 4),
+ * Y [M,N] FP16.  Per element
+ *
+ *     Wd[n,k]  = (code[n,k] * s_u8[n,k/group] + a[n,k/group]) XOR 0x80      (Eq. 12)
+ *     ACC[m,n] = sum_k X[m,k] * Wd[n,k]                  INT8 x INT8 -> INT32 (Sec. 2)
+ *     Y[m,n]   = fp16( (float)ACC[m,n] * s_x[m] * s_w[n] )                    (Sec. 4, 5.3)
+ *
+ * Conventions
+ *   - All functions return 0 on success and a negative LQ_ERR_* code otherwise; no
+ *     exceptions cross the boundary.  w4a8_last_error() returns a thread-local message
+ *     for the last failing call of the calling thread.
+ *   - Every buffer is owned by the caller; the library keeps no pointer after a call
+ *     returns and allocates no caller-visible memory.
+ *   - "host" pointers are ordinary CPU memory; "device" pointers are HIP device memory
+ *     on the current device and must be 16-byte aligned.  Device entry points only
+ *     enqueue work on `hip_stream` (a hipStream_t passed as void*; NULL = default
+ *     stream) and return without synchronising.
+ *   - Shapes: N % 64 == 0, K % 256 == 0, group in {64, 128}, 0 <= M, K <= 131072
+ *     (so that |ACC| <= K * 127 * 127 stays below 2^31).  M = 0 is a successful no-op.
+ *   - The packed weight blob (W_packed, gparams) is opaque, position independent and
+ *     specific to this library version (w4a8_version()); it can be stored and reloaded
+ *     byte for byte.  Its size is given by liquidquant_packed_size().
+ *   - Precondition of the device entry points (not checked on the device): every
+ *     (code, s_u8, a) triple satisfies code * s_u8 + a <= 255 (Eq. 11).  The packers
+ *     below guarantee it; behaviour on hand-made blobs that violate it is undefined
+ *     (the per-byte arithmetic of Eq. 12 would carry into the neighbouring byte).
+ */
+#ifndef LIQUIDGEMM_H
+#define LIQUIDGEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LQ_OK 0
+#define LQ_ERR_INVALID (-1)   /* bad shape, null pointer, unknown variant            */
+#define LQ_ERR_ALIGN (-2)     /* a device pointer is not 16-byte aligned             */
+#define LQ_ERR_WORKSPACE (-3) /* workspace_bytes < w4a8_gemm_workspace_size(...)     */
+#define LQ_ERR_HIP (-4)       /* a HIP runtime call or kernel launch failed          */
+
+/* Library / packed-layout version (changes whenever the blob layout changes). */
+int w4a8_version(void);
+
+/* Message of the last error raised on the calling thread ("" if none). */
+const char *w4a8_last_error(void);
+
+/* ------------------------------------------------------------------------------------
+ * Offline LiquidQuant packer (host, Sec. 4 and Sec. 6 "Offline Quantization")
+ * ------------------------------------------------------------------------------------ */
+
+/* Sizes of the two parts of the packed blob: codes_bytes = N*K/2 (two codes per byte),
+ * gparams_bytes = 2*N*K/group (one (s_u8, a) byte pair per group).  Either output
+ * pointer may be NULL. */
+int liquidquant_packed_size(int N, int K, int group, size_t *codes_bytes, size_t *gparams_bytes);
+
+/* Two-level quantisation of W (host, [N,K] row-major FP32 holding the FP16 weights):
+ *   level 1, per output channel (Sec. 4, Eq. 1 with z = 0, protective range):
+ *       s_w[n] = max_k |W[n,k]| / 119 (FP32; 1 if the row is zero),
+ *       Q_i8 = clamp(rint(W / s_w), -119, 119)
+ *   level 2, per group (Eq. 7): min = min(Q_i8), R = max - min,
+ *       s_u8 = max(1, round(R / 15)), code = min(15, round((Q_i8 - min) / s_u8)),
+ *       a = 128 + min (Eq. 10)
+ * then permutation into the gfx950 MFMA operand order and nibble packing (the analogue
+ * of the dual-MMA packed layout of Sec. 5.2).  Outputs (host): W_packed (codes_bytes),
+ * gparams (gparams_bytes), w_scales [N]. */
+int liquidquant_pack_weights(const float *W, int N, int K, int group, void *W_packed,
+                             uint8_t *gparams, float *w_scales);
+
+/* Same, with W given as IEEE binary16 bit patterns (host, [N,K] row-major). */
+int liquidquant_pack_weights_f16(const uint16_t *W_f16, int N, int K, int group, void *W_packed,
+                                 uint8_t *gparams, float *w_scales);
+
+/* Level 2 and packing only, from level-1 integers Q_i8 (host, [N,K], every |q| <= 119;
+ * values outside that range are rejected with LQ_ERR_INVALID). */
+int liquidquant_pack_from_i8(const int8_t *Q_i8, int N, int K, int group, void *W_packed,
+                             uint8_t *gparams);
+
+/* Inverse of the permutation (host, for tests and tooling): codes [N,K] one code per
+ * byte in natural order, s_u8 [N,K/group], a [N,K/group].  Output pointers may be NULL. */
+int liquidquant_unpack_weights(const void *W_packed, const uint8_t *gparams, int N, int K,
+                               int group, uint8_t *codes, uint8_t *s_u8, uint8_t *a);
+
+/* ------------------------------------------------------------------------------------
+ * W4A8 GEMM (device, Sec. 5: load, unpack, LQQ dequantisation, INT8 MFMA, epilogue)
+ * ------------------------------------------------------------------------------------ */
+
+/* Bytes of device workspace w4a8_gemm* needs for this shape (0 when no kernel that the
+ * dispatcher can choose needs one). */
+size_t w4a8_gemm_workspace_size(int M, int N, int K, int group);
+
+/* Y[M,N] (device, FP16 bits, row-major) = epilogue(X . dequant(W)^T).
+ *   X           device [M,K] INT8 row-major
+ *   act_scales  device [M] FP32, per-token scales s_x (Sec. 6)
+ *   W_packed, gparams  device copies of the packer's outputs
+ *   w_scales    device [N] FP32, per-channel scales s_w
+ *   workspace   device, workspace_bytes >= w4a8_gemm_workspace_size(); may be NULL if 0 */
+int w4a8_gemm(int M, int N, int K, int group, const int8_t *X, const float *act_scales,
+              const void *W_packed, const uint8_t *gparams, const float *w_scales, uint16_t *Y,
+              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Parity hook: the raw INT32 accumulators ACC[M,N] (device, row-major) of the same
+ * kernels, without the scaling epilogue. */
+int w4a8_gemm_i32(int M, int N, int K, int group, const int8_t *X, const void *W_packed,
+                  const uint8_t *gparams, int32_t *ACC, void *workspace, size_t workspace_bytes,
+                  void *hip_stream);
+
+/* Tuning / test hook: run one named kernel variant instead of the dispatcher's choice.
+ * `variant` in [0, w4a8_variant_count()); -1 = dispatcher.  Y and ACC may each be NULL
+ * (at least one must be given; act_scales / w_scales may be NULL when Y is).  Returns
+ * LQ_ERR_INVALID if the variant cannot run this shape (e.g. M too large for a
+ * decode kernel). */
+int w4a8_gemm_variant(int variant, int M, int N, int K, int group, const int8_t *X,
+                      const float *act_scales, const void *W_packed, const uint8_t *gparams,
+                      const float *w_scales, uint16_t *Y, int32_t *ACC, void *workspace,
+                      size_t workspace_bytes, void *hip_stream);
+int w4a8_variant_count(void);
+const char *w4a8_variant_name(int variant);            /* NULL if out of range        */
+int w4a8_select_variant(int M, int N, int K, int group); /* the dispatcher's choice, <0 on error */
+
+/* Layout hook: dequantise the whole packed matrix on the device with the kernels' own
+ * unpack + Eq. 12 code path into Wd [N,K] INT8 row-major (device). */
+int w4a8_dequant_dump(const void *W_packed, const uint8_t *gparams, int N, int K, int group,
+                      int8_t *Wd, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LIQUIDGEMM_H */

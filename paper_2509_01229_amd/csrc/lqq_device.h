@@ -1,0 +1,107 @@
+// Device-side building blocks shared by the gfx950 kernels: vector types, the LiquidQuant
+// register-level dequantisation (paper Sec. 5.3, Eq. 12) and the INT8 MFMA wrapper.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lqq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// (r * s + a) on two 16-bit lanes: one v_pk_mad_u16.  With every byte of r <= 15,
+// s <= 16 and byte*s + a <= 255 (Eq. 11) no byte carries into its neighbour, so this is
+// four independent UINT8 multiply-adds -- the gfx950 stand-in for the 32-bit IMAD of
+// Sec. 5.3 (a 32-bit integer multiply is quarter rate on CDNA; the packed 16-bit one is
+// full rate).
+__device__ __forceinline__ uint32_t pk_mad_u16(uint32_t r, uint32_t s2, uint32_t a4)
+{
+    const u16x2 rv = __builtin_bit_cast(u16x2, r);
+    const u16x2 sv = __builtin_bit_cast(u16x2, s2);
+    const u16x2 av = __builtin_bit_cast(u16x2, a4);
+    return __builtin_bit_cast(uint32_t, (u16x2)(rv * sv + av));
+}
+
+// Broadcast forms of one (s_u8, a) byte pair held in `word`: which = 0 takes bytes 0/1,
+// which = 1 takes bytes 2/3.  s2 = s in both 16-bit lanes, a4 = a in all four bytes.
+__device__ __forceinline__ void expand_params(uint32_t word, int which, uint32_t &s2, uint32_t &a4)
+{
+    s2 = __builtin_amdgcn_perm(word, word, which ? 0x0c020c02u : 0x0c000c00u);
+    a4 = __builtin_amdgcn_perm(word, word, which ? 0x03030303u : 0x01010101u);
+}
+
+// Unpack + dequantise one 16-byte lane load (32 codes): the low nibbles become the four
+// operand registers of the first k-step, the high nibbles those of the second.
+// 7 VALU instructions per 8 codes: and, shift, and, 2 x pk_mad, 2 x xor (Sec. 5.3).
+__device__ __forceinline__ void dequant_chunk(const u32x4 p, uint32_t s2_lo, uint32_t a4_lo,
+                                              uint32_t s2_hi, uint32_t a4_hi, v4i &lo, v4i &hi)
+{
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const uint32_t l = p[d] & 0x0F0F0F0Fu;
+        const uint32_t h = (p[d] >> 4) & 0x0F0F0F0Fu;
+        lo[d] = (int)(pk_mad_u16(l, s2_lo, a4_lo) ^ 0x80808080u);
+        hi[d] = (int)(pk_mad_u16(h, s2_hi, a4_hi) ^ 0x80808080u);
+    }
+}
+
+// Group parameters of one lane's channel for one unit of 256 k.
+// group 64: four pairs (8 bytes); group 128: two pairs (4 bytes).
+template <bool G128>
+struct UnitParams;
+template <>
+struct UnitParams<false> {
+    u32x2 raw;
+    __device__ __forceinline__ void load(const uint8_t *gp, size_t tile_unit, int slot)
+    {
+        raw = *reinterpret_cast<const u32x2 *>(gp + (tile_unit * 16 + slot) * 8);
+    }
+    // parameters of k-step ks (0..3) of the unit
+    __device__ __forceinline__ void get(int ks, uint32_t &s2, uint32_t &a4) const
+    {
+        expand_params((ks & 2) ? raw.y : raw.x, ks & 1, s2, a4);
+    }
+};
+template <>
+struct UnitParams<true> {
+    uint32_t raw;
+    __device__ __forceinline__ void load(const uint8_t *gp, size_t tile_unit, int slot)
+    {
+        raw = *reinterpret_cast<const uint32_t *>(gp + (tile_unit * 16 + slot) * 4);
+    }
+    __device__ __forceinline__ void get(int ks, uint32_t &s2, uint32_t &a4) const
+    {
+        expand_params(raw, ks >> 1, s2, a4);
+    }
+};
+
+// Dequantise chunk c (0 or 1) of a unit: k-steps 2c (low nibbles) and 2c+1 (high).
+template <bool G128>
+__device__ __forceinline__ void dequant_unit_chunk(const u32x4 p, const UnitParams<G128> &up, int c,
+                                                   v4i &lo, v4i &hi)
+{
+    uint32_t s2l, a4l, s2h, a4h;
+    up.get(2 * c, s2l, a4l);
+    if (G128) {
+        s2h = s2l;
+        a4h = a4l;
+    } else {
+        up.get(2 * c + 1, s2h, a4h);
+    }
+    dequant_chunk(p, s2l, a4l, s2h, a4h, lo, hi);
+}
+
+// D(16x16) += A(16x64) * B(64x16), INT8 inputs, INT32 accumulate.  Lane l supplies row
+// l%16 of A and column l%16 of B for k-block l/16 (16 bytes each); it receives
+// D[4*(l/16) + r][l%16] in element r.
+__device__ __forceinline__ v4i mfma_i8(const v4i a, const v4i b, const v4i c)
+{
+    return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
+}
+
+// Channel held by slot j of tile t (see lqq_layout.h).
+__device__ __forceinline__ int channel_of(int t, int j) { return 64 * (t >> 2) + 4 * j + (t & 3); }
+
+}  // namespace lqq

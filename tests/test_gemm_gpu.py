@@ -1,0 +1,191 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle on the
+same seeded inputs.  INT32 accumulators and the dequantised INT8 matrix must match bit
+for bit; FP16 outputs within 1e-3 relative (one FP16 ulp) of the double-precision oracle.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import lqq_oracle as O
+from paper_2509_01229_amd import api
+from paper_2509_01229_amd import workloads as WL
+
+import gpu_helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    import torch
+
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (run with -m 'not gpu' elsewhere)")
+    api.lib()  # must load: there is no fallback
+
+
+# ---------------------------------------------------------------------------------------
+# Layout + dequantisation alone (no MFMA): kernels' unpack/Eq. 12 path vs oracle Eq. 8
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("N,K,g", [(64, 256, 64), (256, 512, 64), (192, 1280, 128), (64, 256, 128)])
+def test_dequant_dump_matches_oracle(N, K, g):
+    import torch
+
+    _say(f"dequant_dump N={N} K={K} g={g}")
+    P = H.Problem(N, K, g, seed=N + K)
+    Wd_ref, _ = P.oracle_wd()
+    Wd = api.w4a8_dequant_dump(P.d_packed, P.d_gparams, N, K, g)
+    torch.cuda.synchronize()
+    assert np.array_equal(Wd.cpu().numpy(), Wd_ref)
+
+
+@pytest.mark.parametrize("style", ["extreme", "constant", "narrow", "uniform"])
+def test_dequant_dump_edge_distributions(style):
+    import torch
+
+    N, K, g = 128, 512, 64
+    _say(f"dequant_dump style={style}")
+    Q = WL.make_q_i8(N, K, seed=5, style=style)
+    P = H.Problem(N, K, g, Q_i8=Q)
+    Wd_ref, _ = P.oracle_wd()
+    Wd = api.w4a8_dequant_dump(P.d_packed, P.d_gparams, N, K, g)
+    torch.cuda.synchronize()
+    assert np.array_equal(Wd.cpu().numpy(), Wd_ref)
+
+
+# ---------------------------------------------------------------------------------------
+# Every kernel variant on small shapes spanning several tiles and ragged tails
+# ---------------------------------------------------------------------------------------
+SMALL = [
+    # M, N, K, g
+    (8, 256, 512, 64),       # the tiny config
+    (1, 64, 256, 64),        # smallest legal problem
+    (16, 320, 768, 128),     # N not a multiple of 256
+    (13, 192, 1024, 64),     # ragged M inside one fragment
+    (31, 128, 512, 128),
+    (77, 448, 768, 64),      # ragged M over several row tiles, N tail
+    (200, 256, 256, 64),     # one k unit only
+    (130, 576, 1280, 128),
+]
+
+
+@pytest.mark.parametrize("M,N,K,g", SMALL)
+def test_every_variant_bit_exact(M, N, K, g):
+    P = H.Problem(N, K, g, seed=M * 7 + N)
+    X, s_x = WL.make_activations(M, K, outlier_frac=0.01, seed=M + K)
+    ACC_ref, Y_ref = P.oracle_gemm(X, s_x)
+    q = P.oracle_full()
+    ref64 = O.scale_epilogue_f64(ACC_ref, s_x, q["s_w"])
+    ran = 0
+    for v in H.variants_for(M):
+        name = api.w4a8_variant_name(v)
+        if name.startswith("stream") and (N // 16) % int(name.split("_")[1][1:]) != 0:
+            continue
+        _say(f"variant {name} M={M} N={N} K={K} g={g}")
+        Y, ACC = P.run(X, s_x, variant=v)
+        assert np.array_equal(ACC, ACC_ref), f"{name}: INT32 accumulators differ"
+        H.assert_fp16_close(Y, ref64, name)
+        ran += 1
+    assert ran >= 2
+    # the dispatcher's own choice, through the two public entry points
+    import torch
+
+    dX = torch.from_numpy(X).cuda()
+    dsx = torch.from_numpy(s_x).cuda()
+    Y = api.w4a8_gemm(dX, dsx, P.d_packed, P.d_gparams, P.d_w_scales, N, K, g)
+    ACC = api.w4a8_gemm_i32(dX, P.d_packed, P.d_gparams, N, K, g)
+    torch.cuda.synchronize()
+    assert np.array_equal(ACC.cpu().numpy(), ACC_ref)
+    H.assert_fp16_close(Y.cpu().numpy(), ref64, "dispatcher")
+
+
+# ---------------------------------------------------------------------------------------
+# Degenerate inputs
+# ---------------------------------------------------------------------------------------
+def test_degenerate_inputs():
+    N, K, g = 128, 512, 64
+    P = H.Problem(N, K, g, seed=3)
+    Wd, s_w = P.oracle_wd()
+    for M in (5, 40):
+        _say(f"degenerate M={M}")
+        X = np.zeros((M, K), dtype=np.int8)
+        X[1, 77] = 1            # one-hot row: picks column 77 of Wd^T
+        X[2, :] = 1             # all ones: row sums
+        X[3, :] = -127          # extreme negative
+        X[4, :] = 127           # extreme positive
+        s_x = np.ones(M, dtype=np.float32)
+        for v in H.variants_for(M):
+            _, ACC = P.run(X, s_x, variant=v, want_y=False)
+            assert (ACC[0] == 0).all()
+            assert np.array_equal(ACC[1], Wd[:, 77].astype(np.int32))
+            assert np.array_equal(ACC[2], Wd.astype(np.int64).sum(axis=1))
+            assert np.array_equal(ACC[3], -127 * Wd.astype(np.int64).sum(axis=1))
+            assert np.array_equal(ACC[4], 127 * Wd.astype(np.int64).sum(axis=1))
+
+
+@pytest.mark.parametrize("style", ["extreme", "constant"])
+def test_extreme_weight_ranges(style):
+    M, N, K, g = 24, 128, 1024, 128
+    _say(f"extreme weights style={style}")
+    Q = WL.make_q_i8(N, K, seed=9, style=style)
+    P = H.Problem(N, K, g, Q_i8=Q)
+    X, s_x = WL.make_activations(M, K, seed=1)
+    X[0, :] = 127
+    ACC_ref, _ = P.oracle_gemm(X, s_x)
+    for v in H.variants_for(M):
+        _, ACC = P.run(X, s_x, variant=v, want_y=False)
+        assert np.array_equal(ACC, ACC_ref), api.w4a8_variant_name(v)
+
+
+def test_fp16_overflow_and_tiny_scales():
+    M, N, K, g = 4, 64, 256, 64
+    _say("fp16 overflow / underflow")
+    P = H.Problem(N, K, g, seed=2)
+    X, _ = WL.make_activations(M, K, seed=2)
+    s_x = np.array([1e4, 1e-3, 1e-9, 1.0], dtype=np.float32)
+    ACC_ref, _ = P.oracle_gemm(X, s_x)
+    ref64 = O.scale_epilogue_f64(ACC_ref, s_x, P.oracle_full()["s_w"])
+    Y, ACC = P.run(X, s_x)
+    assert np.array_equal(ACC, ACC_ref)
+    H.assert_fp16_close(Y, ref64, "overflow")
+
+
+def test_empty_batch_and_determinism():
+    import torch
+
+    N, K, g = 256, 1024, 64
+    P = H.Problem(N, K, g, seed=4)
+    _say("M=0")
+    X0 = torch.empty((0, K), dtype=torch.int8, device="cuda")
+    s0 = torch.empty((0,), dtype=torch.float32, device="cuda")
+    Y0 = api.w4a8_gemm(X0, s0, P.d_packed, P.d_gparams, P.d_w_scales, N, K, g)
+    assert tuple(Y0.shape) == (0, N)
+    _say("determinism")
+    X, s_x = WL.make_activations(16, K, seed=8)
+    a1 = P.run(X, s_x)
+    a2 = P.run(X, s_x)
+    assert np.array_equal(a1[1], a2[1]) and np.array_equal(a1[0].view(np.uint16), a2[0].view(np.uint16))
+
+
+def test_binding_rejects_bad_tensors():
+    import torch
+
+    N, K, g = 64, 256, 64
+    P = H.Problem(N, K, g, seed=1)
+    X = torch.zeros((4, K), dtype=torch.int8, device="cuda")
+    sx = torch.ones(4, dtype=torch.float32, device="cuda")
+    with pytest.raises(TypeError):
+        api.w4a8_gemm(X.cpu(), sx, P.d_packed, P.d_gparams, P.d_w_scales, N, K, g)
+    with pytest.raises(TypeError):
+        api.w4a8_gemm(X.to(torch.int32), sx, P.d_packed, P.d_gparams, P.d_w_scales, N, K, g)
+    with pytest.raises(ValueError):
+        api.w4a8_gemm(X, sx[:3], P.d_packed, P.d_gparams, P.d_w_scales, N, K, g)
+    with pytest.raises(api.LiquidGemmError):
+        api.w4a8_gemm_variant(0, torch.zeros((64, K), dtype=torch.int8, device="cuda"),
+                              torch.ones(64, device="cuda"), P.d_packed, P.d_gparams, P.d_w_scales, N, K, g)
