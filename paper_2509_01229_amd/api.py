@@ -36,6 +36,10 @@ def lib() -> ctypes.CDLL:
         raise FileNotFoundError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2509_01229_amd.build` "
             "(there is no CPU fallback for the GEMM path)")
+    # torch ships its own HIP runtime; load it first so that the library binds to the
+    # same runtime that owns the device pointers and streams it is handed.
+    import torch  # noqa: F401
+
     L = ctypes.CDLL(LIB_PATH)
     i, vp, sz = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
     L.w4a8_version.restype = i

@@ -413,6 +413,7 @@ static int check_device_args(const Args &a, const void *ws, size_t ws_bytes)
         return fail(LQ_ERR_INVALID,
                     "bad shape M=%d N=%d K=%d group=%d (need M>=0, N%%64==0, K%%256==0, group 64|128, K<=131072)",
                     a.M, a.N, a.K, a.group);
+    if (a.M == 0) return LQ_OK;  // nothing to read or write; pointers may be null
     if (!a.Y && !a.ACC) return fail(LQ_ERR_INVALID, "no output pointer");
     if (!a.X || !a.Wp || !a.gp) return fail(LQ_ERR_INVALID, "null input pointer");
     if (a.Y && (!a.sx || !a.sw)) return fail(LQ_ERR_INVALID, "null scale pointer");
@@ -455,7 +456,7 @@ int w4a8_gemm(int M, int N, int K, int group, const int8_t *X, const float *act_
               const void *W_packed, const uint8_t *gparams, const float *w_scales, uint16_t *Y,
               void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    if (!Y) return fail(LQ_ERR_INVALID, "null Y");
+    if (!Y && M != 0) return fail(LQ_ERR_INVALID, "null Y");
     const Args a{M, N, K, group, X, act_scales, static_cast<const u32x4 *>(W_packed), gparams, w_scales,
                  reinterpret_cast<__half *>(Y), nullptr, static_cast<hipStream_t>(hip_stream)};
     return run(-1, a, workspace, workspace_bytes);
@@ -465,7 +466,7 @@ int w4a8_gemm_i32(int M, int N, int K, int group, const int8_t *X, const void *W
                   const uint8_t *gparams, int32_t *ACC, void *workspace, size_t workspace_bytes,
                   void *hip_stream)
 {
-    if (!ACC) return fail(LQ_ERR_INVALID, "null ACC");
+    if (!ACC && M != 0) return fail(LQ_ERR_INVALID, "null ACC");
     const Args a{M, N, K, group, X, nullptr, static_cast<const u32x4 *>(W_packed), gparams, nullptr,
                  nullptr, ACC, static_cast<hipStream_t>(hip_stream)};
     return run(-1, a, workspace, workspace_bytes);
