@@ -124,6 +124,7 @@ int w4a8_gemm_variant(int variant, int M, int N, int K, int group, const int8_t 
                       size_t workspace_bytes, void *hip_stream);
 int w4a8_variant_count(void);
 const char *w4a8_variant_name(int variant);            /* NULL if out of range        */
+int w4a8_variant_supports(int variant, int M, int N, int K, int group); /* 1 if it can run the shape */
 int w4a8_select_variant(int M, int N, int K, int group); /* the dispatcher's choice, <0 on error */
 
 /* Layout hook: dequantise the whole packed matrix on the device with the kernels' own

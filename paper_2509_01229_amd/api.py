@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
     L.w4a8_variant_count.restype = i
     L.w4a8_variant_name.restype = ctypes.c_char_p
     L.w4a8_variant_name.argtypes = [i]
+    L.w4a8_variant_supports.restype = i
+    L.w4a8_variant_supports.argtypes = [i, i, i, i, i]
     L.w4a8_select_variant.restype = i
     L.w4a8_select_variant.argtypes = [i, i, i, i]
     L.w4a8_dequant_dump.restype = i
@@ -247,6 +249,10 @@ def w4a8_variant_name(variant: int):
 
 def w4a8_variant_names():
     return [w4a8_variant_name(i) for i in range(w4a8_variant_count())]
+
+
+def w4a8_variant_supports(variant: int, M: int, N: int, K: int, group: int) -> bool:
+    return bool(lib().w4a8_variant_supports(variant, M, N, K, group))
 
 
 def w4a8_select_variant(M: int, N: int, K: int, group: int) -> int:

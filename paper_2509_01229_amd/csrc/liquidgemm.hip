@@ -3,24 +3,24 @@
 // Two kernel families share the packed layout of lqq_layout.h and the dequantisation of
 // lqq_device.h (paper Sec. 5.3):
 //
-//   stream  (M <= 16*MB): the memory-bound regime of the paper's cost model (Sec. 3.2,
-//           T_LD dominates).  A block owns F tiles of 16 output channels; its NW waves
+//   stream  (M <= 32): the memory-bound regime of the paper's cost model (Sec. 3.2,
+//           T_LD dominates).  A block owns F tiles of 32 output channels; its NW waves
 //           split K between them (in-block split-K), stream the packed weights straight
 //           from HBM into registers with one 16-byte load per lane, dequantise, feed the
 //           MFMA, and reduce their INT32 partials through LDS -- integer sums, so the
 //           result does not depend on the order.  No workspace, one launch.
 //
 //   tile    (larger M): the compute-bound regime (T_DQ + T_MMA dominates).  A block of 4
-//           waves owns WM rows of X and 256 output channels; the X tile is staged in LDS
-//           (double buffered) and shared by the waves, each wave keeps its own 64
+//           waves owns 32*MF rows of X and 256 output channels; the X tile is staged in
+//           LDS (double buffered) and shared by the waves, each wave keeps its own 64
 //           channels' weights in registers (global -> VGPR, never through LDS: the
 //           dequantised operand is consumed by the MFMA of the same wave, which is the
 //           point of the paper's implicit fine-grained pipeline, Sec. 5.1) and reuses
-//           every dequantised fragment for WM/16 MFMAs.
+//           every dequantised fragment for MF MFMAs.
 //
-// Both compute Y = X W^T with the weights on the B operand of v_mfma_i32_16x16x64_i8, so
-// that a lane ends up with 4 adjacent output channels of one row (the tile interleave of
-// the layout) and the epilogue writes 8-byte FP16 pieces that form full 128-byte lines.
+// Both compute Y = X W^T with the weights on the B operand of v_mfma_i32_32x32x32_i8, so
+// that a lane ends up with 2 adjacent output channels of one row (the tile interleave of
+// the layout) and a half-wave writes a full 128-byte line of FP16.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
@@ -34,7 +34,7 @@ namespace lqq {
 
 // ------------------------------------------------------------------------------------
 // Layout hook: packed -> INT8 [N,K] with the kernels' own unpack + Eq. 12 path.
-// One wave per 1 KiB chunk (16 channels x 128 k).
+// One wave per 1 KiB chunk (32 channels x 64 k).
 // ------------------------------------------------------------------------------------
 template <bool G128>
 __global__ __launch_bounds__(256) void dequant_dump_kernel(const u32x4 *__restrict__ Wp,
@@ -42,20 +42,21 @@ __global__ __launch_bounds__(256) void dequant_dump_kernel(const u32x4 *__restri
                                                            int8_t *__restrict__ Wd)
 {
     const int lane = threadIdx.x & 63;
-    const int j = lane & 15, kb = lane >> 4;
-    const int chunks_per_tile = K >> 7;
+    const int j = lane & 31, kb = lane >> 5;
+    const int chunks_per_tile = K >> 6;
     const int t = blockIdx.y;
     const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (c >= chunks_per_tile) return;
-    const size_t chunk = (size_t)t * chunks_per_tile + c;
-    const u32x4 p = Wp[chunk * 64 + lane];
+    const u32x4 p = Wp[((size_t)t * chunks_per_tile + c) * 64 + lane];
     UnitParams<G128> up;
-    up.load(gp, (size_t)t * (K >> 8) + (c >> 1), j);
+    up.load(gp, (size_t)t * (K >> 7) + (c >> 1), j);
+    uint32_t s2, a4;
+    up.get(c & 1, s2, a4);
     v4i lo, hi;
-    dequant_unit_chunk<G128>(p, up, c & 1, lo, hi);
-    int8_t *row = Wd + (size_t)channel_of(t, j) * K + (size_t)c * 128 + 16 * kb;
+    dequant_chunk(p, s2, a4, lo, hi);
+    int8_t *row = Wd + (size_t)channel_of(t, j) * K + (size_t)c * 64 + 16 * kb;
     *reinterpret_cast<v4i *>(row) = lo;
-    *reinterpret_cast<v4i *>(row + 64) = hi;
+    *reinterpret_cast<v4i *>(row + 32) = hi;
 }
 
 // ------------------------------------------------------------------------------------
@@ -67,69 +68,71 @@ __device__ __forceinline__ __half scale_to_half(int acc, float sx, float sw)
 }
 
 // ------------------------------------------------------------------------------------
-// stream kernel
+// stream kernel.  UC = chunks (of 64 k) per pipeline unit: 2 or 4.
 // ------------------------------------------------------------------------------------
-template <int F, int MB, bool G128>
+template <int F, int UC, bool G128>
 struct StreamRegs {
-    u32x4 w[F][2];
-    UnitParams<G128> p[F];
-    u32x4 x[MB][4];
+    u32x4 w[F][UC];
+    UnitParams<G128> p[F][UC / 2];
+    u32x4 x[2 * UC];
 };
 
-template <int F, int NW, int MB, bool G128>
+template <int F, int NW, int UC, bool G128>
 __global__ __launch_bounds__(NW * 64) void w4a8_stream_kernel(
     int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
     __half *__restrict__ Y, int32_t *__restrict__ ACC)
 {
+    extern __shared__ __attribute__((aligned(16))) int red[];  // [NW][F * rmax][64]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int j = lane & 15, kb = lane >> 4;
+    const int j = lane & 31, kb = lane >> 5;
     const int t0 = blockIdx.x * F;
-    const int units = K >> 8;
-    const int chunks_per_tile = K >> 7;
+    const int units = K / (64 * UC);
+    const int chunks_per_tile = K >> 6;
 
-    v4i acc[F][MB];
+    v16i acc[F];
 #pragma unroll
     for (int f = 0; f < F; ++f)
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) acc[f][mb] = v4i{0, 0, 0, 0};
+        for (int r = 0; r < 16; ++r) acc[f][r] = 0;
 
-    auto load_unit = [&](int u, StreamRegs<F, MB, G128> &r) {
+    auto load_unit = [&](int u, StreamRegs<F, UC, G128> &r) {
 #pragma unroll
         for (int f = 0; f < F; ++f) {
-            const u32x4 *base = Wp + ((size_t)(t0 + f) * chunks_per_tile + 2 * u) * 64 + lane;
-            r.w[f][0] = __builtin_nontemporal_load(base);
-            r.w[f][1] = __builtin_nontemporal_load(base + 64);
-            r.p[f].load(gp, (size_t)(t0 + f) * units + u, j);
+            const u32x4 *base = Wp + ((size_t)(t0 + f) * chunks_per_tile + (size_t)u * UC) * 64 + lane;
+#pragma unroll
+            for (int c = 0; c < UC; ++c) r.w[f][c] = __builtin_nontemporal_load(base + 64 * c);
+#pragma unroll
+            for (int pu = 0; pu < UC / 2; ++pu)
+                r.p[f][pu].load(gp, (size_t)(t0 + f) * (K >> 7) + (size_t)u * (UC / 2) + pu, j);
         }
+        // X fragment rows past M are zero (never loaded)
+        const int8_t *xr = X + (size_t)j * K + (size_t)u * (64 * UC) + 16 * kb;
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            // rows past M read row M-1 (their outputs are never stored)
-            const int m = min(16 * mb + j, M - 1);
-            const int8_t *xr = X + (size_t)m * K + (size_t)u * 256 + 16 * kb;
+        for (int ks = 0; ks < 2 * UC; ++ks) r.x[ks] = u32x4{0, 0, 0, 0};
+        if (j < M) {
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) r.x[mb][ks] = *reinterpret_cast<const u32x4 *>(xr + 64 * ks);
+            for (int ks = 0; ks < 2 * UC; ++ks) r.x[ks] = *reinterpret_cast<const u32x4 *>(xr + 32 * ks);
         }
     };
 
-    auto compute_unit = [&](const StreamRegs<F, MB, G128> &r) {
+    auto compute_unit = [&](const StreamRegs<F, UC, G128> &r) {
 #pragma unroll
         for (int f = 0; f < F; ++f)
 #pragma unroll
-            for (int c = 0; c < 2; ++c) {
+            for (int c = 0; c < UC; ++c) {
+                uint32_t s2, a4;
+                r.p[f][c >> 1].get(c & 1, s2, a4);
                 v4i lo, hi;
-                dequant_unit_chunk<G128>(r.w[f][c], r.p[f], c, lo, hi);
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    acc[f][mb] = mfma_i8(__builtin_bit_cast(v4i, r.x[mb][2 * c]), lo, acc[f][mb]);
-                    acc[f][mb] = mfma_i8(__builtin_bit_cast(v4i, r.x[mb][2 * c + 1]), hi, acc[f][mb]);
-                }
+                dequant_chunk(r.w[f][c], s2, a4, lo, hi);
+                acc[f] = mfma_i8(__builtin_bit_cast(v4i, r.x[2 * c]), lo, acc[f]);
+                acc[f] = mfma_i8(__builtin_bit_cast(v4i, r.x[2 * c + 1]), hi, acc[f]);
             }
     };
 
     // Register double buffering: the loads of the next unit are in flight while the
     // current one is dequantised and multiplied.
-    StreamRegs<F, MB, G128> cur, nxt;
+    StreamRegs<F, UC, G128> cur, nxt;
     int u = wave;
     if (u < units) load_unit(u, cur);
     for (; u < units; u += NW) {
@@ -139,26 +142,26 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream_kernel(
         if (more) cur = nxt;
     }
 
-    // In-block split-K reduction (integer, order independent) and epilogue.
-    constexpr int VALS = F * MB * 4;  // accumulator registers per lane
-    __shared__ int red[NW][VALS][64];
+    // In-block split-K reduction (integer, order independent) and epilogue.  Only the
+    // accumulator elements that hold rows < M take part: rows of element r lie in
+    // [8*(r/4), 8*(r/4)+8).
+    const int rmax = 4 * ((M + 7) >> 3);
 #pragma unroll
     for (int f = 0; f < F; ++f)
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) red[wave][(f * MB + mb) * 4 + r][lane] = acc[f][mb][r];
+        for (int r = 0; r < 16; ++r)
+            if (r < rmax) red[((wave * F + f) * rmax + r) * 64 + lane] = acc[f][r];
     __syncthreads();
-    for (int idx = threadIdx.x; idx < VALS * 64; idx += NW * 64) {
+    const int vals = F * rmax;
+    for (int idx = threadIdx.x; idx < vals * 64; idx += NW * 64) {
         const int v = idx >> 6, l = idx & 63;
         int sum = 0;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) sum += red[w][v][l];
-        const int r = v & 3, fm = v >> 2;
-        const int mb = fm % MB, f = fm / MB;
-        const int m = 16 * mb + 4 * (l >> 4) + r;
+        for (int w = 0; w < NW; ++w) sum += red[(w * vals + v) * 64 + l];
+        const int r = v % rmax, f = v / rmax;
+        const int m = acc_row(r, l);
         if (m < M) {
-            const int n = channel_of(t0 + f, l & 15);
+            const int n = channel_of(t0 + f, l & 31);
             if (ACC) ACC[(size_t)m * N + n] = sum;
             if (Y) Y[(size_t)m * N + n] = scale_to_half(sum, sx[m], sw[n]);
         }
@@ -166,87 +169,113 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream_kernel(
 }
 
 // ------------------------------------------------------------------------------------
-// tile kernel
+// tile kernel.  MF = 32-row fragments per wave; block tile = (32*MF) x 256.
 // ------------------------------------------------------------------------------------
-constexpr int kTilePitch = 256 + 16;  // LDS row pitch in bytes: rows shift by 4 banks
+constexpr int kTilePitch = 128 + 16;  // LDS row pitch in bytes: rows shift by 9 x 16 B
 
-template <int WM, bool G128>
-__global__ __launch_bounds__(256) void w4a8_tile_kernel(
+// Block id -> (bm, bn).  Consecutive hardware ids go to different XCDs (8 of them, each
+// with its own L2), so ids are first regrouped so that each XCD owns a contiguous range
+// of logical ids, then walked in groups of 4 row-blocks so that blocks resident together
+// on one XCD share X rows and W columns in its L2.
+__device__ __forceinline__ void block_coords(int blocks_m, int blocks_n, int &bm, int &bn)
+{
+    const int total = blocks_m * blocks_n;
+    int lid = blockIdx.x;
+    if ((total & 7) == 0) lid = (lid & 7) * (total >> 3) + (lid >> 3);
+    constexpr int GM = 4;
+    const int per_group = GM * blocks_n;
+    const int first = (lid / per_group) * GM;
+    const int gsz = min(blocks_m - first, GM);
+    const int in_group = lid % per_group;
+    bm = first + in_group % gsz;
+    bn = in_group / gsz;
+}
+
+template <int MF, bool G128>
+__global__ __launch_bounds__(256, (MF <= 4 ? 2 : 1)) void w4a8_tile_kernel(
     int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
-    __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_n)
+    __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n)
 {
-    constexpr int MI = WM / 16;        // m fragments per wave
-    constexpr int XP = WM * 16 / 256;  // 16-byte X pieces per thread per unit
+    constexpr int WM = 32 * MF;
+    constexpr int XP = MF;  // 16-byte X pieces per thread per stage of 128 k
+    constexpr int STAGE = WM * kTilePitch;
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int j = lane & 15, kb = lane >> 4;
-    const int bn = blockIdx.x % blocks_n, bm = blockIdx.x / blocks_n;
+    const int j = lane & 31, kb = lane >> 5;
+    int bm, bn;
+    block_coords(blocks_m, blocks_n, bm, bn);
     const int m0 = bm * WM;
     const int ng = bn * 4 + wave;  // 64-channel group of this wave
     const bool active = ng < (N >> 6);
     // A wave past the last group recomputes the last one and stores nothing, so that the
     // main loop has no divergent path around its barriers.
-    const int t0 = 4 * (active ? ng : (N >> 6) - 1);
-    const int units = K >> 8;
-    const int chunks_per_tile = K >> 7;
+    const int t0 = 2 * (active ? ng : (N >> 6) - 1);
+    const int stages = K >> 7;
+    const int chunks_per_tile = K >> 6;
 
-    v4i acc[MI][4];
+    v16i acc[MF][2];
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
+    for (int mf = 0; mf < MF; ++mf)
 #pragma unroll
-        for (int f = 0; f < 4; ++f) acc[mi][f] = v4i{0, 0, 0, 0};
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mf][t][r] = 0;
 
     u32x4 xr[XP];
-    u32x4 wc[4][2], wn[4][2];
-    UnitParams<G128> pc[4], pn[4];
+    u32x4 wc[2][2], wn[2][2];
+    UnitParams<G128> pc[2], pn[2];
 
     // Rows past M read row M-1: an output row depends only on its own X row, and rows
     // past M are never stored.
-    auto load_x = [&](int u) {
+    auto load_x = [&](int s) {
 #pragma unroll
         for (int i = 0; i < XP; ++i) {
             const int q = tid + 256 * i;
-            const int row = q >> 4, col = q & 15;
+            const int row = q >> 3, col = q & 7;
             const int m = min(m0 + row, M - 1);
-            xr[i] = *reinterpret_cast<const u32x4 *>(X + (size_t)m * K + (size_t)u * 256 + 16 * col);
+            xr[i] = *reinterpret_cast<const u32x4 *>(X + (size_t)m * K + (size_t)s * 128 + 16 * col);
         }
     };
-    auto store_x = [&](int stage) {
-        int8_t *base = lds + stage * (WM * kTilePitch);
+    auto store_x = [&](int buf) {
+        int8_t *base = lds + buf * STAGE;
 #pragma unroll
         for (int i = 0; i < XP; ++i) {
             const int q = tid + 256 * i;
-            const int row = q >> 4, col = q & 15;
+            const int row = q >> 3, col = q & 7;
             *reinterpret_cast<u32x4 *>(base + row * kTilePitch + 16 * col) = xr[i];
         }
     };
-    auto load_w = [&](int u, u32x4 (&w)[4][2], UnitParams<G128> (&p)[4]) {
+    auto load_w = [&](int s, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
 #pragma unroll
-        for (int f = 0; f < 4; ++f) {
-            const u32x4 *base = Wp + ((size_t)(t0 + f) * chunks_per_tile + 2 * u) * 64 + lane;
-            w[f][0] = base[0];
-            w[f][1] = base[64];
-            p[f].load(gp, (size_t)(t0 + f) * units + u, j);
+        for (int t = 0; t < 2; ++t) {
+            const u32x4 *base = Wp + ((size_t)(t0 + t) * chunks_per_tile + 2 * (size_t)s) * 64 + lane;
+            w[t][0] = base[0];
+            w[t][1] = base[64];
+            p[t].load(gp, (size_t)(t0 + t) * stages + s, j);
         }
     };
-    auto compute = [&](int stage) {
-        const int8_t *xs = lds + stage * (WM * kTilePitch) + j * kTilePitch + 16 * kb;
+    auto compute = [&](int buf) {
+        const int8_t *xs = lds + buf * STAGE + j * kTilePitch + 16 * kb;
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
-            v4i blo[4], bhi[4];
+            v4i blo[2], bhi[2];
 #pragma unroll
-            for (int f = 0; f < 4; ++f) dequant_unit_chunk<G128>(wc[f][c], pc[f], c, blo[f], bhi[f]);
+            for (int t = 0; t < 2; ++t) {
+                uint32_t s2, a4;
+                pc[t].get(c, s2, a4);
+                dequant_chunk(wc[t][c], s2, a4, blo[t], bhi[t]);
+            }
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi) {
-                const v4i a0 = *reinterpret_cast<const v4i *>(xs + mi * 16 * kTilePitch + 128 * c);
-                const v4i a1 = *reinterpret_cast<const v4i *>(xs + mi * 16 * kTilePitch + 128 * c + 64);
+            for (int mf = 0; mf < MF; ++mf) {
+                const v4i a0 = *reinterpret_cast<const v4i *>(xs + mf * 32 * kTilePitch + 64 * c);
+                const v4i a1 = *reinterpret_cast<const v4i *>(xs + mf * 32 * kTilePitch + 64 * c + 32);
 #pragma unroll
-                for (int f = 0; f < 4; ++f) acc[mi][f] = mfma_i8(a0, blo[f], acc[mi][f]);
+                for (int t = 0; t < 2; ++t) acc[mf][t] = mfma_i8(a0, blo[t], acc[mf][t]);
 #pragma unroll
-                for (int f = 0; f < 4; ++f) acc[mi][f] = mfma_i8(a1, bhi[f], acc[mi][f]);
+                for (int t = 0; t < 2; ++t) acc[mf][t] = mfma_i8(a1, bhi[t], acc[mf][t]);
             }
         }
     };
@@ -256,48 +285,48 @@ __global__ __launch_bounds__(256) void w4a8_tile_kernel(
     store_x(0);
     __syncthreads();
 
-    // Steady state: the global loads of unit u+1 are issued before the MFMAs of unit u
+    // Steady state: the global loads of stage s+1 are issued before the MFMAs of stage s
     // and land in LDS / registers after them.
-    for (int u = 0; u + 1 < units; ++u) {
-        load_x(u + 1);
-        load_w(u + 1, wn, pn);
-        compute(u & 1);
-        store_x((u + 1) & 1);
+    for (int s = 0; s + 1 < stages; ++s) {
+        load_x(s + 1);
+        load_w(s + 1, wn, pn);
+        __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of the MFMAs
+        compute(s & 1);
+        __builtin_amdgcn_sched_barrier(0);
+        store_x((s + 1) & 1);
         __syncthreads();
 #pragma unroll
-        for (int f = 0; f < 4; ++f) {
-            wc[f][0] = wn[f][0];
-            wc[f][1] = wn[f][1];
-            pc[f] = pn[f];
+        for (int t = 0; t < 2; ++t) {
+            wc[t][0] = wn[t][0];
+            wc[t][1] = wn[t][1];
+            pc[t] = pn[t];
         }
     }
-    compute((units - 1) & 1);
+    compute((stages - 1) & 1);
 
     if (!active) return;
-    // Epilogue: lane holds, for row m = m0 + 16*mi + 4*kb + r, the 4 adjacent channels
-    // n0 + 4*j + f (f = 0..3).
-    const int n = 64 * ng + 4 * j;
-    float4 swv = float4{0, 0, 0, 0};
-    if (Y) swv = *reinterpret_cast<const float4 *>(sw + n);
+    // Epilogue: element r of acc[mf][t] is row m0 + 32*mf + acc_row(r), channel
+    // 64*ng + 2*j + t: the two tiles give 2 adjacent channels per lane.
+    const int n = 64 * ng + 2 * j;
+    float2 swv = float2{0, 0};
+    if (Y) swv = *reinterpret_cast<const float2 *>(sw + n);
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
+    for (int mf = 0; mf < MF; ++mf)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int m = m0 + 16 * mi + 4 * kb + r;
+        for (int r = 0; r < 16; ++r) {
+            const int m = m0 + 32 * mf + acc_row(r, lane);
             if (m < M) {
-                const int a0 = acc[mi][0][r], a1 = acc[mi][1][r], a2 = acc[mi][2][r], a3 = acc[mi][3][r];
-                if (ACC) *reinterpret_cast<v4i *>(ACC + (size_t)m * N + n) = v4i{a0, a1, a2, a3};
+                const int a0 = acc[mf][0][r], a1 = acc[mf][1][r];
+                if (ACC) *reinterpret_cast<int2 *>(ACC + (size_t)m * N + n) = int2{a0, a1};
                 if (Y) {
                     const float s = sx[m];
                     union {
-                        __half h[4];
-                        uint2 u;
+                        __half h[2];
+                        uint32_t u;
                     } o;
                     o.h[0] = scale_to_half(a0, s, swv.x);
                     o.h[1] = scale_to_half(a1, s, swv.y);
-                    o.h[2] = scale_to_half(a2, s, swv.z);
-                    o.h[3] = scale_to_half(a3, s, swv.w);
-                    *reinterpret_cast<uint2 *>(Y + (size_t)m * N + n) = o.u;
+                    *reinterpret_cast<uint32_t *>(Y + (size_t)m * N + n) = o.u;
                 }
             }
         }
@@ -320,66 +349,86 @@ struct Args {
 
 typedef int (*LaunchFn)(const Args &);
 
-template <int F, int NW, int MB>
-static int launch_stream(const Args &a)
+template <class Kernel>
+static int allow_lds(Kernel kernel, size_t bytes)
 {
-    if (a.M > 16 * MB) return fail(LQ_ERR_INVALID, "stream variant handles M <= %d, got %d", 16 * MB, a.M);
-    if ((a.N / 16) % F != 0) return fail(LQ_ERR_INVALID, "N/16 not a multiple of F=%d", F);
-    const dim3 grid(a.N / (16 * F)), block(NW * 64);
-    if (a.group == 128)
-        hipLaunchKernelGGL((w4a8_stream_kernel<F, NW, MB, true>), grid, block, 0, a.stream, a.M, a.N, a.K,
-                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC);
-    else
-        hipLaunchKernelGGL((w4a8_stream_kernel<F, NW, MB, false>), grid, block, 0, a.stream, a.M, a.N, a.K,
-                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC);
+    if (bytes <= 48 * 1024) return LQ_OK;
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess)
+        return fail(LQ_ERR_HIP, "hipFuncSetAttribute(%zu bytes of LDS): %s", bytes, hipGetErrorString(e));
     return LQ_OK;
 }
 
-template <int WM>
+template <int F, int NW, int UC>
+static int launch_stream(const Args &a)
+{
+    if (a.M > 32) return fail(LQ_ERR_INVALID, "stream variants handle M <= 32, got %d", a.M);
+    if ((a.N / 32) % F != 0) return fail(LQ_ERR_INVALID, "N/32 not a multiple of F=%d", F);
+    if ((a.K / 64) % UC != 0) return fail(LQ_ERR_INVALID, "K/64 not a multiple of %d", UC);
+    const dim3 grid(a.N / (32 * F)), block(NW * 64);
+    const int rmax = 4 * ((a.M + 7) / 8);
+    const size_t lds_bytes = (size_t)NW * F * rmax * 64 * sizeof(int);
+    if (a.group == 128) {
+        if (int rc = allow_lds(&w4a8_stream_kernel<F, NW, UC, true>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_stream_kernel<F, NW, UC, true>), grid, block, lds_bytes, a.stream, a.M, a.N,
+                           a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC);
+    } else {
+        if (int rc = allow_lds(&w4a8_stream_kernel<F, NW, UC, false>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_stream_kernel<F, NW, UC, false>), grid, block, lds_bytes, a.stream, a.M, a.N,
+                           a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC);
+    }
+    return LQ_OK;
+}
+
+template <int MF>
 static int launch_tile(const Args &a)
 {
+    constexpr int WM = 32 * MF;
     const int blocks_n = (a.N + 255) / 256, blocks_m = (a.M + WM - 1) / WM;
     const size_t lds_bytes = 2 * (size_t)WM * kTilePitch;
     const dim3 grid((unsigned)(blocks_n * blocks_m)), block(256);
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4a8_tile_kernel<WM, true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&w4a8_tile_kernel<WM, false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess)
-            return fail(LQ_ERR_HIP, "hipFuncSetAttribute(%zu bytes of LDS): %s", lds_bytes, hipGetErrorString(e));
-        attr_done = true;
+    if (a.group == 128) {
+        if (int rc = allow_lds(&w4a8_tile_kernel<MF, true>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_tile_kernel<MF, true>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
+                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
+    } else {
+        if (int rc = allow_lds(&w4a8_tile_kernel<MF, false>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_tile_kernel<MF, false>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
+                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
     }
-    if (a.group == 128)
-        hipLaunchKernelGGL((w4a8_tile_kernel<WM, true>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
-                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_n);
-    else
-        hipLaunchKernelGGL((w4a8_tile_kernel<WM, false>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
-                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_n);
     return LQ_OK;
 }
 
 struct Variant {
     const char *name;
     LaunchFn fn;
-    int max_m;  // 0 = unlimited
+    int max_m;      // 0 = unlimited
+    int tiles_div;  // N/32 must be a multiple of this
+    int chunks_div; // K/64 must be a multiple of this
 };
 
+// stream_f<F>_w<NW>_u<UC>: F tiles per block, NW waves splitting K, UC chunks per unit.
 static const Variant kVariants[] = {
-    {"stream_f1_w16_m16", &launch_stream<1, 16, 1>, 16},
-    {"stream_f1_w8_m16", &launch_stream<1, 8, 1>, 16},
-    {"stream_f2_w8_m16", &launch_stream<2, 8, 1>, 16},
-    {"stream_f4_w4_m16", &launch_stream<4, 4, 1>, 16},
-    {"stream_f4_w8_m16", &launch_stream<4, 8, 1>, 16},
-    {"stream_f2_w8_m32", &launch_stream<2, 8, 2>, 32},
-    {"stream_f4_w4_m32", &launch_stream<4, 4, 2>, 32},
-    {"tile_m32", &launch_tile<32>, 0},
-    {"tile_m64", &launch_tile<64>, 0},
-    {"tile_m128", &launch_tile<128>, 0},
+    {"stream_f1_w16_u2", &launch_stream<1, 16, 2>, 32, 1, 2},
+    {"stream_f1_w8_u4", &launch_stream<1, 8, 4>, 32, 1, 4},
+    {"stream_f2_w8_u4", &launch_stream<2, 8, 4>, 32, 2, 4},
+    {"stream_f2_w8_u2", &launch_stream<2, 8, 2>, 32, 2, 2},
+    {"stream_f2_w4_u4", &launch_stream<2, 4, 4>, 32, 2, 4},
+    {"stream_f4_w4_u2", &launch_stream<4, 4, 2>, 32, 4, 2},
+    {"stream_f4_w8_u2", &launch_stream<4, 8, 2>, 32, 4, 2},
+    {"tile_m32", &launch_tile<1>, 0, 1, 1},
+    {"tile_m64", &launch_tile<2>, 0, 1, 1},
+    {"tile_m128", &launch_tile<4>, 0, 1, 1},
+    {"tile_m256", &launch_tile<8>, 0, 1, 1},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
+
+static bool variant_supports(int v, int M, int N, int K)
+{
+    const Variant &x = kVariants[v];
+    return (x.max_m == 0 || M <= x.max_m) && (N / 32) % x.tiles_div == 0 && (K / 64) % x.chunks_div == 0;
+}
 
 static int find_variant(const char *name)
 {
@@ -390,19 +439,21 @@ static int find_variant(const char *name)
 
 // Shape -> kernel.  Decode-sized batches stream the weights with in-block split-K sized
 // so that the grid fills the 256 CUs; larger batches use the LDS-tiled kernel with the
-// largest row tile that M fills.
+// largest row tile that still gives every CU a block.
 static int select_variant(int M, int N, int K)
 {
     (void)K;
-    if (M <= 16) {
-        const int tiles = N / 16;
-        if (tiles <= 512) return find_variant("stream_f1_w16_m16");
-        if (tiles <= 1024) return find_variant("stream_f1_w8_m16");
-        return find_variant("stream_f2_w8_m16");
+    if (M <= 32) {
+        const int tiles = N / 32;
+        if (tiles <= 256) return find_variant("stream_f1_w16_u2");
+        if (tiles <= 512) return find_variant("stream_f1_w8_u4");
+        return find_variant("stream_f2_w8_u4");
     }
-    if (M <= 32) return find_variant(N / 16 <= 1024 ? "stream_f2_w8_m32" : "stream_f4_w4_m32");
+    const int blocks_n = (N + 255) / 256;
+    if (M <= 32) return find_variant("tile_m32");
     if (M <= 64) return find_variant("tile_m64");
-    return find_variant("tile_m128");
+    if (M <= 128 || ((M + 255) / 256) * blocks_n < 256) return find_variant("tile_m128");
+    return find_variant("tile_m256");
 }
 
 static int check_device_args(const Args &a, const void *ws, size_t ws_bytes)
@@ -429,6 +480,9 @@ static int run(int variant, const Args &a, const void *ws, size_t ws_bytes)
     if (a.M == 0) return LQ_OK;
     if (variant < 0) variant = select_variant(a.M, a.N, a.K);
     if (variant < 0 || variant >= kNumVariants) return fail(LQ_ERR_INVALID, "unknown variant %d", variant);
+    if (!variant_supports(variant, a.M, a.N, a.K))
+        return fail(LQ_ERR_INVALID, "variant %s cannot run M=%d N=%d K=%d", kVariants[variant].name, a.M, a.N,
+                    a.K);
     (void)hipGetLastError();
     if (int rc = kVariants[variant].fn(a)) return rc;
     const hipError_t e = hipGetLastError();
@@ -490,6 +544,12 @@ const char *w4a8_variant_name(int variant)
     return (variant >= 0 && variant < kNumVariants) ? kVariants[variant].name : nullptr;
 }
 
+int w4a8_variant_supports(int variant, int M, int N, int K, int group)
+{
+    if (variant < 0 || variant >= kNumVariants || M < 0 || !shape_ok(N, K, group)) return 0;
+    return variant_supports(variant, M, N, K) ? 1 : 0;
+}
+
 int w4a8_select_variant(int M, int N, int K, int group)
 {
     if (M < 0 || !shape_ok(N, K, group)) return fail(LQ_ERR_INVALID, "bad shape");
@@ -503,7 +563,7 @@ int w4a8_dequant_dump(const void *W_packed, const uint8_t *gparams, int N, int K
     if (!W_packed || !gparams || !Wd) return fail(LQ_ERR_INVALID, "null pointer");
     if (((uintptr_t)W_packed | (uintptr_t)gparams | (uintptr_t)Wd) & 15)
         return fail(LQ_ERR_ALIGN, "device pointers must be 16-byte aligned");
-    const dim3 grid((unsigned)((K / 128 + 3) / 4), (unsigned)(N / 16)), block(256);
+    const dim3 grid((unsigned)((K / 64 + 3) / 4), (unsigned)(N / 32)), block(256);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     (void)hipGetLastError();
     if (group == 128)

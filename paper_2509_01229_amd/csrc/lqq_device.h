@@ -7,9 +7,9 @@
 namespace lqq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 // (r * s + a) on two 16-bit lanes: one v_pk_mad_u16.  With every byte of r <= 15,
 // s <= 16 and byte*s + a <= 255 (Eq. 11) no byte carries into its neighbour, so this is
@@ -32,76 +32,57 @@ __device__ __forceinline__ void expand_params(uint32_t word, int which, uint32_t
     a4 = __builtin_amdgcn_perm(word, word, which ? 0x03030303u : 0x01010101u);
 }
 
-// Unpack + dequantise one 16-byte lane load (32 codes): the low nibbles become the four
-// operand registers of the first k-step, the high nibbles those of the second.
-// 7 VALU instructions per 8 codes: and, shift, and, 2 x pk_mad, 2 x xor (Sec. 5.3).
-__device__ __forceinline__ void dequant_chunk(const u32x4 p, uint32_t s2_lo, uint32_t a4_lo,
-                                              uint32_t s2_hi, uint32_t a4_hi, v4i &lo, v4i &hi)
+// Unpack + dequantise one 16-byte lane load (32 codes of one channel, one group): the low
+// nibbles become the four operand registers of the first k-step, the high nibbles those
+// of the second.  7 VALU instructions per 8 codes: and, shift, and, 2 x pk_mad, 2 x xor
+// (Sec. 5.3).
+__device__ __forceinline__ void dequant_chunk(const u32x4 p, uint32_t s2, uint32_t a4, v4i &lo, v4i &hi)
 {
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
         const uint32_t l = p[d] & 0x0F0F0F0Fu;
         const uint32_t h = (p[d] >> 4) & 0x0F0F0F0Fu;
-        lo[d] = (int)(pk_mad_u16(l, s2_lo, a4_lo) ^ 0x80808080u);
-        hi[d] = (int)(pk_mad_u16(h, s2_hi, a4_hi) ^ 0x80808080u);
+        lo[d] = (int)(pk_mad_u16(l, s2, a4) ^ 0x80808080u);
+        hi[d] = (int)(pk_mad_u16(h, s2, a4) ^ 0x80808080u);
     }
 }
 
-// Group parameters of one lane's channel for one unit of 256 k.
-// group 64: four pairs (8 bytes); group 128: two pairs (4 bytes).
+// Group parameters of one lane's channel for one unit of 128 k (two chunks).
+// group 64: two (s, a) pairs in 4 bytes; group 128: one pair in 2 bytes.
 template <bool G128>
 struct UnitParams;
 template <>
 struct UnitParams<false> {
-    u32x2 raw;
+    uint32_t raw;
     __device__ __forceinline__ void load(const uint8_t *gp, size_t tile_unit, int slot)
     {
-        raw = *reinterpret_cast<const u32x2 *>(gp + (tile_unit * 16 + slot) * 8);
+        raw = *reinterpret_cast<const uint32_t *>(gp + (tile_unit * 32 + slot) * 4);
     }
-    // parameters of k-step ks (0..3) of the unit
-    __device__ __forceinline__ void get(int ks, uint32_t &s2, uint32_t &a4) const
-    {
-        expand_params((ks & 2) ? raw.y : raw.x, ks & 1, s2, a4);
-    }
+    // broadcast parameters of chunk c (0 or 1) of the unit
+    __device__ __forceinline__ void get(int c, uint32_t &s2, uint32_t &a4) const { expand_params(raw, c, s2, a4); }
 };
 template <>
 struct UnitParams<true> {
     uint32_t raw;
     __device__ __forceinline__ void load(const uint8_t *gp, size_t tile_unit, int slot)
     {
-        raw = *reinterpret_cast<const uint32_t *>(gp + (tile_unit * 16 + slot) * 4);
+        raw = *reinterpret_cast<const uint16_t *>(gp + (tile_unit * 32 + slot) * 2);
     }
-    __device__ __forceinline__ void get(int ks, uint32_t &s2, uint32_t &a4) const
-    {
-        expand_params(raw, ks >> 1, s2, a4);
-    }
+    __device__ __forceinline__ void get(int, uint32_t &s2, uint32_t &a4) const { expand_params(raw, 0, s2, a4); }
 };
 
-// Dequantise chunk c (0 or 1) of a unit: k-steps 2c (low nibbles) and 2c+1 (high).
-template <bool G128>
-__device__ __forceinline__ void dequant_unit_chunk(const u32x4 p, const UnitParams<G128> &up, int c,
-                                                   v4i &lo, v4i &hi)
+// D(32x32) += A(32x32) * B(32x32), INT8 inputs, INT32 accumulate.  Lane l supplies row
+// l%32 of A and column l%32 of B for k-block l/32 (16 bytes each); it receives
+// D[8*(r/4) + 4*(l/32) + r%4][l%32] in element r (r = 0..15).
+__device__ __forceinline__ v16i mfma_i8(const v4i a, const v4i b, const v16i c)
 {
-    uint32_t s2l, a4l, s2h, a4h;
-    up.get(2 * c, s2l, a4l);
-    if (G128) {
-        s2h = s2l;
-        a4h = a4l;
-    } else {
-        up.get(2 * c + 1, s2h, a4h);
-    }
-    dequant_chunk(p, s2l, a4l, s2h, a4h, lo, hi);
+    return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
 }
 
-// D(16x16) += A(16x64) * B(64x16), INT8 inputs, INT32 accumulate.  Lane l supplies row
-// l%16 of A and column l%16 of B for k-block l/16 (16 bytes each); it receives
-// D[4*(l/16) + r][l%16] in element r.
-__device__ __forceinline__ v4i mfma_i8(const v4i a, const v4i b, const v4i c)
-{
-    return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
-}
+// Row of the 32x32 MFMA result held in accumulator element r of lane l.
+__device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 
 // Channel held by slot j of tile t (see lqq_layout.h).
-__device__ __forceinline__ int channel_of(int t, int j) { return 64 * (t >> 2) + 4 * j + (t & 3); }
+__device__ __forceinline__ int channel_of(int t, int j) { return 64 * (t >> 1) + 2 * j + (t & 1); }
 
 }  // namespace lqq

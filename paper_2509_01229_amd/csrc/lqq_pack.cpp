@@ -117,9 +117,8 @@ int pack_float_rows(LoadRow load_row, int N, int K, int group, void *W_packed, u
 {
     uint8_t *codes = static_cast<uint8_t *>(W_packed);
     std::memset(codes, 0, (size_t)N * K / 2);
-    // Channels n, n+1, n+2, n+3 of one 64-group share no byte with other channels' codes
-    // except through the low/high nibble of the same byte, which belong to the same
-    // channel; so rows can be packed concurrently.
+    // The two nibbles of a byte belong to the same channel, so distinct channels never
+    // touch the same byte and rows can be packed concurrently.
     parallel_rows(N, [&](int nb, int ne) {
         std::vector<float> w(K);
         std::vector<int8_t> q(K);
@@ -148,7 +147,7 @@ using namespace lqq;
 
 extern "C" {
 
-int w4a8_version(void) { return 1; }
+int w4a8_version(void) { return 2; }
 
 const char *w4a8_last_error(void) { return lqq::last_error(); }
 

@@ -99,15 +99,6 @@ def assert_fp16_close(Y, ref_f64, what=""):
     assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} outputs off, worst rel {np.max(err / (np.abs(ref[ok]) + 1e-30)):.3e}"
 
 
-def variants_for(M):
-    """Indices of every kernel variant able to run a batch of M rows."""
-    out = []
-    for i, name in enumerate(api.w4a8_variant_names()):
-        m = None
-        for part in name.split("_"):
-            if part.startswith("m") and part[1:].isdigit():
-                m = int(part[1:])
-        if name.startswith("stream") and m is not None and M > m:
-            continue
-        out.append(i)
-    return out
+def variants_for(M, N, K, group):
+    """Indices of every kernel variant able to run this shape."""
+    return [i for i in range(api.w4a8_variant_count()) if api.w4a8_variant_supports(i, M, N, K, group)]
