@@ -25,9 +25,9 @@ FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False, extra_flags=()) -> str:
+def build_library(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    cmd = [HIPCC, *FLAGS, *extra_flags, "-o", LIB, *srcs]
+    cmd = [HIPCC, *FLAGS, *extra_flags, "-o", out, *srcs]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -36,7 +36,7 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
         raise RuntimeError("hipcc failed building libliquidgemm.so")
     if verbose and res.stderr:
         sys.stderr.write(res.stderr)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

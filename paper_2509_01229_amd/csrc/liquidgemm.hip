@@ -169,6 +169,51 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream_kernel(
 }
 
 // ------------------------------------------------------------------------------------
+// Epilogue shared by the tiled kernels.  Element r of acc[mf][t] is row
+// m0 + 32*mf + acc_row(r, lane) and channel n + t (n = 64*group + 2*slot): the two tiles
+// give 2 adjacent channels per lane, so each store is 4 bytes of FP16 (8 of INT32) and a
+// half-wave writes a full 128-byte line.  Scales are fetched up front, four consecutive
+// rows at a time (rows past M read s_x[M-1]; only the stores are predicated), so no
+// load sits behind a branch.
+// ------------------------------------------------------------------------------------
+template <int MF>
+__device__ __forceinline__ void store_tile(const v16i (&acc)[MF][2], int M, int N, int m0, int n, int lane,
+                                           const float *__restrict__ sx, const float *__restrict__ sw,
+                                           __half *__restrict__ Y, int32_t *__restrict__ ACC)
+{
+    const int kb = lane >> 5;
+    if (ACC) {
+#pragma unroll
+        for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + 32 * mf + 8 * (r >> 2) + 4 * kb + (r & 3);
+                if (m < M) *reinterpret_cast<int2 *>(ACC + (size_t)m * N + n) = int2{acc[mf][0][r], acc[mf][1][r]};
+            }
+    }
+    if (Y) {
+        const float2 swv = *reinterpret_cast<const float2 *>(sw + n);
+#pragma unroll
+        for (int mf = 0; mf < MF; ++mf) {
+            float sxv[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sxv[r] = sx[min(m0 + 32 * mf + 8 * (r >> 2) + 4 * kb + (r & 3), M - 1)];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + 32 * mf + 8 * (r >> 2) + 4 * kb + (r & 3);
+                union {
+                    __half h[2];
+                    uint32_t u;
+                } o;
+                o.h[0] = scale_to_half(acc[mf][0][r], sxv[r], swv.x);
+                o.h[1] = scale_to_half(acc[mf][1][r], sxv[r], swv.y);
+                if (m < M) *reinterpret_cast<uint32_t *>(Y + (size_t)m * N + n) = o.u;
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------
 // tile kernel.  MF = 32-row fragments per wave; block tile = (32*MF) x 256.
 // ------------------------------------------------------------------------------------
 constexpr int kTilePitch = 128 + 16;  // LDS row pitch in bytes: rows shift by 9 x 16 B
@@ -307,29 +352,198 @@ __global__ __launch_bounds__(256, (MF <= 4 ? 2 : 1)) void w4a8_tile_kernel(
     if (!active) return;
     // Epilogue: element r of acc[mf][t] is row m0 + 32*mf + acc_row(r), channel
     // 64*ng + 2*j + t: the two tiles give 2 adjacent channels per lane.
-    const int n = 64 * ng + 2 * j;
-    float2 swv = float2{0, 0};
-    if (Y) swv = *reinterpret_cast<const float2 *>(sw + n);
+    store_tile<MF>(acc, M, N, m0, 64 * ng + 2 * j, lane, sx, sw, Y, ACC);
+}
+
+// ------------------------------------------------------------------------------------
+// pipe kernel: the tile kernel with an explicit software pipeline for one wave per SIMD.
+//
+// Same block tile ((32*MF) x 256, 4 waves, each 64 channels) and LDS layout as the tile
+// kernel.  A stage (128 k) is cut into 4 groups (chunk c, half h) of 2*MF MFMAs:
+//   * the X fragments of group g+1 are read from LDS while the MFMAs of group g run;
+//   * the dequantisation of chunk 1 is issued among the MFMAs of group 0, that of chunk 0
+//     of the next stage among those of group 2, so the VALU work hides under the matrix
+//     pipe of the same wave (the intra-wave form of the paper's implicit pipeline,
+//     Sec. 5.1: no hand-off between dequantisation and MMA);
+//   * global loads run ahead: X pieces wait two stages in registers before they are
+//     written to the other LDS buffer at the top of a stage, W chunks are re-issued into
+//     their registers as soon as their last dequantisation is done;
+//   * the single barrier of a stage sits before its last group and waits only for LDS
+//     traffic, never for outstanding global loads.
+// ------------------------------------------------------------------------------------
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Ask the scheduler for `n` repetitions of {1 MFMA, `valu` VALU} in this order.
+template <int N, int VALU>
+__device__ __forceinline__ void interleave_mfma_valu()
+{
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (VALU > 0) __builtin_amdgcn_sched_group_barrier(0x002, VALU, 0);
+    }
+}
+
+// ABL (bit mask, experiments only; 0 in every shipped variant): 1 = no X global loads / LDS
+// stores after the prologue, 2 = no W reloads, 4 = no LDS fragment reads, 8 = no
+// dequantisation, 16 = no barrier.  Results are wrong for ABL != 0.
+template <int MF, bool G128, int ABL = 0>
+__global__ __launch_bounds__(256, (MF <= 4 ? 2 : 1)) void w4a8_pipe_kernel(
+    int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
+    const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
+    __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n)
+{
+    constexpr int WM = 32 * MF;
+    constexpr int XP = MF;
+    constexpr int STAGE = WM * kTilePitch;
+    extern __shared__ __attribute__((aligned(16))) int8_t lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 31, kb = lane >> 5;
+    int bm, bn;
+    block_coords(blocks_m, blocks_n, bm, bn);
+    const int m0 = bm * WM;
+    const int ng = bn * 4 + wave;
+    const bool active = ng < (N >> 6);
+    const int t0 = 2 * (active ? ng : (N >> 6) - 1);
+    const int stages = K >> 7;  // even, since K % 256 == 0
+    const int chunks_per_tile = K >> 6;
+
+    v16i acc[MF][2];
 #pragma unroll
     for (int mf = 0; mf < MF; ++mf)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int m = m0 + 32 * mf + acc_row(r, lane);
-            if (m < M) {
-                const int a0 = acc[mf][0][r], a1 = acc[mf][1][r];
-                if (ACC) *reinterpret_cast<int2 *>(ACC + (size_t)m * N + n) = int2{a0, a1};
-                if (Y) {
-                    const float s = sx[m];
-                    union {
-                        __half h[2];
-                        uint32_t u;
-                    } o;
-                    o.h[0] = scale_to_half(a0, s, swv.x);
-                    o.h[1] = scale_to_half(a1, s, swv.y);
-                    *reinterpret_cast<uint32_t *>(Y + (size_t)m * N + n) = o.u;
-                }
-            }
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mf][t][r] = 0;
+
+    // per-thread constant parts of the addresses
+    const int8_t *xg[XP];
+    int xl[XP];
+#pragma unroll
+    for (int i = 0; i < XP; ++i) {
+        const int q = tid + 256 * i;
+        const int row = q >> 3, col = q & 7;
+        xg[i] = X + (size_t)min(m0 + row, M - 1) * K + 16 * col;  // rows past M read row M-1
+        xl[i] = row * kTilePitch + 16 * col;
+    }
+    const u32x4 *wg[2];
+    const uint8_t *pg[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        wg[t] = Wp + (size_t)(t0 + t) * chunks_per_tile * 64 + lane;
+        pg[t] = gp + ((size_t)(t0 + t) * stages * 32 + j) * (G128 ? 2 : 4);
+    }
+    const int8_t *xs = lds + j * kTilePitch + 16 * kb;  // this lane's fragment row in a stage
+
+    u32x4 xr[2][XP];          // X pieces in flight; set p holds a stage of parity p
+    u32x4 wr[2][2][2];        // W chunks: [stage parity][tile][chunk]
+    UnitParams<G128> pr[2][2];
+    v4i bf[2][2][2];          // dequantised B fragments: [chunk][tile][half]
+    v4i af[2][MF];            // X fragments of the current / next group
+
+    auto load_x = [&](int s, u32x4 (&dst)[XP]) {
+        s = min(s, stages - 1);  // past the end: harmless reload of the last stage
+#pragma unroll
+        for (int i = 0; i < XP; ++i) dst[i] = *reinterpret_cast<const u32x4 *>(xg[i] + (size_t)s * 128);
+    };
+    auto store_x = [&](int buf, const u32x4 (&src)[XP]) {
+#pragma unroll
+        for (int i = 0; i < XP; ++i) *reinterpret_cast<u32x4 *>(lds + buf * STAGE + xl[i]) = src[i];
+    };
+    auto load_w = [&](int s, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
+        s = min(s, stages - 1);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            w[t][0] = wg[t][(size_t)s * 128];
+            w[t][1] = wg[t][(size_t)s * 128 + 64];
+            if (G128)
+                p[t].raw = *reinterpret_cast<const uint16_t *>(pg[t] + (size_t)s * 64);
+            else
+                p[t].raw = *reinterpret_cast<const uint32_t *>(pg[t] + (size_t)s * 128);
         }
+    };
+    auto dequant = [&](const u32x4 (&w)[2][2], const UnitParams<G128> (&p)[2], int c, v4i (&b)[2][2]) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            uint32_t s2, a4;
+            p[t].get(c, s2, a4);
+            dequant_chunk(w[t][c], s2, a4, b[t][0], b[t][1]);
+        }
+    };
+    // X fragments of group (c, h) of the stage in LDS buffer `buf`
+    auto read_group = [&](int buf, int c, int h, v4i (&a)[MF]) {
+#pragma unroll
+        for (int mf = 0; mf < MF; ++mf)
+            a[mf] = *reinterpret_cast<const v4i *>(xs + buf * STAGE + mf * 32 * kTilePitch + 64 * c + 32 * h);
+    };
+    auto mma_group = [&](const v4i (&a)[MF], const v4i (&b)[2][2], int h) {
+#pragma unroll
+        for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) acc[mf][t] = mfma_i8(a[mf], b[t][h], acc[mf][t]);
+    };
+
+    // One stage.  xs_set holds X(s+1) on entry and X(s+3) on exit; w_cur = W(s) on entry and
+    // W(s+2) on exit; w_nxt = W(s+1).  af[0] holds group 0 of this stage on entry.
+    auto stage = [&](int s, u32x4 (&xs_set)[XP], u32x4 (&w_cur)[2][2], UnitParams<G128> (&p_cur)[2],
+                     u32x4 (&w_nxt)[2][2], UnitParams<G128> (&p_nxt)[2], int buf) {
+        if (!(ABL & 1)) {
+            store_x(buf ^ 1, xs_set);  // X(s+1): its buffer was released by the previous barrier
+            load_x(s + 3, xs_set);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // group 0 = (chunk 0, half 0); dequantise chunk 1 underneath
+        if (!(ABL & 4)) read_group(buf, 0, 1, af[1]);
+        if (!(ABL & 8)) dequant(w_cur, p_cur, 1, bf[1]);
+        mma_group(af[0], bf[0], 0);
+        interleave_mfma_valu<2 * MF, 4>();
+        __builtin_amdgcn_sched_barrier(0);
+        // group 1 = (chunk 0, half 1); W(s) is no longer needed: fetch W(s+2)
+        if (!(ABL & 2)) load_w(s + 2, w_cur, p_cur);
+        if (!(ABL & 4)) read_group(buf, 1, 0, af[0]);
+        mma_group(af[1], bf[0], 1);
+        __builtin_amdgcn_sched_barrier(0);
+        // group 2 = (chunk 1, half 0); dequantise chunk 0 of stage s+1 underneath
+        if (!(ABL & 4)) read_group(buf, 1, 1, af[1]);
+        if (!(ABL & 8)) dequant(w_nxt, p_nxt, 0, bf[0]);
+        mma_group(af[0], bf[1], 0);
+        interleave_mfma_valu<2 * MF, 4>();
+        __builtin_amdgcn_sched_barrier(0);
+        // group 3 = (chunk 1, half 1); after the barrier the next stage's buffer is readable
+        if (!(ABL & 16)) lds_barrier();
+        if (!(ABL & 4)) read_group(buf ^ 1, 0, 0, af[0]);
+        mma_group(af[1], bf[1], 1);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // prologue: X(0) -> LDS, X(1) and X(2) in registers, W(0), W(1) in registers
+    load_x(0, xr[0]);
+    load_w(0, wr[0], pr[0]);
+    load_w(1, wr[1], pr[1]);
+    load_x(1, xr[1]);
+    store_x(0, xr[0]);
+    load_x(2, xr[0]);
+    dequant(wr[0], pr[0], 0, bf[0]);
+    dequant(wr[0], pr[0], 1, bf[1]);
+    lds_barrier();
+    read_group(0, 0, 0, af[0]);
+    read_group(0, 0, 1, af[1]);
+    __builtin_amdgcn_sched_barrier(0);
+
+    for (int s = 0; s < stages; s += 2) {
+        stage(s, xr[1], wr[0], pr[0], wr[1], pr[1], 0);
+        stage(s + 1, xr[0], wr[1], pr[1], wr[0], pr[0], 1);
+    }
+
+    if (!active) return;
+    store_tile<MF>(acc, M, N, m0, 64 * ng + 2 * j, lane, sx, sw, Y, ACC);
 }
 
 // ------------------------------------------------------------------------------------
@@ -400,6 +614,25 @@ static int launch_tile(const Args &a)
     return LQ_OK;
 }
 
+template <int MF, int ABL = 0>
+static int launch_pipe(const Args &a)
+{
+    constexpr int WM = 32 * MF;
+    const int blocks_n = (a.N + 255) / 256, blocks_m = (a.M + WM - 1) / WM;
+    const size_t lds_bytes = 2 * (size_t)WM * kTilePitch;
+    const dim3 grid((unsigned)(blocks_n * blocks_m)), block(256);
+    if (a.group == 128) {
+        if (int rc = allow_lds(&w4a8_pipe_kernel<MF, true, ABL>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_pipe_kernel<MF, true, ABL>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
+                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
+    } else {
+        if (int rc = allow_lds(&w4a8_pipe_kernel<MF, false, ABL>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_pipe_kernel<MF, false, ABL>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
+                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
+    }
+    return LQ_OK;
+}
+
 struct Variant {
     const char *name;
     LaunchFn fn;
@@ -421,6 +654,19 @@ static const Variant kVariants[] = {
     {"tile_m64", &launch_tile<2>, 0, 1, 1},
     {"tile_m128", &launch_tile<4>, 0, 1, 1},
     {"tile_m256", &launch_tile<8>, 0, 1, 1},
+    {"pipe_m128", &launch_pipe<4>, 0, 1, 1},
+    {"pipe_m256", &launch_pipe<8>, 0, 1, 1},
+#ifdef LQ_ABLATE
+    {"abl_m256_noX", &launch_pipe<8, 1>, 0, 1, 1},
+    {"abl_m256_noW", &launch_pipe<8, 2>, 0, 1, 1},
+    {"abl_m256_noXW", &launch_pipe<8, 3>, 0, 1, 1},
+    {"abl_m256_noLdsRead", &launch_pipe<8, 4>, 0, 1, 1},
+    {"abl_m256_noDequant", &launch_pipe<8, 8>, 0, 1, 1},
+    {"abl_m256_noBarrier", &launch_pipe<8, 16>, 0, 1, 1},
+    {"abl_m256_noXW_noDq", &launch_pipe<8, 11>, 0, 1, 1},
+    {"abl_m256_mfmaOnly", &launch_pipe<8, 31>, 0, 1, 1},
+    {"abl_m256_noXWLds", &launch_pipe<8, 7>, 0, 1, 1},
+#endif
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
