@@ -378,14 +378,19 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// Ask the scheduler for `n` repetitions of {1 MFMA, `valu` VALU} in this order.
-template <int N, int VALU>
-__device__ __forceinline__ void interleave_mfma_valu()
+// Ask the scheduler for NM repetitions of {1 MFMA, NV VALU, at most one LDS read, one LDS
+// write and one global load}: NR reads go behind the first NR MFMAs, NWR writes and NG
+// loads behind every other MFMA, so that no wave sends a burst of memory instructions.
+template <int NM, int NV, int NR, int NWR, int NG>
+__device__ __forceinline__ void interleave()
 {
 #pragma unroll
-    for (int i = 0; i < N; ++i) {
+    for (int i = 0; i < NM; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (VALU > 0) __builtin_amdgcn_sched_group_barrier(0x002, VALU, 0);
+        if (NV > 0) __builtin_amdgcn_sched_group_barrier(0x002, NV, 0);
+        if (i < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        if ((i & 1) == 0 && (i >> 1) < NWR) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        if ((i & 1) == 1 && (i >> 1) < NG) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
     }
 }
 
@@ -492,34 +497,47 @@ __global__ __launch_bounds__(256, (MF <= 4 ? 2 : 1)) void w4a8_pipe_kernel(
 
     // One stage.  xs_set holds X(s+1) on entry and X(s+3) on exit; w_cur = W(s) on entry and
     // W(s+2) on exit; w_nxt = W(s+1).  af[0] holds group 0 of this stage on entry.
+    // X pieces [lo, hi) of xs_set: write X(s+1) to the other buffer, then refill with X(s+3)
+    auto xfer_x = [&](int s, int buf, u32x4 (&set)[XP], int lo, int hi) {
+        const int sl = min(s + 3, stages - 1);  // past the end: harmless reload of the last stage
+#pragma unroll
+        for (int i = 0; i < XP; ++i)
+            if (i >= lo && i < hi) {
+                *reinterpret_cast<u32x4 *>(lds + (buf ^ 1) * STAGE + xl[i]) = set[i];
+                set[i] = *reinterpret_cast<const u32x4 *>(xg[i] + (size_t)sl * 128);
+            }
+    };
+    constexpr int XB1 = (XP + 2) / 3, XB2 = (2 * XB1 < XP) ? 2 * XB1 : XP;  // piece ranges of groups 0..2
+    constexpr int NM = 2 * MF;                                             // MFMAs per group
+
     auto stage = [&](int s, u32x4 (&xs_set)[XP], u32x4 (&w_cur)[2][2], UnitParams<G128> (&p_cur)[2],
                      u32x4 (&w_nxt)[2][2], UnitParams<G128> (&p_nxt)[2], int buf) {
-        if (!(ABL & 1)) {
-            store_x(buf ^ 1, xs_set);  // X(s+1): its buffer was released by the previous barrier
-            load_x(s + 3, xs_set);
-        }
-        __builtin_amdgcn_sched_barrier(0);
         // group 0 = (chunk 0, half 0); dequantise chunk 1 underneath
+        if (!(ABL & 1)) xfer_x(s, buf, xs_set, 0, XB1);
         if (!(ABL & 4)) read_group(buf, 0, 1, af[1]);
         if (!(ABL & 8)) dequant(w_cur, p_cur, 1, bf[1]);
         mma_group(af[0], bf[0], 0);
-        interleave_mfma_valu<2 * MF, 4>();
+        interleave<NM, 4, MF, XB1, XB1>();
         __builtin_amdgcn_sched_barrier(0);
         // group 1 = (chunk 0, half 1); W(s) is no longer needed: fetch W(s+2)
+        if (!(ABL & 1)) xfer_x(s, buf, xs_set, XB1, XB2);
         if (!(ABL & 2)) load_w(s + 2, w_cur, p_cur);
         if (!(ABL & 4)) read_group(buf, 1, 0, af[0]);
         mma_group(af[1], bf[0], 1);
+        interleave<NM, 1, MF, XB2 - XB1, XB2 - XB1 + 6>();
         __builtin_amdgcn_sched_barrier(0);
         // group 2 = (chunk 1, half 0); dequantise chunk 0 of stage s+1 underneath
+        if (!(ABL & 1)) xfer_x(s, buf, xs_set, XB2, XP);
         if (!(ABL & 4)) read_group(buf, 1, 1, af[1]);
         if (!(ABL & 8)) dequant(w_nxt, p_nxt, 0, bf[0]);
         mma_group(af[0], bf[1], 0);
-        interleave_mfma_valu<2 * MF, 4>();
+        interleave<NM, 4, MF, XP - XB2, XP - XB2>();
         __builtin_amdgcn_sched_barrier(0);
         // group 3 = (chunk 1, half 1); after the barrier the next stage's buffer is readable
         if (!(ABL & 16)) lds_barrier();
         if (!(ABL & 4)) read_group(buf ^ 1, 0, 0, af[0]);
         mma_group(af[1], bf[1], 1);
+        interleave<NM, 0, MF, 0, 0>();
         __builtin_amdgcn_sched_barrier(0);
     };
 
@@ -540,6 +558,165 @@ __global__ __launch_bounds__(256, (MF <= 4 ? 2 : 1)) void w4a8_pipe_kernel(
     for (int s = 0; s < stages; s += 2) {
         stage(s, xr[1], wr[0], pr[0], wr[1], pr[1], 0);
         stage(s + 1, xr[0], wr[1], pr[1], wr[0], pr[0], 1);
+    }
+
+    if (!active) return;
+    store_tile<MF>(acc, M, N, m0, 64 * ng + 2 * j, lane, sx, sw, Y, ACC);
+}
+
+// ------------------------------------------------------------------------------------
+// duo kernel: two waves per SIMD.
+//
+// On CDNA a wave issues in order and its own MFMA keeps it busy for the whole instruction,
+// so the VALU work of the dequantisation only overlaps with matrix work of ANOTHER wave on
+// the same SIMD -- exactly the observation behind the paper's implicit fine-grained
+// pipeline (Sec. 5.1: dequantisation in one compute group overlaps MMA in another, with
+// the hardware arbitrating).  This kernel therefore keeps every wave at <= 256 registers
+// (wave tile 128 x 64, block tile 128 x 256, two blocks per CU) and software-pipelines each
+// wave at the granularity of one k-step (32 k): while the 8 MFMAs of a k-step run, the
+// B operand of the next k-step is dequantised and its X fragments are read from LDS.
+// ------------------------------------------------------------------------------------
+template <bool G128>
+__global__ __launch_bounds__(256, 2) void w4a8_duo_kernel(
+    int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
+    const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
+    __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n)
+{
+    constexpr int MF = 4, WM = 128, XP = 4;
+    constexpr int STAGE = WM * kTilePitch;
+    extern __shared__ __attribute__((aligned(16))) int8_t lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 31, kb = lane >> 5;
+    int bm, bn;
+    block_coords(blocks_m, blocks_n, bm, bn);
+    const int m0 = bm * WM;
+    const int ng = bn * 4 + wave;
+    const bool active = ng < (N >> 6);
+    const int t0 = 2 * (active ? ng : (N >> 6) - 1);
+    const int stages = K >> 7;  // even, since K % 256 == 0
+    const int chunks_per_tile = K >> 6;
+
+    v16i acc[MF][2];
+#pragma unroll
+    for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mf][t][r] = 0;
+
+    // X piece i of this thread: row (tid>>3) + 32*i, 16-byte column tid&7
+    const int xrow = tid >> 3, xcol = tid & 7;
+    const int8_t *xg[XP];
+#pragma unroll
+    for (int i = 0; i < XP; ++i) xg[i] = X + (size_t)min(m0 + xrow + 32 * i, M - 1) * K + 16 * xcol;
+    const int xl = xrow * kTilePitch + 16 * xcol;
+    const u32x4 *wg[2];
+    const uint8_t *pg[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        wg[t] = Wp + (size_t)(t0 + t) * chunks_per_tile * 64 + lane;
+        pg[t] = gp + ((size_t)(t0 + t) * stages * 32 + j) * (G128 ? 2 : 4);
+    }
+    const int8_t *xs = lds + j * kTilePitch + 16 * kb;
+
+    u32x4 xr[XP];
+    u32x4 wr[2][2][2];  // [stage parity][tile][chunk]
+    UnitParams<G128> pr[2][2];
+    v4i bf[2][2];       // [ping-pong][tile]
+    v4i af[2][MF];      // [ping-pong][m fragment]
+
+    auto load_x = [&](int s) {
+        s = min(s, stages - 1);
+#pragma unroll
+        for (int i = 0; i < XP; ++i) xr[i] = *reinterpret_cast<const u32x4 *>(xg[i] + (size_t)s * 128);
+    };
+    auto store_x = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < XP; ++i)
+            *reinterpret_cast<u32x4 *>(lds + buf * STAGE + xl + i * 32 * kTilePitch) = xr[i];
+    };
+    auto load_w = [&](int s, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
+        s = min(s, stages - 1);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            w[t][0] = wg[t][(size_t)s * 128];
+            w[t][1] = wg[t][(size_t)s * 128 + 64];
+            if (G128)
+                p[t].raw = *reinterpret_cast<const uint16_t *>(pg[t] + (size_t)s * 64);
+            else
+                p[t].raw = *reinterpret_cast<const uint32_t *>(pg[t] + (size_t)s * 128);
+        }
+    };
+    // B operand of k-step (c, h) for both tiles
+    auto build_b = [&](const u32x4 (&w)[2][2], const UnitParams<G128> (&p)[2], int c, int h, v4i (&b)[2]) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            uint32_t s2, a4;
+            p[t].get(c, s2, a4);
+            dequant_half(w[t][c], s2, a4, h, b[t]);
+        }
+    };
+    auto read_a = [&](int buf, int c, int h, v4i (&a)[MF]) {
+#pragma unroll
+        for (int mf = 0; mf < MF; ++mf)
+            a[mf] = *reinterpret_cast<const v4i *>(xs + buf * STAGE + mf * 32 * kTilePitch + 64 * c + 32 * h);
+    };
+    auto mma = [&](const v4i (&a)[MF], const v4i (&b)[2]) {
+#pragma unroll
+        for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) acc[mf][t] = mfma_i8(a[mf], b[t], acc[mf][t]);
+    };
+
+    // One stage: w_cur = W(s) on entry and W(s+2) on exit, w_nxt = W(s+1); af[0], bf[0] hold
+    // k-step (0,0) of this stage on entry and of the next stage on exit; xr holds X(s+1).
+    auto stage = [&](int s, u32x4 (&w_cur)[2][2], UnitParams<G128> (&p_cur)[2], u32x4 (&w_nxt)[2][2],
+                     UnitParams<G128> (&p_nxt)[2], int buf) {
+        // k-step (0,0)
+        store_x(buf ^ 1);  // X(s+1); that buffer was released by the previous barrier
+        read_a(buf, 0, 1, af[1]);
+        build_b(w_cur, p_cur, 0, 1, bf[1]);
+        mma(af[0], bf[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        // k-step (0,1)
+        load_x(s + 2);
+        read_a(buf, 1, 0, af[0]);
+        build_b(w_cur, p_cur, 1, 0, bf[0]);
+        mma(af[1], bf[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        // k-step (1,0)
+        read_a(buf, 1, 1, af[1]);
+        build_b(w_cur, p_cur, 1, 1, bf[1]);
+        mma(af[0], bf[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        // k-step (1,1): W(s) is fully consumed, the next stage's X is complete after the barrier
+        lds_barrier();
+        read_a(buf ^ 1, 0, 0, af[0]);
+        build_b(w_nxt, p_nxt, 0, 0, bf[0]);
+        load_w(s + 2, w_cur, p_cur);
+        mma(af[1], bf[1]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // prologue (the W loads are issued after X(1) so that, as in the steady state, the
+    // only loads younger than an X stage are one stage of W)
+    load_x(0);
+    store_x(0);
+    load_x(1);
+    __builtin_amdgcn_sched_barrier(0);
+    load_w(0, wr[0], pr[0]);
+    load_w(1, wr[1], pr[1]);
+    __builtin_amdgcn_sched_barrier(0);
+    build_b(wr[0], pr[0], 0, 0, bf[0]);
+    lds_barrier();
+    read_a(0, 0, 0, af[0]);
+    __builtin_amdgcn_sched_barrier(0);
+
+    for (int s = 0; s < stages; s += 2) {
+        stage(s, wr[0], pr[0], wr[1], pr[1], 0);
+        stage(s + 1, wr[1], pr[1], wr[0], pr[0], 1);
     }
 
     if (!active) return;
@@ -633,6 +810,21 @@ static int launch_pipe(const Args &a)
     return LQ_OK;
 }
 
+static int launch_duo(const Args &a)
+{
+    constexpr int WM = 128;
+    const int blocks_n = (a.N + 255) / 256, blocks_m = (a.M + WM - 1) / WM;
+    const size_t lds_bytes = 2 * (size_t)WM * kTilePitch;
+    const dim3 grid((unsigned)(blocks_n * blocks_m)), block(256);
+    if (a.group == 128)
+        hipLaunchKernelGGL(w4a8_duo_kernel<true>, grid, block, lds_bytes, a.stream, a.M, a.N, a.K, a.X, a.sx,
+                           a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
+    else
+        hipLaunchKernelGGL(w4a8_duo_kernel<false>, grid, block, lds_bytes, a.stream, a.M, a.N, a.K, a.X, a.sx,
+                           a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
+    return LQ_OK;
+}
+
 struct Variant {
     const char *name;
     LaunchFn fn;
@@ -656,6 +848,7 @@ static const Variant kVariants[] = {
     {"tile_m256", &launch_tile<8>, 0, 1, 1},
     {"pipe_m128", &launch_pipe<4>, 0, 1, 1},
     {"pipe_m256", &launch_pipe<8>, 0, 1, 1},
+    {"duo_m128", &launch_duo, 0, 1, 1},
 #ifdef LQ_ABLATE
     {"abl_m256_noX", &launch_pipe<8, 1>, 0, 1, 1},
     {"abl_m256_noW", &launch_pipe<8, 2>, 0, 1, 1},
@@ -695,11 +888,8 @@ static int select_variant(int M, int N, int K)
         if (tiles <= 512) return find_variant("stream_f1_w8_u4");
         return find_variant("stream_f2_w8_u4");
     }
-    const int blocks_n = (N + 255) / 256;
-    if (M <= 32) return find_variant("tile_m32");
     if (M <= 64) return find_variant("tile_m64");
-    if (M <= 128 || ((M + 255) / 256) * blocks_n < 256) return find_variant("tile_m128");
-    return find_variant("tile_m256");
+    return find_variant("duo_m128");
 }
 
 static int check_device_args(const Args &a, const void *ws, size_t ws_bytes)

@@ -47,6 +47,17 @@ __device__ __forceinline__ void dequant_chunk(const u32x4 p, uint32_t s2, uint32
     }
 }
 
+// Half of dequant_chunk: the low (h = 0) or high (h = 1) nibbles only, i.e. the operand
+// registers of one k-step of 32.
+__device__ __forceinline__ void dequant_half(const u32x4 p, uint32_t s2, uint32_t a4, int h, v4i &out)
+{
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const uint32_t v = (h ? (p[d] >> 4) : p[d]) & 0x0F0F0F0Fu;
+        out[d] = (int)(pk_mad_u16(v, s2, a4) ^ 0x80808080u);
+    }
+}
+
 // Group parameters of one lane's channel for one unit of 128 k (two chunks).
 // group 64: two (s, a) pairs in 4 bytes; group 128: one pair in 2 bytes.
 template <bool G128>
