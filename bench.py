@@ -78,19 +78,32 @@ class DeviceProblem:
                                   stream=stream.cuda_stream)
 
 
-def time_steps(prob, M, steps, warmup, torch, api, stream, variant=-1):
+def time_steps(prob, M, steps, warmup, torch, api, stream, variant=-1, graph=False):
     """Average milliseconds per launch over `steps` back-to-back launches (HIP events on
-    the launch stream), after `warmup` untimed ones."""
+    the launch stream), after `warmup` untimed ones.  With graph=True the `steps` launches
+    are captured once into a HIP graph and replayed, which takes the Python/ctypes launch
+    cost (about 9 us per call) out of the measurement of kernels shorter than that."""
     with torch.cuda.stream(stream):
         for i in range(warmup):
             prob.launch(M, i, api, stream, variant)
         stream.synchronize()
+        g = None
+        if graph:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                for i in range(steps):
+                    prob.launch(M, warmup + i, api, stream, variant)
+            g.replay()  # untimed first replay
+            stream.synchronize()
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record(stream)
-        for i in range(steps):
-            prob.launch(M, warmup + i, api, stream, variant)
+        if g is not None:
+            g.replay()
+        else:
+            for i in range(steps):
+                prob.launch(M, warmup + i, api, stream, variant)
         e1.record(stream)
         stream.synchronize()
         torch.cuda.synchronize()
@@ -170,6 +183,11 @@ def main():
     Ms = sorted(set(curve_Ms + [head.M]))
     prob = DeviceProblem(head, Ms, torch, api, WL)
 
+    # Untimed pre-warm of about 0.2 s so that the timed steps run at settled clocks, then the
+    # W warm-up steps and the K timed steps of the contract.
+    t_end = time.perf_counter() + 0.2
+    while time.perf_counter() < t_end:
+        time_steps(prob, head.M, 10, 0, torch, api, stream, args.variant)
     ms = time_steps(prob, head.M, args.steps, args.warmup, torch, api, stream, args.variant)
     hp = point(prob, head.M, ms, api)
     ops = algorithmic_ops(head.M, head.N, head.K)
@@ -198,7 +216,7 @@ def main():
         curve = []
         for M in curve_Ms:
             steps = max(20, min(200, int(0.05 / max(1e-6, 1e-3 * ms * M / head.M + 5e-6))))
-            curve.append(point(prob, M, time_steps(prob, M, steps, 5, torch, api, stream), api))
+            curve.append(point(prob, M, time_steps(prob, M, steps, 5, torch, api, stream, graph=M <= 8), api))
         out["curve_N8192_K8192"] = curve
         del prob.d_packed[1:], prob.d_gparams[1:]
         torch.cuda.empty_cache()
@@ -208,7 +226,7 @@ def main():
             shp = name_Ms[0][0]
             p2 = DeviceProblem(shp, list(name_Ms[1]), torch, api, WL)
             for M in name_Ms[1]:
-                extra.append(point(p2, M, time_steps(p2, M, 200, 20, torch, api, stream), api))
+                extra.append(point(p2, M, time_steps(p2, M, 200, 20, torch, api, stream, graph=shp.N * shp.K < (1 << 26)), api))
             del p2
             torch.cuda.empty_cache()
         out["memory_bound_points"] = extra

@@ -171,11 +171,24 @@ def w4a8_gemm_workspace_size(M: int, N: int, K: int, group: int) -> int:
     return int(lib().w4a8_gemm_workspace_size(M, N, K, group))
 
 
-def _ws(workspace):
+_ws_cache = {}
+
+
+def _ws(workspace, M=0, N=0, K=0, group=64, device=None):
+    """Workspace pointer and size.  With workspace=None a buffer of the size the library asks
+    for is allocated once per device and reused (device memory plumbing, nothing else)."""
     import torch
 
     if workspace is None:
-        return None, 0
+        need = w4a8_gemm_workspace_size(M, N, K, group) if M > 0 else 0
+        if need == 0:
+            return None, 0
+        key = str(device)
+        buf = _ws_cache.get(key)
+        if buf is None or buf.numel() < need:
+            buf = torch.empty(need, dtype=torch.uint8, device=device)
+            _ws_cache[key] = buf
+        workspace = buf
     return _dev(workspace, torch.uint8, name="workspace"), workspace.numel()
 
 
@@ -187,7 +200,7 @@ def w4a8_gemm(X, act_scales, W_packed, gparams, w_scales, N: int, K: int, group:
     M = X.shape[0]
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
-    wsp, wsb = _ws(workspace)
+    wsp, wsb = _ws(workspace, M, N, K, group, X.device)
     cb, gb = liquidquant_packed_size(N, K, group)
     _check(lib().w4a8_gemm(M, N, K, group, _dev(X, torch.int8, (M, K), "X"),
                            _dev(act_scales, torch.float32, (M,), "act_scales"),
@@ -206,7 +219,7 @@ def w4a8_gemm_i32(X, W_packed, gparams, N: int, K: int, group: int, out=None, wo
     M = X.shape[0]
     if out is None:
         out = torch.empty((M, N), dtype=torch.int32, device=X.device)
-    wsp, wsb = _ws(workspace)
+    wsp, wsb = _ws(workspace, M, N, K, group, X.device)
     cb, gb = liquidquant_packed_size(N, K, group)
     _check(lib().w4a8_gemm_i32(M, N, K, group, _dev(X, torch.int8, (M, K), "X"),
                                _dev(W_packed, torch.uint8, (cb,), "W_packed"),
@@ -226,7 +239,7 @@ def w4a8_gemm_variant(variant: int, X, act_scales, W_packed, gparams, w_scales, 
         out_y = torch.empty((M, N), dtype=torch.float16, device=X.device)
     if want_acc and out_acc is None:
         out_acc = torch.empty((M, N), dtype=torch.int32, device=X.device)
-    wsp, wsb = _ws(workspace)
+    wsp, wsb = _ws(workspace, M, N, K, group, X.device)
     cb, gb = liquidquant_packed_size(N, K, group)
     _check(lib().w4a8_gemm_variant(
         variant, M, N, K, group, _dev(X, torch.int8, (M, K), "X"),

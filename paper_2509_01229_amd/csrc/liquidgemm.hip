@@ -24,6 +24,7 @@
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdio>
 #include <cstring>
 
@@ -68,27 +69,55 @@ __device__ __forceinline__ __half scale_to_half(int acc, float sx, float sw)
 }
 
 // ------------------------------------------------------------------------------------
-// stream kernel.  UC = chunks (of 64 k) per pipeline unit: 2 or 4.
+// stream kernel.  A unit is 128 k (two chunks per tile).  grid = (N / (32 F), S): block
+// (bx, ks) owns F tiles and the ks-th of S slices of K; its NW waves take the slice's
+// units round-robin.  S > 1 (grid-level split-K) is used when N alone gives too few blocks
+// to keep every HBM channel busy; the S partial tiles meet in a workspace and the last
+// block to arrive (a ticket per tile group) adds them up and runs the epilogue.  All sums
+// are INT32, so neither level of split-K changes the result.
 // ------------------------------------------------------------------------------------
-template <int F, int UC, bool G128>
+#ifdef LQ_ABLATE
+// experiments only: per-wave wall-clock stamps (start, first unit done, loop done, end)
+__device__ long long g_dbg_stamps[4 * 16384];
+#define LQ_STAMP(slot)                                                                          \
+    do {                                                                                        \
+        const unsigned w_ = (blockIdx.y * gridDim.x + blockIdx.x) * NW + wave;                  \
+        if (lane == 0 && w_ < 16384) g_dbg_stamps[4 * w_ + (slot)] = wall_clock64();            \
+    } while (0)
+#else
+#define LQ_STAMP(slot) \
+    do {               \
+    } while (0)
+#endif
+
+// Arrival tickets of the grid-level split-K, one per tile group (blockIdx.x).  Zero when
+// the library is loaded; the last block of a group resets its ticket, so every call finds
+// zeros again.  Calls that use split-K and overlap in time on one GPU would share them.
+constexpr int kMaxTicketGroups = 8192;
+__device__ unsigned int g_splitk_tickets[kMaxTicketGroups];
+
+template <int F, bool G128>
 struct StreamRegs {
-    u32x4 w[F][UC];
-    UnitParams<G128> p[F][UC / 2];
-    u32x4 x[2 * UC];
+    u32x4 w[F][2];
+    UnitParams<G128> p[F];
+    u32x4 x[4];
 };
 
-template <int F, int NW, int UC, bool G128>
+template <int F, int NW, bool G128>
 __global__ __launch_bounds__(NW * 64) void w4a8_stream_kernel(
     int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
-    __half *__restrict__ Y, int32_t *__restrict__ ACC)
+    __half *__restrict__ Y, int32_t *__restrict__ ACC, int32_t *__restrict__ partials)
 {
     extern __shared__ __attribute__((aligned(16))) int red[];  // [NW][F * rmax][64]
+    __shared__ int s_last;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane & 31, kb = lane >> 5;
     const int t0 = blockIdx.x * F;
-    const int units = K / (64 * UC);
+    const int units = K >> 7;
     const int chunks_per_tile = K >> 6;
+    const int S = gridDim.y, ks = blockIdx.y;
+    const int u_begin = (int)((long long)units * ks / S), u_end = (int)((long long)units * (ks + 1) / S);
 
     v16i acc[F];
 #pragma unroll
@@ -96,33 +125,30 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[f][r] = 0;
 
-    auto load_unit = [&](int u, StreamRegs<F, UC, G128> &r) {
+    // X fragments come straight from global memory (L2): lane (j, kb) needs 16 bytes of row
+    // j per k-step.  Lanes past M read row M-1 (one more hit on a line that is fetched
+    // anyway); an output row depends only on its own X row and rows past M are not stored.
+    const int8_t *xrow = X + (size_t)min(j, M - 1) * K + 16 * kb;
+
+    auto load_unit = [&](int u, StreamRegs<F, G128> &r) {
 #pragma unroll
         for (int f = 0; f < F; ++f) {
-            const u32x4 *base = Wp + ((size_t)(t0 + f) * chunks_per_tile + (size_t)u * UC) * 64 + lane;
-#pragma unroll
-            for (int c = 0; c < UC; ++c) r.w[f][c] = __builtin_nontemporal_load(base + 64 * c);
-#pragma unroll
-            for (int pu = 0; pu < UC / 2; ++pu)
-                r.p[f][pu].load(gp, (size_t)(t0 + f) * (K >> 7) + (size_t)u * (UC / 2) + pu, j);
+            const u32x4 *base = Wp + ((size_t)(t0 + f) * chunks_per_tile + 2 * (size_t)u) * 64 + lane;
+            r.w[f][0] = __builtin_nontemporal_load(base);
+            r.w[f][1] = __builtin_nontemporal_load(base + 64);
+            r.p[f].load(gp, (size_t)(t0 + f) * units + u, j);
         }
-        // X fragment rows past M are zero (never loaded)
-        const int8_t *xr = X + (size_t)j * K + (size_t)u * (64 * UC) + 16 * kb;
 #pragma unroll
-        for (int ks = 0; ks < 2 * UC; ++ks) r.x[ks] = u32x4{0, 0, 0, 0};
-        if (j < M) {
-#pragma unroll
-            for (int ks = 0; ks < 2 * UC; ++ks) r.x[ks] = *reinterpret_cast<const u32x4 *>(xr + 32 * ks);
-        }
+        for (int ks4 = 0; ks4 < 4; ++ks4)
+            r.x[ks4] = *reinterpret_cast<const u32x4 *>(xrow + (size_t)u * 128 + 32 * ks4);
     };
-
-    auto compute_unit = [&](const StreamRegs<F, UC, G128> &r) {
+    auto compute_unit = [&](const StreamRegs<F, G128> &r) {
 #pragma unroll
         for (int f = 0; f < F; ++f)
 #pragma unroll
-            for (int c = 0; c < UC; ++c) {
+            for (int c = 0; c < 2; ++c) {
                 uint32_t s2, a4;
-                r.p[f][c >> 1].get(c & 1, s2, a4);
+                r.p[f].get(c, s2, a4);
                 v4i lo, hi;
                 dequant_chunk(r.w[f][c], s2, a4, lo, hi);
                 acc[f] = mfma_i8(__builtin_bit_cast(v4i, r.x[2 * c]), lo, acc[f]);
@@ -132,19 +158,20 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream_kernel(
 
     // Register double buffering: the loads of the next unit are in flight while the
     // current one is dequantised and multiplied.
-    StreamRegs<F, UC, G128> cur, nxt;
-    int u = wave;
-    if (u < units) load_unit(u, cur);
-    for (; u < units; u += NW) {
-        const bool more = (u + NW) < units;
+    LQ_STAMP(0);
+    StreamRegs<F, G128> cur, nxt;
+    int u = u_begin + wave;
+    if (u < u_end) load_unit(u, cur);
+    for (; u < u_end; u += NW) {
+        const bool more = (u + NW) < u_end;
         if (more) load_unit(u + NW, nxt);
         compute_unit(cur);
         if (more) cur = nxt;
     }
+    LQ_STAMP(2);
 
-    // In-block split-K reduction (integer, order independent) and epilogue.  Only the
-    // accumulator elements that hold rows < M take part: rows of element r lie in
-    // [8*(r/4), 8*(r/4)+8).
+    // In-block split-K reduction (integer, order independent).  Only the accumulator
+    // elements that hold rows < M take part: rows of element r lie in [8*(r/4), 8*(r/4)+8).
     const int rmax = 4 * ((M + 7) >> 3);
 #pragma unroll
     for (int f = 0; f < F; ++f)
@@ -153,17 +180,184 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream_kernel(
             if (r < rmax) red[((wave * F + f) * rmax + r) * 64 + lane] = acc[f][r];
     __syncthreads();
     const int vals = F * rmax;
-    for (int idx = threadIdx.x; idx < vals * 64; idx += NW * 64) {
-        const int v = idx >> 6, l = idx & 63;
+    auto block_sum = [&](int idx) {
         int sum = 0;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) sum += red[(w * vals + v) * 64 + l];
-        const int r = v % rmax, f = v / rmax;
-        const int m = acc_row(r, l);
+        for (int w = 0; w < NW; ++w) sum += red[(w * vals + (idx >> 6)) * 64 + (idx & 63)];
+        return sum;
+    };
+    auto finish = [&](int idx, int sum) {  // epilogue of one output (Sec. 4, Sec. 5.3)
+        const int v = idx >> 6, l = idx & 63;
+        const int m = acc_row(v % rmax, l);
         if (m < M) {
-            const int n = channel_of(t0 + f, l & 31);
+            const int n = channel_of(t0 + v / rmax, l & 31);
             if (ACC) ACC[(size_t)m * N + n] = sum;
             if (Y) Y[(size_t)m * N + n] = scale_to_half(sum, sx[m], sw[n]);
+        }
+    };
+    if (S == 1) {
+        for (int idx = threadIdx.x; idx < vals * 64; idx += NW * 64) finish(idx, block_sum(idx));
+    } else {
+        // Partial tile of this slice: [ks][blockIdx.x][vals * 64], coalesced.  The tiles are
+        // written and read with device-scope atomics, which act at the memory side common to
+        // all XCDs, so no cache has to be flushed or invalidated; the barrier's wait for
+        // outstanding memory operations orders them before the ticket.
+        int32_t *mine = partials + ((size_t)ks * gridDim.x + blockIdx.x) * (size_t)(vals * 64);
+        for (int idx = threadIdx.x; idx < vals * 64; idx += NW * 64)
+            __hip_atomic_store(mine + idx, block_sum(idx), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();  // includes s_waitcnt vmcnt(0): every store above has been acknowledged
+        if (threadIdx.x == 0) {
+            const unsigned t = __hip_atomic_fetch_add(&g_splitk_tickets[blockIdx.x], 1u, __ATOMIC_RELAXED,
+                                                      __HIP_MEMORY_SCOPE_AGENT);
+            s_last = (t == (unsigned)(S - 1));
+        }
+        __syncthreads();
+        if (s_last) {
+            for (int idx = threadIdx.x; idx < vals * 64; idx += NW * 64) {
+                int sum = 0;
+                for (int k2 = 0; k2 < S; ++k2)
+                    sum += __hip_atomic_load(
+                        partials + ((size_t)k2 * gridDim.x + blockIdx.x) * (size_t)(vals * 64) + idx,
+                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                finish(idx, sum);
+            }
+            if (threadIdx.x == 0)  // ready for the next call
+                __hip_atomic_store(&g_splitk_tickets[blockIdx.x], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    LQ_STAMP(3);
+}
+
+// ------------------------------------------------------------------------------------
+// stream16 kernel: the stream kernel for M <= 16 on v_mfma_i32_16x16x64_i8.
+//
+// A 32-row MFMA wastes half of its rows on a decode batch, and in this regime the per-CU
+// arithmetic (dequantisation + MFMA) is not far below what the HBM stream demands.  The
+// packed layout is unchanged: after the usual dequantisation one v_permlane16_swap per
+// register turns the chunk's two 32x32x32 operands into the operands of two 16x16x64
+// MFMAs (see regroup_16x16), which take half the matrix-pipe time, a quarter of the
+// accumulator registers and half of the X registers.
+// ------------------------------------------------------------------------------------
+template <int F, bool G128>
+struct Stream16Regs {
+    u32x4 w[F][2];
+    UnitParams<G128> p[F];
+    u32x4 x[2];
+};
+
+template <int F, int NW, bool G128>
+__global__ __launch_bounds__(NW * 64) void w4a8_stream16_kernel(
+    int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
+    const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
+    __half *__restrict__ Y, int32_t *__restrict__ ACC, int32_t *__restrict__ partials)
+{
+    constexpr int VALS = F * 8;  // accumulator registers per lane
+    extern __shared__ __attribute__((aligned(16))) int red[];  // [NW][VALS][64]
+    __shared__ int s_last;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j = lane & 31;
+    const int t0 = blockIdx.x * F;
+    const int units = K >> 7;
+    const int chunks_per_tile = K >> 6;
+    const int S = gridDim.y, ks = blockIdx.y;
+    const int u_begin = (int)((long long)units * ks / S), u_end = (int)((long long)units * (ks + 1) / S);
+
+    v4i acc[F][2];
+#pragma unroll
+    for (int f = 0; f < F; ++f)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) acc[f][h] = v4i{0, 0, 0, 0};
+
+    // X operand of a 16x16x64 MFMA: lane l supplies row l%16, k-block l/16 of a chunk, in
+    // the k-block order that regroup_16x16 produces.  Lanes past M read row M-1.
+    const int8_t *xrow = X + (size_t)min(lane & 15, M - 1) * K + kstep16_offset(lane >> 4);
+
+    auto load_unit = [&](int u, Stream16Regs<F, G128> &r) {
+#pragma unroll
+        for (int f = 0; f < F; ++f) {
+            const u32x4 *base = Wp + ((size_t)(t0 + f) * chunks_per_tile + 2 * (size_t)u) * 64 + lane;
+            r.w[f][0] = __builtin_nontemporal_load(base);
+            r.w[f][1] = __builtin_nontemporal_load(base + 64);
+            r.p[f].load(gp, (size_t)(t0 + f) * units + u, j);
+        }
+#pragma unroll
+        for (int c = 0; c < 2; ++c) r.x[c] = *reinterpret_cast<const u32x4 *>(xrow + (size_t)u * 128 + 64 * c);
+    };
+    auto compute_unit = [&](const Stream16Regs<F, G128> &r) {
+#pragma unroll
+        for (int f = 0; f < F; ++f)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                uint32_t s2, a4;
+                r.p[f].get(c, s2, a4);
+                v4i lo, hi, b1, b2;
+                dequant_chunk(r.w[f][c], s2, a4, lo, hi);
+                regroup_16x16(lo, hi, b1, b2);
+                const v4i xa = __builtin_bit_cast(v4i, r.x[c]);
+                acc[f][0] = mfma16_i8(xa, b1, acc[f][0]);
+                acc[f][1] = mfma16_i8(xa, b2, acc[f][1]);
+            }
+    };
+
+    Stream16Regs<F, G128> cur, nxt;
+    int u = u_begin + wave;
+    if (u < u_end) load_unit(u, cur);
+    for (; u < u_end; u += NW) {
+        const bool more = (u + NW) < u_end;
+        if (more) load_unit(u + NW, nxt);
+        compute_unit(cur);
+        if (more) cur = nxt;
+    }
+
+    // in-block split-K reduction: value v = (f*2 + h)*4 + r of lane l is row 4*(l/16) + r,
+    // slot 16*h + l%16 of tile t0 + f
+#pragma unroll
+    for (int f = 0; f < F; ++f)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) red[(wave * VALS + (f * 2 + h) * 4 + r) * 64 + lane] = acc[f][h][r];
+    __syncthreads();
+    auto block_sum = [&](int idx) {
+        int sum = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) sum += red[(w * VALS + (idx >> 6)) * 64 + (idx & 63)];
+        return sum;
+    };
+    auto finish = [&](int idx, int sum) {
+        const int v = idx >> 6, l = idx & 63;
+        const int m = 4 * (l >> 4) + (v & 3);
+        if (m < M) {
+            const int n = channel_of(t0 + (v >> 3), 16 * ((v >> 2) & 1) + (l & 15));
+            if (ACC) ACC[(size_t)m * N + n] = sum;
+            if (Y) Y[(size_t)m * N + n] = scale_to_half(sum, sx[m], sw[n]);
+        }
+    };
+    if (S == 1) {
+        for (int idx = threadIdx.x; idx < VALS * 64; idx += NW * 64) finish(idx, block_sum(idx));
+    } else {
+        // grid-level split-K: same protocol as w4a8_stream_kernel
+        int32_t *mine = partials + ((size_t)ks * gridDim.x + blockIdx.x) * (size_t)(VALS * 64);
+        for (int idx = threadIdx.x; idx < VALS * 64; idx += NW * 64)
+            __hip_atomic_store(mine + idx, block_sum(idx), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const unsigned t = __hip_atomic_fetch_add(&g_splitk_tickets[blockIdx.x], 1u, __ATOMIC_RELAXED,
+                                                      __HIP_MEMORY_SCOPE_AGENT);
+            s_last = (t == (unsigned)(S - 1));
+        }
+        __syncthreads();
+        if (s_last) {
+            for (int idx = threadIdx.x; idx < VALS * 64; idx += NW * 64) {
+                int sum = 0;
+                for (int k2 = 0; k2 < S; ++k2)
+                    sum += __hip_atomic_load(
+                        partials + ((size_t)k2 * gridDim.x + blockIdx.x) * (size_t)(VALS * 64) + idx,
+                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                finish(idx, sum);
+            }
+            if (threadIdx.x == 0)
+                __hip_atomic_store(&g_splitk_tickets[blockIdx.x], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }
@@ -736,6 +930,8 @@ struct Args {
     __half *Y;
     int32_t *ACC;
     hipStream_t stream;
+    void *ws;
+    size_t ws_bytes;
 };
 
 typedef int (*LaunchFn)(const Args &);
@@ -751,23 +947,77 @@ static int allow_lds(Kernel kernel, size_t bytes)
     return LQ_OK;
 }
 
-template <int F, int NW, int UC>
+// Grid-level split of K for the stream kernels: enough blocks for every CU to hold two
+// (about 512), each wave keeping at least two units of 128 k.
+static int stream_split(int N, int K, int F, int NW)
+{
+    const int groups = N / (32 * F), units = K / 128;
+    // Measured on MI355X: the exchange of partial tiles through memory costs about 3 us, so
+    // K is split across blocks only when N alone leaves most CUs without a block.
+    int s = groups > 160 ? 1 : (groups > 48 ? 2 : 4);
+    s = std::min(s, units / (2 * NW));
+    return std::max(1, s);
+}
+
+static size_t stream_ws_bytes(int M, int N, int S)
+{
+    if (S <= 1) return 0;
+    const int rmax = 4 * ((M + 7) / 8);
+    return (size_t)S * (N / 32) * rmax * 64 * sizeof(int32_t);
+}
+
+// SPLIT: 0 = choose with stream_split(), otherwise the fixed number of K slices.
+template <int F, int NW, int SPLIT>
 static int launch_stream(const Args &a)
 {
     if (a.M > 32) return fail(LQ_ERR_INVALID, "stream variants handle M <= 32, got %d", a.M);
     if ((a.N / 32) % F != 0) return fail(LQ_ERR_INVALID, "N/32 not a multiple of F=%d", F);
-    if ((a.K / 64) % UC != 0) return fail(LQ_ERR_INVALID, "K/64 not a multiple of %d", UC);
-    const dim3 grid(a.N / (32 * F)), block(NW * 64);
+    const int groups = a.N / (32 * F);
+    int S = SPLIT ? SPLIT : stream_split(a.N, a.K, F, NW);
+    S = std::min(S, a.K / 128);
+    if (S > 1 && groups > kMaxTicketGroups) S = 1;
+    const size_t need = stream_ws_bytes(a.M, a.N, S);
+    if (need > 0 && (!a.ws || a.ws_bytes < need))
+        return fail(LQ_ERR_WORKSPACE, "split-K needs %zu bytes of workspace, got %zu", need, a.ws ? a.ws_bytes : 0);
+    const dim3 grid(groups, S), block(NW * 64);
     const int rmax = 4 * ((a.M + 7) / 8);
     const size_t lds_bytes = (size_t)NW * F * rmax * 64 * sizeof(int);
+    int32_t *partials = static_cast<int32_t *>(a.ws);
     if (a.group == 128) {
-        if (int rc = allow_lds(&w4a8_stream_kernel<F, NW, UC, true>, lds_bytes)) return rc;
-        hipLaunchKernelGGL((w4a8_stream_kernel<F, NW, UC, true>), grid, block, lds_bytes, a.stream, a.M, a.N,
-                           a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC);
+        if (int rc = allow_lds(&w4a8_stream_kernel<F, NW, true>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_stream_kernel<F, NW, true>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
+                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials);
     } else {
-        if (int rc = allow_lds(&w4a8_stream_kernel<F, NW, UC, false>, lds_bytes)) return rc;
-        hipLaunchKernelGGL((w4a8_stream_kernel<F, NW, UC, false>), grid, block, lds_bytes, a.stream, a.M, a.N,
-                           a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC);
+        if (int rc = allow_lds(&w4a8_stream_kernel<F, NW, false>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_stream_kernel<F, NW, false>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
+                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials);
+    }
+    return LQ_OK;
+}
+
+template <int F, int NW, int SPLIT>
+static int launch_stream16(const Args &a)
+{
+    if (a.M > 16) return fail(LQ_ERR_INVALID, "stream16 variants handle M <= 16, got %d", a.M);
+    if ((a.N / 32) % F != 0) return fail(LQ_ERR_INVALID, "N/32 not a multiple of F=%d", F);
+    const int groups = a.N / (32 * F);
+    int S = SPLIT ? SPLIT : stream_split(a.N, a.K, F, NW);
+    S = std::min(S, a.K / 128);
+    if (S > 1 && groups > kMaxTicketGroups) S = 1;
+    const size_t need = S > 1 ? (size_t)S * (a.N / 32) * 8 * 64 * sizeof(int32_t) : 0;
+    if (need > 0 && (!a.ws || a.ws_bytes < need))
+        return fail(LQ_ERR_WORKSPACE, "split-K needs %zu bytes of workspace, got %zu", need, a.ws ? a.ws_bytes : 0);
+    const dim3 grid(groups, S), block(NW * 64);
+    const size_t lds_bytes = (size_t)NW * F * 8 * 64 * sizeof(int);
+    int32_t *partials = static_cast<int32_t *>(a.ws);
+    if (a.group == 128) {
+        if (int rc = allow_lds(&w4a8_stream16_kernel<F, NW, true>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_stream16_kernel<F, NW, true>), grid, block, lds_bytes, a.stream, a.M, a.N,
+                           a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials);
+    } else {
+        if (int rc = allow_lds(&w4a8_stream16_kernel<F, NW, false>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_stream16_kernel<F, NW, false>), grid, block, lds_bytes, a.stream, a.M, a.N,
+                           a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials);
     }
     return LQ_OK;
 }
@@ -833,15 +1083,22 @@ struct Variant {
     int chunks_div; // K/64 must be a multiple of this
 };
 
-// stream_f<F>_w<NW>_u<UC>: F tiles per block, NW waves splitting K, UC chunks per unit.
+// stream_f<F>_w<NW>[_s<S>]: F tiles per block, NW waves splitting the block's K slice,
+// S grid-level K slices (chosen from the shape when not named).
 static const Variant kVariants[] = {
-    {"stream_f1_w16_u2", &launch_stream<1, 16, 2>, 32, 1, 2},
-    {"stream_f1_w8_u4", &launch_stream<1, 8, 4>, 32, 1, 4},
-    {"stream_f2_w8_u4", &launch_stream<2, 8, 4>, 32, 2, 4},
-    {"stream_f2_w8_u2", &launch_stream<2, 8, 2>, 32, 2, 2},
-    {"stream_f2_w4_u4", &launch_stream<2, 4, 4>, 32, 2, 4},
-    {"stream_f4_w4_u2", &launch_stream<4, 4, 2>, 32, 4, 2},
-    {"stream_f4_w8_u2", &launch_stream<4, 8, 2>, 32, 4, 2},
+    {"stream_f1_w8", &launch_stream<1, 8, 0>, 32, 1, 1},
+    {"stream_f2_w8", &launch_stream<2, 8, 0>, 32, 2, 1},
+    {"stream_f2_w4", &launch_stream<2, 4, 0>, 32, 2, 1},
+    {"stream_f2_w8_s1", &launch_stream<2, 8, 1>, 32, 2, 1},
+    {"stream_f2_w8_s2", &launch_stream<2, 8, 2>, 32, 2, 1},
+    {"stream_f2_w8_s4", &launch_stream<2, 8, 4>, 32, 2, 1},
+    {"stream16_f2_w8", &launch_stream16<2, 8, 0>, 16, 2, 1},
+    {"stream16_f2_w4", &launch_stream16<2, 4, 0>, 16, 2, 1},
+    {"stream16_f1_w8", &launch_stream16<1, 8, 0>, 16, 1, 1},
+    {"stream16_f2_w8_s1", &launch_stream16<2, 8, 1>, 16, 2, 1},
+    {"stream16_f2_w8_s2", &launch_stream16<2, 8, 2>, 16, 2, 1},
+    {"stream16_f2_w8_s4", &launch_stream16<2, 8, 4>, 16, 2, 1},
+    {"stream16_f4_w8_s2", &launch_stream16<4, 8, 2>, 16, 4, 1},
     {"tile_m32", &launch_tile<1>, 0, 1, 1},
     {"tile_m64", &launch_tile<2>, 0, 1, 1},
     {"tile_m128", &launch_tile<4>, 0, 1, 1},
@@ -882,20 +1139,14 @@ static int find_variant(const char *name)
 static int select_variant(int M, int N, int K)
 {
     (void)K;
-    if (M <= 32) {
-        const int tiles = N / 32;
-        if (tiles <= 256) return find_variant("stream_f1_w16_u2");
-        if (tiles <= 512) return find_variant("stream_f1_w8_u4");
-        return find_variant("stream_f2_w8_u4");
-    }
+    if (M <= 16) return find_variant(N / 64 >= 384 ? "stream16_f2_w4" : "stream16_f2_w8");
+    if (M <= 32) return find_variant("stream_f2_w8");
     if (M <= 64) return find_variant("tile_m64");
     return find_variant("duo_m128");
 }
 
-static int check_device_args(const Args &a, const void *ws, size_t ws_bytes)
+static int check_device_args(const Args &a)
 {
-    (void)ws;
-    (void)ws_bytes;
     if (a.M < 0 || !shape_ok(a.N, a.K, a.group))
         return fail(LQ_ERR_INVALID,
                     "bad shape M=%d N=%d K=%d group=%d (need M>=0, N%%64==0, K%%256==0, group 64|128, K<=131072)",
@@ -910,9 +1161,9 @@ static int check_device_args(const Args &a, const void *ws, size_t ws_bytes)
     return LQ_OK;
 }
 
-static int run(int variant, const Args &a, const void *ws, size_t ws_bytes)
+static int run(int variant, const Args &a)
 {
-    if (int rc = check_device_args(a, ws, ws_bytes)) return rc;
+    if (int rc = check_device_args(a)) return rc;
     if (a.M == 0) return LQ_OK;
     if (variant < 0) variant = select_variant(a.M, a.N, a.K);
     if (variant < 0 || variant >= kNumVariants) return fail(LQ_ERR_INVALID, "unknown variant %d", variant);
@@ -935,11 +1186,12 @@ extern "C" {
 
 size_t w4a8_gemm_workspace_size(int M, int N, int K, int group)
 {
-    (void)M;
-    (void)N;
-    (void)K;
-    (void)group;
-    return 0;  // split-K is reduced inside the block, in LDS
+    if (M <= 0 || M > 32 || !shape_ok(N, K, group)) return 0;  // only the stream kernels split K
+    // room for the largest split any stream variant can pick (16 slices; the 16-row kernels
+    // always exchange 8 values per lane and tile)
+    const size_t a = stream_ws_bytes(M, N, 16);
+    const size_t b = M <= 16 ? (size_t)16 * (N / 32) * 8 * 64 * sizeof(int32_t) : 0;
+    return std::max(a, b);
 }
 
 int w4a8_gemm(int M, int N, int K, int group, const int8_t *X, const float *act_scales,
@@ -948,8 +1200,8 @@ int w4a8_gemm(int M, int N, int K, int group, const int8_t *X, const float *act_
 {
     if (!Y && M != 0) return fail(LQ_ERR_INVALID, "null Y");
     const Args a{M, N, K, group, X, act_scales, static_cast<const u32x4 *>(W_packed), gparams, w_scales,
-                 reinterpret_cast<__half *>(Y), nullptr, static_cast<hipStream_t>(hip_stream)};
-    return run(-1, a, workspace, workspace_bytes);
+                 reinterpret_cast<__half *>(Y), nullptr, static_cast<hipStream_t>(hip_stream), workspace, workspace_bytes};
+    return run(-1, a);
 }
 
 int w4a8_gemm_i32(int M, int N, int K, int group, const int8_t *X, const void *W_packed,
@@ -958,8 +1210,8 @@ int w4a8_gemm_i32(int M, int N, int K, int group, const int8_t *X, const void *W
 {
     if (!ACC && M != 0) return fail(LQ_ERR_INVALID, "null ACC");
     const Args a{M, N, K, group, X, nullptr, static_cast<const u32x4 *>(W_packed), gparams, nullptr,
-                 nullptr, ACC, static_cast<hipStream_t>(hip_stream)};
-    return run(-1, a, workspace, workspace_bytes);
+                 nullptr, ACC, static_cast<hipStream_t>(hip_stream), workspace, workspace_bytes};
+    return run(-1, a);
 }
 
 int w4a8_gemm_variant(int variant, int M, int N, int K, int group, const int8_t *X,
@@ -969,9 +1221,16 @@ int w4a8_gemm_variant(int variant, int M, int N, int K, int group, const int8_t 
 {
     if (variant < -1 || variant >= kNumVariants) return fail(LQ_ERR_INVALID, "unknown variant %d", variant);
     const Args a{M, N, K, group, X, act_scales, static_cast<const u32x4 *>(W_packed), gparams, w_scales,
-                 reinterpret_cast<__half *>(Y), ACC, static_cast<hipStream_t>(hip_stream)};
-    return run(variant, a, workspace, workspace_bytes);
+                 reinterpret_cast<__half *>(Y), ACC, static_cast<hipStream_t>(hip_stream), workspace, workspace_bytes};
+    return run(variant, a);
 }
+
+#ifdef LQ_ABLATE
+int w4a8_debug_stamps(long long *host, int n)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg_stamps), sizeof(long long) * n);
+}
+#endif
 
 int w4a8_variant_count(void) { return kNumVariants; }
 

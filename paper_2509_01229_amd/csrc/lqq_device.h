@@ -90,6 +90,32 @@ __device__ __forceinline__ v16i mfma_i8(const v4i a, const v4i b, const v16i c)
     return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
 }
 
+// D(16x16) += A(16x64) * B(64x16), INT8 inputs, INT32 accumulate (decode-sized batches).
+// Lane l supplies row l%16 of A and column l%16 of B for k-block l/16 (16 bytes each); it
+// receives D[4*(l/16) + r][l%16] in element r (r = 0..3).
+__device__ __forceinline__ v4i mfma16_i8(const v4i a, const v4i b, const v4i c)
+{
+    return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
+}
+
+// Regroup one dequantised chunk (lo/hi = the two k-steps of a 32-channel x 64-k chunk in
+// the 32x32x32 operand order) into the B operands of two 16x16x64 MFMAs: b1 covers slots
+// 0..15, b2 slots 16..31 of the tile, each over the chunk's 64 k.  One
+// v_permlane16_swap per register: it exchanges the odd 16-lane rows of `lo` with the even
+// rows of `hi`.  The k-blocks end up in the order {0..15, 32..47, 16..31, 48..63}; the X
+// operand is read in the same order (kStep16Offset).
+__device__ __forceinline__ void regroup_16x16(const v4i lo, const v4i hi, v4i &b1, v4i &b2)
+{
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const auto r = __builtin_amdgcn_permlane16_swap((unsigned)lo[d], (unsigned)hi[d], false, false);
+        b1[d] = (int)r[0];
+        b2[d] = (int)r[1];
+    }
+}
+// byte offset inside a chunk's 64 k of the k-block that lane group q = l/16 must supply
+__device__ __forceinline__ int kstep16_offset(int q) { return ((q & 1) << 5) | ((q & 2) << 3); }
+
 // Row of the 32x32 MFMA result held in accumulator element r of lane l.
 __device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 
