@@ -1,0 +1,105 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times
+(the dispatcher's own kernel choice through w4a8_gemm / w4a8_gemm_i32).
+
+A full element-by-element oracle run is out of reach at these sizes, so every shape is
+checked three ways against the oracle's quantised weights:
+  * sampled outputs: a random set of rows x channels recomputed one by one by the oracle
+    (INT32 bit-exact, FP16 within one ulp);
+  * checksums over every output: row sums  sum_n ACC[m,n] = X[m,:] . colsum(Wd)  and column
+    sums  sum_m ACC[m,n] = Wd[n,:] . colsum(X), both exact in int64/float64, so a single
+    wrong accumulator anywhere fails;
+  * the whole FP16 matrix against fp16(ACC * s_x * s_w) recomputed in double from the
+    kernel's own (already verified) accumulators.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import lqq_oracle as O
+from paper_2509_01229_amd import api
+from paper_2509_01229_amd import workloads as WL
+
+import gpu_helpers as H
+
+pytestmark = pytest.mark.gpu
+
+FAMILIES = [
+    ("decode", WL.DECODE),
+    ("mlp7b_up", WL.MLP_7B[:3]),
+    ("mlp7b_down", WL.MLP_7B[3:]),
+    ("l70b_up", WL.LAYERS_70B[0:3]),
+    ("l70b_down", WL.LAYERS_70B[3:6]),
+    ("l70b_qkv", WL.LAYERS_70B[6:9]),
+    ("prefill", WL.PREFILL),
+]
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _oracle_column_sums(P, xsums, block=2048):
+    """colsum[k] = sum_n Wd[n,k] and, per activation set, Wd @ colsum(X): exact (int64 /
+    float64 on integers below 2^53), computed from the oracle's quantisation in row blocks."""
+    N, K = P.N, P.K
+    colsum = np.zeros(K, dtype=np.int64)
+    rowdot = {M: np.empty(N, dtype=np.float64) for M in xsums}
+    s_w = np.empty(N, dtype=np.float32)
+    for r0 in range(0, N, block):
+        rows = np.arange(r0, min(N, r0 + block))
+        Wd, s_w[rows] = P.oracle_wd(rows)
+        colsum += Wd.astype(np.int64).sum(axis=0)
+        Wf = Wd.astype(np.float64)
+        for M, xs in xsums.items():
+            rowdot[M][rows] = Wf @ xs
+    return colsum, rowdot, s_w
+
+
+@pytest.mark.parametrize("name,shapes", FAMILIES, ids=[f[0] for f in FAMILIES])
+def test_full_size_family(name, shapes):
+    import torch
+
+    s0 = shapes[0]
+    _say(f"{name}: generating and packing W [{s0.N} x {s0.K}] group {s0.group}")
+    rng = np.random.Generator(np.random.PCG64(s0.seed))
+    W = WL.make_weights(s0.N, s0.K, s0.sigma_w, rng=rng)
+    P = H.Problem(s0.N, s0.K, s0.group, W=W)
+    acts = {}
+    for shp in shapes:
+        acts[shp.M] = WL.make_activations(shp.M, shp.K, shp.outlier_frac, seed=shp.seed + 1000 + shp.M)
+    xsums = {M: X.astype(np.float64).sum(axis=0) for M, (X, _) in acts.items()}
+    _say(f"{name}: oracle column sums")
+    colsum, rowdot, s_w_oracle = _oracle_column_sums(P, xsums)
+    assert np.array_equal(P.w_scales.view(np.uint32), s_w_oracle.view(np.uint32)), "level-1 scales differ"
+
+    pick = np.random.default_rng(17)
+    n_idx = np.sort(pick.choice(s0.N, size=192, replace=False))
+    for shp in shapes:
+        M = shp.M
+        X, s_x = acts[M]
+        vname = api.w4a8_variant_name(api.w4a8_select_variant(M, shp.N, shp.K, shp.group))
+        _say(f"{shp.name}: GPU run ({vname})")
+        dX, dsx = torch.from_numpy(X).cuda(), torch.from_numpy(s_x).cuda()
+        Y = api.w4a8_gemm(dX, dsx, P.d_packed, P.d_gparams, P.d_w_scales, shp.N, shp.K, shp.group)
+        ACC = api.w4a8_gemm_i32(dX, P.d_packed, P.d_gparams, shp.N, shp.K, shp.group)
+        torch.cuda.synchronize()
+        ACC = ACC.cpu().numpy()
+        Y = Y.cpu().numpy()
+        # checksums over every accumulator
+        got_rows = ACC.sum(axis=1, dtype=np.int64)
+        assert np.array_equal(got_rows, X.astype(np.int64) @ colsum), f"{shp.name}: row checksums differ"
+        got_cols = ACC.sum(axis=0, dtype=np.int64).astype(np.float64)
+        assert np.array_equal(got_cols, rowdot[M]), f"{shp.name}: column checksums differ"
+        # sampled outputs against the oracle, element by element
+        m_idx = np.arange(M) if M <= 48 else np.sort(pick.choice(M, size=48, replace=False))
+        ACC_ref, Y_ref64 = P.oracle_sampled(X, s_x, m_idx, n_idx)
+        assert np.array_equal(ACC[np.ix_(m_idx, n_idx)], ACC_ref), f"{shp.name}: sampled accumulators differ"
+        H.assert_fp16_close(Y[np.ix_(m_idx, n_idx)], Y_ref64, shp.name)
+        # whole FP16 matrix against the epilogue definition applied to the accumulators
+        ref64 = O.scale_epilogue_f64(ACC, s_x, s_w_oracle)
+        H.assert_fp16_close(Y, ref64, shp.name + " (all outputs)")
+        del ACC, Y, ref64, dX
+    del P
+    torch.cuda.empty_cache()
