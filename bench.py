@@ -163,6 +163,9 @@ def main():
     ap.add_argument("--variant", type=int, default=-1, help="force a kernel variant (tuning)")
     ap.add_argument("--no-curve", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--copy-ref", action="store_true",
+                    help="only run a plain device-to-device copy of 1 GiB five times (reference "
+                         "for scaling the profiler's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path has no collective); use --gpus 1")
@@ -174,6 +177,14 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
+    if args.copy_ref:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_ref_bytes_read": 1 << 30, "copy_ref_bytes_written": 1 << 30, "copies": 5}))
+        return
     api.lib()
     torch.cuda.set_device(0)
     stream = torch.cuda.Stream()
