@@ -96,6 +96,26 @@ __device__ long long g_dbg_stamps[4 * 16384];
 constexpr int kMaxTicketGroups = 8192;
 __device__ unsigned int g_splitk_tickets[kMaxTicketGroups];
 
+// Device-scope (write-through / cache-bypassing) 16-byte accesses for the exchange of
+// split-K partial tiles between blocks that may sit on different XCDs: the sc1 forms of
+// the plain global load and store, which is what a relaxed agent-scope atomic compiles to.
+__device__ __forceinline__ void store_sc1_x4(int32_t *p, const v4i v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ v4i load_sc1_x4(const int32_t *p)
+{
+    v4i v;
+    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
+    return v;
+}
+__device__ __forceinline__ void wait_vmcnt0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// the same wait, tied to the registers that the loads above are filling
+__device__ __forceinline__ void wait_vmcnt0(v4i &a, v4i &b, v4i &c, v4i &d)
+{
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d)::"memory");
+}
+
 template <int F, bool G128>
 struct StreamRegs {
     u32x4 w[F][2];
@@ -774,11 +794,13 @@ template <bool G128>
 __global__ __launch_bounds__(256, 2) void w4a8_duo_kernel(
     int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
-    __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n)
+    __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n,
+    int32_t *__restrict__ partials)
 {
     constexpr int MF = 4, WM = 128, XP = 4;
     constexpr int STAGE = WM * kTilePitch;
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
+    __shared__ int s_last;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -789,7 +811,12 @@ __global__ __launch_bounds__(256, 2) void w4a8_duo_kernel(
     const int ng = bn * 4 + wave;
     const bool active = ng < (N >> 6);
     const int t0 = 2 * (active ? ng : (N >> 6) - 1);
-    const int stages = K >> 7;  // even, since K % 256 == 0
+    // grid-level split-K: slice ks of S covers whole units of 256 k
+    const int S = gridDim.y, ks = blockIdx.y;
+    const int u_begin = (int)((long long)(K >> 8) * ks / S), u_end = (int)((long long)(K >> 8) * (ks + 1) / S);
+    const int s_begin = 2 * u_begin;
+    const int stages = 2 * (u_end - u_begin);  // stages of 128 k in this slice (even)
+    const int stages_total = K >> 7;
     const int chunks_per_tile = K >> 6;
 
     v16i acc[MF][2];
@@ -804,14 +831,15 @@ __global__ __launch_bounds__(256, 2) void w4a8_duo_kernel(
     const int xrow = tid >> 3, xcol = tid & 7;
     const int8_t *xg[XP];
 #pragma unroll
-    for (int i = 0; i < XP; ++i) xg[i] = X + (size_t)min(m0 + xrow + 32 * i, M - 1) * K + 16 * xcol;
+    for (int i = 0; i < XP; ++i)
+        xg[i] = X + (size_t)min(m0 + xrow + 32 * i, M - 1) * K + (size_t)s_begin * 128 + 16 * xcol;
     const int xl = xrow * kTilePitch + 16 * xcol;
     const u32x4 *wg[2];
     const uint8_t *pg[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-        wg[t] = Wp + (size_t)(t0 + t) * chunks_per_tile * 64 + lane;
-        pg[t] = gp + ((size_t)(t0 + t) * stages * 32 + j) * (G128 ? 2 : 4);
+        wg[t] = Wp + ((size_t)(t0 + t) * chunks_per_tile + 2 * (size_t)s_begin) * 64 + lane;
+        pg[t] = gp + (((size_t)(t0 + t) * stages_total + s_begin) * 32 + j) * (G128 ? 2 : 4);
     }
     const int8_t *xs = lds + j * kTilePitch + 16 * kb;
 
@@ -913,6 +941,51 @@ __global__ __launch_bounds__(256, 2) void w4a8_duo_kernel(
         stage(s + 1, wr[1], pr[1], wr[0], pr[0], 1);
     }
 
+    if (S > 1) {
+        // Grid-level split-K (same protocol as the stream kernels): every block publishes its
+        // INT32 partial tile with device-scope write-through stores, takes a ticket, and the
+        // last one of the S slices adds the others to its registers and runs the epilogue.
+        // Layout: [tile][slice][wave][32 x (64 lanes x 16 B)], fully coalesced.
+        const size_t tile = blockIdx.x;
+        int32_t *mine = partials + (((tile * S + ks) * 4 + wave) * 32) * 256 + lane * 4;
+#pragma unroll
+        for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const v4i v = v4i{acc[mf][t][4 * q], acc[mf][t][4 * q + 1], acc[mf][t][4 * q + 2],
+                                      acc[mf][t][4 * q + 3]};
+                    store_sc1_x4(mine + ((mf * 2 + t) * 4 + q) * 256, v);
+                }
+        wait_vmcnt0();
+        __syncthreads();
+        if (tid == 0) {
+            const unsigned tk = __hip_atomic_fetch_add(&g_splitk_tickets[tile], 1u, __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT);
+            s_last = (tk == (unsigned)(S - 1));
+        }
+        __syncthreads();
+        if (!s_last) return;
+        for (int k2 = 0; k2 < S; ++k2) {
+            if (k2 == ks) continue;
+            const int32_t *other = partials + (((tile * S + k2) * 4 + wave) * 32) * 256 + lane * 4;
+#pragma unroll
+            for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    v4i v[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) v[q] = load_sc1_x4(other + ((mf * 2 + t) * 4 + q) * 256);
+                    wait_vmcnt0(v[0], v[1], v[2], v[3]);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[mf][t][4 * q + e] += v[q][e];
+                }
+        }
+        if (tid == 0) __hip_atomic_store(&g_splitk_tickets[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     if (!active) return;
     store_tile<MF>(acc, M, N, m0, 64 * ng + 2 * j, lane, sx, sw, Y, ACC);
 }
@@ -1060,18 +1133,44 @@ static int launch_pipe(const Args &a)
     return LQ_OK;
 }
 
+// Grid-level split of K for the duo kernel: used when the output alone gives fewer tiles
+// than CUs; slices hold at least 512 k.
+static int duo_split(int M, int N, int K)
+{
+    const int tiles = ((M + 127) / 128) * ((N + 255) / 256);
+    if (tiles >= 128 || tiles > kMaxTicketGroups) return 1;
+    // measured: the exchange of 128 KiB partial tiles is expensive, so split sparingly
+    int s = tiles >= 40 ? 2 : 4;
+    s = std::min(s, K / 512);
+    return std::max(1, s);
+}
+static size_t duo_ws_bytes(int M, int N, int S)
+{
+    if (S <= 1) return 0;
+    const size_t tiles = (size_t)((M + 127) / 128) * ((N + 255) / 256);
+    return tiles * S * 4 * 32 * 256 * sizeof(int32_t);
+}
+
+template <int SPLIT>
 static int launch_duo(const Args &a)
 {
     constexpr int WM = 128;
     const int blocks_n = (a.N + 255) / 256, blocks_m = (a.M + WM - 1) / WM;
+    int S = SPLIT ? SPLIT : duo_split(a.M, a.N, a.K);
+    S = std::min(S, a.K / 256);
+    if (blocks_n * blocks_m > kMaxTicketGroups) S = 1;
+    const size_t need = duo_ws_bytes(a.M, a.N, S);
+    if (need > 0 && (!a.ws || a.ws_bytes < need))
+        return fail(LQ_ERR_WORKSPACE, "split-K needs %zu bytes of workspace, got %zu", need, a.ws ? a.ws_bytes : 0);
     const size_t lds_bytes = 2 * (size_t)WM * kTilePitch;
-    const dim3 grid((unsigned)(blocks_n * blocks_m)), block(256);
+    const dim3 grid((unsigned)(blocks_n * blocks_m), (unsigned)S), block(256);
+    int32_t *partials = static_cast<int32_t *>(a.ws);
     if (a.group == 128)
         hipLaunchKernelGGL(w4a8_duo_kernel<true>, grid, block, lds_bytes, a.stream, a.M, a.N, a.K, a.X, a.sx,
-                           a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
+                           a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n, partials);
     else
         hipLaunchKernelGGL(w4a8_duo_kernel<false>, grid, block, lds_bytes, a.stream, a.M, a.N, a.K, a.X, a.sx,
-                           a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
+                           a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n, partials);
     return LQ_OK;
 }
 
@@ -1105,7 +1204,11 @@ static const Variant kVariants[] = {
     {"tile_m256", &launch_tile<8>, 0, 1, 1},
     {"pipe_m128", &launch_pipe<4>, 0, 1, 1},
     {"pipe_m256", &launch_pipe<8>, 0, 1, 1},
-    {"duo_m128", &launch_duo, 0, 1, 1},
+    {"duo_m128", &launch_duo<0>, 0, 1, 1},
+    {"duo_m128_s1", &launch_duo<1>, 0, 1, 1},
+    {"duo_m128_s2", &launch_duo<2>, 0, 1, 1},
+    {"duo_m128_s4", &launch_duo<4>, 0, 1, 1},
+    {"duo_m128_s8", &launch_duo<8>, 0, 1, 1},
 #ifdef LQ_ABLATE
     {"abl_m256_noX", &launch_pipe<8, 1>, 0, 1, 1},
     {"abl_m256_noW", &launch_pipe<8, 2>, 0, 1, 1},
@@ -1186,12 +1289,15 @@ extern "C" {
 
 size_t w4a8_gemm_workspace_size(int M, int N, int K, int group)
 {
-    if (M <= 0 || M > 32 || !shape_ok(N, K, group)) return 0;  // only the stream kernels split K
-    // room for the largest split any stream variant can pick (16 slices; the 16-row kernels
-    // always exchange 8 values per lane and tile)
-    const size_t a = stream_ws_bytes(M, N, 16);
-    const size_t b = M <= 16 ? (size_t)16 * (N / 32) * 8 * 64 * sizeof(int32_t) : 0;
-    return std::max(a, b);
+    if (M <= 0 || !shape_ok(N, K, group)) return 0;
+    // Enough for any variant that can run the shape.  Tiled kernels split K only while the
+    // output has fewer tiles than CUs (at most 8 slices); stream kernels take at most 16
+    // slices (the 16-row kernels always exchange 8 values per lane and tile).
+    const int tiles = ((M + 127) / 128) * ((N + 255) / 256);
+    size_t need = tiles >= 192 ? 0 : duo_ws_bytes(M, N, 8);
+    if (M <= 32) need = std::max(need, stream_ws_bytes(M, N, 16));
+    if (M <= 16) need = std::max(need, (size_t)16 * (N / 32) * 8 * 64 * sizeof(int32_t));
+    return need;
 }
 
 int w4a8_gemm(int M, int N, int K, int group, const int8_t *X, const float *act_scales,
