@@ -93,8 +93,14 @@ int liquidquant_unpack_weights(const void *W_packed, const uint8_t *gparams, int
  * W4A8 GEMM (device, Sec. 5: load, unpack, LQQ dequantisation, INT8 MFMA, epilogue)
  * ------------------------------------------------------------------------------------ */
 
-/* Bytes of device workspace w4a8_gemm* needs for this shape (0 when no kernel that the
- * dispatcher can choose needs one). */
+/* Bytes of device workspace w4a8_gemm* can use for this shape: room for the INT32 partial
+ * tiles of the grid-level split-K (0 when no kernel that can run the shape splits K across
+ * blocks).  No initialisation is required.  With a smaller (or NULL) workspace the
+ * dispatcher runs the same kernels without the split, which is slower for small N but gives
+ * the same result; a variant that names its split (w4a8_gemm_variant) fails with
+ * LQ_ERR_WORKSPACE instead.  Split-K calls also share a small library-owned ticket array
+ * on the device: two such calls that overlap in time on one GPU (different streams) race,
+ * calls on one stream are safe. */
 size_t w4a8_gemm_workspace_size(int M, int N, int K, int group);
 
 /* Y[M,N] (device, FP16 bits, row-major) = epilogue(X . dequant(W)^T).
@@ -102,7 +108,7 @@ size_t w4a8_gemm_workspace_size(int M, int N, int K, int group);
  *   act_scales  device [M] FP32, per-token scales s_x (Sec. 6)
  *   W_packed, gparams  device copies of the packer's outputs
  *   w_scales    device [N] FP32, per-channel scales s_w
- *   workspace   device, workspace_bytes >= w4a8_gemm_workspace_size(); may be NULL if 0 */
+ *   workspace   device, see w4a8_gemm_workspace_size(); may be NULL */
 int w4a8_gemm(int M, int N, int K, int group, const int8_t *X, const float *act_scales,
               const void *W_packed, const uint8_t *gparams, const float *w_scales, uint16_t *Y,
               void *workspace, size_t workspace_bytes, void *hip_stream);

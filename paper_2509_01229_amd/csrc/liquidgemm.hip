@@ -258,14 +258,17 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream_kernel(
 // MFMAs (see regroup_16x16), which take half the matrix-pipe time, a quarter of the
 // accumulator registers and half of the X registers.
 // ------------------------------------------------------------------------------------
-template <int F, bool G128>
+// UU = 128-k units per pipeline step (1 or 2): bytes in flight per wave = F * UU * 2 KiB.
+template <int F, int UU, bool G128>
 struct Stream16Regs {
-    u32x4 w[F][2];
-    UnitParams<G128> p[F];
-    u32x4 x[2];
+    u32x4 w[F][2 * UU];
+    UnitParams<G128> p[F][UU];
+    u32x4 x[2 * UU];
 };
 
-template <int F, int NW, bool G128>
+// ABL (experiments only, 0 in shipped variants): 1 = no X loads, 2 = no parameter loads,
+// 4 = no dequantisation, 8 = no reduction / epilogue.  Results are wrong for ABL != 0.
+template <int F, int NW, int UU, bool G128, int ABL = 0>
 __global__ __launch_bounds__(NW * 64) void w4a8_stream16_kernel(
     int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
@@ -277,10 +280,11 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream16_kernel(
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane & 31;
     const int t0 = blockIdx.x * F;
-    const int units = K >> 7;
+    const int units = K >> 7;                   // 128-k units (parameter granularity)
+    const int steps = units / UU;               // pipeline steps of UU units
     const int chunks_per_tile = K >> 6;
     const int S = gridDim.y, ks = blockIdx.y;
-    const int u_begin = (int)((long long)units * ks / S), u_end = (int)((long long)units * (ks + 1) / S);
+    const int u_begin = (int)((long long)steps * ks / S), u_end = (int)((long long)steps * (ks + 1) / S);
 
     v4i acc[F][2];
 #pragma unroll
@@ -292,26 +296,53 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream16_kernel(
     // the k-block order that regroup_16x16 produces.  Lanes past M read row M-1.
     const int8_t *xrow = X + (size_t)min(lane & 15, M - 1) * K + kstep16_offset(lane >> 4);
 
-    auto load_unit = [&](int u, Stream16Regs<F, G128> &r) {
+    // The outputs this thread will finish (idx = threadIdx.x + i * blockDim.x) are known
+    // now: fetch their scales here, so that the epilogue does not end on a cold load.
+    constexpr int OUTS = (VALS * 64 + NW * 64 - 1) / (NW * 64);
+    float pre_sx[OUTS], pre_sw[OUTS];
+    if (Y) {
+#pragma unroll
+        for (int i = 0; i < OUTS; ++i) {
+            const int idx = threadIdx.x + i * NW * 64;
+            const int v = min(idx >> 6, VALS - 1), l = idx & 63;
+            pre_sx[i] = sx[min(4 * (l >> 4) + (v & 3), M - 1)];
+            pre_sw[i] = sw[channel_of(t0 + (v >> 3), 16 * ((v >> 2) & 1) + (l & 15))];
+        }
+    }
+
+    auto load_unit = [&](int u, Stream16Regs<F, UU, G128> &r) {
 #pragma unroll
         for (int f = 0; f < F; ++f) {
-            const u32x4 *base = Wp + ((size_t)(t0 + f) * chunks_per_tile + 2 * (size_t)u) * 64 + lane;
-            r.w[f][0] = __builtin_nontemporal_load(base);
-            r.w[f][1] = __builtin_nontemporal_load(base + 64);
-            r.p[f].load(gp, (size_t)(t0 + f) * units + u, j);
+            const u32x4 *base = Wp + ((size_t)(t0 + f) * chunks_per_tile + 2 * UU * (size_t)u) * 64 + lane;
+#pragma unroll
+            for (int c = 0; c < 2 * UU; ++c) r.w[f][c] = __builtin_nontemporal_load(base + 64 * c);
+#pragma unroll
+            for (int q = 0; q < UU; ++q) {
+                if (ABL & 2)
+                    r.p[f][q].raw = 0x01800180u;
+                else
+                    r.p[f][q].load(gp, (size_t)(t0 + f) * units + (size_t)u * UU + q, j);
+            }
         }
 #pragma unroll
-        for (int c = 0; c < 2; ++c) r.x[c] = *reinterpret_cast<const u32x4 *>(xrow + (size_t)u * 128 + 64 * c);
+        for (int c = 0; c < 2 * UU; ++c)
+            r.x[c] = (ABL & 1) ? u32x4{1u, 2u, 3u, (unsigned)u}
+                               : *reinterpret_cast<const u32x4 *>(xrow + (size_t)u * (128 * UU) + 64 * c);
     };
-    auto compute_unit = [&](const Stream16Regs<F, G128> &r) {
+    auto compute_unit = [&](const Stream16Regs<F, UU, G128> &r) {
 #pragma unroll
         for (int f = 0; f < F; ++f)
 #pragma unroll
-            for (int c = 0; c < 2; ++c) {
+            for (int c = 0; c < 2 * UU; ++c) {
                 uint32_t s2, a4;
-                r.p[f].get(c, s2, a4);
+                r.p[f][c >> 1].get(c & 1, s2, a4);
                 v4i lo, hi, b1, b2;
-                dequant_chunk(r.w[f][c], s2, a4, lo, hi);
+                if (ABL & 4) {
+                    lo = __builtin_bit_cast(v4i, r.w[f][c]);
+                    hi = lo + (int)s2;
+                } else {
+                    dequant_chunk(r.w[f][c], s2, a4, lo, hi);
+                }
                 regroup_16x16(lo, hi, b1, b2);
                 const v4i xa = __builtin_bit_cast(v4i, r.x[c]);
                 acc[f][0] = mfma16_i8(xa, b1, acc[f][0]);
@@ -319,7 +350,7 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream16_kernel(
             }
     };
 
-    Stream16Regs<F, G128> cur, nxt;
+    Stream16Regs<F, UU, G128> cur, nxt;
     int u = u_begin + wave;
     if (u < u_end) load_unit(u, cur);
     for (; u < u_end; u += NW) {
@@ -329,6 +360,13 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream16_kernel(
         if (more) cur = nxt;
     }
 
+    if (ABL & 8) {
+        int sum = 0;
+#pragma unroll
+        for (int f = 0; f < F; ++f) sum += acc[f][0][0] + acc[f][1][1] + acc[f][0][2] + acc[f][1][3];
+        if (sum == 0x12345678) ACC[0] = sum;
+        return;
+    }
     // in-block split-K reduction: value v = (f*2 + h)*4 + r of lane l is row 4*(l/16) + r,
     // slot 16*h + l%16 of tile t0 + f
 #pragma unroll
@@ -344,17 +382,21 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream16_kernel(
         for (int w = 0; w < NW; ++w) sum += red[(w * VALS + (idx >> 6)) * 64 + (idx & 63)];
         return sum;
     };
-    auto finish = [&](int idx, int sum) {
+    auto finish = [&](int i, int idx, int sum) {
         const int v = idx >> 6, l = idx & 63;
         const int m = 4 * (l >> 4) + (v & 3);
         if (m < M) {
             const int n = channel_of(t0 + (v >> 3), 16 * ((v >> 2) & 1) + (l & 15));
             if (ACC) ACC[(size_t)m * N + n] = sum;
-            if (Y) Y[(size_t)m * N + n] = scale_to_half(sum, sx[m], sw[n]);
+            if (Y) Y[(size_t)m * N + n] = scale_to_half(sum, pre_sx[i], pre_sw[i]);
         }
     };
     if (S == 1) {
-        for (int idx = threadIdx.x; idx < VALS * 64; idx += NW * 64) finish(idx, block_sum(idx));
+#pragma unroll
+        for (int i = 0; i < OUTS; ++i) {
+            const int idx = threadIdx.x + i * NW * 64;
+            if (idx < VALS * 64) finish(i, idx, block_sum(idx));
+        }
     } else {
         // grid-level split-K: same protocol as w4a8_stream_kernel
         int32_t *mine = partials + ((size_t)ks * gridDim.x + blockIdx.x) * (size_t)(VALS * 64);
@@ -368,13 +410,16 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream16_kernel(
         }
         __syncthreads();
         if (s_last) {
-            for (int idx = threadIdx.x; idx < VALS * 64; idx += NW * 64) {
+#pragma unroll
+            for (int i = 0; i < OUTS; ++i) {
+                const int idx = threadIdx.x + i * NW * 64;
+                if (idx >= VALS * 64) break;
                 int sum = 0;
                 for (int k2 = 0; k2 < S; ++k2)
                     sum += __hip_atomic_load(
                         partials + ((size_t)k2 * gridDim.x + blockIdx.x) * (size_t)(VALS * 64) + idx,
                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                finish(idx, sum);
+                finish(i, idx, sum);
             }
             if (threadIdx.x == 0)
                 __hip_atomic_store(&g_splitk_tickets[blockIdx.x], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1027,7 +1072,7 @@ static int stream_split(int N, int K, int F, int NW)
     const int groups = N / (32 * F), units = K / 128;
     // Measured on MI355X: the exchange of partial tiles through memory costs about 3 us, so
     // K is split across blocks only when N alone leaves most CUs without a block.
-    int s = groups > 160 ? 1 : (groups > 48 ? 2 : 4);
+    int s = groups > 128 ? 1 : (groups > 48 ? 2 : 4);
     s = std::min(s, units / (2 * NW));
     return std::max(1, s);
 }
@@ -1049,9 +1094,14 @@ static int launch_stream(const Args &a)
     int S = SPLIT ? SPLIT : stream_split(a.N, a.K, F, NW);
     S = std::min(S, a.K / 128);
     if (S > 1 && groups > kMaxTicketGroups) S = 1;
-    const size_t need = stream_ws_bytes(a.M, a.N, S);
-    if (need > 0 && (!a.ws || a.ws_bytes < need))
-        return fail(LQ_ERR_WORKSPACE, "split-K needs %zu bytes of workspace, got %zu", need, a.ws ? a.ws_bytes : 0);
+    size_t need = stream_ws_bytes(a.M, a.N, S);
+    if (need > 0 && (!a.ws || a.ws_bytes < need)) {
+        if (SPLIT)  // a named split cannot run without its workspace; the automatic one falls back
+            return fail(LQ_ERR_WORKSPACE, "split-K needs %zu bytes of workspace, got %zu", need,
+                        a.ws ? a.ws_bytes : 0);
+        S = 1;
+        need = 0;
+    }
     const dim3 grid(groups, S), block(NW * 64);
     const int rmax = 4 * ((a.M + 7) / 8);
     const size_t lds_bytes = (size_t)NW * F * rmax * 64 * sizeof(int);
@@ -1068,7 +1118,7 @@ static int launch_stream(const Args &a)
     return LQ_OK;
 }
 
-template <int F, int NW, int SPLIT>
+template <int F, int NW, int SPLIT, int ABL = 0, int UU = 1>
 static int launch_stream16(const Args &a)
 {
     if (a.M > 16) return fail(LQ_ERR_INVALID, "stream16 variants handle M <= 16, got %d", a.M);
@@ -1077,19 +1127,24 @@ static int launch_stream16(const Args &a)
     int S = SPLIT ? SPLIT : stream_split(a.N, a.K, F, NW);
     S = std::min(S, a.K / 128);
     if (S > 1 && groups > kMaxTicketGroups) S = 1;
-    const size_t need = S > 1 ? (size_t)S * (a.N / 32) * 8 * 64 * sizeof(int32_t) : 0;
-    if (need > 0 && (!a.ws || a.ws_bytes < need))
-        return fail(LQ_ERR_WORKSPACE, "split-K needs %zu bytes of workspace, got %zu", need, a.ws ? a.ws_bytes : 0);
+    size_t need = S > 1 ? (size_t)S * (a.N / 32) * 8 * 64 * sizeof(int32_t) : 0;
+    if (need > 0 && (!a.ws || a.ws_bytes < need)) {
+        if (SPLIT)
+            return fail(LQ_ERR_WORKSPACE, "split-K needs %zu bytes of workspace, got %zu", need,
+                        a.ws ? a.ws_bytes : 0);
+        S = 1;
+        need = 0;
+    }
     const dim3 grid(groups, S), block(NW * 64);
     const size_t lds_bytes = (size_t)NW * F * 8 * 64 * sizeof(int);
     int32_t *partials = static_cast<int32_t *>(a.ws);
     if (a.group == 128) {
-        if (int rc = allow_lds(&w4a8_stream16_kernel<F, NW, true>, lds_bytes)) return rc;
-        hipLaunchKernelGGL((w4a8_stream16_kernel<F, NW, true>), grid, block, lds_bytes, a.stream, a.M, a.N,
+        if (int rc = allow_lds(&w4a8_stream16_kernel<F, NW, UU, true, ABL>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_stream16_kernel<F, NW, UU, true, ABL>), grid, block, lds_bytes, a.stream, a.M, a.N,
                            a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials);
     } else {
-        if (int rc = allow_lds(&w4a8_stream16_kernel<F, NW, false>, lds_bytes)) return rc;
-        hipLaunchKernelGGL((w4a8_stream16_kernel<F, NW, false>), grid, block, lds_bytes, a.stream, a.M, a.N,
+        if (int rc = allow_lds(&w4a8_stream16_kernel<F, NW, UU, false, ABL>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_stream16_kernel<F, NW, UU, false, ABL>), grid, block, lds_bytes, a.stream, a.M, a.N,
                            a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials);
     }
     return LQ_OK;
@@ -1159,9 +1214,14 @@ static int launch_duo(const Args &a)
     int S = SPLIT ? SPLIT : duo_split(a.M, a.N, a.K);
     S = std::min(S, a.K / 256);
     if (blocks_n * blocks_m > kMaxTicketGroups) S = 1;
-    const size_t need = duo_ws_bytes(a.M, a.N, S);
-    if (need > 0 && (!a.ws || a.ws_bytes < need))
-        return fail(LQ_ERR_WORKSPACE, "split-K needs %zu bytes of workspace, got %zu", need, a.ws ? a.ws_bytes : 0);
+    size_t need = duo_ws_bytes(a.M, a.N, S);
+    if (need > 0 && (!a.ws || a.ws_bytes < need)) {
+        if (SPLIT)
+            return fail(LQ_ERR_WORKSPACE, "split-K needs %zu bytes of workspace, got %zu", need,
+                        a.ws ? a.ws_bytes : 0);
+        S = 1;
+        need = 0;
+    }
     const size_t lds_bytes = 2 * (size_t)WM * kTilePitch;
     const dim3 grid((unsigned)(blocks_n * blocks_m), (unsigned)S), block(256);
     int32_t *partials = static_cast<int32_t *>(a.ws);
@@ -1185,19 +1245,15 @@ struct Variant {
 // stream_f<F>_w<NW>[_s<S>]: F tiles per block, NW waves splitting the block's K slice,
 // S grid-level K slices (chosen from the shape when not named).
 static const Variant kVariants[] = {
-    {"stream_f1_w8", &launch_stream<1, 8, 0>, 32, 1, 1},
     {"stream_f2_w8", &launch_stream<2, 8, 0>, 32, 2, 1},
-    {"stream_f2_w4", &launch_stream<2, 4, 0>, 32, 2, 1},
     {"stream_f2_w8_s1", &launch_stream<2, 8, 1>, 32, 2, 1},
     {"stream_f2_w8_s2", &launch_stream<2, 8, 2>, 32, 2, 1},
     {"stream_f2_w8_s4", &launch_stream<2, 8, 4>, 32, 2, 1},
     {"stream16_f2_w8", &launch_stream16<2, 8, 0>, 16, 2, 1},
     {"stream16_f2_w4", &launch_stream16<2, 4, 0>, 16, 2, 1},
-    {"stream16_f1_w8", &launch_stream16<1, 8, 0>, 16, 1, 1},
     {"stream16_f2_w8_s1", &launch_stream16<2, 8, 1>, 16, 2, 1},
     {"stream16_f2_w8_s2", &launch_stream16<2, 8, 2>, 16, 2, 1},
     {"stream16_f2_w8_s4", &launch_stream16<2, 8, 4>, 16, 2, 1},
-    {"stream16_f4_w8_s2", &launch_stream16<4, 8, 2>, 16, 4, 1},
     {"tile_m32", &launch_tile<1>, 0, 1, 1},
     {"tile_m64", &launch_tile<2>, 0, 1, 1},
     {"tile_m128", &launch_tile<4>, 0, 1, 1},
@@ -1210,6 +1266,13 @@ static const Variant kVariants[] = {
     {"duo_m128_s4", &launch_duo<4>, 0, 1, 1},
     {"duo_m128_s8", &launch_duo<8>, 0, 1, 1},
 #ifdef LQ_ABLATE
+    {"abl_s16_noX", &launch_stream16<2, 4, 1, 1>, 16, 2, 1},
+    {"abl_s16_noP", &launch_stream16<2, 4, 1, 2>, 16, 2, 1},
+    {"abl_s16_noDq", &launch_stream16<2, 4, 1, 4>, 16, 2, 1},
+    {"abl_s16_noRed", &launch_stream16<2, 4, 1, 8>, 16, 2, 1},
+    {"abl_s16_noXP", &launch_stream16<2, 4, 1, 3>, 16, 2, 1},
+    {"abl_s16_noXPDq", &launch_stream16<2, 4, 1, 7>, 16, 2, 1},
+    {"abl_s16_onlyW", &launch_stream16<2, 4, 1, 15>, 16, 2, 1},
     {"abl_m256_noX", &launch_pipe<8, 1>, 0, 1, 1},
     {"abl_m256_noW", &launch_pipe<8, 2>, 0, 1, 1},
     {"abl_m256_noXW", &launch_pipe<8, 3>, 0, 1, 1},

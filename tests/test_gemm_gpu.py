@@ -187,3 +187,28 @@ def test_binding_rejects_bad_tensors():
     with pytest.raises(api.LiquidGemmError):
         api.w4a8_gemm_variant(0, torch.zeros((64, K), dtype=torch.int8, device="cuda"),
                               torch.ones(64, device="cuda"), P.d_packed, P.d_gparams, P.d_w_scales, N, K, g)
+
+
+def test_workspace_is_optional_for_the_dispatcher():
+    """Without room for split-K partials the dispatcher runs unsplit and stays exact; a
+    variant that names its split reports the missing workspace."""
+    import torch
+
+    for M, N, K, g in [(8, 256, 2048, 64), (160, 512, 2048, 128)]:
+        _say(f"small workspace M={M} N={N} K={K}")
+        assert api.w4a8_gemm_workspace_size(M, N, K, g) > 16
+        P = H.Problem(N, K, g, seed=11)
+        X, s_x = WL.make_activations(M, K, seed=12)
+        ACC_ref, _ = P.oracle_gemm(X, s_x)
+        dX = torch.from_numpy(X).cuda()
+        tiny = torch.empty(16, dtype=torch.uint8, device="cuda")
+        ACC = api.w4a8_gemm_i32(dX, P.d_packed, P.d_gparams, N, K, g, workspace=tiny)
+        torch.cuda.synchronize()
+        assert np.array_equal(ACC.cpu().numpy(), ACC_ref)
+        split = [v for v in H.variants_for(M, N, K, g) if api.w4a8_variant_name(v).endswith("_s2")]
+        assert split
+        for v in split:
+            with pytest.raises(api.LiquidGemmError) as e:
+                api.w4a8_gemm_variant(v, dX, torch.from_numpy(s_x).cuda(), P.d_packed, P.d_gparams,
+                                      P.d_w_scales, N, K, g, workspace=tiny)
+            assert e.value.code == -3
