@@ -25,6 +25,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 
@@ -486,7 +487,10 @@ __device__ __forceinline__ void block_coords(int blocks_m, int blocks_n, int &bm
     const int total = blocks_m * blocks_n;
     int lid = blockIdx.x;
     if ((total & 7) == 0) lid = (lid & 7) * (total >> 3) + (lid >> 3);
-    constexpr int GM = 4;
+#ifndef LQ_GM
+#define LQ_GM 4
+#endif
+    constexpr int GM = LQ_GM;
     const int per_group = GM * blocks_n;
     const int first = (lid / per_group) * GM;
     const int gsz = min(blocks_m - first, GM);
@@ -835,8 +839,14 @@ __global__ __launch_bounds__(256, (MF <= 4 ? 2 : 1)) void w4a8_pipe_kernel(
 // wave at the granularity of one k-step (32 k): while the 8 MFMAs of a k-step run, the
 // B operand of the next k-step is dequantised and its X fragments are read from LDS.
 // ------------------------------------------------------------------------------------
-template <bool G128>
-__global__ __launch_bounds__(256, 2) void w4a8_duo_kernel(
+//
+// KG = 2 is the variant for grids of at most one block per CU: the block then holds two
+// groups of four waves that work on the same 128 x 256 tile, each on its own half of the
+// block's k range with its own LDS stages, and exchange halves of their accumulators
+// through LDS at the end (in-block split-K).  Every SIMD again has two waves, which a
+// single 4-wave block per CU would not give.
+template <bool G128, int KG>
+__global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
     int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
     __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n,
@@ -847,7 +857,8 @@ __global__ __launch_bounds__(256, 2) void w4a8_duo_kernel(
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     __shared__ int s_last;
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x & 255;  // thread within its k group
+    const int grp = KG == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 8));
     const int lane = tid & 63, wave = tid >> 6;
     const int j = lane & 31, kb = lane >> 5;
     int bm, bn;
@@ -856,11 +867,16 @@ __global__ __launch_bounds__(256, 2) void w4a8_duo_kernel(
     const int ng = bn * 4 + wave;
     const bool active = ng < (N >> 6);
     const int t0 = 2 * (active ? ng : (N >> 6) - 1);
-    // grid-level split-K: slice ks of S covers whole units of 256 k
+    // grid-level split-K: slice ks of S covers whole units of 256 k ...
     const int S = gridDim.y, ks = blockIdx.y;
     const int u_begin = (int)((long long)(K >> 8) * ks / S), u_end = (int)((long long)(K >> 8) * (ks + 1) / S);
-    const int s_begin = 2 * u_begin;
-    const int stages = 2 * (u_end - u_begin);  // stages of 128 k in this slice (even)
+    // ... and the in-block split gives group 0 the first ceil(half) of them.  All groups run
+    // the loop of group 0 (the barriers are block-wide); a group with one unit less feeds
+    // zeros as X in its last pass.
+    const int u_first = (u_end - u_begin + KG - 1) / KG;
+    const int s_begin = 2 * (u_begin + (grp ? u_first : 0));
+    const int my_stages = 2 * (grp ? u_end - u_begin - u_first : u_first);
+    const int stages = 2 * u_first;  // loop length in stages of 128 k (even)
     const int stages_total = K >> 7;
     const int chunks_per_tile = K >> 6;
 
@@ -886,7 +902,8 @@ __global__ __launch_bounds__(256, 2) void w4a8_duo_kernel(
         wg[t] = Wp + ((size_t)(t0 + t) * chunks_per_tile + 2 * (size_t)s_begin) * 64 + lane;
         pg[t] = gp + (((size_t)(t0 + t) * stages_total + s_begin) * 32 + j) * (G128 ? 2 : 4);
     }
-    const int8_t *xs = lds + j * kTilePitch + 16 * kb;
+    int8_t *lds_g = lds + grp * (2 * STAGE);  // the two X stages of this k group
+    const int8_t *xs = lds_g + j * kTilePitch + 16 * kb;
 
     u32x4 xr[XP];
     u32x4 wr[2][2][2];  // [stage parity][tile][chunk]
@@ -895,17 +912,22 @@ __global__ __launch_bounds__(256, 2) void w4a8_duo_kernel(
     v4i af[2][MF];      // [ping-pong][m fragment]
 
     auto load_x = [&](int s) {
-        s = min(s, stages - 1);
+        if (KG > 1 && s >= my_stages) {  // past this group's slice: contributes nothing
+#pragma unroll
+            for (int i = 0; i < XP; ++i) xr[i] = u32x4{0, 0, 0, 0};
+            return;
+        }
+        s = min(s, my_stages - 1);
 #pragma unroll
         for (int i = 0; i < XP; ++i) xr[i] = *reinterpret_cast<const u32x4 *>(xg[i] + (size_t)s * 128);
     };
     auto store_x = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < XP; ++i)
-            *reinterpret_cast<u32x4 *>(lds + buf * STAGE + xl + i * 32 * kTilePitch) = xr[i];
+            *reinterpret_cast<u32x4 *>(lds_g + buf * STAGE + xl + i * 32 * kTilePitch) = xr[i];
     };
     auto load_w = [&](int s, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
-        s = min(s, stages - 1);
+        s = min(s, my_stages - 1);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             w[t][0] = wg[t][(size_t)s * 128];
@@ -986,53 +1008,94 @@ __global__ __launch_bounds__(256, 2) void w4a8_duo_kernel(
         stage(s + 1, wr[1], pr[1], wr[0], pr[0], 1);
     }
 
-    if (S > 1) {
-        // Grid-level split-K (same protocol as the stream kernels): every block publishes its
-        // INT32 partial tile with device-scope write-through stores, takes a ticket, and the
-        // last one of the S slices adds the others to its registers and runs the epilogue.
-        // Layout: [tile][slice][wave][32 x (64 lanes x 16 B)], fully coalesced.
-        const size_t tile = blockIdx.x;
-        int32_t *mine = partials + (((tile * S + ks) * 4 + wave) * 32) * 256 + lane * 4;
+    // What is left is written once per k group with compile-time fragment indices: group G
+    // finishes the MFK = MF / KG row fragments starting at MF0 = G * MFK.
+    auto finish = [&](auto group_tag) {
+        constexpr int G = decltype(group_tag)::value;
+        constexpr int MFK = MF / KG, MF0 = G * MFK, GIVE0 = (KG - 1 - G) * MFK;
+        if (KG > 1) {
+            // In-block reduction through LDS (the X stages are dead by now), one column tile
+            // at a time so that 64 KiB suffice: every wave hands the fragments it does not
+            // finish to the wave of the other group that owns the same 128 x 64 sub-tile.
+            v4i *ex = reinterpret_cast<v4i *>(lds);
+            lds_barrier();
 #pragma unroll
-        for (int mf = 0; mf < MF; ++mf)
+            for (int t = 0; t < 2; ++t) {
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const v4i v = v4i{acc[mf][t][4 * q], acc[mf][t][4 * q + 1], acc[mf][t][4 * q + 2],
-                                      acc[mf][t][4 * q + 3]};
-                    store_sc1_x4(mine + ((mf * 2 + t) * 4 + q) * 256, v);
-                }
-        wait_vmcnt0();
-        __syncthreads();
-        if (tid == 0) {
-            const unsigned tk = __hip_atomic_fetch_add(&g_splitk_tickets[tile], 1u, __ATOMIC_RELAXED,
-                                                       __HIP_MEMORY_SCOPE_AGENT);
-            s_last = (tk == (unsigned)(S - 1));
-        }
-        __syncthreads();
-        if (!s_last) return;
-        for (int k2 = 0; k2 < S; ++k2) {
-            if (k2 == ks) continue;
-            const int32_t *other = partials + (((tile * S + k2) * 4 + wave) * 32) * 256 + lane * 4;
-#pragma unroll
-            for (int mf = 0; mf < MF; ++mf)
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    v4i v[4];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) v[q] = load_sc1_x4(other + ((mf * 2 + t) * 4 + q) * 256);
-                    wait_vmcnt0(v[0], v[1], v[2], v[3]);
+                for (int i = 0; i < MFK; ++i)
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
+                        ex[(((G * 4 + wave) * MFK + i) * 4 + q) * 64 + lane] =
+                            v4i{acc[GIVE0 + i][t][4 * q], acc[GIVE0 + i][t][4 * q + 1],
+                                acc[GIVE0 + i][t][4 * q + 2], acc[GIVE0 + i][t][4 * q + 3]};
+                lds_barrier();
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) acc[mf][t][4 * q + e] += v[q][e];
-                }
+                for (int i = 0; i < MFK; ++i)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const v4i v = ex[((((KG - 1 - G) * 4 + wave) * MFK + i) * 4 + q) * 64 + lane];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[MF0 + i][t][4 * q + e] += v[e];
+                    }
+                if (t == 0) lds_barrier();
+            }
         }
-        if (tid == 0) __hip_atomic_store(&g_splitk_tickets[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    if (!active) return;
-    store_tile<MF>(acc, M, N, m0, 64 * ng + 2 * j, lane, sx, sw, Y, ACC);
+        if (S > 1) {
+            // Grid-level split-K (same protocol as the stream kernels): every block publishes its
+            // INT32 partial tile with device-scope write-through stores, takes a ticket, and the
+            // last one of the S slices adds the others to its registers and runs the epilogue.
+            // Layout: [tile][slice][wave of the block][MFK*8 x (64 lanes x 16 B)], fully coalesced.
+            constexpr int EPW = MFK * 8;
+            const size_t tile = blockIdx.x;
+            const int bw = G * 4 + wave;
+            int32_t *mine = partials + (((tile * S + ks) * (4 * KG) + bw) * EPW) * 256 + lane * 4;
+#pragma unroll
+            for (int i = 0; i < MFK; ++i)
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const v4i v = v4i{acc[MF0 + i][t][4 * q], acc[MF0 + i][t][4 * q + 1],
+                                          acc[MF0 + i][t][4 * q + 2], acc[MF0 + i][t][4 * q + 3]};
+                        store_sc1_x4(mine + ((i * 2 + t) * 4 + q) * 256, v);
+                    }
+            wait_vmcnt0();
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                const unsigned tk = __hip_atomic_fetch_add(&g_splitk_tickets[tile], 1u, __ATOMIC_RELAXED,
+                                                           __HIP_MEMORY_SCOPE_AGENT);
+                s_last = (tk == (unsigned)(S - 1));
+            }
+            __syncthreads();
+            if (!s_last) return;
+            for (int k2 = 0; k2 < S; ++k2) {
+                if (k2 == ks) continue;
+                const int32_t *other = partials + (((tile * S + k2) * (4 * KG) + bw) * EPW) * 256 + lane * 4;
+#pragma unroll
+                for (int i = 0; i < MFK; ++i)
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        v4i v[4];
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) v[q] = load_sc1_x4(other + ((i * 2 + t) * 4 + q) * 256);
+                        wait_vmcnt0(v[0], v[1], v[2], v[3]);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) acc[MF0 + i][t][4 * q + e] += v[q][e];
+                    }
+            }
+            if (threadIdx.x == 0)
+                __hip_atomic_store(&g_splitk_tickets[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (!active) return;
+        store_tile<MFK>(*reinterpret_cast<const v16i(*)[MFK][2]>(&acc[MF0]), M, N, m0 + 32 * MF0,
+                        64 * ng + 2 * j, lane, sx, sw, Y, ACC);
+    };
+    if (KG == 1 || grp == 0)
+        finish(std::integral_constant<int, 0>{});
+    else
+        finish(std::integral_constant<int, KG - 1>{});
 }
 
 // ------------------------------------------------------------------------------------
@@ -1188,15 +1251,18 @@ static int launch_pipe(const Args &a)
     return LQ_OK;
 }
 
-// Grid-level split of K for the duo kernel: used when the output alone gives fewer tiles
-// than CUs; slices hold at least 512 k.
+// Grid-level split of K for the duo kernel with two k groups per block (grids of at most
+// one block per CU).  Measured: a slice costs about as much in partial-tile exchange
+// (128 KiB per tile and slice, added up by the last block) as half a 256-k unit costs in
+// matrix work, which puts the best slice count near 0.75 * sqrt(K / 256); more slices than
+// CUs per tile would only queue up.
 static int duo_split(int M, int N, int K)
 {
     const int tiles = ((M + 127) / 128) * ((N + 255) / 256);
-    if (tiles >= 128 || tiles > kMaxTicketGroups) return 1;
-    // measured: the exchange of 128 KiB partial tiles is expensive, so split sparingly
-    int s = tiles >= 40 ? 2 : 4;
-    s = std::min(s, K / 512);
+    if (tiles > 128 || tiles > kMaxTicketGroups) return 1;
+    const int units = K / 256;
+    int s = (int)(0.75 * std::sqrt((double)units) + 0.5);
+    s = std::min(std::min(s, 256 / tiles), std::min(units / 2, 8));
     return std::max(1, s);
 }
 static size_t duo_ws_bytes(int M, int N, int S)
@@ -1206,14 +1272,13 @@ static size_t duo_ws_bytes(int M, int N, int S)
     return tiles * S * 4 * 32 * 256 * sizeof(int32_t);
 }
 
-template <int SPLIT>
-static int launch_duo(const Args &a)
+template <int SPLIT, int KG>
+static int launch_duo_as(const Args &a, int S)
 {
     constexpr int WM = 128;
     const int blocks_n = (a.N + 255) / 256, blocks_m = (a.M + WM - 1) / WM;
-    int S = SPLIT ? SPLIT : duo_split(a.M, a.N, a.K);
-    S = std::min(S, a.K / 256);
-    if (blocks_n * blocks_m > kMaxTicketGroups) S = 1;
+    S = std::min(S, a.K / (256 * KG));  // every k group of every slice gets at least one unit
+    if (blocks_n * blocks_m > kMaxTicketGroups || S < 1) S = 1;
     size_t need = duo_ws_bytes(a.M, a.N, S);
     if (need > 0 && (!a.ws || a.ws_bytes < need)) {
         if (SPLIT)
@@ -1222,16 +1287,33 @@ static int launch_duo(const Args &a)
         S = 1;
         need = 0;
     }
-    const size_t lds_bytes = 2 * (size_t)WM * kTilePitch;
-    const dim3 grid((unsigned)(blocks_n * blocks_m), (unsigned)S), block(256);
+    // KG groups x 2 stages of X; the in-block reduction reuses them and needs 64 KiB
+    const size_t lds_bytes = KG == 1 ? 2 * (size_t)WM * kTilePitch
+                                     : std::max<size_t>(KG * 2 * (size_t)WM * kTilePitch, 64 * 1024);
+    const dim3 grid((unsigned)(blocks_n * blocks_m), (unsigned)S), block(256 * KG);
     int32_t *partials = static_cast<int32_t *>(a.ws);
-    if (a.group == 128)
-        hipLaunchKernelGGL(w4a8_duo_kernel<true>, grid, block, lds_bytes, a.stream, a.M, a.N, a.K, a.X, a.sx,
-                           a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n, partials);
-    else
-        hipLaunchKernelGGL(w4a8_duo_kernel<false>, grid, block, lds_bytes, a.stream, a.M, a.N, a.K, a.X, a.sx,
-                           a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n, partials);
+    if (a.group == 128) {
+        if (int rc = allow_lds(w4a8_duo_kernel<true, KG>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_duo_kernel<true, KG>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K, a.X,
+                           a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n, partials);
+    } else {
+        if (int rc = allow_lds(w4a8_duo_kernel<false, KG>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_duo_kernel<false, KG>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K, a.X,
+                           a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n, partials);
+    }
     return LQ_OK;
+}
+
+// KGSEL: 0 = choose from the grid size, 1 / 2 = fixed number of k groups per block.
+template <int SPLIT, int KGSEL>
+static int launch_duo(const Args &a)
+{
+    const int tiles = ((a.M + 127) / 128) * ((a.N + 255) / 256);
+    int kg = KGSEL, S = SPLIT;
+    if (!kg) kg = (tiles * std::max(1, SPLIT) <= 256 && a.K >= 512) ? 2 : 1;
+    if (a.K < 512) kg = 1;
+    if (!S) S = kg == 2 ? duo_split(a.M, a.N, a.K) : 1;
+    return kg == 2 ? launch_duo_as<SPLIT, 2>(a, S) : launch_duo_as<SPLIT, 1>(a, S);
 }
 
 struct Variant {
@@ -1260,11 +1342,17 @@ static const Variant kVariants[] = {
     {"tile_m256", &launch_tile<8>, 0, 1, 1},
     {"pipe_m128", &launch_pipe<4>, 0, 1, 1},
     {"pipe_m256", &launch_pipe<8>, 0, 1, 1},
-    {"duo_m128", &launch_duo<0>, 0, 1, 1},
-    {"duo_m128_s1", &launch_duo<1>, 0, 1, 1},
-    {"duo_m128_s2", &launch_duo<2>, 0, 1, 1},
-    {"duo_m128_s4", &launch_duo<4>, 0, 1, 1},
-    {"duo_m128_s8", &launch_duo<8>, 0, 1, 1},
+    {"duo_m128", &launch_duo<0, 0>, 0, 1, 1},
+    {"duo_m128_s1", &launch_duo<1, 1>, 0, 1, 1},
+    {"duo_m128_s2", &launch_duo<2, 1>, 0, 1, 1},
+    {"duo_m128_s4", &launch_duo<4, 1>, 0, 1, 1},
+    {"duo_m128_s8", &launch_duo<8, 1>, 0, 1, 1},
+    {"duo_m128_g2", &launch_duo<0, 2>, 0, 1, 1},
+    {"duo_m128_g2_s1", &launch_duo<1, 2>, 0, 1, 1},
+    {"duo_m128_g2_s2", &launch_duo<2, 2>, 0, 1, 1},
+    {"duo_m128_g2_s3", &launch_duo<3, 2>, 0, 1, 1},
+    {"duo_m128_g2_s4", &launch_duo<4, 2>, 0, 1, 1},
+    {"duo_m128_g2_s6", &launch_duo<6, 2>, 0, 1, 1},
 #ifdef LQ_ABLATE
     {"abl_s16_noX", &launch_stream16<2, 4, 1, 1>, 16, 2, 1},
     {"abl_s16_noP", &launch_stream16<2, 4, 1, 2>, 16, 2, 1},
@@ -1299,15 +1387,15 @@ static int find_variant(const char *name)
     return -1;
 }
 
-// Shape -> kernel.  Decode-sized batches stream the weights with in-block split-K sized
-// so that the grid fills the 256 CUs; larger batches use the LDS-tiled kernel with the
-// largest row tile that still gives every CU a block.
+// Shape -> kernel.  Up to 32 rows the weights are streamed once with X fragments in
+// registers (16-row MFMA shape up to 16 rows); anything larger runs the 128 x 256 tiles of
+// the duo kernel, whose launcher adds in-block and grid-level split-K while the output
+// alone gives at most one tile per CU.
 static int select_variant(int M, int N, int K)
 {
     (void)K;
     if (M <= 16) return find_variant(N / 64 >= 384 ? "stream16_f2_w4" : "stream16_f2_w8");
     if (M <= 32) return find_variant("stream_f2_w8");
-    if (M <= 64) return find_variant("tile_m64");
     return find_variant("duo_m128");
 }
 
