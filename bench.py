@@ -30,6 +30,14 @@ import numpy as np  # noqa: E402
 PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, published
 PEAK_INT8_TOPS = 5033.0   # dense INT8 MFMA: 256 CU x 4 SIMD x 2048 ops/clk x 2.4 GHz
 ROTATE_BYTES = 512 << 20
+# HBM-side bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE counter runs of this file
+# (scaled by what the same counters read for a plain 1 GiB copy, --copy-ref); the commands
+# and raw figures are in profiles/.  Counters cannot be read from inside a timed run, so
+# the figure is carried here per (workload, kernel) and is null for anything not profiled.
+MEASURED_TRAFFIC_BYTES = {
+    ("prefill_M4096_N8192_K8192", "duo_m128"): 477.6e6,
+    ("l70b_up_M16_N28672_K8192", "stream16_f2_w4"): 123.3e6,
+}
 
 
 def algorithmic_bytes(M, N, K, g):
@@ -210,8 +218,9 @@ def main():
         roof = {"bound": "hbm", "achieved": round(byt / (ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
                 "unit": "GB/s"}
     roof["frac"] = round(roof["achieved"] / roof["peak"], 4)
-    roof["traffic"] = None
     roof["kernel"] = hp["variant"]
+    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((head.name, hp["variant"]))
+    roof["algorithmic_bytes"] = byt
 
     out = {
         "metric": "W4A8 GEMM TOPS and % of HBM / int8-MFMA roofline vs M (1..4096)",
@@ -243,7 +252,9 @@ def main():
         out["memory_bound_points"] = extra
         hb = extra[-1]
         out["roofline_hbm"] = {"bound": "hbm", "achieved": hb["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                               "frac": round(hb["gbs"] / PEAK_HBM_GBS, 4), "traffic": None,
+                               "frac": round(hb["gbs"] / PEAK_HBM_GBS, 4),
+                               "traffic": MEASURED_TRAFFIC_BYTES.get((shp.name, hb["variant"])),
+                               "algorithmic_bytes": algorithmic_bytes(hb["M"], hb["N"], hb["K"], hb["group"]),
                                "kernel": hb["variant"],
                                "workload": f"l70b_up M=16 N={hb['N']} K={hb['K']} group {hb['group']}"}
 
