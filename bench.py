@@ -1,16 +1,23 @@
 #!/usr/bin/env python3
 """Benchmark of the LiquidQuant W4A8 GEMM on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-curve] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+                    [--no-curve] [--no-configs] [--no-calib] [--no-cpu]
 
 A step is one pass of the whole hot path (load packed W4 + group parameters, unpack,
 LiquidQuant dequantisation, INT8 MFMA, per-token x per-channel scaling, FP16 store) over
 one batch of synthetic activations, with every input already resident in HBM.  Weights
 rotate through enough distinct copies (> 512 MB in total) that the 256 MB Infinity Cache
 cannot serve them.  The headline workload is the compute-bound end of the metric's M
-range (prefill, M=4096, N=K=8192, group 64); the same JSON line carries the TOPS-vs-M
-curve (M = 1..4096), the HBM-bound point (70B up-projection at M=16), the roofline of
-the dominant kernel and the CPU oracle timed on a bounded sample.
+range (prefill, M=4096, N=K=8192, group 64).  The same JSON line carries
+  * roofline / roofline_hbm: the dominant kernel of the headline and of the HBM-bound
+    point (70B up-projection at M=16) against the nominal peaks;
+  * calibration: what this GPU reaches on a pure streaming read and on a register-only
+    INT8 MFMA loop (constant and random operands);
+  * curve_N8192_K8192: TOPS and fraction of the roofline for M = 1..4096;
+  * configs: every workload row (decode, 7B MLP, 70B layers, prefill sweep), median of five
+    batches, with rotating weights and with one weight buffer (cache-warm) side by side;
+  * cpu_baseline: the CPU oracle timed on a bounded sample.
 """
 from __future__ import annotations
 
@@ -18,6 +25,7 @@ import argparse
 import json
 import math
 import os
+import statistics
 import sys
 import time
 
@@ -74,8 +82,8 @@ class DeviceProblem:
             self.dsx[M] = torch.from_numpy(sx).to(dev)
             self.dY[M] = torch.empty((M, N), dtype=torch.float16, device=dev)
 
-    def launch(self, M, i, api, stream, variant=-1):
-        c = i % self.copies
+    def launch(self, M, i, api, stream, variant=-1, rotate=True):
+        c = i % self.copies if rotate else 0
         s = self.shape
         if variant < 0:
             api.w4a8_gemm(self.dX[M], self.dsx[M], self.d_packed[c], self.d_gparams[c], self.d_w_scales,
@@ -86,21 +94,21 @@ class DeviceProblem:
                                   stream=stream.cuda_stream)
 
 
-def time_steps(prob, M, steps, warmup, torch, api, stream, variant=-1, graph=False):
-    """Average milliseconds per launch over `steps` back-to-back launches (HIP events on
-    the launch stream), after `warmup` untimed ones.  With graph=True the `steps` launches
-    are captured once into a HIP graph and replayed, which takes the Python/ctypes launch
-    cost (about 9 us per call) out of the measurement of kernels shorter than that."""
+def time_launches(launch, steps, warmup, torch, stream, graph=False):
+    """Average milliseconds per launch over `steps` back-to-back calls of launch(i) (HIP
+    events on the launch stream), after `warmup` untimed ones.  With graph=True the `steps`
+    launches are captured once into a HIP graph and replayed, which takes the Python/ctypes
+    launch cost (about 9 us per call) out of the measurement of kernels shorter than that."""
     with torch.cuda.stream(stream):
         for i in range(warmup):
-            prob.launch(M, i, api, stream, variant)
+            launch(i)
         stream.synchronize()
         g = None
         if graph:
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=stream):
                 for i in range(steps):
-                    prob.launch(M, warmup + i, api, stream, variant)
+                    launch(warmup + i)
             g.replay()  # untimed first replay
             stream.synchronize()
         e0 = torch.cuda.Event(enable_timing=True)
@@ -111,25 +119,79 @@ def time_steps(prob, M, steps, warmup, torch, api, stream, variant=-1, graph=Fal
             g.replay()
         else:
             for i in range(steps):
-                prob.launch(M, warmup + i, api, stream, variant)
+                launch(warmup + i)
         e1.record(stream)
         stream.synchronize()
         torch.cuda.synchronize()
     return e0.elapsed_time(e1) / steps
 
 
-def point(prob, M, ms, api):
-    s = prob.shape
+def time_steps(prob, M, steps, warmup, torch, api, stream, variant=-1, graph=False, rotate=True):
+    return time_launches(lambda i: prob.launch(M, i, api, stream, variant, rotate), steps, warmup, torch,
+                         stream, graph)
+
+
+def is_tiny(shape, M):
+    """Kernels expected to run shorter than a Python launch: timed inside a HIP graph."""
+    return shape.N * shape.K < (1 << 26) and M <= 32
+
+
+def time_median(prob, M, torch, api, stream, rotate=True, batches=5, est_ms=None):
+    """Median over `batches` of the per-launch average of a batch of back-to-back launches."""
+    graph = is_tiny(prob.shape, M)
+    if est_ms is None:
+        est_ms = time_steps(prob, M, 10, 3, torch, api, stream, graph=False, rotate=rotate)
+    steps = max(20, min(200, int(8.0 / max(est_ms, 1e-3))))
+    ts = [time_steps(prob, M, steps, 3 if b == 0 else 0, torch, api, stream, graph=graph, rotate=rotate)
+          for b in range(batches)]
+    return statistics.median(ts)
+
+
+def point(shape, M, ms, api, calib=None, ms_same=None):
     t = ms * 1e-3
-    ops, byt = algorithmic_ops(M, s.N, s.K), algorithmic_bytes(M, s.N, s.K, s.group)
+    ops, byt = algorithmic_ops(M, shape.N, shape.K), algorithmic_bytes(M, shape.N, shape.K, shape.group)
     t_mem, t_mma = byt / (PEAK_HBM_GBS * 1e9), ops / (PEAK_INT8_TOPS * 1e12)
-    return {
-        "M": M, "N": s.N, "K": s.K, "group": s.group, "us": round(ms * 1e3, 3),
+    p = {
+        "M": M, "N": shape.N, "K": shape.K, "group": shape.group, "us": round(ms * 1e3, 3),
         "tops": round(ops / t / 1e12, 3), "gbs": round(byt / t / 1e9, 1),
         "bound": "hbm" if t_mem >= t_mma else "mfma",
         "frac_of_roofline": round(max(t_mem, t_mma) / t, 4),
-        "variant": api.w4a8_variant_name(api.w4a8_select_variant(M, s.N, s.K, s.group)),
+        "variant": api.w4a8_variant_name(api.w4a8_select_variant(M, shape.N, shape.K, shape.group)),
     }
+    if ms_same is not None:
+        p["us_same_buffer"] = round(ms_same * 1e3, 3)
+    if calib:
+        # the same roofline with this GPU's measured streaming rate and random-operand MFMA rate
+        t_meas = max(byt / (calib["stream_read_gbs"] * 1e9), ops / (calib["mfma_i8_random_tops"] * 1e12))
+        p["frac_of_measured"] = round(t_meas / t, 4)
+    return p
+
+
+def calibrate(torch, api, stream):
+    """Pure streaming read (512 MiB per launch, and 120 MB slices of it in turn) and the
+    register-only MFMA loop, each as the median of five batches."""
+    buf = torch.randint(0, 256, (ROTATE_BYTES + (96 << 20),), dtype=torch.uint8, device="cuda:0")
+    big = buf[:ROTATE_BYTES]
+    out = {}
+
+    def med(launch, steps):
+        return statistics.median(time_launches(launch, steps, 2, torch, stream) for _ in range(5))
+
+    ms = med(lambda i: api.w4a8_calib_stream_read(big, stream.cuda_stream), 10)
+    out["stream_read_gbs"] = round(ROTATE_BYTES / (ms * 1e-3) / 1e9, 1)
+    slice_bytes = 120 << 20
+    slices = [buf[j * slice_bytes:(j + 1) * slice_bytes] for j in range(buf.numel() // slice_bytes)]
+    ms = med(lambda i: api.w4a8_calib_stream_read(slices[i % len(slices)], stream.cuda_stream), 50)
+    out["stream_read_gbs_120MiB_launches"] = round(slice_bytes / (ms * 1e-3) / 1e9, 1)
+    del slices, big, buf
+    torch.cuda.empty_cache()
+    for key, rnd in (("mfma_i8_constant_tops", False), ("mfma_i8_random_tops", True)):
+        ops = []
+        ms = med(lambda i: ops.append(api.w4a8_calib_mfma_i8(500, rnd, stream.cuda_stream)), 10)
+        out[key] = round(ops[0] / (ms * 1e-3) / 1e12, 1)
+    out["note"] = ("read: 16-byte non-temporal loads over 512 MiB per launch; mfma: 64 x 500 "
+                   "v_mfma_i32_32x32x32_i8 per wave, two waves per SIMD, register operands")
+    return out
 
 
 def cpu_baseline(prob, M, budget_s=15.0):
@@ -170,6 +232,8 @@ def main():
     ap.add_argument("--workload", default="prefill_M4096_N8192_K8192")
     ap.add_argument("--variant", type=int, default=-1, help="force a kernel variant (tuning)")
     ap.add_argument("--no-curve", action="store_true")
+    ap.add_argument("--no-configs", action="store_true")
+    ap.add_argument("--no-calib", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--copy-ref", action="store_true",
                     help="only run a plain device-to-device copy of 1 GiB five times (reference "
@@ -199,7 +263,8 @@ def main():
 
     head = WL.by_name(args.workload)
     curve_Ms = [] if args.no_curve else [1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096]
-    Ms = sorted(set(curve_Ms + [head.M]))
+    family = [s for s in WL.ALL_SHAPES if (s.N, s.K, s.group, s.seed) == (head.N, head.K, head.group, head.seed)]
+    Ms = sorted(set(curve_Ms + [head.M] + ([] if args.no_configs else [s.M for s in family])))
     prob = DeviceProblem(head, Ms, torch, api, WL)
 
     # Untimed pre-warm of about 0.2 s so that the timed steps run at settled clocks, then the
@@ -208,7 +273,7 @@ def main():
     while time.perf_counter() < t_end:
         time_steps(prob, head.M, 10, 0, torch, api, stream, args.variant)
     ms = time_steps(prob, head.M, args.steps, args.warmup, torch, api, stream, args.variant)
-    hp = point(prob, head.M, ms, api)
+    hp = point(head, head.M, ms, api)
     ops = algorithmic_ops(head.M, head.N, head.K)
     byt = algorithmic_bytes(head.M, head.N, head.K, head.group)
     if hp["bound"] == "mfma":
@@ -221,6 +286,7 @@ def main():
     roof["kernel"] = hp["variant"]
     roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((head.name, hp["variant"]))
     roof["algorithmic_bytes"] = byt
+    roof["algorithmic_ops"] = ops
 
     out = {
         "metric": "W4A8 GEMM TOPS and % of HBM / int8-MFMA roofline vs M (1..4096)",
@@ -232,31 +298,55 @@ def main():
         "roofline": roof,
     }
 
+    calib = None
+    if not args.no_calib:
+        calib = calibrate(torch, api, stream)
+        out["calibration"] = calib
+        if roof["bound"] == "mfma":
+            roof["frac_of_measured_random_operand_mfma"] = round(roof["achieved"] / calib["mfma_i8_random_tops"], 4)
+        else:
+            roof["frac_of_measured_stream_read"] = round(roof["achieved"] / calib["stream_read_gbs"], 4)
+
     if not args.no_curve:
-        curve = []
-        for M in curve_Ms:
-            steps = max(20, min(200, int(0.05 / max(1e-6, 1e-3 * ms * M / head.M + 5e-6))))
-            curve.append(point(prob, M, time_steps(prob, M, steps, 5, torch, api, stream, graph=M <= 8), api))
-        out["curve_N8192_K8192"] = curve
-        del prob.d_packed[1:], prob.d_gparams[1:]
-        torch.cuda.empty_cache()
-        # decode shapes (N = K = 4096) and the HBM-bound 70B point
-        extra = []
-        for name_Ms in ((WL.DECODE, (1, 4, 16)), (WL.LAYERS_70B[:1], (16,))):
-            shp = name_Ms[0][0]
-            p2 = DeviceProblem(shp, list(name_Ms[1]), torch, api, WL)
-            for M in name_Ms[1]:
-                extra.append(point(p2, M, time_steps(p2, M, 200, 20, torch, api, stream, graph=shp.N * shp.K < (1 << 26)), api))
-            del p2
-            torch.cuda.empty_cache()
-        out["memory_bound_points"] = extra
-        hb = extra[-1]
-        out["roofline_hbm"] = {"bound": "hbm", "achieved": hb["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                               "frac": round(hb["gbs"] / PEAK_HBM_GBS, 4),
-                               "traffic": MEASURED_TRAFFIC_BYTES.get((shp.name, hb["variant"])),
-                               "algorithmic_bytes": algorithmic_bytes(hb["M"], hb["N"], hb["K"], hb["group"]),
-                               "kernel": hb["variant"],
-                               "workload": f"l70b_up M=16 N={hb['N']} K={hb['K']} group {hb['group']}"}
+        out["curve_N8192_K8192" if (head.N, head.K) == (8192, 8192) else f"curve_N{head.N}_K{head.K}"] = [
+            point(head, M, time_median(prob, M, torch, api, stream, batches=3), api, calib) for M in curve_Ms]
+
+    if not args.no_configs:
+        # every workload row: rotating weights (HBM-cold) and one weight buffer side by side
+        rows = []
+        groups = []
+        for s in WL.DECODE + WL.MLP_7B + WL.LAYERS_70B + WL.PREFILL:
+            key = (s.N, s.K, s.group, s.seed)
+            if not groups or groups[-1][0] != key:
+                groups.append((key, []))
+            groups[-1][1].append(s)
+        for key, shapes in groups:
+            if key == (head.N, head.K, head.group, head.seed):
+                p2 = prob
+            else:
+                p2 = DeviceProblem(shapes[0], [s.M for s in shapes], torch, api, WL)
+            for s in shapes:
+                if s.M not in p2.dX:
+                    continue
+                cold = time_median(p2, s.M, torch, api, stream, rotate=True)
+                warm = time_median(p2, s.M, torch, api, stream, rotate=False, est_ms=cold)
+                r = point(s, s.M, cold, api, calib, ms_same=warm)
+                r["workload"] = s.name
+                rows.append(r)
+            if p2 is not prob:
+                del p2
+                torch.cuda.empty_cache()
+        out["configs"] = rows
+        hb = next((r for r in rows if r["workload"] == "l70b_up_M16_N28672_K8192"), None)
+        if hb:
+            out["roofline_hbm"] = {
+                "bound": "hbm", "achieved": hb["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(hb["gbs"] / PEAK_HBM_GBS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get((hb["workload"], hb["variant"])),
+                "algorithmic_bytes": algorithmic_bytes(hb["M"], hb["N"], hb["K"], hb["group"]),
+                "kernel": hb["variant"], "workload": hb["workload"]}
+            if calib:
+                out["roofline_hbm"]["frac_of_measured_stream_read"] = round(hb["gbs"] / calib["stream_read_gbs"], 4)
 
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(prob, head.M)

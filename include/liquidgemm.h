@@ -138,6 +138,23 @@ int w4a8_select_variant(int M, int N, int K, int group); /* the dispatcher's cho
 int w4a8_dequant_dump(const void *W_packed, const uint8_t *gparams, int N, int K, int group,
                       int8_t *Wd, void *hip_stream);
 
+/* ------------------------------------------------------------------------------------
+ * Calibration (measurement support): what this GPU delivers on the two resources of the
+ * cost model of Sec. 3.2 with nothing else in the way.  Both only enqueue a kernel on
+ * `hip_stream`; the caller times them.
+ * ------------------------------------------------------------------------------------ */
+
+/* T_LD: read `bytes` (rounded down to 16) of device memory at `buf` once, with the same
+ * 16-byte non-temporal loads the GEMM kernels use for W; nothing of size is written. */
+int w4a8_calib_stream_read(const void *buf, size_t bytes, void *hip_stream);
+
+/* T_MMA: `iters` x 64 back-to-back INT8 32x32x32 MFMAs per wave on register operands, two
+ * waves per SIMD on every CU.  random_operands = 0: constant operands; 1: pseudo-random
+ * bytes that change from one MFMA to the next (the multipliers of this chip draw more power
+ * on such data and clock lower).  *ops (host, may be NULL) receives the operation count
+ * (2 per multiply-accumulate) of the launch. */
+int w4a8_calib_mfma_i8(int iters, int random_operands, double *ops, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -71,6 +71,10 @@ def lib() -> ctypes.CDLL:
     L.w4a8_select_variant.argtypes = [i, i, i, i]
     L.w4a8_dequant_dump.restype = i
     L.w4a8_dequant_dump.argtypes = [vp, vp, i, i, i, vp, vp]
+    L.w4a8_calib_stream_read.restype = i
+    L.w4a8_calib_stream_read.argtypes = [vp, sz, vp]
+    L.w4a8_calib_mfma_i8.restype = i
+    L.w4a8_calib_mfma_i8.argtypes = [i, i, ctypes.POINTER(ctypes.c_double), vp]
     _lib = L
     return L
 
@@ -286,3 +290,19 @@ def w4a8_dequant_dump(W_packed, gparams, N: int, K: int, group: int, out=None, s
                                    _dev(gparams, torch.uint8, (gb,), "gparams"), N, K, group,
                                    _dev(out, torch.int8, (N, K), "out"), _stream(stream)))
     return out
+
+
+def w4a8_calib_stream_read(buf, stream=None) -> int:
+    """Enqueue one pure read of the whole uint8 device tensor `buf`; returns the bytes read."""
+    import torch
+
+    n = buf.numel() // 16 * 16
+    _check(lib().w4a8_calib_stream_read(_dev(buf, torch.uint8, name="buf"), n, _stream(stream)))
+    return n
+
+
+def w4a8_calib_mfma_i8(iters: int, random_operands: bool, stream=None) -> float:
+    """Enqueue the register-only INT8 MFMA loop; returns the operation count of the launch."""
+    ops = ctypes.c_double(0.0)
+    _check(lib().w4a8_calib_mfma_i8(iters, 1 if random_operands else 0, ctypes.byref(ops), _stream(stream)))
+    return ops.value
