@@ -23,7 +23,10 @@ Pinning status (tests/test_oracle_pins.py):
                      pinned on exactly representable cases only.  The exact FP16
                      rounding of the product is not fixed by the paper:
                      "parity unpinned" beyond the 1-ulp tolerance.
-  activation side    not part of the oracle (inputs arrive already as INT8).
+  quantize_activations  pinned: hand example with a tie (round half to even), the
+                     extreme element maps to +-127, zero row, exact power-of-two scale
+                     invariance, reconstruction error <= s_x / 2, smooth divide
+                     against exact rational arithmetic.
 
 Readings of the paper taken here (the paper is silent or ambiguous on them):
   * s_u8 is an integer: round(R / 15) with R = max - min of the group, computed
@@ -32,6 +35,10 @@ Readings of the paper taken here (the paper is silent or ambiguous on them):
   * a constant group (R = 0) takes s_u8 = 1.
   * codes are rounded half-up in integers, (2 q_u + s) // (2 s), and clamped to
     15 (s rounded down can otherwise give 16 or more).
+  * activations (Sec. 6 "Serving System": dynamic per-token INT8 after dividing by the
+    smooth scale) are quantized symmetrically per token over the full INT8 range:
+    x' = X / smooth in FP32, s_x = max_k |x'| / 127 in FP32 (1 for an all-zero token),
+    Q = clamp(rint(x' / s_x), -127, 127).
   * level 1 is symmetric per output channel with the protective range:
     s_w = amax / 119 in FP32, Q = clamp(rint(W / s_w), -119, 119); an all-zero
     channel takes s_w = 1.
@@ -42,6 +49,27 @@ import numpy as np
 
 Q_PROTECT = 119  # protective INT8 range of Sec. 4 ("Quantization")
 U4_MAX = 15
+
+
+# --------------------------------------------------------------------------
+# Activations: FP16 -> INT8, per token  (Sec. 6 "Serving System")
+# --------------------------------------------------------------------------
+def quantize_activations(X, smooth=None):
+    """Dynamic per-token symmetric INT8 quantization after the smooth divide.
+
+    X: [M, K] FP16 values (any float dtype holding them); smooth: [K] positive FP32
+    smooth scales or None.  The arithmetic is FP32 because its roundings decide
+    integers and the library takes the same decisions in FP32: every operation below is
+    one correctly rounded IEEE binary32 operation.  Returns (Q_i8 [M, K] int8,
+    s_x [M] float32).
+    """
+    Xs = np.asarray(X, dtype=np.float32)
+    if smooth is not None:
+        Xs = Xs / np.asarray(smooth, dtype=np.float32)[None, :]
+    amax = np.max(np.abs(Xs), axis=1).astype(np.float32) if Xs.shape[1] else np.zeros(Xs.shape[0], np.float32)
+    s_x = np.where(amax > 0, amax / np.float32(127), np.float32(1.0)).astype(np.float32)
+    q = np.rint(Xs / s_x[:, None])  # FP32 quotient, round half to even
+    return np.clip(q, -127, 127).astype(np.int8), s_x
 
 
 # --------------------------------------------------------------------------

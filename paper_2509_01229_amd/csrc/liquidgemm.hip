@@ -85,9 +85,18 @@ __device__ long long g_dbg_stamps[4 * 16384];
         const unsigned w_ = (blockIdx.y * gridDim.x + blockIdx.x) * NW + wave;                  \
         if (lane == 0 && w_ < 16384) g_dbg_stamps[4 * w_ + (slot)] = wall_clock64();            \
     } while (0)
+// same for the duo kernel: 8 slots per wave
+#define LQ_DSTAMP(slot)                                                                         \
+    do {                                                                                        \
+        const unsigned w_ = (blockIdx.y * gridDim.x + blockIdx.x) * (4 * KG) + (threadIdx.x >> 6); \
+        if ((threadIdx.x & 63) == 0 && w_ < 8192) g_dbg_stamps[8 * w_ + (slot)] = wall_clock64(); \
+    } while (0)
 #else
 #define LQ_STAMP(slot) \
     do {               \
+    } while (0)
+#define LQ_DSTAMP(slot) \
+    do {                \
     } while (0)
 #endif
 
@@ -880,6 +889,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
     const int stages_total = K >> 7;
     const int chunks_per_tile = K >> 6;
 
+    LQ_DSTAMP(0);
     v16i acc[MF][2];
 #pragma unroll
     for (int mf = 0; mf < MF; ++mf)
@@ -1003,10 +1013,12 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
     read_a(0, 0, 0, af[0]);
     __builtin_amdgcn_sched_barrier(0);
 
+    LQ_DSTAMP(1);
     for (int s = 0; s < stages; s += 2) {
         stage(s, wr[0], pr[0], wr[1], pr[1], 0);
         stage(s + 1, wr[1], pr[1], wr[0], pr[0], 1);
     }
+    LQ_DSTAMP(2);
 
     // What is left is written once per k group with compile-time fragment indices: group G
     // finishes the MFK = MF / KG row fragments starting at MF0 = G * MFK.
@@ -1040,6 +1052,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
                 if (t == 0) lds_barrier();
             }
         }
+        LQ_DSTAMP(3);
         if (S > 1) {
             // Grid-level split-K (same protocol as the stream kernels): every block publishes its
             // INT32 partial tile with device-scope write-through stores, takes a ticket, and the
@@ -1049,8 +1062,11 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
             const size_t tile = blockIdx.x;
             const int bw = G * 4 + wave;
             int32_t *mine = partials + (((tile * S + ks) * (4 * KG) + bw) * EPW) * 256 + lane * 4;
+            // row fragments that lie wholly past M are neither published nor read back
+            auto live = [&](int i) { return m0 + 32 * (MF0 + i) < M; };
 #pragma unroll
-            for (int i = 0; i < MFK; ++i)
+            for (int i = 0; i < MFK; ++i) {
+                if (!live(i)) continue;
 #pragma unroll
                 for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -1059,7 +1075,9 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
                                           acc[MF0 + i][t][4 * q + 2], acc[MF0 + i][t][4 * q + 3]};
                         store_sc1_x4(mine + ((i * 2 + t) * 4 + q) * 256, v);
                     }
+            }
             wait_vmcnt0();
+            LQ_DSTAMP(4);
             __syncthreads();
             if (threadIdx.x == 0) {
                 const unsigned tk = __hip_atomic_fetch_add(&g_splitk_tickets[tile], 1u, __ATOMIC_RELAXED,
@@ -1067,30 +1085,46 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
                 s_last = (tk == (unsigned)(S - 1));
             }
             __syncthreads();
+            LQ_DSTAMP(5);
             if (!s_last) return;
+            // 16 loads of 16 bytes per lane are in flight before the first is waited for: the
+            // latency of these device-scope reads, not their volume, is what this tail costs.
             for (int k2 = 0; k2 < S; ++k2) {
                 if (k2 == ks) continue;
                 const int32_t *other = partials + (((tile * S + k2) * (4 * KG) + bw) * EPW) * 256 + lane * 4;
 #pragma unroll
-                for (int i = 0; i < MFK; ++i)
+                for (int i0 = 0; i0 < MFK; i0 += 2) {
+                    v4i v[2][2][4];
 #pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        v4i v[4];
+                    for (int i = 0; i < 2; ++i)
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) v[q] = load_sc1_x4(other + ((i * 2 + t) * 4 + q) * 256);
-                        wait_vmcnt0(v[0], v[1], v[2], v[3]);
+                        for (int t = 0; t < 2; ++t)
 #pragma unroll
-                        for (int q = 0; q < 4; ++q)
+                            for (int q = 0; q < 4; ++q)
+                                v[i][t][q] = live(i0 + i) ? load_sc1_x4(other + (((i0 + i) * 2 + t) * 4 + q) * 256)
+                                                          : v4i{0, 0, 0, 0};
+                    wait_vmcnt0(v[0][0][0], v[0][0][1], v[0][0][2], v[0][0][3]);
+                    wait_vmcnt0(v[0][1][0], v[0][1][1], v[0][1][2], v[0][1][3]);
+                    wait_vmcnt0(v[1][0][0], v[1][0][1], v[1][0][2], v[1][0][3]);
+                    wait_vmcnt0(v[1][1][0], v[1][1][1], v[1][1][2], v[1][1][3]);
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) acc[MF0 + i][t][4 * q + e] += v[q][e];
-                    }
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int t = 0; t < 2; ++t)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) acc[MF0 + i0 + i][t][4 * q + e] += v[i][t][q][e];
+                }
             }
+            LQ_DSTAMP(6);
             if (threadIdx.x == 0)
                 __hip_atomic_store(&g_splitk_tickets[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (!active) return;
         store_tile<MFK>(*reinterpret_cast<const v16i(*)[MFK][2]>(&acc[MF0]), M, N, m0 + 32 * MF0,
                         64 * ng + 2 * j, lane, sx, sw, Y, ACC);
+        LQ_DSTAMP(7);
     };
     if (KG == 1 || grp == 0)
         finish(std::integral_constant<int, 0>{});

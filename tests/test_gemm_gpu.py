@@ -212,3 +212,19 @@ def test_workspace_is_optional_for_the_dispatcher():
                 api.w4a8_gemm_variant(v, dX, torch.from_numpy(s_x).cuda(), P.d_packed, P.d_gparams,
                                       P.d_w_scales, N, K, g, workspace=tiny)
             assert e.value.code == -3
+
+
+def test_calibration_kernels_run():
+    import torch
+
+    _say("calibration kernels")
+    buf = torch.zeros((1 << 20) + 8, dtype=torch.uint8, device="cuda")
+    assert api.w4a8_calib_stream_read(buf[: 1 << 20]) == 1 << 20
+    ops = api.w4a8_calib_mfma_i8(2, True)
+    assert ops == 512 * 4 * 2 * 64 * 2.0 * 32 ** 3
+    assert api.w4a8_calib_mfma_i8(1, False) == ops / 2
+    torch.cuda.synchronize()
+    with pytest.raises(api.LiquidGemmError):
+        api.w4a8_calib_mfma_i8(0, True)
+    with pytest.raises(api.LiquidGemmError):
+        api.w4a8_calib_stream_read(buf[8:])  # not 16-byte aligned

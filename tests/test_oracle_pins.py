@@ -310,3 +310,70 @@ def test_planted_mistakes_are_caught(all_groups):
         assert not np.array_equal(bad, good)
     # floor instead of round for s would break the worked example (223/15 -> 14)
     assert 223 // 15 != 15
+
+
+# ---------------------------------------------------------------------------------------
+# Activation quantization (Sec. 6: dynamic per-token INT8 after the smooth divide)
+# ---------------------------------------------------------------------------------------
+def test_activation_quant_hand_example_with_tie():
+    # amax = 1 -> s = 1/127; -0.5 -> -63.5 -> -64 (half to even), 0.25 -> 31.75 -> 32
+    X = np.array([[1.0, -0.5, 0.25, 0.0], [0.0, 0.0, 0.0, 0.0], [-3.0, 3.0, 1.5, -1.5]], dtype=np.float16)
+    q, s = O.quantize_activations(X)
+    assert s.dtype == np.float32 and q.dtype == np.int8
+    assert s[0] == np.float32(1.0) / np.float32(127) and s[1] == np.float32(1.0)
+    assert q[0].tolist() == [127, -64, 32, 0]
+    assert q[1].tolist() == [0, 0, 0, 0]
+    # 1.5 / (3/127) = 63.5 -> 64 (half to even)
+    assert q[2].tolist() == [-127, 127, 64, -64]
+
+
+def test_activation_quant_properties():
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((37, 512)).astype(np.float16)
+    X[:, 7] *= 20
+    q, s = O.quantize_activations(X)
+    Xf = X.astype(np.float64)
+    amax = np.abs(Xf).max(axis=1)
+    # the extreme element of every token maps to +-127 and nothing exceeds it
+    assert (np.abs(q).max(axis=1) == 127).all()
+    pos = np.argmax(np.abs(Xf), axis=1)
+    assert (np.abs(q[np.arange(37), pos]) == 127).all()
+    assert np.array_equal(np.sign(q[np.abs(q) > 0]), np.sign(Xf[np.abs(q) > 0]))
+    # scale = amax / 127 to FP32 accuracy; reconstruction within half a step (plus FP32 slack)
+    assert np.allclose(s, amax / 127, rtol=2e-7, atol=0)
+    assert (np.abs(q.astype(np.float64) * s[:, None].astype(np.float64) - Xf) <= 0.5 * s[:, None] * (1 + 1e-5)).all()
+    # exact invariance under a power-of-two rescale of a token
+    q2, s2 = O.quantize_activations(X * np.float16(4.0))
+    assert np.array_equal(q2, q) and np.array_equal(s2, s * np.float32(4.0))
+    # sign symmetry
+    q3, s3 = O.quantize_activations(-X)
+    assert np.array_equal(q3, -q) and np.array_equal(s3, s)
+
+
+def test_activation_quant_smooth_divide_against_rationals():
+    from fractions import Fraction
+
+    rng = np.random.default_rng(6)
+    M, K = 5, 24
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    smooth = np.exp(rng.standard_normal(K) * 0.5).astype(np.float32)
+    q, s = O.quantize_activations(X, smooth)
+
+    for m in range(M):
+        xs = []
+        for k in range(K):
+            # exact quotient, rounded once to FP32: float(Fraction) is correctly rounded to
+            # FP64, and rounding a quotient of two 24-bit numbers to 53 bits and then to 24
+            # bits gives the same result as rounding it once (53 >= 2 * 24 + 2)
+            xs.append(np.float32(float(Fraction(float(X[m, k])) / Fraction(float(smooth[k])))))
+        amax = max(abs(v) for v in xs)
+        sm = np.float32(float(Fraction(float(amax)) / 127))
+        assert s[m] == sm
+        for k in range(K):
+            exact = Fraction(float(xs[k])) / Fraction(float(sm))
+            quo = np.float32(float(exact))          # the FP32 quotient the definition rounds
+            want = int(np.clip(np.rint(quo), -127, 127))
+            assert q[m, k] == want, (m, k)
+    # planted mistake: multiplying by the smooth scale instead of dividing gives other codes
+    q_mul, _ = O.quantize_activations(X, np.float32(1.0) / smooth)
+    assert not np.array_equal(q_mul, q)
