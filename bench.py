@@ -17,6 +17,7 @@ range (prefill, M=4096, N=K=8192, group 64).  The same JSON line carries
   * curve_N8192_K8192: TOPS and fraction of the roofline for M = 1..4096;
   * configs: every workload row (decode, 7B MLP, 70B layers, prefill sweep), median of five
     batches, with rotating weights and with one weight buffer (cache-warm) side by side;
+  * activation_quant: the per-token FP16 -> INT8 quantisation kernel upstream of the GEMM;
   * cpu_baseline: the CPU oracle timed on a bounded sample.
 """
 from __future__ import annotations
@@ -194,6 +195,34 @@ def calibrate(torch, api, stream):
     return out
 
 
+def activation_quant_points(torch, api, WL, stream, calib):
+    """The per-token FP16 -> INT8 quantisation upstream of the GEMM (with smooth divide):
+    algorithmic bytes 2*M*K in + M*K out + scales; HBM-bound."""
+    rows = []
+    for M, K in ((16, 8192), (4096, 8192), (2048, 28672)):
+        X = torch.from_numpy(WL.make_activations_f16(M, K, 0.001, seed=M + K)).to("cuda:0")
+        copies = max(1, min(8, math.ceil(ROTATE_BYTES / (3 * M * K))))
+        Xs = [X] + [X.clone() for _ in range(copies - 1)]
+        smooth = torch.from_numpy(WL.make_smooth(K, seed=K)).to("cuda:0")
+        q = torch.empty((M, K), dtype=torch.int8, device="cuda:0")
+        sc = torch.empty((M,), dtype=torch.float32, device="cuda:0")
+
+        def launch(i):
+            api.w4a8_quantize_activations(Xs[i % copies], smooth, out_q=q, out_scales=sc, stream=stream.cuda_stream)
+
+        tiny = M * K < (1 << 22)
+        ms = statistics.median(time_launches(launch, 50, 5, torch, stream, graph=tiny) for _ in range(5))
+        byt = 3 * M * K + 4 * M + 4 * K
+        r = {"M": M, "K": K, "us": round(ms * 1e3, 3), "gbs": round(byt / (ms * 1e-3) / 1e9, 1),
+             "frac_of_roofline": round(byt / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "bound": "hbm"}
+        if calib:
+            r["frac_of_measured"] = round(r["gbs"] / calib["stream_read_gbs"], 4)
+        rows.append(r)
+        del Xs, X, q
+        torch.cuda.empty_cache()
+    return rows
+
+
 def cpu_baseline(prob, M, budget_s=15.0):
     """The C oracle (as it stands) on a bounded row sample of the same workload."""
     from oracle import c_oracle
@@ -347,6 +376,9 @@ def main():
                 "kernel": hb["variant"], "workload": hb["workload"]}
             if calib:
                 out["roofline_hbm"]["frac_of_measured_stream_read"] = round(hb["gbs"] / calib["stream_read_gbs"], 4)
+
+    if not args.no_configs:
+        out["activation_quant"] = activation_quant_points(torch, api, WL, stream, calib)
 
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(prob, head.M)

@@ -139,6 +139,22 @@ int w4a8_dequant_dump(const void *W_packed, const uint8_t *gparams, int N, int K
                       int8_t *Wd, void *hip_stream);
 
 /* ------------------------------------------------------------------------------------
+ * Activation quantisation (device, Sec. 6 "Serving System": dynamic per-token INT8 after
+ * dividing by the smooth scale) -- produces the X and act_scales that w4a8_gemm consumes.
+ * ------------------------------------------------------------------------------------ */
+
+/*   X_f16       device [M,K] IEEE binary16 bit patterns, row-major
+ *   smooth      device [K] FP32 smooth scales (positive, finite), or NULL for none
+ *   X_i8        device [M,K] INT8 out:  clamp(rint(x' / s_x[m]), -127, 127),
+ *               x' = (float)X / smooth
+ *   act_scales  device [M] FP32 out:    s_x[m] = max_k |x'| / 127   (1 if the token is zero)
+ * All arithmetic is correctly rounded FP32, so the result is defined bit for bit.
+ * K % 8 == 0; M = 0 is a successful no-op.  Tokens containing NaN or infinity (or whose
+ * divide overflows) give unspecified codes for that token only. */
+int w4a8_quantize_activations(int M, int K, const uint16_t *X_f16, const float *smooth,
+                              int8_t *X_i8, float *act_scales, void *hip_stream);
+
+/* ------------------------------------------------------------------------------------
  * Calibration (measurement support): what this GPU delivers on the two resources of the
  * cost model of Sec. 3.2 with nothing else in the way.  Both only enqueue a kernel on
  * `hip_stream`; the caller times them.

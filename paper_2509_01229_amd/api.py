@@ -71,6 +71,8 @@ def lib() -> ctypes.CDLL:
     L.w4a8_select_variant.argtypes = [i, i, i, i]
     L.w4a8_dequant_dump.restype = i
     L.w4a8_dequant_dump.argtypes = [vp, vp, i, i, i, vp, vp]
+    L.w4a8_quantize_activations.restype = i
+    L.w4a8_quantize_activations.argtypes = [i, i, vp, vp, vp, vp, vp]
     L.w4a8_calib_stream_read.restype = i
     L.w4a8_calib_stream_read.argtypes = [vp, sz, vp]
     L.w4a8_calib_mfma_i8.restype = i
@@ -306,3 +308,21 @@ def w4a8_calib_mfma_i8(iters: int, random_operands: bool, stream=None) -> float:
     ops = ctypes.c_double(0.0)
     _check(lib().w4a8_calib_mfma_i8(iters, 1 if random_operands else 0, ctypes.byref(ops), _stream(stream)))
     return ops.value
+
+
+def w4a8_quantize_activations(X_f16, smooth=None, out_q=None, out_scales=None, stream=None):
+    """Per-token INT8 quantisation of FP16 activations [M,K] on the GPU (after dividing by
+    the optional FP32 smooth scales [K]); returns (X_i8 [M,K] int8, act_scales [M] float32)."""
+    import torch
+
+    M, K = X_f16.shape
+    if out_q is None:
+        out_q = torch.empty((M, K), dtype=torch.int8, device=X_f16.device)
+    if out_scales is None:
+        out_scales = torch.empty((M,), dtype=torch.float32, device=X_f16.device)
+    _check(lib().w4a8_quantize_activations(
+        M, K, _dev(X_f16, torch.float16, (M, K), "X_f16"),
+        _dev(smooth, torch.float32, (K,), "smooth") if smooth is not None else None,
+        _dev(out_q, torch.int8, (M, K), "out_q"), _dev(out_scales, torch.float32, (M,), "out_scales"),
+        _stream(stream)))
+    return out_q, out_scales

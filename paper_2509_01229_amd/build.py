@@ -14,7 +14,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libliquidgemm.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-SOURCES = ["liquidgemm.hip", "calib.hip", "lqq_pack.cpp"]
+SOURCES = ["liquidgemm.hip", "actquant.hip", "calib.hip", "lqq_pack.cpp"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # keep hipcc from forming packed-FP32 instructions out of ordinary float code

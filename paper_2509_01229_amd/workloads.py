@@ -72,16 +72,26 @@ def make_weights(N, K, sigma=0.02, seed=0, rng=None):
     return W.astype(np.float16).astype(np.float32)
 
 
-def make_activations(M, K, outlier_frac=0.0, seed=0, rng=None):
-    """INT8 activations and per-token scales: (X_i8 [M,K], s_x [M])."""
+def make_activations_f16(M, K, outlier_frac=0.0, seed=0, rng=None):
+    """FP16 activations X [M,K] before quantization (outlier channels multiplied by 20)."""
     rng = rng or np.random.Generator(np.random.PCG64(seed))
     X = rng.standard_normal((M, K), dtype=np.float32).astype(np.float16).astype(np.float32)
     if outlier_frac > 0:
         n_out = max(1, int(round(outlier_frac * K)))
         idx = rng.choice(K, size=n_out, replace=False)
         X[:, idx] *= np.float32(20.0)
-        X = X.astype(np.float16).astype(np.float32)
-    return quantize_activations(X)
+    return X.astype(np.float16)
+
+
+def make_smooth(K, seed=0):
+    """Positive FP32 smooth scales [K], log-normal around 1 (stand-in for SmoothQuant's)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    return np.exp(rng.standard_normal(K, dtype=np.float32) * np.float32(0.5)).astype(np.float32)
+
+
+def make_activations(M, K, outlier_frac=0.0, seed=0, rng=None):
+    """INT8 activations and per-token scales: (X_i8 [M,K], s_x [M])."""
+    return quantize_activations(make_activations_f16(M, K, outlier_frac, seed, rng).astype(np.float32))
 
 
 def make_problem(shape: GemmShape):
