@@ -165,6 +165,16 @@ def point(shape, M, ms, api, calib=None, ms_same=None):
         # the same roofline with this GPU's measured streaming rate and random-operand MFMA rate
         t_meas = max(byt / (calib["stream_read_gbs"] * 1e9), ops / (calib["mfma_i8_random_tops"] * 1e12))
         p["frac_of_measured"] = round(t_meas / t, 4)
+        # the paper's cost model (Sec. 3.2, Eq. 6) fed with the measured rates and the row tile
+        # of the kernel that runs: as printed (dequantisation and MMA in series) and with the
+        # two overlapped
+        from paper_2509_01229_amd import cost_model as CM
+
+        rates = CM.Rates(calib["stream_read_gbs"] * 1e9, calib["mfma_i8_random_tops"] * 1e12,
+                         CM.NOMINAL_VALU_LANE_OPS_PER_S)
+        m_tile = 16 if M <= 16 else (32 if M <= 32 else 128)
+        pr = CM.predict(M, shape.N, shape.K, shape.group, rates, m_tile)
+        p["model_us"] = {"eq6_serial": round(pr["serial"] * 1e6, 2), "overlapped": round(pr["overlapped"] * 1e6, 2)}
     return p
 
 
@@ -220,6 +230,31 @@ def activation_quant_points(torch, api, WL, stream, calib):
         rows.append(r)
         del Xs, X, q
         torch.cuda.empty_cache()
+    return rows
+
+
+def vendor_w8a8_reference(torch, stream):
+    """Context only: the vendor INT8 GEMM (torch._int_mm, W8A8, no dequantisation, INT32 out)
+    on N = K = 8192 with Gaussian-like INT8 operands and rotating weights -- the role the
+    W8A8 baseline plays in the paper's kernel comparison (Sec. 7.3)."""
+    rows = []
+    try:
+        N = K = 8192
+        gen = torch.Generator(device="cuda:0").manual_seed(0)
+        Bs = [torch.clamp(torch.randn((K, N), device="cuda:0", generator=gen) * 40, -127, 127).to(torch.int8)
+              for _ in range(8)]
+        for M in (32, 256, 1024, 4096):
+            A = torch.clamp(torch.randn((M, K), device="cuda:0", generator=gen) * 40, -127, 127).to(torch.int8)
+            out = torch.empty((M, N), dtype=torch.int32, device="cuda:0")
+
+            def launch(i):
+                torch._int_mm(A, Bs[i % 8], out=out)
+
+            ms = statistics.median(time_launches(launch, 30, 5, torch, stream) for _ in range(3))
+            rows.append({"M": M, "N": N, "K": K, "us": round(ms * 1e3, 2),
+                         "tops": round(algorithmic_ops(M, N, K) / (ms * 1e-3) / 1e12, 1)})
+    except Exception as e:  # the reference is optional; the product does not depend on it
+        rows.append({"error": f"{type(e).__name__}: {e}"[:200]})
     return rows
 
 
@@ -379,6 +414,9 @@ def main():
 
     if not args.no_configs:
         out["activation_quant"] = activation_quant_points(torch, api, WL, stream, calib)
+        del prob.d_packed[1:], prob.d_gparams[1:]
+        torch.cuda.empty_cache()
+        out["reference_w8a8_vendor"] = vendor_w8a8_reference(torch, stream)
 
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(prob, head.M)
