@@ -134,7 +134,7 @@ def time_steps(prob, M, steps, warmup, torch, api, stream, variant=-1, graph=Fal
 
 def is_tiny(shape, M):
     """Kernels expected to run shorter than a Python launch: timed inside a HIP graph."""
-    return shape.N * shape.K < (1 << 26) and M <= 32
+    return shape.N * shape.K <= (1 << 26) and M <= 32
 
 
 def time_median(prob, M, torch, api, stream, rotate=True, batches=5, est_ms=None):

@@ -1169,7 +1169,7 @@ static int stream_split(int N, int K, int F, int NW)
     const int groups = N / (32 * F), units = K / 128;
     // Measured on MI355X: the exchange of partial tiles through memory costs about 3 us, so
     // K is split across blocks only when N alone leaves most CUs without a block.
-    int s = groups > 128 ? 1 : (groups > 48 ? 2 : 4);
+    int s = groups > 128 ? 1 : (groups > 64 ? 2 : 4);
     s = std::min(s, units / (2 * NW));
     return std::max(1, s);
 }
@@ -1222,7 +1222,10 @@ static int launch_stream16(const Args &a)
     if ((a.N / 32) % F != 0) return fail(LQ_ERR_INVALID, "N/32 not a multiple of F=%d", F);
     const int groups = a.N / (32 * F);
     int S = SPLIT ? SPLIT : stream_split(a.N, a.K, F, NW);
-    S = std::min(S, a.K / 128);
+    // the deep-prefetch form (small shapes) keeps whole K in one block unless N gives very few
+    if (!SPLIT && UU == 4) S = groups <= 64 ? 2 : 1;
+    if ((a.K / 128) % UU != 0) return fail(LQ_ERR_INVALID, "K/128 not a multiple of UU=%d", UU);
+    S = std::min(S, a.K / (128 * UU));
     if (S > 1 && groups > kMaxTicketGroups) S = 1;
     size_t need = S > 1 ? (size_t)S * (a.N / 32) * 8 * 64 * sizeof(int32_t) : 0;
     if (need > 0 && (!a.ws || a.ws_bytes < need)) {
@@ -1370,6 +1373,9 @@ static const Variant kVariants[] = {
     {"stream16_f2_w8_s1", &launch_stream16<2, 8, 1>, 16, 2, 1},
     {"stream16_f2_w8_s2", &launch_stream16<2, 8, 2>, 16, 2, 1},
     {"stream16_f2_w8_s4", &launch_stream16<2, 8, 4>, 16, 2, 1},
+    {"stream16_f1_w8_u4", &launch_stream16<1, 8, 0, 0, 4>, 16, 1, 8},
+    {"stream16_f1_w8_u4_s1", &launch_stream16<1, 8, 1, 0, 4>, 16, 1, 8},
+    {"stream16_f1_w8_u4_s2", &launch_stream16<1, 8, 2, 0, 4>, 16, 1, 8},
     {"tile_m32", &launch_tile<1>, 0, 1, 1},
     {"tile_m64", &launch_tile<2>, 0, 1, 1},
     {"tile_m128", &launch_tile<4>, 0, 1, 1},
@@ -1427,8 +1433,12 @@ static int find_variant(const char *name)
 // alone gives at most one tile per CU.
 static int select_variant(int M, int N, int K)
 {
-    (void)K;
-    if (M <= 16) return find_variant(N / 64 >= 384 ? "stream16_f2_w4" : "stream16_f2_w8");
+    if (M <= 16) {
+        // small weight matrices are bound by launch and first-load latency: one tile per
+        // block and all of a wave's loads (512 k) in flight at once
+        if (K % 512 == 0 && K <= 8192 && N / 32 <= 256) return find_variant("stream16_f1_w8_u4");
+        return find_variant(N / 64 >= 384 ? "stream16_f2_w4" : "stream16_f2_w8");
+    }
     if (M <= 32) return find_variant("stream_f2_w8");
     return find_variant("duo_m128");
 }
