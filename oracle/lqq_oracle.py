@@ -28,6 +28,10 @@ Pinning status (tests/test_oracle_pins.py):
                      invariance, reconstruction error <= s_x / 2, smooth divide
                      against exact rational arithmetic.
 
+  grouped_w4a8_gemm  pinned: brute force in Python integers on a tiny case, independence of
+                     every expert's rows from the other experts' weights, empty experts,
+                     the single-expert case.
+
 Readings of the paper taken here (the paper is silent or ambiguous on them):
   * s_u8 is an integer: round(R / 15) with R = max - min of the group, computed
     as (2R + 15) // 30 (no ties are possible since 15 is odd); matches the
@@ -218,3 +222,27 @@ def w4a8_gemm(X_i8, s_x, packed, s_u8, a, s_w, g):
     assert np.array_equal(Wd, dequant_bits(Q_u4, s_u8, a, g)), "Eq. 8 and Eq. 12 disagree"
     ACC = matmul_i64(X_i8, Wd)
     return ACC, scale_epilogue(ACC, s_x, s_w)
+
+
+# --------------------------------------------------------------------------
+# Grouped GEMM (mixture-of-experts layers, Sec. 7.3: a batch of independent GEMMs, one
+# per expert, over disjoint runs of tokens)
+# --------------------------------------------------------------------------
+def grouped_w4a8_gemm(X_i8, s_x, row_offsets, experts):
+    """Expert e owns tokens row_offsets[e] .. row_offsets[e+1]-1 of X and multiplies them
+    with its own quantized weights experts[e] (a dict as returned by quantize_weights);
+    nothing is shared between experts.  Returns (ACC int32 [M, N], Y float16 [M, N])."""
+    X_i8 = np.asarray(X_i8)
+    row_offsets = [int(r) for r in row_offsets]
+    assert len(row_offsets) == len(experts) + 1 and row_offsets[0] == 0 and row_offsets[-1] == X_i8.shape[0]
+    N = experts[0]["Q_u4"].shape[0]
+    ACC = np.zeros((X_i8.shape[0], N), dtype=np.int32)
+    Y = np.zeros((X_i8.shape[0], N), dtype=np.float16)
+    for e, q in enumerate(experts):
+        r0, r1 = row_offsets[e], row_offsets[e + 1]
+        assert r1 >= r0
+        if r1 == r0:
+            continue
+        ACC[r0:r1], Y[r0:r1] = w4a8_gemm(X_i8[r0:r1], np.asarray(s_x)[r0:r1], q["packed"], q["s_u8"], q["a"],
+                                         q["s_w"], q["g"])
+    return ACC, Y

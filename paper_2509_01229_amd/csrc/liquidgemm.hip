@@ -126,6 +126,17 @@ __device__ __forceinline__ void wait_vmcnt0(v4i &a, v4i &b, v4i &c, v4i &d)
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d)::"memory");
 }
 
+// Where a block works: gx = its tile group (or output tile) among gnx, ks = its slice of S
+// K slices.  Plain launches take these from the grid (blockIdx.x, gridDim.x, blockIdx.y,
+// gridDim.y); grouped launches compute them per expert.
+struct Place {
+    int gx, gnx, ks, S;
+};
+__device__ __forceinline__ Place grid_place()
+{
+    return Place{(int)blockIdx.x, (int)gridDim.x, (int)blockIdx.y, (int)gridDim.y};
+}
+
 template <int F, bool G128>
 struct StreamRegs {
     u32x4 w[F][2];
@@ -134,8 +145,8 @@ struct StreamRegs {
 };
 
 template <int F, int NW, bool G128>
-__global__ __launch_bounds__(NW * 64) void w4a8_stream_kernel(
-    int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
+__device__ __forceinline__ void stream_block(
+    const Place pl, int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
     __half *__restrict__ Y, int32_t *__restrict__ ACC, int32_t *__restrict__ partials)
 {
@@ -143,10 +154,10 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream_kernel(
     __shared__ int s_last;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane & 31, kb = lane >> 5;
-    const int t0 = blockIdx.x * F;
+    const int t0 = pl.gx * F;
     const int units = K >> 7;
     const int chunks_per_tile = K >> 6;
-    const int S = gridDim.y, ks = blockIdx.y;
+    const int S = pl.S, ks = pl.ks;
     const int u_begin = (int)((long long)units * ks / S), u_end = (int)((long long)units * (ks + 1) / S);
 
     v16i acc[F];
@@ -232,12 +243,12 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream_kernel(
         // written and read with device-scope atomics, which act at the memory side common to
         // all XCDs, so no cache has to be flushed or invalidated; the barrier's wait for
         // outstanding memory operations orders them before the ticket.
-        int32_t *mine = partials + ((size_t)ks * gridDim.x + blockIdx.x) * (size_t)(vals * 64);
+        int32_t *mine = partials + ((size_t)ks * pl.gnx + pl.gx) * (size_t)(vals * 64);
         for (int idx = threadIdx.x; idx < vals * 64; idx += NW * 64)
             __hip_atomic_store(mine + idx, block_sum(idx), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();  // includes s_waitcnt vmcnt(0): every store above has been acknowledged
         if (threadIdx.x == 0) {
-            const unsigned t = __hip_atomic_fetch_add(&g_splitk_tickets[blockIdx.x], 1u, __ATOMIC_RELAXED,
+            const unsigned t = __hip_atomic_fetch_add(&g_splitk_tickets[pl.gx], 1u, __ATOMIC_RELAXED,
                                                       __HIP_MEMORY_SCOPE_AGENT);
             s_last = (t == (unsigned)(S - 1));
         }
@@ -247,15 +258,24 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream_kernel(
                 int sum = 0;
                 for (int k2 = 0; k2 < S; ++k2)
                     sum += __hip_atomic_load(
-                        partials + ((size_t)k2 * gridDim.x + blockIdx.x) * (size_t)(vals * 64) + idx,
+                        partials + ((size_t)k2 * pl.gnx + pl.gx) * (size_t)(vals * 64) + idx,
                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 finish(idx, sum);
             }
             if (threadIdx.x == 0)  // ready for the next call
-                __hip_atomic_store(&g_splitk_tickets[blockIdx.x], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&g_splitk_tickets[pl.gx], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     LQ_STAMP(3);
+}
+
+template <int F, int NW, bool G128>
+__global__ __launch_bounds__(NW * 64) void w4a8_stream_kernel(
+    int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
+    const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
+    __half *__restrict__ Y, int32_t *__restrict__ ACC, int32_t *__restrict__ partials)
+{
+    stream_block<F, NW, G128>(grid_place(), M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
 }
 
 // ------------------------------------------------------------------------------------
@@ -279,8 +299,8 @@ struct Stream16Regs {
 // ABL (experiments only, 0 in shipped variants): 1 = no X loads, 2 = no parameter loads,
 // 4 = no dequantisation, 8 = no reduction / epilogue.  Results are wrong for ABL != 0.
 template <int F, int NW, int UU, bool G128, int ABL = 0>
-__global__ __launch_bounds__(NW * 64) void w4a8_stream16_kernel(
-    int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
+__device__ __forceinline__ void stream16_block(
+    const Place pl, int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
     __half *__restrict__ Y, int32_t *__restrict__ ACC, int32_t *__restrict__ partials)
 {
@@ -289,11 +309,11 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream16_kernel(
     __shared__ int s_last;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane & 31;
-    const int t0 = blockIdx.x * F;
+    const int t0 = pl.gx * F;
     const int units = K >> 7;                   // 128-k units (parameter granularity)
     const int steps = units / UU;               // pipeline steps of UU units
     const int chunks_per_tile = K >> 6;
-    const int S = gridDim.y, ks = blockIdx.y;
+    const int S = pl.S, ks = pl.ks;
     const int u_begin = (int)((long long)steps * ks / S), u_end = (int)((long long)steps * (ks + 1) / S);
 
     v4i acc[F][2];
@@ -409,12 +429,12 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream16_kernel(
         }
     } else {
         // grid-level split-K: same protocol as w4a8_stream_kernel
-        int32_t *mine = partials + ((size_t)ks * gridDim.x + blockIdx.x) * (size_t)(VALS * 64);
+        int32_t *mine = partials + ((size_t)ks * pl.gnx + pl.gx) * (size_t)(VALS * 64);
         for (int idx = threadIdx.x; idx < VALS * 64; idx += NW * 64)
             __hip_atomic_store(mine + idx, block_sum(idx), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
         if (threadIdx.x == 0) {
-            const unsigned t = __hip_atomic_fetch_add(&g_splitk_tickets[blockIdx.x], 1u, __ATOMIC_RELAXED,
+            const unsigned t = __hip_atomic_fetch_add(&g_splitk_tickets[pl.gx], 1u, __ATOMIC_RELAXED,
                                                       __HIP_MEMORY_SCOPE_AGENT);
             s_last = (t == (unsigned)(S - 1));
         }
@@ -427,14 +447,23 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream16_kernel(
                 int sum = 0;
                 for (int k2 = 0; k2 < S; ++k2)
                     sum += __hip_atomic_load(
-                        partials + ((size_t)k2 * gridDim.x + blockIdx.x) * (size_t)(VALS * 64) + idx,
+                        partials + ((size_t)k2 * pl.gnx + pl.gx) * (size_t)(VALS * 64) + idx,
                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 finish(i, idx, sum);
             }
             if (threadIdx.x == 0)
-                __hip_atomic_store(&g_splitk_tickets[blockIdx.x], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&g_splitk_tickets[pl.gx], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
+}
+
+template <int F, int NW, int UU, bool G128, int ABL = 0>
+__global__ __launch_bounds__(NW * 64) void w4a8_stream16_kernel(
+    int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
+    const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
+    __half *__restrict__ Y, int32_t *__restrict__ ACC, int32_t *__restrict__ partials)
+{
+    stream16_block<F, NW, UU, G128, ABL>(grid_place(), M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
 }
 
 // ------------------------------------------------------------------------------------
@@ -855,10 +884,10 @@ __global__ __launch_bounds__(256, (MF <= 4 ? 2 : 1)) void w4a8_pipe_kernel(
 // through LDS at the end (in-block split-K).  Every SIMD again has two waves, which a
 // single 4-wave block per CU would not give.
 template <bool G128, int KG>
-__global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
-    int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
-    const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
-    __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n,
+__device__ __forceinline__ void duo_block(
+    const Place pl, const int bm, const int bn, int M, int N, int K, const int8_t *__restrict__ X,
+    const float *__restrict__ sx, const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp,
+    const float *__restrict__ sw, __half *__restrict__ Y, int32_t *__restrict__ ACC,
     int32_t *__restrict__ partials)
 {
     constexpr int MF = 4, WM = 128, XP = 4;
@@ -870,14 +899,12 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
     const int grp = KG == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 8));
     const int lane = tid & 63, wave = tid >> 6;
     const int j = lane & 31, kb = lane >> 5;
-    int bm, bn;
-    block_coords(blocks_m, blocks_n, bm, bn);
     const int m0 = bm * WM;
     const int ng = bn * 4 + wave;
     const bool active = ng < (N >> 6);
     const int t0 = 2 * (active ? ng : (N >> 6) - 1);
     // grid-level split-K: slice ks of S covers whole units of 256 k ...
-    const int S = gridDim.y, ks = blockIdx.y;
+    const int S = pl.S, ks = pl.ks;
     const int u_begin = (int)((long long)(K >> 8) * ks / S), u_end = (int)((long long)(K >> 8) * (ks + 1) / S);
     // ... and the in-block split gives group 0 the first ceil(half) of them.  All groups run
     // the loop of group 0 (the barriers are block-wide); a group with one unit less feeds
@@ -1059,7 +1086,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
             // last one of the S slices adds the others to its registers and runs the epilogue.
             // Layout: [tile][slice][wave of the block][MFK*8 x (64 lanes x 16 B)], fully coalesced.
             constexpr int EPW = MFK * 8;
-            const size_t tile = blockIdx.x;
+            const size_t tile = pl.gx;
             const int bw = G * 4 + wave;
             int32_t *mine = partials + (((tile * S + ks) * (4 * KG) + bw) * EPW) * 256 + lane * 4;
             // row fragments that lie wholly past M are neither published nor read back
@@ -1130,6 +1157,18 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
         finish(std::integral_constant<int, 0>{});
     else
         finish(std::integral_constant<int, KG - 1>{});
+}
+
+template <bool G128, int KG>
+__global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
+    int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
+    const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
+    __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n,
+    int32_t *__restrict__ partials)
+{
+    int bm, bn;
+    block_coords(blocks_m, blocks_n, bm, bn);
+    duo_block<G128, KG>(grid_place(), bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
 }
 
 // ------------------------------------------------------------------------------------

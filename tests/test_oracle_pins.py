@@ -377,3 +377,42 @@ def test_activation_quant_smooth_divide_against_rationals():
     # planted mistake: multiplying by the smooth scale instead of dividing gives other codes
     q_mul, _ = O.quantize_activations(X, np.float32(1.0) / smooth)
     assert not np.array_equal(q_mul, q)
+
+
+# ---------------------------------------------------------------------------------------
+# Grouped (mixture-of-experts) GEMM: independent GEMMs over disjoint runs of tokens
+# ---------------------------------------------------------------------------------------
+def _tiny_experts(E, N, K, g, seed):
+    rng = np.random.default_rng(seed)
+    return [O.quantize_weights(rng.standard_normal((N, K)).astype(np.float16).astype(np.float32) * 0.05, g)
+            for _ in range(E)]
+
+
+def test_grouped_gemm_brute_force_and_independence():
+    E, N, K, g = 3, 4, 64, 64
+    experts = _tiny_experts(E, N, K, g, seed=11)
+    offs = [0, 2, 2, 5]                     # expert 1 has no tokens
+    rng = np.random.default_rng(12)
+    X = rng.integers(-127, 128, size=(5, K)).astype(np.int8)
+    s_x = np.ones(5, dtype=np.float32)
+    ACC, Y = O.grouped_w4a8_gemm(X, s_x, offs, experts)
+    owner = [0, 0, 2, 2, 2]
+    for m in range(5):
+        q = experts[owner[m]]
+        for n in range(N):
+            tot = 0
+            for k in range(K):
+                w = int(q["Q_u4"][n, k]) * int(q["s_u8"][n, k // g]) + int(q["mn"][n, k // g])
+                tot += int(X[m, k]) * w
+            assert ACC[m, n] == tot
+            assert Y[m, n] == np.float16(float(tot) * float(q["s_w"][n]))
+    # rows of one expert do not move when another expert's weights change
+    other = list(experts)
+    other[0] = _tiny_experts(1, N, K, g, seed=99)[0]
+    ACC2, _ = O.grouped_w4a8_gemm(X, s_x, offs, other)
+    assert np.array_equal(ACC2[2:], ACC[2:]) and not np.array_equal(ACC2[:2], ACC[:2])
+    # one expert owning every token is the plain GEMM
+    q = experts[2]
+    A1, Y1 = O.grouped_w4a8_gemm(X, s_x, [0, 5], [q])
+    A0, Y0 = O.w4a8_gemm(X, s_x, q["packed"], q["s_u8"], q["a"], q["s_w"], g)
+    assert np.array_equal(A1, A0) and np.array_equal(Y1.view(np.uint16), Y0.view(np.uint16))
