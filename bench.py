@@ -18,6 +18,7 @@ range (prefill, M=4096, N=K=8192, group 64).  The same JSON line carries
   * configs: every workload row (decode, 7B MLP, 70B layers, prefill sweep), median of five
     batches, with rotating weights and with one weight buffer (cache-warm) side by side;
   * activation_quant: the per-token FP16 -> INT8 quantisation kernel upstream of the GEMM;
+  * grouped_moe: mixture-of-experts layers in one grouped call vs one call per expert;
   * cpu_baseline: the CPU oracle timed on a bounded sample.
 """
 from __future__ import annotations
@@ -258,6 +259,62 @@ def vendor_w8a8_reference(torch, stream):
     return rows
 
 
+def grouped_moe_points(torch, api, WL, stream):
+    """Mixture-of-experts layers shaped like Mixtral-8x7B (8 experts, top-2 routing, hidden
+    4096, intermediate 14336; Sec. 7.3 of the paper): one grouped call against one
+    w4a8_gemm call per expert, same kernels, rotating weight copies."""
+    rows_out = []
+    E = 8
+    for lname, N, K in (("moe_up", 14336, 4096), ("moe_down", 4096, 14336)):
+        g = 64
+        # two distinct experts' weights, repeated: timing does not depend on the values
+        packs = [api.liquidquant_pack_weights(WL.make_weights(N, K, 0.02, seed=70 + e), g) for e in range(2)]
+        codes = np.concatenate([packs[e % 2][0] for e in range(E)])
+        gps = np.concatenate([packs[e % 2][1] for e in range(E)])
+        sws = np.stack([packs[e % 2][2] for e in range(E)])
+        copies = max(1, math.ceil(ROTATE_BYTES / (codes.nbytes + gps.nbytes)))
+        d_codes = [torch.from_numpy(codes).to("cuda:0") for _ in range(copies)]
+        d_gps = [torch.from_numpy(gps).to("cuda:0") for _ in range(copies)]
+        d_sw = torch.from_numpy(sws).to("cuda:0")
+        cb, gb = api.liquidquant_packed_size(N, K, g)
+        for B in (16, 256, 4096):
+            rng = np.random.Generator(np.random.PCG64(B))
+            rows = rng.multinomial(2 * B, [1.0 / E] * E)
+            offs = np.concatenate([[0], np.cumsum(rows)]).astype(int)
+            M = int(offs[-1])
+            X, sx = WL.make_activations(M, K, 0.0, seed=B)
+            dX, dsx = torch.from_numpy(X).to("cuda:0"), torch.from_numpy(sx).to("cuda:0")
+            Y = torch.empty((M, N), dtype=torch.float16, device="cuda:0")
+            Xe = [dX[offs[e]:offs[e + 1]] for e in range(E)]
+            sxe = [dsx[offs[e]:offs[e + 1]].clone() for e in range(E)]  # own allocations: 16-byte aligned
+            Ye = [Y[offs[e]:offs[e + 1]] for e in range(E)]
+
+            def grouped(i):
+                api.w4a8_grouped_gemm(offs, dX, dsx, d_codes[i % copies], d_gps[i % copies], d_sw, N, K, g,
+                                      out_y=Y, stream=stream.cuda_stream)
+
+            def sequential(i):
+                c = i % copies
+                for e in range(E):
+                    if rows[e]:
+                        api.w4a8_gemm(Xe[e], sxe[e], d_codes[c][e * cb:(e + 1) * cb], d_gps[c][e * gb:(e + 1) * gb],
+                                      d_sw[e], N, K, g, out=Ye[e], stream=stream.cuda_stream)
+
+            # both inside a HIP graph: eight short launches from Python would otherwise be
+            # timed by the interpreter, not by the GPU
+            t_g = statistics.median(time_launches(grouped, 10, 2, torch, stream, graph=True) for _ in range(3))
+            t_s = statistics.median(time_launches(sequential, 10, 2, torch, stream, graph=True) for _ in range(3))
+            ops = algorithmic_ops(M, N, K)
+            byt = E * (cb + gb) + M * K + 2 * M * N
+            rows_out.append({"layer": lname, "experts": E, "N": N, "K": K, "tokens": B, "rows": rows.tolist(),
+                             "us_grouped": round(t_g * 1e3, 2), "us_per_expert_calls": round(t_s * 1e3, 2),
+                             "speedup": round(t_s / t_g, 2), "tops": round(ops / (t_g * 1e-3) / 1e12, 1),
+                             "gbs": round(byt / (t_g * 1e-3) / 1e9, 1)})
+        del d_codes, d_gps
+        torch.cuda.empty_cache()
+    return rows_out
+
+
 def cpu_baseline(prob, M, budget_s=15.0):
     """The C oracle (as it stands) on a bounded row sample of the same workload."""
     from oracle import c_oracle
@@ -417,6 +474,7 @@ def main():
         del prob.d_packed[1:], prob.d_gparams[1:]
         torch.cuda.empty_cache()
         out["reference_w8a8_vendor"] = vendor_w8a8_reference(torch, stream)
+        out["grouped_moe"] = grouped_moe_points(torch, api, WL, stream)
 
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(prob, head.M)

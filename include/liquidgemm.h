@@ -139,6 +139,25 @@ int w4a8_dequant_dump(const void *W_packed, const uint8_t *gparams, int N, int K
                       int8_t *Wd, void *hip_stream);
 
 /* ------------------------------------------------------------------------------------
+ * Grouped GEMM (device; mixture-of-experts layers, Sec. 7.3): E independent W4A8 GEMMs that
+ * share N, K and group, over disjoint runs of tokens, in at most three kernel launches.
+ * ------------------------------------------------------------------------------------ */
+
+/*   row_offsets host [E+1], row_offsets[0] = 0, non-decreasing: expert e owns rows
+ *               row_offsets[e] .. row_offsets[e+1]-1 of X, act_scales and Y (experts without
+ *               rows are skipped); read before the call returns
+ *   X           device [row_offsets[E], K] INT8;  act_scales device [row_offsets[E]] FP32
+ *   W_packed    device, the E packed code blobs back to back (codes_bytes each, in expert
+ *               order); gparams likewise (gparams_bytes each); w_scales device [E, N] FP32
+ *   Y           device [row_offsets[E], N] FP16 bits, or NULL
+ *   ACC         device [row_offsets[E], N] raw INT32 accumulators (parity hook), or NULL
+ * 1 <= E <= 64.  Per expert the result is exactly that of w4a8_gemm / w4a8_gemm_i32 on its
+ * rows.  No workspace: the grid over all experts replaces the split of K. */
+int w4a8_grouped_gemm(int E, const int *row_offsets, int N, int K, int group, const int8_t *X,
+                      const float *act_scales, const void *W_packed, const uint8_t *gparams,
+                      const float *w_scales, uint16_t *Y, int32_t *ACC, void *hip_stream);
+
+/* ------------------------------------------------------------------------------------
  * Activation quantisation (device, Sec. 6 "Serving System": dynamic per-token INT8 after
  * dividing by the smooth scale) -- produces the X and act_scales that w4a8_gemm consumes.
  * ------------------------------------------------------------------------------------ */

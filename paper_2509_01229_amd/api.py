@@ -71,6 +71,8 @@ def lib() -> ctypes.CDLL:
     L.w4a8_select_variant.argtypes = [i, i, i, i]
     L.w4a8_dequant_dump.restype = i
     L.w4a8_dequant_dump.argtypes = [vp, vp, i, i, i, vp, vp]
+    L.w4a8_grouped_gemm.restype = i
+    L.w4a8_grouped_gemm.argtypes = [i, ctypes.POINTER(ctypes.c_int), i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
     L.w4a8_quantize_activations.restype = i
     L.w4a8_quantize_activations.argtypes = [i, i, vp, vp, vp, vp, vp]
     L.w4a8_calib_stream_read.restype = i
@@ -326,3 +328,29 @@ def w4a8_quantize_activations(X_f16, smooth=None, out_q=None, out_scales=None, s
         _dev(out_q, torch.int8, (M, K), "out_q"), _dev(out_scales, torch.float32, (M,), "out_scales"),
         _stream(stream)))
     return out_q, out_scales
+
+
+def w4a8_grouped_gemm(row_offsets, X, act_scales, W_packed, gparams, w_scales, N: int, K: int, group: int,
+                      want_y=True, want_acc=False, out_y=None, out_acc=None, stream=None):
+    """E independent W4A8 GEMMs over disjoint runs of tokens (mixture-of-experts layers).
+    row_offsets: E+1 host integers; W_packed / gparams: the experts' blobs back to back on the
+    GPU; w_scales: [E, N].  Returns (Y or None, ACC or None)."""
+    import torch
+
+    offs = [int(r) for r in row_offsets]
+    E = len(offs) - 1
+    M = offs[-1]
+    if want_y and out_y is None:
+        out_y = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    if want_acc and out_acc is None:
+        out_acc = torch.empty((M, N), dtype=torch.int32, device=X.device)
+    cb, gb = liquidquant_packed_size(N, K, group)
+    c_offs = (ctypes.c_int * (E + 1))(*offs)
+    _check(lib().w4a8_grouped_gemm(
+        E, c_offs, N, K, group, _dev(X, torch.int8, (M, K), "X"),
+        _dev(act_scales, torch.float32, (M,), "act_scales"),
+        _dev(W_packed, torch.uint8, (E * cb,), "W_packed"), _dev(gparams, torch.uint8, (E * gb,), "gparams"),
+        _dev(w_scales, torch.float32, (E, N), "w_scales"),
+        _dev(out_y, torch.float16, (M, N), "out_y") if want_y else None,
+        _dev(out_acc, torch.int32, (M, N), "out_acc") if want_acc else None, _stream(stream)))
+    return (out_y if want_y else None), (out_acc if want_acc else None)

@@ -1172,6 +1172,74 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
 }
 
 // ------------------------------------------------------------------------------------
+// Grouped launches (mixture-of-experts layers, Sec. 7.3): one launch runs the same per-block
+// code over several experts that share N, K and the group size.  Expert i of the launch
+// owns rows row_off[i] .. row_off[i] + rows[i] - 1 of X / Y and the expert[i]-th weight
+// blob.  The table travels by value in the kernel arguments (no device copy, nothing to
+// allocate), which bounds a call to 64 experts.
+// ------------------------------------------------------------------------------------
+constexpr int kMaxExperts = 64;
+struct GroupTable {
+    int count;
+    int block_end[kMaxExperts];  // running total of blocks up to and including entry i
+    int expert[kMaxExperts];
+    int row_off[kMaxExperts];
+    int rows[kMaxExperts];
+};
+struct GroupedPtrs {
+    const int8_t *X;
+    const float *sx;
+    const u32x4 *Wp;
+    const uint8_t *gp;
+    const float *sw;
+    __half *Y;
+    int32_t *ACC;
+    size_t w_stride;   // u32x4 elements between the packed codes of consecutive experts
+    size_t gp_stride;  // bytes between their group parameters
+};
+
+template <int NW, int UU, bool G128>
+__global__ __launch_bounds__(NW * 64) void w4a8_stream16_grouped_kernel(const GroupTable g, const GroupedPtrs p,
+                                                                        int N, int K, int groups)
+{
+    const int i = blockIdx.x / groups, gx = blockIdx.x % groups;
+    const int e = g.expert[i], r0 = g.row_off[i];
+    stream16_block<2, NW, UU, G128>(Place{gx, groups, 0, 1}, g.rows[i], N, K, p.X + (size_t)r0 * K, p.sx + r0,
+                                    p.Wp + e * p.w_stride, p.gp + e * p.gp_stride, p.sw + (size_t)e * N,
+                                    p.Y ? p.Y + (size_t)r0 * N : nullptr, p.ACC ? p.ACC + (size_t)r0 * N : nullptr,
+                                    nullptr);
+}
+
+template <int NW, bool G128>
+__global__ __launch_bounds__(NW * 64) void w4a8_stream_grouped_kernel(const GroupTable g, const GroupedPtrs p,
+                                                                      int N, int K, int groups)
+{
+    const int i = blockIdx.x / groups, gx = blockIdx.x % groups;
+    const int e = g.expert[i], r0 = g.row_off[i];
+    stream_block<2, NW, G128>(Place{gx, groups, 0, 1}, g.rows[i], N, K, p.X + (size_t)r0 * K, p.sx + r0,
+                              p.Wp + e * p.w_stride, p.gp + e * p.gp_stride, p.sw + (size_t)e * N,
+                              p.Y ? p.Y + (size_t)r0 * N : nullptr, p.ACC ? p.ACC + (size_t)r0 * N : nullptr,
+                              nullptr);
+}
+
+template <bool G128, int KG>
+__global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_grouped_kernel(const GroupTable g,
+                                                                                     const GroupedPtrs p, int N,
+                                                                                     int K)
+{
+    int i = 0;
+    while (i < g.count - 1 && (int)blockIdx.x >= g.block_end[i]) ++i;
+    const int local = (int)blockIdx.x - (i ? g.block_end[i - 1] : 0);
+    const int M = g.rows[i], e = g.expert[i], r0 = g.row_off[i];
+    // row tiles of one column block are neighbours, so they meet on the expert's W columns
+    const int blocks_m = (M + 127) >> 7;
+    const int bm = local % blocks_m, bn = local / blocks_m;
+    duo_block<G128, KG>(Place{0, 1, 0, 1}, bm, bn, M, N, K, p.X + (size_t)r0 * K, p.sx + r0,
+                        p.Wp + e * p.w_stride, p.gp + e * p.gp_stride, p.sw + (size_t)e * N,
+                        p.Y ? p.Y + (size_t)r0 * N : nullptr, p.ACC ? p.ACC + (size_t)r0 * N : nullptr, nullptr);
+}
+
+// ------------------------------------------------------------------------------------
 // Variant table and dispatcher
 // ------------------------------------------------------------------------------------
 struct Args {
@@ -1515,6 +1583,98 @@ static int run(int variant, const Args &a)
     return LQ_OK;
 }
 
+// ------------------------------------------------------------------------------------
+// Grouped GEMM: experts are sorted by their number of rows into the three kernel families
+// (<= 16 rows: 16-row stream kernel, <= 32: 32-row stream kernel, more: 128 x 256 tiles),
+// and each family that is not empty gets one launch over all of its experts.
+// ------------------------------------------------------------------------------------
+struct GroupedArgs {
+    int E, N, K, group;
+    const int *row_offsets;  // host, E + 1
+    GroupedPtrs p;
+    hipStream_t stream;
+};
+
+template <class Kernel, class... A>
+static int launch_checked(const char *what, Kernel kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st,
+                          A... args)
+{
+    if (int rc = allow_lds(kernel, lds)) return rc;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(kernel, grid, block, lds, st, args...);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(LQ_ERR_HIP, "launch of %s failed: %s", what, hipGetErrorString(e));
+    return LQ_OK;
+}
+
+static int grouped_run(const GroupedArgs &a)
+{
+    GroupTable small{}, mid{}, big{};
+    long long big_blocks = 0;
+    const int blocks_n = (a.N + 255) / 256;
+    for (int e = 0; e < a.E; ++e) {
+        const int r0 = a.row_offsets[e], rows = a.row_offsets[e + 1] - r0;
+        if (rows == 0) continue;
+        GroupTable &t = rows <= 16 ? small : (rows <= 32 ? mid : big);
+        const int i = t.count++;
+        t.expert[i] = e, t.row_off[i] = r0, t.rows[i] = rows;
+        if (&t == &big) {
+            big_blocks += (long long)((rows + 127) / 128) * blocks_n;
+            if (big_blocks > 0x7fffffff) return fail(LQ_ERR_INVALID, "grouped GEMM too large for one launch");
+            t.block_end[i] = (int)big_blocks;
+        }
+    }
+    const bool g128 = a.group == 128;
+    const int groups = a.N / 64;  // stream kernels: two tiles of 32 channels per block
+    if (small.count) {
+        const dim3 grid((unsigned)(small.count * groups));
+        // four waves per block once the grid alone gives every CU several blocks
+        const bool w4 = (long long)small.count * groups >= 384 * 2;
+        const size_t lds = (size_t)(w4 ? 4 : 8) * 2 * 8 * 64 * sizeof(int);
+        int rc;
+        if (w4)
+            rc = g128 ? launch_checked("grouped stream16", w4a8_stream16_grouped_kernel<4, 1, true>, grid, dim3(256),
+                                       lds, a.stream, small, a.p, a.N, a.K, groups)
+                      : launch_checked("grouped stream16", w4a8_stream16_grouped_kernel<4, 1, false>, grid, dim3(256),
+                                       lds, a.stream, small, a.p, a.N, a.K, groups);
+        else
+            rc = g128 ? launch_checked("grouped stream16", w4a8_stream16_grouped_kernel<8, 1, true>, grid, dim3(512),
+                                       lds, a.stream, small, a.p, a.N, a.K, groups)
+                      : launch_checked("grouped stream16", w4a8_stream16_grouped_kernel<8, 1, false>, grid, dim3(512),
+                                       lds, a.stream, small, a.p, a.N, a.K, groups);
+        if (rc) return rc;
+    }
+    if (mid.count) {
+        const dim3 grid((unsigned)(mid.count * groups));
+        const size_t lds = (size_t)8 * 2 * 16 * 64 * sizeof(int);
+        const int rc = g128 ? launch_checked("grouped stream", w4a8_stream_grouped_kernel<8, true>, grid, dim3(512), lds,
+                                             a.stream, mid, a.p, a.N, a.K, groups)
+                            : launch_checked("grouped stream", w4a8_stream_grouped_kernel<8, false>, grid, dim3(512),
+                                             lds, a.stream, mid, a.p, a.N, a.K, groups);
+        if (rc) return rc;
+    }
+    if (big.count) {
+        const dim3 grid((unsigned)big_blocks);
+        // as for single GEMMs: two k groups per block while the grid gives at most one block per CU
+        const bool kg2 = big_blocks <= 256 && a.K >= 512;
+        const size_t lds1 = 2 * (size_t)128 * kTilePitch;
+        const size_t lds2 = std::max<size_t>(2 * lds1, 64 * 1024);
+        int rc;
+        if (kg2)
+            rc = g128 ? launch_checked("grouped duo", w4a8_duo_grouped_kernel<true, 2>, grid, dim3(512), lds2, a.stream,
+                                       big, a.p, a.N, a.K)
+                      : launch_checked("grouped duo", w4a8_duo_grouped_kernel<false, 2>, grid, dim3(512), lds2, a.stream,
+                                       big, a.p, a.N, a.K);
+        else
+            rc = g128 ? launch_checked("grouped duo", w4a8_duo_grouped_kernel<true, 1>, grid, dim3(256), lds1, a.stream,
+                                       big, a.p, a.N, a.K)
+                      : launch_checked("grouped duo", w4a8_duo_grouped_kernel<false, 1>, grid, dim3(256), lds1, a.stream,
+                                       big, a.p, a.N, a.K);
+        if (rc) return rc;
+    }
+    return LQ_OK;
+}
+
 }  // namespace lqq
 
 using namespace lqq;
@@ -1610,6 +1770,32 @@ int w4a8_dequant_dump(const void *W_packed, const uint8_t *gparams, int N, int K
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(LQ_ERR_HIP, "dequant_dump launch failed: %s", hipGetErrorString(e));
     return LQ_OK;
+}
+
+int w4a8_grouped_gemm(int E, const int *row_offsets, int N, int K, int group, const int8_t *X,
+                      const float *act_scales, const void *W_packed, const uint8_t *gparams,
+                      const float *w_scales, uint16_t *Y, int32_t *ACC, void *hip_stream)
+{
+    if (E < 1 || E > kMaxExperts) return fail(LQ_ERR_INVALID, "E=%d out of range (1..%d)", E, kMaxExperts);
+    if (!shape_ok(N, K, group))
+        return fail(LQ_ERR_INVALID, "bad shape N=%d K=%d group=%d (need N%%64==0, K%%256==0, group 64|128, K<=131072)",
+                    N, K, group);
+    if (!row_offsets || row_offsets[0] != 0) return fail(LQ_ERR_INVALID, "row_offsets must start at 0");
+    for (int e = 0; e < E; ++e)
+        if (row_offsets[e + 1] < row_offsets[e]) return fail(LQ_ERR_INVALID, "row_offsets must not decrease");
+    if (row_offsets[E] == 0) return LQ_OK;
+    if (!Y && !ACC) return fail(LQ_ERR_INVALID, "no output pointer");
+    if (!X || !W_packed || !gparams) return fail(LQ_ERR_INVALID, "null input pointer");
+    if (Y && (!act_scales || !w_scales)) return fail(LQ_ERR_INVALID, "null scale pointer");
+    const uintptr_t bits = (uintptr_t)X | (uintptr_t)W_packed | (uintptr_t)gparams | (uintptr_t)act_scales |
+                           (uintptr_t)w_scales | (uintptr_t)Y | (uintptr_t)ACC;
+    if (bits & 15) return fail(LQ_ERR_ALIGN, "device pointers must be 16-byte aligned");
+    GroupedArgs a{};
+    a.E = E, a.N = N, a.K = K, a.group = group, a.row_offsets = row_offsets;
+    a.p = GroupedPtrs{X, act_scales, static_cast<const u32x4 *>(W_packed), gparams, w_scales,
+                      reinterpret_cast<__half *>(Y), ACC, (size_t)N * K / 32, (size_t)2 * N * K / group};
+    a.stream = static_cast<hipStream_t>(hip_stream);
+    return grouped_run(a);
 }
 
 }  // extern "C"

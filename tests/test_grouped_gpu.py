@@ -1,0 +1,115 @@
+"""GPU parity of the grouped (mixture-of-experts) W4A8 GEMM against the CPU oracle: INT32
+accumulators bit for bit, FP16 outputs within one ulp, for mixes of expert sizes that reach
+all three kernel families, empty experts, ragged tails, and the limits of the interface."""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import lqq_oracle as O
+from paper_2509_01229_amd import api
+from paper_2509_01229_amd import workloads as WL
+
+import gpu_helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+class Experts:
+    def __init__(self, E, N, K, g, seed):
+        import torch
+
+        self.E, self.N, self.K, self.g = E, N, K, g
+        Ws = [WL.make_weights(N, K, 0.02, seed=seed + e) for e in range(E)]
+        packs = [api.liquidquant_pack_weights(W, g) for W in Ws]
+        self.oracle = [O.quantize_weights(W, g) for W in Ws]
+        self.d_packed = torch.from_numpy(np.concatenate([p[0] for p in packs])).cuda()
+        self.d_gparams = torch.from_numpy(np.concatenate([p[1] for p in packs])).cuda()
+        self.w_scales = np.stack([p[2] for p in packs])
+        self.d_w_scales = torch.from_numpy(self.w_scales).cuda()
+
+    def check(self, rows, seed, what):
+        import torch
+
+        offs = np.concatenate([[0], np.cumsum(rows)]).astype(int)
+        M = int(offs[-1])
+        X, s_x = WL.make_activations(M, self.K, outlier_frac=0.01, seed=seed)
+        ACC_ref, _ = O.grouped_w4a8_gemm(X, s_x, offs, self.oracle)
+        s_w_rows = np.concatenate([np.repeat(self.oracle[e]["s_w"][None, :], rows[e], axis=0)
+                                   for e in range(self.E)]) if M else np.zeros((0, self.N), np.float32)
+        ref64 = ACC_ref.astype(np.float64) * s_x.astype(np.float64)[:, None] * s_w_rows.astype(np.float64)
+        dX, dsx = torch.from_numpy(X).cuda(), torch.from_numpy(s_x).cuda()
+        Y, ACC = api.w4a8_grouped_gemm(offs, dX, dsx, self.d_packed, self.d_gparams, self.d_w_scales,
+                                       self.N, self.K, self.g, want_y=True, want_acc=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(ACC.cpu().numpy(), ACC_ref), f"{what}: INT32 accumulators differ"
+        H.assert_fp16_close(Y.cpu().numpy(), ref64, what)
+        return dX, dsx, offs, ACC
+
+
+CASES = [
+    # E, N, K, g, rows per expert
+    (5, 256, 512, 64, [3, 0, 20, 40, 200]),        # all three families and an empty expert
+    (8, 448, 768, 128, [1, 16, 7, 0, 2, 16, 9, 4]),  # decode-like: every expert small
+    (3, 320, 1024, 64, [130, 77, 300]),            # only tiled experts, ragged rows, N tail
+    (4, 128, 256, 64, [32, 17, 33, 31]),           # around the family boundaries, one k unit
+    (2, 64, 2048, 128, [0, 5]),                    # smallest N, leading empty expert
+]
+
+
+@pytest.mark.parametrize("E,N,K,g,rows", CASES)
+def test_grouped_gemm_matches_oracle(E, N, K, g, rows):
+    _say(f"grouped E={E} N={N} K={K} g={g} rows={rows}")
+    ex = Experts(E, N, K, g, seed=N + K)
+    ex.check(rows, seed=E, what=f"rows={rows}")
+
+
+def test_grouped_equals_separate_calls_and_many_experts():
+    import torch
+
+    E, N, K, g = 64, 64, 256, 64
+    _say("grouped E=64")
+    ex = Experts(E, N, K, g, seed=500)
+    rng = np.random.default_rng(3)
+    rows = rng.integers(0, 40, size=E).tolist()
+    dX, dsx, offs, ACC = ex.check(rows, seed=9, what="64 experts")
+    cb, gb = api.liquidquant_packed_size(N, K, g)
+    for e in (0, 17, 63):
+        r0, r1 = offs[e], offs[e + 1]
+        if r1 == r0:
+            continue
+        one = api.w4a8_gemm_i32(dX[r0:r1].contiguous(), ex.d_packed[e * cb:(e + 1) * cb],
+                                ex.d_gparams[e * gb:(e + 1) * gb], N, K, g)
+        torch.cuda.synchronize()
+        assert torch.equal(one, ACC[r0:r1])
+
+
+def test_grouped_interface_limits():
+    import torch
+
+    N, K, g = 64, 256, 64
+    ex = Experts(1, N, K, g, seed=1)
+    X = torch.zeros((4, K), dtype=torch.int8, device="cuda")
+    sx = torch.ones(4, dtype=torch.float32, device="cuda")
+    # no tokens at all: a successful no-op
+    Y, _ = api.w4a8_grouped_gemm([0, 0], X[:0], sx[:0], ex.d_packed, ex.d_gparams, ex.d_w_scales, N, K, g)
+    assert tuple(Y.shape) == (0, N)
+    L = api.lib()
+    import ctypes
+
+    def raw(E, offs):
+        arr = (ctypes.c_int * len(offs))(*offs)
+        return L.w4a8_grouped_gemm(E, arr, N, K, g, ctypes.c_void_p(X.data_ptr()), ctypes.c_void_p(sx.data_ptr()),
+                                   ctypes.c_void_p(ex.d_packed.data_ptr()), ctypes.c_void_p(ex.d_gparams.data_ptr()),
+                                   ctypes.c_void_p(ex.d_w_scales.data_ptr()), None, None, None)
+
+    assert raw(65, [0] * 66) == -1          # too many experts
+    assert raw(0, [0]) == -1
+    assert raw(1, [1, 4]) == -1             # must start at 0
+    assert raw(2, [0, 3, 2]) == -1          # must not decrease
+    assert raw(1, [0, 4]) == -1             # no output pointer
