@@ -1480,6 +1480,9 @@ static const Variant kVariants[] = {
     {"stream16_f2_w8_s1", &launch_stream16<2, 8, 1>, 16, 2, 1},
     {"stream16_f2_w8_s2", &launch_stream16<2, 8, 2>, 16, 2, 1},
     {"stream16_f2_w8_s4", &launch_stream16<2, 8, 4>, 16, 2, 1},
+    {"stream16_f1_w8_s1", &launch_stream16<1, 8, 1>, 16, 1, 1},
+    {"stream16_f2_w16_s1", &launch_stream16<2, 16, 1>, 16, 2, 1},
+    {"stream16_f1_w16_s1", &launch_stream16<1, 16, 1>, 16, 1, 1},
     {"stream16_f1_w8_u4", &launch_stream16<1, 8, 0, 0, 4>, 16, 1, 8},
     {"stream16_f1_w8_u4_s1", &launch_stream16<1, 8, 1, 0, 4>, 16, 1, 8},
     {"stream16_f1_w8_u4_s2", &launch_stream16<1, 8, 2, 0, 4>, 16, 1, 8},
