@@ -137,20 +137,24 @@ __device__ __forceinline__ Place grid_place()
     return Place{(int)blockIdx.x, (int)gridDim.x, (int)blockIdx.y, (int)gridDim.y};
 }
 
-template <int F, bool G128>
+template <int F, int MF, bool G128>
 struct StreamRegs {
     u32x4 w[F][2];
     UnitParams<G128> p[F];
-    u32x4 x[4];
+    u32x4 x[MF][4];
 };
 
-template <int F, int NW, bool G128>
+// MF = row fragments of 32 per wave: 1 for M <= 32, 2 for M <= 64 (the weights are still
+// streamed once; the dequantised operand of a chunk feeds MF MFMAs).  Four fragments were
+// measured too: the X fragments, which every block reads for itself from L2, then outweigh
+// the weights four to one and the 128 x 256 tiles with X shared through LDS are faster.
+template <int F, int NW, int MF, bool G128>
 __device__ __forceinline__ void stream_block(
     const Place pl, int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
     __half *__restrict__ Y, int32_t *__restrict__ ACC, int32_t *__restrict__ partials)
 {
-    extern __shared__ __attribute__((aligned(16))) int red[];  // [NW][F * rmax][64]
+    extern __shared__ __attribute__((aligned(16))) int red[];  // [NW][F * MF * rmax][64]
     __shared__ int s_last;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane & 31, kb = lane >> 5;
@@ -160,18 +164,23 @@ __device__ __forceinline__ void stream_block(
     const int S = pl.S, ks = pl.ks;
     const int u_begin = (int)((long long)units * ks / S), u_end = (int)((long long)units * (ks + 1) / S);
 
-    v16i acc[F];
+    v16i acc[F][MF];
 #pragma unroll
     for (int f = 0; f < F; ++f)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[f][r] = 0;
+        for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[f][mf][r] = 0;
 
     // X fragments come straight from global memory (L2): lane (j, kb) needs 16 bytes of row
-    // j per k-step.  Lanes past M read row M-1 (one more hit on a line that is fetched
-    // anyway); an output row depends only on its own X row and rows past M are not stored.
-    const int8_t *xrow = X + (size_t)min(j, M - 1) * K + 16 * kb;
+    // j (+ 32 per further fragment) per k-step.  Lanes past M read row M-1 (one more hit on
+    // a line that is fetched anyway); an output row depends only on its own X row and rows
+    // past M are not stored.
+    const int8_t *xrow[MF];
+#pragma unroll
+    for (int mf = 0; mf < MF; ++mf) xrow[mf] = X + (size_t)min(j + 32 * mf, M - 1) * K + 16 * kb;
 
-    auto load_unit = [&](int u, StreamRegs<F, G128> &r) {
+    auto load_unit = [&](int u, StreamRegs<F, MF, G128> &r) {
 #pragma unroll
         for (int f = 0; f < F; ++f) {
             const u32x4 *base = Wp + ((size_t)(t0 + f) * chunks_per_tile + 2 * (size_t)u) * 64 + lane;
@@ -180,10 +189,12 @@ __device__ __forceinline__ void stream_block(
             r.p[f].load(gp, (size_t)(t0 + f) * units + u, j);
         }
 #pragma unroll
-        for (int ks4 = 0; ks4 < 4; ++ks4)
-            r.x[ks4] = *reinterpret_cast<const u32x4 *>(xrow + (size_t)u * 128 + 32 * ks4);
+        for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+            for (int ks4 = 0; ks4 < 4; ++ks4)
+                r.x[mf][ks4] = *reinterpret_cast<const u32x4 *>(xrow[mf] + (size_t)u * 128 + 32 * ks4);
     };
-    auto compute_unit = [&](const StreamRegs<F, G128> &r) {
+    auto compute_unit = [&](const StreamRegs<F, MF, G128> &r) {
 #pragma unroll
         for (int f = 0; f < F; ++f)
 #pragma unroll
@@ -192,15 +203,18 @@ __device__ __forceinline__ void stream_block(
                 r.p[f].get(c, s2, a4);
                 v4i lo, hi;
                 dequant_chunk(r.w[f][c], s2, a4, lo, hi);
-                acc[f] = mfma_i8(__builtin_bit_cast(v4i, r.x[2 * c]), lo, acc[f]);
-                acc[f] = mfma_i8(__builtin_bit_cast(v4i, r.x[2 * c + 1]), hi, acc[f]);
+#pragma unroll
+                for (int mf = 0; mf < MF; ++mf) {
+                    acc[f][mf] = mfma_i8(__builtin_bit_cast(v4i, r.x[mf][2 * c]), lo, acc[f][mf]);
+                    acc[f][mf] = mfma_i8(__builtin_bit_cast(v4i, r.x[mf][2 * c + 1]), hi, acc[f][mf]);
+                }
             }
     };
 
     // Register double buffering: the loads of the next unit are in flight while the
     // current one is dequantised and multiplied.
     LQ_STAMP(0);
-    StreamRegs<F, G128> cur, nxt;
+    StreamRegs<F, MF, G128> cur, nxt;
     int u = u_begin + wave;
     if (u < u_end) load_unit(u, cur);
     for (; u < u_end; u += NW) {
@@ -211,16 +225,20 @@ __device__ __forceinline__ void stream_block(
     }
     LQ_STAMP(2);
 
-    // In-block split-K reduction (integer, order independent).  Only the accumulator
-    // elements that hold rows < M take part: rows of element r lie in [8*(r/4), 8*(r/4)+8).
-    const int rmax = 4 * ((M + 7) >> 3);
+    // In-block split-K reduction (integer, order independent).  With one row fragment only
+    // the accumulator elements that hold rows < M take part: rows of element r lie in
+    // [8*(r/4), 8*(r/4)+8).  Value v = (f * MF + mf) * rmax + r of lane l is row
+    // 32*mf + acc_row(r, l), slot l%32 of tile t0 + f.
+    const int rmax = MF == 1 ? 4 * ((M + 7) >> 3) : 16;
 #pragma unroll
     for (int f = 0; f < F; ++f)
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-            if (r < rmax) red[((wave * F + f) * rmax + r) * 64 + lane] = acc[f][r];
+        for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (r < rmax) red[((wave * F * MF + f * MF + mf) * rmax + r) * 64 + lane] = acc[f][mf][r];
     __syncthreads();
-    const int vals = F * rmax;
+    const int vals = F * MF * rmax;
     auto block_sum = [&](int idx) {
         int sum = 0;
 #pragma unroll
@@ -229,9 +247,10 @@ __device__ __forceinline__ void stream_block(
     };
     auto finish = [&](int idx, int sum) {  // epilogue of one output (Sec. 4, Sec. 5.3)
         const int v = idx >> 6, l = idx & 63;
-        const int m = acc_row(v % rmax, l);
+        const int fm = v / rmax;
+        const int m = 32 * (fm % MF) + acc_row(v % rmax, l);
         if (m < M) {
-            const int n = channel_of(t0 + v / rmax, l & 31);
+            const int n = channel_of(t0 + fm / MF, l & 31);
             if (ACC) ACC[(size_t)m * N + n] = sum;
             if (Y) Y[(size_t)m * N + n] = scale_to_half(sum, sx[m], sw[n]);
         }
@@ -269,13 +288,13 @@ __device__ __forceinline__ void stream_block(
     LQ_STAMP(3);
 }
 
-template <int F, int NW, bool G128>
+template <int F, int NW, int MF, bool G128>
 __global__ __launch_bounds__(NW * 64) void w4a8_stream_kernel(
     int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
     __half *__restrict__ Y, int32_t *__restrict__ ACC, int32_t *__restrict__ partials)
 {
-    stream_block<F, NW, G128>(grid_place(), M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+    stream_block<F, NW, MF, G128>(grid_place(), M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
 }
 
 // ------------------------------------------------------------------------------------
@@ -1216,7 +1235,7 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream_grouped_kernel(const Grou
 {
     const int i = blockIdx.x / groups, gx = blockIdx.x % groups;
     const int e = g.expert[i], r0 = g.row_off[i];
-    stream_block<2, NW, G128>(Place{gx, groups, 0, 1}, g.rows[i], N, K, p.X + (size_t)r0 * K, p.sx + r0,
+    stream_block<2, NW, 1, G128>(Place{gx, groups, 0, 1}, g.rows[i], N, K, p.X + (size_t)r0 * K, p.sx + r0,
                               p.Wp + e * p.w_stride, p.gp + e * p.gp_stride, p.sw + (size_t)e * N,
                               p.Y ? p.Y + (size_t)r0 * N : nullptr, p.ACC ? p.ACC + (size_t)r0 * N : nullptr,
                               nullptr);
@@ -1281,45 +1300,63 @@ static int stream_split(int N, int K, int F, int NW)
     return std::max(1, s);
 }
 
-static size_t stream_ws_bytes(int M, int N, int S)
+static size_t stream_ws_bytes(int M, int N, int S, int MF = 1)
 {
     if (S <= 1) return 0;
-    const int rmax = 4 * ((M + 7) / 8);
-    return (size_t)S * (N / 32) * rmax * 64 * sizeof(int32_t);
+    const int rmax = MF == 1 ? 4 * ((M + 7) / 8) : 16;
+    return (size_t)S * (N / 32) * MF * rmax * 64 * sizeof(int32_t);
 }
 
-// SPLIT: 0 = choose with stream_split(), otherwise the fixed number of K slices.
-template <int F, int NW, int SPLIT>
-static int launch_stream(const Args &a)
+// S = requested number of K slices; `named` = the variant names its split (then a missing
+// workspace is an error instead of a fall-back to one slice).
+template <int F, int NW, int MF>
+static int launch_stream_as(const Args &a, int S, bool named)
 {
-    if (a.M > 32) return fail(LQ_ERR_INVALID, "stream variants handle M <= 32, got %d", a.M);
+    if (a.M > 32 * MF) return fail(LQ_ERR_INVALID, "this stream variant handles M <= %d, got %d", 32 * MF, a.M);
     if ((a.N / 32) % F != 0) return fail(LQ_ERR_INVALID, "N/32 not a multiple of F=%d", F);
     const int groups = a.N / (32 * F);
-    int S = SPLIT ? SPLIT : stream_split(a.N, a.K, F, NW);
-    S = std::min(S, a.K / 128);
+    S = std::max(1, std::min(S, a.K / 128));
     if (S > 1 && groups > kMaxTicketGroups) S = 1;
-    size_t need = stream_ws_bytes(a.M, a.N, S);
+    size_t need = stream_ws_bytes(a.M, a.N, S, MF);
     if (need > 0 && (!a.ws || a.ws_bytes < need)) {
-        if (SPLIT)  // a named split cannot run without its workspace; the automatic one falls back
+        if (named)
             return fail(LQ_ERR_WORKSPACE, "split-K needs %zu bytes of workspace, got %zu", need,
                         a.ws ? a.ws_bytes : 0);
         S = 1;
         need = 0;
     }
     const dim3 grid(groups, S), block(NW * 64);
-    const int rmax = 4 * ((a.M + 7) / 8);
-    const size_t lds_bytes = (size_t)NW * F * rmax * 64 * sizeof(int);
+    const int rmax = MF == 1 ? 4 * ((a.M + 7) / 8) : 16;
+    const size_t lds_bytes = (size_t)NW * F * MF * rmax * 64 * sizeof(int);
     int32_t *partials = static_cast<int32_t *>(a.ws);
     if (a.group == 128) {
-        if (int rc = allow_lds(&w4a8_stream_kernel<F, NW, true>, lds_bytes)) return rc;
-        hipLaunchKernelGGL((w4a8_stream_kernel<F, NW, true>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
+        if (int rc = allow_lds(&w4a8_stream_kernel<F, NW, MF, true>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_stream_kernel<F, NW, MF, true>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
                            a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials);
     } else {
-        if (int rc = allow_lds(&w4a8_stream_kernel<F, NW, false>, lds_bytes)) return rc;
-        hipLaunchKernelGGL((w4a8_stream_kernel<F, NW, false>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
+        if (int rc = allow_lds(&w4a8_stream_kernel<F, NW, MF, false>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_stream_kernel<F, NW, MF, false>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
                            a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials);
     }
     return LQ_OK;
+}
+
+// SPLIT: 0 = choose with stream_split(), otherwise the fixed number of K slices.
+template <int F, int NW, int SPLIT, int MF = 1>
+static int launch_stream(const Args &a)
+{
+    return launch_stream_as<F, NW, MF>(a, SPLIT ? SPLIT : stream_split(a.N, a.K, F, NW), SPLIT != 0);
+}
+
+// 64-row stream kernel with the block shape chosen from N.  Measured: its 8-wave blocks
+// (about 140 / 190 registers) run one per CU, so the best grid is the largest one of at
+// most 256 blocks: one tile per block while N / 32 <= 256, else two; K is split across
+// blocks while that still fits.
+static int launch_stream_m64(const Args &a)
+{
+    const int tiles = a.N / 32;
+    if (tiles <= 256) return launch_stream_as<1, 8, 2>(a, std::min(4, 256 / tiles), false);
+    return launch_stream_as<2, 8, 2>(a, std::min(4, 512 / tiles), false);
 }
 
 template <int F, int NW, int SPLIT, int ABL = 0, int UU = 1>
@@ -1475,6 +1512,13 @@ static const Variant kVariants[] = {
     {"stream_f2_w8_s1", &launch_stream<2, 8, 1>, 32, 2, 1},
     {"stream_f2_w8_s2", &launch_stream<2, 8, 2>, 32, 2, 1},
     {"stream_f2_w8_s4", &launch_stream<2, 8, 4>, 32, 2, 1},
+    {"stream_m64", &launch_stream_m64, 64, 2, 1},
+    {"stream_m64_f2_w8", &launch_stream<2, 8, 0, 2>, 64, 2, 1},
+    {"stream_m64_f2_w8_s1", &launch_stream<2, 8, 1, 2>, 64, 2, 1},
+    {"stream_m64_f2_w8_s2", &launch_stream<2, 8, 2, 2>, 64, 2, 1},
+    {"stream_m64_f2_w8_s4", &launch_stream<2, 8, 4, 2>, 64, 2, 1},
+    {"stream_m64_f1_w8_s1", &launch_stream<1, 8, 1, 2>, 64, 1, 1},
+    {"stream_m64_f1_w8_s2", &launch_stream<1, 8, 2, 2>, 64, 1, 1},
     {"stream16_f2_w8", &launch_stream16<2, 8, 0>, 16, 2, 1},
     {"stream16_f2_w4", &launch_stream16<2, 4, 0>, 16, 2, 1},
     {"stream16_f2_w8_s1", &launch_stream16<2, 8, 1>, 16, 2, 1},
@@ -1550,6 +1594,9 @@ static int select_variant(int M, int N, int K)
         return find_variant(N / 64 >= 384 ? "stream16_f2_w4" : "stream16_f2_w8");
     }
     if (M <= 32) return find_variant("stream_f2_w8");
+    // up to 64 rows the weights are still best streamed once per block column unless N alone
+    // fills the chip with 128 x 256 tiles
+    if (M <= 64 && N / 32 <= 512) return find_variant("stream_m64");
     return find_variant("duo_m128");
 }
 
@@ -1693,6 +1740,7 @@ size_t w4a8_gemm_workspace_size(int M, int N, int K, int group)
     const int tiles = ((M + 127) / 128) * ((N + 255) / 256);
     size_t need = tiles >= 192 ? 0 : duo_ws_bytes(M, N, 8);
     if (M <= 32) need = std::max(need, stream_ws_bytes(M, N, 16));
+    if (M <= 64) need = std::max(need, stream_ws_bytes(M, N, 16, 2));
     if (M <= 16) need = std::max(need, (size_t)16 * (N / 32) * 8 * 64 * sizeof(int32_t));
     return need;
 }

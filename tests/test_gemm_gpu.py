@@ -69,7 +69,10 @@ SMALL = [
     (16, 320, 768, 128),     # N not a multiple of 256
     (13, 192, 1024, 64),     # ragged M inside one fragment
     (31, 128, 512, 128),
+    (50, 192, 768, 64),      # two row fragments of the 64-row stream kernel, ragged
+    (64, 128, 512, 128),     # exactly 64 rows
     (77, 448, 768, 64),      # ragged M over several row tiles, N tail
+    (128, 64, 512, 64),      # exactly 128 rows: four row fragments of the stream kernel
     (200, 256, 256, 64),     # one k unit only
     (130, 576, 1280, 128),
 ]
