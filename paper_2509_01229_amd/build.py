@@ -20,6 +20,8 @@ FLAGS = [
     # keep hipcc from forming packed-FP32 instructions out of ordinary float code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function", "-Wno-unknown-pragmas",
+    # per-kernel register / scratch report on stderr, checked below
+    "-Rpass-analysis=kernel-resource-usage",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
     "-lpthread",
 ]
@@ -34,9 +36,34 @@ def build_library(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     if res.returncode != 0:
         sys.stderr.write(res.stdout + res.stderr)
         raise RuntimeError("hipcc failed building libliquidgemm.so")
-    if verbose and res.stderr:
-        sys.stderr.write(res.stderr)
+    usage = kernel_resource_usage(res.stderr)
+    spilling = {k: v for k, v in usage.items() if v.get("ScratchSize [bytes/lane]", 0) > 0}
+    if spilling and "-DLQ_ABLATE" not in extra_flags:
+        raise RuntimeError("kernels must not use scratch memory, but these do: "
+                           + ", ".join(f"{k} ({v['ScratchSize [bytes/lane]']} B/lane)" for k, v in spilling.items()))
+    if verbose:
+        other = "\n".join(l for l in res.stderr.splitlines() if "kernel-resource-usage" not in l
+                          and not l.lstrip().startswith(("|", "^")) and l.strip())
+        if other:
+            sys.stderr.write(other + "\n")
+        print(f"{len(usage)} kernels, max VGPRs {max(v.get('VGPRs', 0) for v in usage.values())}, no scratch")
     return out
+
+
+def kernel_resource_usage(stderr_text: str) -> dict:
+    """Parse hipcc's -Rpass-analysis=kernel-resource-usage remarks: {kernel: {field: int}}."""
+    import re
+
+    usage, cur = {}, None
+    for line in stderr_text.splitlines():
+        m = re.search(r"remark:\s+Function Name: (\S+)", line)
+        if m:
+            cur = usage.setdefault(m.group(1), {})
+            continue
+        m = re.search(r"remark:\s+([A-Za-z][^:]*): (\d+) \[-Rpass-analysis", line)
+        if m and cur is not None:
+            cur[m.group(1).strip()] = int(m.group(2))
+    return usage
 
 
 if __name__ == "__main__":

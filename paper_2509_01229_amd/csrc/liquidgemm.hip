@@ -3,24 +3,30 @@
 // Two kernel families share the packed layout of lqq_layout.h and the dequantisation of
 // lqq_device.h (paper Sec. 5.3):
 //
-//   stream  (M <= 32): the memory-bound regime of the paper's cost model (Sec. 3.2,
+//   stream  (M <= 64): the memory-bound regime of the paper's cost model (Sec. 3.2,
 //           T_LD dominates).  A block owns F tiles of 32 output channels; its NW waves
 //           split K between them (in-block split-K), stream the packed weights straight
 //           from HBM into registers with one 16-byte load per lane, dequantise, feed the
 //           MFMA, and reduce their INT32 partials through LDS -- integer sums, so the
-//           result does not depend on the order.  No workspace, one launch.
+//           result does not depend on the order.  stream16 is the same on the 16-row MFMA
+//           shape for M <= 16.  Optional grid-level split-K through a workspace.
 //
-//   tile    (larger M): the compute-bound regime (T_DQ + T_MMA dominates).  A block of 4
-//           waves owns 32*MF rows of X and 256 output channels; the X tile is staged in
-//           LDS (double buffered) and shared by the waves, each wave keeps its own 64
-//           channels' weights in registers (global -> VGPR, never through LDS: the
-//           dequantised operand is consumed by the MFMA of the same wave, which is the
-//           point of the paper's implicit fine-grained pipeline, Sec. 5.1) and reuses
-//           every dequantised fragment for MF MFMAs.
+//   tiled   (larger M): the compute-bound regime (T_DQ + T_MMA dominates).  A block owns
+//           128 rows of X and 256 output channels; the X tile is staged in LDS (double
+//           buffered) and shared by the waves, each wave keeps its own 64 channels'
+//           weights in registers (global -> VGPR, never through LDS: the dequantised
+//           operand is consumed by the MFMA of the same wave, which is the point of the
+//           paper's implicit fine-grained pipeline, Sec. 5.1) and reuses every dequantised
+//           fragment for 4 MFMAs.  `duo` is the kernel that is dispatched (two waves per
+//           SIMD); `tile` is its plain predecessor, kept as a named variant.
 //
-// Both compute Y = X W^T with the weights on the B operand of v_mfma_i32_32x32x32_i8, so
-// that a lane ends up with 2 adjacent output channels of one row (the tile interleave of
-// the layout) and a half-wave writes a full 128-byte line of FP16.
+// All compute Y = X W^T with the weights on the B operand of the INT8 MFMA, so that a lane
+// ends up with 2 adjacent output channels of one row (the tile interleave of the layout)
+// and a half-wave writes a full 128-byte line of FP16.
+//
+// Every kernel here must compile without scratch memory (the build checks it): register
+// spills next to the divergent single-thread sections of the split-K protocol are not
+// something to rely on.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
@@ -109,14 +115,18 @@ __device__ unsigned int g_splitk_tickets[kMaxTicketGroups];
 // Device-scope (write-through / cache-bypassing) 16-byte accesses for the exchange of
 // split-K partial tiles between blocks that may sit on different XCDs: the sc1 forms of
 // the plain global load and store, which is what a relaxed agent-scope atomic compiles to.
+// OFF = constant byte offset (0 .. 4095) folded into the instruction, so that the four
+// accesses of one accumulator fragment share one address register pair.
+template <int OFF = 0>
 __device__ __forceinline__ void store_sc1_x4(int32_t *p, const v4i v)
 {
-    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off offset:%2 sc1" ::"v"(p), "v"(v), "n"(OFF) : "memory");
 }
+template <int OFF = 0>
 __device__ __forceinline__ v4i load_sc1_x4(const int32_t *p)
 {
     v4i v;
-    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
+    asm volatile("global_load_dwordx4 %0, %1, off offset:%2 sc1" : "=v"(v) : "v"(p), "n"(OFF) : "memory");
     return v;
 }
 __device__ __forceinline__ void wait_vmcnt0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
@@ -557,7 +567,7 @@ __device__ __forceinline__ void block_coords(int blocks_m, int blocks_n, int &bm
 }
 
 template <int MF, bool G128>
-__global__ __launch_bounds__(256, (MF <= 4 ? 2 : 1)) void w4a8_tile_kernel(
+__global__ __launch_bounds__(256, 2) void w4a8_tile_kernel(
     int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
     __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n)
@@ -675,213 +685,13 @@ __global__ __launch_bounds__(256, (MF <= 4 ? 2 : 1)) void w4a8_tile_kernel(
     store_tile<MF>(acc, M, N, m0, 64 * ng + 2 * j, lane, sx, sw, Y, ACC);
 }
 
-// ------------------------------------------------------------------------------------
-// pipe kernel: the tile kernel with an explicit software pipeline for one wave per SIMD.
-//
-// Same block tile ((32*MF) x 256, 4 waves, each 64 channels) and LDS layout as the tile
-// kernel.  A stage (128 k) is cut into 4 groups (chunk c, half h) of 2*MF MFMAs:
-//   * the X fragments of group g+1 are read from LDS while the MFMAs of group g run;
-//   * the dequantisation of chunk 1 is issued among the MFMAs of group 0, that of chunk 0
-//     of the next stage among those of group 2, so the VALU work hides under the matrix
-//     pipe of the same wave (the intra-wave form of the paper's implicit pipeline,
-//     Sec. 5.1: no hand-off between dequantisation and MMA);
-//   * global loads run ahead: X pieces wait two stages in registers before they are
-//     written to the other LDS buffer at the top of a stage, W chunks are re-issued into
-//     their registers as soon as their last dequantisation is done;
-//   * the single barrier of a stage sits before its last group and waits only for LDS
-//     traffic, never for outstanding global loads.
-// ------------------------------------------------------------------------------------
+// Block barrier that orders LDS traffic only: __syncthreads() would also wait for every
+// outstanding global load (vmcnt(0)), which is exactly what the prefetches must not do.
 __device__ __forceinline__ void lds_barrier()
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-// Ask the scheduler for NM repetitions of {1 MFMA, NV VALU, at most one LDS read, one LDS
-// write and one global load}: NR reads go behind the first NR MFMAs, NWR writes and NG
-// loads behind every other MFMA, so that no wave sends a burst of memory instructions.
-template <int NM, int NV, int NR, int NWR, int NG>
-__device__ __forceinline__ void interleave()
-{
-#pragma unroll
-    for (int i = 0; i < NM; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (NV > 0) __builtin_amdgcn_sched_group_barrier(0x002, NV, 0);
-        if (i < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        if ((i & 1) == 0 && (i >> 1) < NWR) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-        if ((i & 1) == 1 && (i >> 1) < NG) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-    }
-}
-
-// ABL (bit mask, experiments only; 0 in every shipped variant): 1 = no X global loads / LDS
-// stores after the prologue, 2 = no W reloads, 4 = no LDS fragment reads, 8 = no
-// dequantisation, 16 = no barrier.  Results are wrong for ABL != 0.
-template <int MF, bool G128, int ABL = 0>
-__global__ __launch_bounds__(256, (MF <= 4 ? 2 : 1)) void w4a8_pipe_kernel(
-    int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
-    const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
-    __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n)
-{
-    constexpr int WM = 32 * MF;
-    constexpr int XP = MF;
-    constexpr int STAGE = WM * kTilePitch;
-    extern __shared__ __attribute__((aligned(16))) int8_t lds[];
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int j = lane & 31, kb = lane >> 5;
-    int bm, bn;
-    block_coords(blocks_m, blocks_n, bm, bn);
-    const int m0 = bm * WM;
-    const int ng = bn * 4 + wave;
-    const bool active = ng < (N >> 6);
-    const int t0 = 2 * (active ? ng : (N >> 6) - 1);
-    const int stages = K >> 7;  // even, since K % 256 == 0
-    const int chunks_per_tile = K >> 6;
-
-    v16i acc[MF][2];
-#pragma unroll
-    for (int mf = 0; mf < MF; ++mf)
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mf][t][r] = 0;
-
-    // per-thread constant parts of the addresses
-    const int8_t *xg[XP];
-    int xl[XP];
-#pragma unroll
-    for (int i = 0; i < XP; ++i) {
-        const int q = tid + 256 * i;
-        const int row = q >> 3, col = q & 7;
-        xg[i] = X + (size_t)min(m0 + row, M - 1) * K + 16 * col;  // rows past M read row M-1
-        xl[i] = row * kTilePitch + 16 * col;
-    }
-    const u32x4 *wg[2];
-    const uint8_t *pg[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        wg[t] = Wp + (size_t)(t0 + t) * chunks_per_tile * 64 + lane;
-        pg[t] = gp + ((size_t)(t0 + t) * stages * 32 + j) * (G128 ? 2 : 4);
-    }
-    const int8_t *xs = lds + j * kTilePitch + 16 * kb;  // this lane's fragment row in a stage
-
-    u32x4 xr[2][XP];          // X pieces in flight; set p holds a stage of parity p
-    u32x4 wr[2][2][2];        // W chunks: [stage parity][tile][chunk]
-    UnitParams<G128> pr[2][2];
-    v4i bf[2][2][2];          // dequantised B fragments: [chunk][tile][half]
-    v4i af[2][MF];            // X fragments of the current / next group
-
-    auto load_x = [&](int s, u32x4 (&dst)[XP]) {
-        s = min(s, stages - 1);  // past the end: harmless reload of the last stage
-#pragma unroll
-        for (int i = 0; i < XP; ++i) dst[i] = *reinterpret_cast<const u32x4 *>(xg[i] + (size_t)s * 128);
-    };
-    auto store_x = [&](int buf, const u32x4 (&src)[XP]) {
-#pragma unroll
-        for (int i = 0; i < XP; ++i) *reinterpret_cast<u32x4 *>(lds + buf * STAGE + xl[i]) = src[i];
-    };
-    auto load_w = [&](int s, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
-        s = min(s, stages - 1);
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            w[t][0] = wg[t][(size_t)s * 128];
-            w[t][1] = wg[t][(size_t)s * 128 + 64];
-            if (G128)
-                p[t].raw = *reinterpret_cast<const uint16_t *>(pg[t] + (size_t)s * 64);
-            else
-                p[t].raw = *reinterpret_cast<const uint32_t *>(pg[t] + (size_t)s * 128);
-        }
-    };
-    auto dequant = [&](const u32x4 (&w)[2][2], const UnitParams<G128> (&p)[2], int c, v4i (&b)[2][2]) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            uint32_t s2, a4;
-            p[t].get(c, s2, a4);
-            dequant_chunk(w[t][c], s2, a4, b[t][0], b[t][1]);
-        }
-    };
-    // X fragments of group (c, h) of the stage in LDS buffer `buf`
-    auto read_group = [&](int buf, int c, int h, v4i (&a)[MF]) {
-#pragma unroll
-        for (int mf = 0; mf < MF; ++mf)
-            a[mf] = *reinterpret_cast<const v4i *>(xs + buf * STAGE + mf * 32 * kTilePitch + 64 * c + 32 * h);
-    };
-    auto mma_group = [&](const v4i (&a)[MF], const v4i (&b)[2][2], int h) {
-#pragma unroll
-        for (int mf = 0; mf < MF; ++mf)
-#pragma unroll
-            for (int t = 0; t < 2; ++t) acc[mf][t] = mfma_i8(a[mf], b[t][h], acc[mf][t]);
-    };
-
-    // One stage.  xs_set holds X(s+1) on entry and X(s+3) on exit; w_cur = W(s) on entry and
-    // W(s+2) on exit; w_nxt = W(s+1).  af[0] holds group 0 of this stage on entry.
-    // X pieces [lo, hi) of xs_set: write X(s+1) to the other buffer, then refill with X(s+3)
-    auto xfer_x = [&](int s, int buf, u32x4 (&set)[XP], int lo, int hi) {
-        const int sl = min(s + 3, stages - 1);  // past the end: harmless reload of the last stage
-#pragma unroll
-        for (int i = 0; i < XP; ++i)
-            if (i >= lo && i < hi) {
-                *reinterpret_cast<u32x4 *>(lds + (buf ^ 1) * STAGE + xl[i]) = set[i];
-                set[i] = *reinterpret_cast<const u32x4 *>(xg[i] + (size_t)sl * 128);
-            }
-    };
-    constexpr int XB1 = (XP + 2) / 3, XB2 = (2 * XB1 < XP) ? 2 * XB1 : XP;  // piece ranges of groups 0..2
-    constexpr int NM = 2 * MF;                                             // MFMAs per group
-
-    auto stage = [&](int s, u32x4 (&xs_set)[XP], u32x4 (&w_cur)[2][2], UnitParams<G128> (&p_cur)[2],
-                     u32x4 (&w_nxt)[2][2], UnitParams<G128> (&p_nxt)[2], int buf) {
-        // group 0 = (chunk 0, half 0); dequantise chunk 1 underneath
-        if (!(ABL & 1)) xfer_x(s, buf, xs_set, 0, XB1);
-        if (!(ABL & 4)) read_group(buf, 0, 1, af[1]);
-        if (!(ABL & 8)) dequant(w_cur, p_cur, 1, bf[1]);
-        mma_group(af[0], bf[0], 0);
-        interleave<NM, 4, MF, XB1, XB1>();
-        __builtin_amdgcn_sched_barrier(0);
-        // group 1 = (chunk 0, half 1); W(s) is no longer needed: fetch W(s+2)
-        if (!(ABL & 1)) xfer_x(s, buf, xs_set, XB1, XB2);
-        if (!(ABL & 2)) load_w(s + 2, w_cur, p_cur);
-        if (!(ABL & 4)) read_group(buf, 1, 0, af[0]);
-        mma_group(af[1], bf[0], 1);
-        interleave<NM, 1, MF, XB2 - XB1, XB2 - XB1 + 6>();
-        __builtin_amdgcn_sched_barrier(0);
-        // group 2 = (chunk 1, half 0); dequantise chunk 0 of stage s+1 underneath
-        if (!(ABL & 1)) xfer_x(s, buf, xs_set, XB2, XP);
-        if (!(ABL & 4)) read_group(buf, 1, 1, af[1]);
-        if (!(ABL & 8)) dequant(w_nxt, p_nxt, 0, bf[0]);
-        mma_group(af[0], bf[1], 0);
-        interleave<NM, 4, MF, XP - XB2, XP - XB2>();
-        __builtin_amdgcn_sched_barrier(0);
-        // group 3 = (chunk 1, half 1); after the barrier the next stage's buffer is readable
-        if (!(ABL & 16)) lds_barrier();
-        if (!(ABL & 4)) read_group(buf ^ 1, 0, 0, af[0]);
-        mma_group(af[1], bf[1], 1);
-        interleave<NM, 0, MF, 0, 0>();
-        __builtin_amdgcn_sched_barrier(0);
-    };
-
-    // prologue: X(0) -> LDS, X(1) and X(2) in registers, W(0), W(1) in registers
-    load_x(0, xr[0]);
-    load_w(0, wr[0], pr[0]);
-    load_w(1, wr[1], pr[1]);
-    load_x(1, xr[1]);
-    store_x(0, xr[0]);
-    load_x(2, xr[0]);
-    dequant(wr[0], pr[0], 0, bf[0]);
-    dequant(wr[0], pr[0], 1, bf[1]);
-    lds_barrier();
-    read_group(0, 0, 0, af[0]);
-    read_group(0, 0, 1, af[1]);
-    __builtin_amdgcn_sched_barrier(0);
-
-    for (int s = 0; s < stages; s += 2) {
-        stage(s, xr[1], wr[0], pr[0], wr[1], pr[1], 0);
-        stage(s + 1, xr[0], wr[1], pr[1], wr[0], pr[0], 1);
-    }
-
-    if (!active) return;
-    store_tile<MF>(acc, M, N, m0, 64 * ng + 2 * j, lane, sx, sw, Y, ACC);
 }
 
 // ------------------------------------------------------------------------------------
@@ -902,21 +712,25 @@ __global__ __launch_bounds__(256, (MF <= 4 ? 2 : 1)) void w4a8_pipe_kernel(
 // block's k range with its own LDS stages, and exchange halves of their accumulators
 // through LDS at the end (in-block split-K).  Every SIMD again has two waves, which a
 // single 4-wave block per CU would not give.
-template <bool G128, int KG>
-__device__ __forceinline__ void duo_block(
+// MF = row fragments of 32 that the block computes (4, or 2 for a row tile with at most 64
+// rows below M: a ragged last tile, an expert with few tokens): such a tile pays for half
+// the MFMAs, X staging and fragment reads.  The tile grid is that of 128-row tiles either way.
+template <bool G128, int KG, int MF>
+__device__ __forceinline__ void duo_tile(
     const Place pl, const int bm, const int bn, int M, int N, int K, const int8_t *__restrict__ X,
     const float *__restrict__ sx, const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp,
     const float *__restrict__ sw, __half *__restrict__ Y, int32_t *__restrict__ ACC,
     int32_t *__restrict__ partials)
 {
-    constexpr int MF = 4, WM = 128, XP = 4;
+    constexpr int WM = 128, XP = MF;
     constexpr int STAGE = WM * kTilePitch;
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     __shared__ int s_last;
 
     const int tid = threadIdx.x & 255;  // thread within its k group
     const int grp = KG == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 8));
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it in an SGPR
     const int j = lane & 31, kb = lane >> 5;
     const int m0 = bm * WM;
     const int ng = bn * 4 + wave;
@@ -946,18 +760,19 @@ __device__ __forceinline__ void duo_block(
 
     // X piece i of this thread: row (tid>>3) + 32*i, 16-byte column tid&7
     const int xrow = tid >> 3, xcol = tid & 7;
-    const int8_t *xg[XP];
+    // 32-bit offsets from block-uniform bases instead of one 64-bit pointer per piece: the
+    // kernel runs at the 256-register limit and X has fewer than 2^32 bytes (K <= 131072 and
+    // the host rejects M * K >= 2^32).
+    const int8_t *xbase = X + (size_t)s_begin * 128;
+    uint32_t xg[XP];
 #pragma unroll
-    for (int i = 0; i < XP; ++i)
-        xg[i] = X + (size_t)min(m0 + xrow + 32 * i, M - 1) * K + (size_t)s_begin * 128 + 16 * xcol;
+    for (int i = 0; i < XP; ++i) xg[i] = (uint32_t)min(m0 + xrow + 32 * i, M - 1) * (uint32_t)K + 16 * xcol;
     const int xl = xrow * kTilePitch + 16 * xcol;
-    const u32x4 *wg[2];
-    const uint8_t *pg[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        wg[t] = Wp + ((size_t)(t0 + t) * chunks_per_tile + 2 * (size_t)s_begin) * 64 + lane;
-        pg[t] = gp + (((size_t)(t0 + t) * stages_total + s_begin) * 32 + j) * (G128 ? 2 : 4);
-    }
+    // tile t0 + 1 lies one tile stream behind t0 (block-uniform strides)
+    const u32x4 *wg0 = Wp + ((size_t)t0 * chunks_per_tile + 2 * (size_t)s_begin) * 64 + lane;
+    const uint8_t *pg0 = gp + (((size_t)t0 * stages_total + s_begin) * 32 + j) * (G128 ? 2 : 4);
+    const size_t wg_stride = (size_t)chunks_per_tile * 64;
+    const size_t pg_stride = (size_t)stages_total * 32 * (G128 ? 2 : 4);
     int8_t *lds_g = lds + grp * (2 * STAGE);  // the two X stages of this k group
     const int8_t *xs = lds_g + j * kTilePitch + 16 * kb;
 
@@ -975,7 +790,8 @@ __device__ __forceinline__ void duo_block(
         }
         s = min(s, my_stages - 1);
 #pragma unroll
-        for (int i = 0; i < XP; ++i) xr[i] = *reinterpret_cast<const u32x4 *>(xg[i] + (size_t)s * 128);
+        for (int i = 0; i < XP; ++i)
+            xr[i] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)s * 128 + xg[i]);
     };
     auto store_x = [&](int buf) {
 #pragma unroll
@@ -986,12 +802,14 @@ __device__ __forceinline__ void duo_block(
         s = min(s, my_stages - 1);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            w[t][0] = wg[t][(size_t)s * 128];
-            w[t][1] = wg[t][(size_t)s * 128 + 64];
+            const u32x4 *wg = wg0 + t * wg_stride;
+            const uint8_t *pg = pg0 + t * pg_stride;
+            w[t][0] = wg[(size_t)s * 128];
+            w[t][1] = wg[(size_t)s * 128 + 64];
             if (G128)
-                p[t].raw = *reinterpret_cast<const uint16_t *>(pg[t] + (size_t)s * 64);
+                p[t].raw = *reinterpret_cast<const uint16_t *>(pg + (size_t)s * 64);
             else
-                p[t].raw = *reinterpret_cast<const uint32_t *>(pg[t] + (size_t)s * 128);
+                p[t].raw = *reinterpret_cast<const uint32_t *>(pg + (size_t)s * 128);
         }
     };
     // B operand of k-step (c, h) for both tiles
@@ -1104,7 +922,7 @@ __device__ __forceinline__ void duo_block(
             // INT32 partial tile with device-scope write-through stores, takes a ticket, and the
             // last one of the S slices adds the others to its registers and runs the epilogue.
             // Layout: [tile][slice][wave of the block][MFK*8 x (64 lanes x 16 B)], fully coalesced.
-            constexpr int EPW = MFK * 8;
+            constexpr int EPW = (4 / KG) * 8;  // slots of a full 4-fragment tile, whatever MF is
             const size_t tile = pl.gx;
             const int bw = G * 4 + wave;
             int32_t *mine = partials + (((tile * S + ks) * (4 * KG) + bw) * EPW) * 256 + lane * 4;
@@ -1114,13 +932,17 @@ __device__ __forceinline__ void duo_block(
             for (int i = 0; i < MFK; ++i) {
                 if (!live(i)) continue;
 #pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const v4i v = v4i{acc[MF0 + i][t][4 * q], acc[MF0 + i][t][4 * q + 1],
-                                          acc[MF0 + i][t][4 * q + 2], acc[MF0 + i][t][4 * q + 3]};
-                        store_sc1_x4(mine + ((i * 2 + t) * 4 + q) * 256, v);
-                    }
+                for (int t = 0; t < 2; ++t) {
+                    int32_t *frag = mine + (i * 2 + t) * 4 * 256;
+                    auto part = [&](int q) {
+                        return v4i{acc[MF0 + i][t][4 * q], acc[MF0 + i][t][4 * q + 1], acc[MF0 + i][t][4 * q + 2],
+                                   acc[MF0 + i][t][4 * q + 3]};
+                    };
+                    store_sc1_x4<0>(frag, part(0));
+                    store_sc1_x4<1024>(frag, part(1));
+                    store_sc1_x4<2048>(frag, part(2));
+                    store_sc1_x4<3072>(frag, part(3));
+                }
             }
             wait_vmcnt0();
             LQ_DSTAMP(4);
@@ -1133,34 +955,32 @@ __device__ __forceinline__ void duo_block(
             __syncthreads();
             LQ_DSTAMP(5);
             if (!s_last) return;
-            // 16 loads of 16 bytes per lane are in flight before the first is waited for: the
-            // latency of these device-scope reads, not their volume, is what this tail costs.
+            // The 8 loads of one row fragment (2 column tiles x 4 pieces of 16 bytes per lane)
+            // are in flight before the first is waited for: the latency of these device-scope
+            // reads, not their volume, is what this tail costs.
             for (int k2 = 0; k2 < S; ++k2) {
                 if (k2 == ks) continue;
                 const int32_t *other = partials + (((tile * S + k2) * (4 * KG) + bw) * EPW) * 256 + lane * 4;
 #pragma unroll
-                for (int i0 = 0; i0 < MFK; i0 += 2) {
-                    v4i v[2][2][4];
+                for (int i = 0; i < MFK; ++i) {
+                    if (!live(i)) continue;
+                    v4i v[2][4];
 #pragma unroll
-                    for (int i = 0; i < 2; ++i)
+                    for (int t = 0; t < 2; ++t) {
+                        const int32_t *frag = other + (i * 2 + t) * 4 * 256;
+                        v[t][0] = load_sc1_x4<0>(frag);
+                        v[t][1] = load_sc1_x4<1024>(frag);
+                        v[t][2] = load_sc1_x4<2048>(frag);
+                        v[t][3] = load_sc1_x4<3072>(frag);
+                    }
+                    wait_vmcnt0(v[0][0], v[0][1], v[0][2], v[0][3]);
+                    wait_vmcnt0(v[1][0], v[1][1], v[1][2], v[1][3]);
 #pragma unroll
-                        for (int t = 0; t < 2; ++t)
+                    for (int t = 0; t < 2; ++t)
 #pragma unroll
-                            for (int q = 0; q < 4; ++q)
-                                v[i][t][q] = live(i0 + i) ? load_sc1_x4(other + (((i0 + i) * 2 + t) * 4 + q) * 256)
-                                                          : v4i{0, 0, 0, 0};
-                    wait_vmcnt0(v[0][0][0], v[0][0][1], v[0][0][2], v[0][0][3]);
-                    wait_vmcnt0(v[0][1][0], v[0][1][1], v[0][1][2], v[0][1][3]);
-                    wait_vmcnt0(v[1][0][0], v[1][0][1], v[1][0][2], v[1][0][3]);
-                    wait_vmcnt0(v[1][1][0], v[1][1][1], v[1][1][2], v[1][1][3]);
+                        for (int q = 0; q < 4; ++q)
 #pragma unroll
-                    for (int i = 0; i < 2; ++i)
-#pragma unroll
-                        for (int t = 0; t < 2; ++t)
-#pragma unroll
-                            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                                for (int e = 0; e < 4; ++e) acc[MF0 + i0 + i][t][4 * q + e] += v[i][t][q][e];
+                            for (int e = 0; e < 4; ++e) acc[MF0 + i][t][4 * q + e] += v[t][q][e];
                 }
             }
             LQ_DSTAMP(6);
@@ -1176,6 +996,19 @@ __device__ __forceinline__ void duo_block(
         finish(std::integral_constant<int, 0>{});
     else
         finish(std::integral_constant<int, KG - 1>{});
+}
+
+template <bool G128, int KG>
+__device__ __forceinline__ void duo_block(
+    const Place pl, const int bm, const int bn, int M, int N, int K, const int8_t *__restrict__ X,
+    const float *__restrict__ sx, const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp,
+    const float *__restrict__ sw, __half *__restrict__ Y, int32_t *__restrict__ ACC,
+    int32_t *__restrict__ partials)
+{
+    if (M - 128 * bm <= 64)  // block-uniform
+        duo_tile<G128, KG, 2>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+    else
+        duo_tile<G128, KG, 4>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
 }
 
 template <bool G128, int KG>
@@ -1413,25 +1246,6 @@ static int launch_tile(const Args &a)
     return LQ_OK;
 }
 
-template <int MF, int ABL = 0>
-static int launch_pipe(const Args &a)
-{
-    constexpr int WM = 32 * MF;
-    const int blocks_n = (a.N + 255) / 256, blocks_m = (a.M + WM - 1) / WM;
-    const size_t lds_bytes = 2 * (size_t)WM * kTilePitch;
-    const dim3 grid((unsigned)(blocks_n * blocks_m)), block(256);
-    if (a.group == 128) {
-        if (int rc = allow_lds(&w4a8_pipe_kernel<MF, true, ABL>, lds_bytes)) return rc;
-        hipLaunchKernelGGL((w4a8_pipe_kernel<MF, true, ABL>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
-                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
-    } else {
-        if (int rc = allow_lds(&w4a8_pipe_kernel<MF, false, ABL>, lds_bytes)) return rc;
-        hipLaunchKernelGGL((w4a8_pipe_kernel<MF, false, ABL>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
-                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
-    }
-    return LQ_OK;
-}
-
 // Grid-level split of K for the duo kernel with two k groups per block (grids of at most
 // one block per CU).  Measured: a slice costs about as much in partial-tile exchange
 // (128 KiB per tile and slice, added up by the last block) as half a 256-k unit costs in
@@ -1458,6 +1272,9 @@ static int launch_duo_as(const Args &a, int S)
 {
     constexpr int WM = 128;
     const int blocks_n = (a.N + 255) / 256, blocks_m = (a.M + WM - 1) / WM;
+    if ((long long)a.M * a.K >= (1ll << 32))
+        return fail(LQ_ERR_INVALID, "M * K = %lld is beyond the 2^32 - 1 bytes of X one call addresses; split the batch",
+                    (long long)a.M * a.K);
     S = std::min(S, a.K / (256 * KG));  // every k group of every slice gets at least one unit
     if (blocks_n * blocks_m > kMaxTicketGroups || S < 1) S = 1;
     size_t need = duo_ws_bytes(a.M, a.N, S);
@@ -1533,9 +1350,6 @@ static const Variant kVariants[] = {
     {"tile_m32", &launch_tile<1>, 0, 1, 1},
     {"tile_m64", &launch_tile<2>, 0, 1, 1},
     {"tile_m128", &launch_tile<4>, 0, 1, 1},
-    {"tile_m256", &launch_tile<8>, 0, 1, 1},
-    {"pipe_m128", &launch_pipe<4>, 0, 1, 1},
-    {"pipe_m256", &launch_pipe<8>, 0, 1, 1},
     {"duo_m128", &launch_duo<0, 0>, 0, 1, 1},
     {"duo_m128_s1", &launch_duo<1, 1>, 0, 1, 1},
     {"duo_m128_s2", &launch_duo<2, 1>, 0, 1, 1},
@@ -1555,15 +1369,6 @@ static const Variant kVariants[] = {
     {"abl_s16_noXP", &launch_stream16<2, 4, 1, 3>, 16, 2, 1},
     {"abl_s16_noXPDq", &launch_stream16<2, 4, 1, 7>, 16, 2, 1},
     {"abl_s16_onlyW", &launch_stream16<2, 4, 1, 15>, 16, 2, 1},
-    {"abl_m256_noX", &launch_pipe<8, 1>, 0, 1, 1},
-    {"abl_m256_noW", &launch_pipe<8, 2>, 0, 1, 1},
-    {"abl_m256_noXW", &launch_pipe<8, 3>, 0, 1, 1},
-    {"abl_m256_noLdsRead", &launch_pipe<8, 4>, 0, 1, 1},
-    {"abl_m256_noDequant", &launch_pipe<8, 8>, 0, 1, 1},
-    {"abl_m256_noBarrier", &launch_pipe<8, 16>, 0, 1, 1},
-    {"abl_m256_noXW_noDq", &launch_pipe<8, 11>, 0, 1, 1},
-    {"abl_m256_mfmaOnly", &launch_pipe<8, 31>, 0, 1, 1},
-    {"abl_m256_noXWLds", &launch_pipe<8, 7>, 0, 1, 1},
 #endif
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));

@@ -59,6 +59,10 @@ CASES = [
     (3, 320, 1024, 64, [130, 77, 300]),            # only tiled experts, ragged rows, N tail
     (4, 128, 256, 64, [32, 17, 33, 31]),           # around the family boundaries, one k unit
     (2, 64, 2048, 128, [0, 5]),                    # smallest N, leading empty expert
+    # wide layers with many experts: large grids in every family
+    (4, 16384, 256, 64, [20, 64, 33, 50]),
+    (8, 16384, 256, 128, [17, 32, 25, 30, 64, 40, 50, 60]),
+    (16, 16384, 256, 64, [18, 33] * 8),
 ]
 
 
