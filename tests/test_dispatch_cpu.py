@@ -1,0 +1,66 @@
+"""Host logic of the library that needs no GPU: the shape -> kernel dispatcher, the variant
+table and the workspace sizing."""
+import pytest
+
+from paper_2509_01229_amd import api
+from paper_2509_01229_amd import workloads as WL
+
+
+def _pick(M, N, K, g=64):
+    return api.w4a8_variant_name(api.w4a8_select_variant(M, N, K, g))
+
+
+def test_dispatcher_families_on_the_workloads():
+    for s in WL.ALL_SHAPES:
+        name = _pick(s.M, s.N, s.K, s.group)
+        if s.M <= 16:
+            assert name.startswith("stream16_"), (s.name, name)
+        elif s.M <= 32:
+            assert name.startswith("stream_f"), (s.name, name)
+        elif s.M <= 64 and s.N <= 16384:
+            assert name == "stream_m64", (s.name, name)
+        else:
+            assert name == "duo_m128", (s.name, name)
+        v = api.w4a8_select_variant(s.M, s.N, s.K, s.group)
+        assert api.w4a8_variant_supports(v, s.M, s.N, s.K, s.group)
+
+
+def test_dispatcher_boundaries():
+    assert _pick(16, 4096, 4096) == "stream16_f1_w8_u4"        # small matrix: deep prefetch, one tile per block
+    assert _pick(16, 4096, 11008) == "stream16_f2_w8"          # K not a multiple of 512
+    assert _pick(16, 28672, 8192, 128) == "stream16_f2_w4"     # N alone fills the chip
+    assert _pick(17, 4096, 4096).startswith("stream_f2")
+    assert _pick(33, 4096, 4096) == "stream_m64" and _pick(64, 16384, 4096) == "stream_m64"
+    assert _pick(64, 28672, 8192) == "duo_m128" and _pick(65, 4096, 4096) == "duo_m128"
+    with pytest.raises(api.LiquidGemmError):
+        api.w4a8_select_variant(8, 100, 512, 64)                # bad shape
+
+
+def test_variant_table_is_consistent():
+    names = api.w4a8_variant_names()
+    assert len(names) == len(set(names)) == api.w4a8_variant_count()
+    for v, name in enumerate(names):
+        # row limits are part of the names' families
+        limit = (16 if name.startswith("stream16") else 64 if name.startswith("stream_m64")
+                 else 32 if name.startswith("stream_f") else None)
+        if limit:
+            assert api.w4a8_variant_supports(v, limit, 256, 1024, 64)
+            assert not api.w4a8_variant_supports(v, limit + 1, 256, 1024, 64)
+        else:
+            assert api.w4a8_variant_supports(v, 4096, 256, 1024, 64)
+        assert not api.w4a8_variant_supports(v, 8, 96, 1024, 64)   # N % 64 != 0
+    assert not api.w4a8_variant_supports(-1, 8, 256, 1024, 64)
+    assert not api.w4a8_variant_supports(len(names), 8, 256, 1024, 64)
+
+
+def test_workspace_sizes():
+    ws = api.w4a8_gemm_workspace_size
+    assert ws(0, 4096, 4096, 64) == 0 and ws(16, 100, 4096, 64) == 0     # nothing to do / bad shape
+    assert ws(4096, 8192, 8192, 64) == 0                                  # enough tiles: no split-K
+    small = ws(16, 4096, 4096, 64)
+    assert small > 0 and small % 16 == 0
+    # room for 16 slices of the 16-row kernels' partial tiles at least
+    assert small >= 16 * (4096 // 32) * 8 * 64 * 4
+    # the tiled kernel's partial tiles (128 x 256 INT32 per tile and slice, up to 8 slices)
+    assert ws(128, 4096, 4096, 64) >= 16 * 8 * 128 * 256 * 4
+    assert ws(128, 4096, 4096, 64) <= 1 << 30
