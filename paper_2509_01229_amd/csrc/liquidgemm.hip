@@ -83,6 +83,9 @@ __device__ __forceinline__ __half scale_to_half(int acc, float sx, float sw)
 // block to arrive (a ticket per tile group) adds them up and runs the epilogue.  All sums
 // are INT32, so neither level of split-K changes the result.
 // ------------------------------------------------------------------------------------
+#ifndef LQ_DUO_ABL
+#define LQ_DUO_ABL 0
+#endif
 #ifdef LQ_ABLATE
 // experiments only: per-wave wall-clock stamps (start, first unit done, loop done, end)
 __device__ long long g_dbg_stamps[4 * 16384];
@@ -816,12 +819,19 @@ __device__ __forceinline__ void duo_tile(
     auto build_b = [&](const u32x4 (&w)[2][2], const UnitParams<G128> (&p)[2], int c, int h, v4i (&b)[2]) {
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
+#if defined(LQ_ABLATE) && (LQ_DUO_ABL & 1)  // experiments only: raw bytes instead of the dequantised operand
+            b[t] = __builtin_bit_cast(v4i, w[t][c]) + h + (int)p[t].raw;
+#else
             uint32_t s2, a4;
             p[t].get(c, s2, a4);
             dequant_half(w[t][c], s2, a4, h, b[t]);
+#endif
         }
     };
     auto read_a = [&](int buf, int c, int h, v4i (&a)[MF]) {
+#if defined(LQ_ABLATE) && (LQ_DUO_ABL & 2)  // experiments only: no X fragment reads from LDS
+        if (buf + c + h == -1)
+#endif
 #pragma unroll
         for (int mf = 0; mf < MF; ++mf)
             a[mf] = *reinterpret_cast<const v4i *>(xs + buf * STAGE + mf * 32 * kTilePitch + 64 * c + 32 * h);
