@@ -14,7 +14,7 @@ range (prefill, M=4096, N=K=8192, group 64).  The same JSON line carries
     point (70B up-projection at M=16) against the nominal peaks;
   * calibration: what this GPU reaches on a pure streaming read and on a register-only
     INT8 MFMA loop (constant and random operands);
-  * curve_N8192_K8192: TOPS and fraction of the roofline for M = 1..4096;
+  * curve_N8192_K8192, curve_N4096_K4096: TOPS and fraction of the roofline for M = 1..4096;
   * configs: every workload row (decode, 7B MLP, 70B layers, prefill sweep), median of five
     batches, with rotating weights and with one weight buffer (cache-warm) side by side;
   * activation_quant: the per-token FP16 -> INT8 quantisation kernel upstream of the GEMM;
@@ -445,7 +445,12 @@ def main():
             if key == (head.N, head.K, head.group, head.seed):
                 p2 = prob
             else:
-                p2 = DeviceProblem(shapes[0], [s.M for s in shapes], torch, api, WL)
+                extra_Ms = curve_Ms if (shapes[0].N, shapes[0].K) == (4096, 4096) else []
+                p2 = DeviceProblem(shapes[0], sorted(set([s.M for s in shapes] + extra_Ms)), torch, api, WL)
+                if extra_Ms:  # the second curve of the metric: decode-sized weights
+                    out["curve_N4096_K4096"] = [
+                        point(shapes[0], M, time_median(p2, M, torch, api, stream, batches=3), api, calib)
+                        for M in extra_Ms]
             for s in shapes:
                 if s.M not in p2.dX:
                     continue

@@ -1191,15 +1191,16 @@ static int launch_stream(const Args &a)
     return launch_stream_as<F, NW, MF>(a, SPLIT ? SPLIT : stream_split(a.N, a.K, F, NW), SPLIT != 0);
 }
 
-// 64-row stream kernel with the block shape chosen from N.  Measured: its 8-wave blocks
-// (about 140 / 190 registers) run one per CU, so the best grid is the largest one of at
-// most 256 blocks: one tile per block while N / 32 <= 256, else two; K is split across
-// blocks while that still fits.
-static int launch_stream_m64(const Args &a)
+// 32-row (MF = 1) and 64-row (MF = 2) stream kernels with the block shape chosen from N.
+// Measured for both: the best grid is the largest one of at most 256 blocks of 8 waves --
+// one tile per block while N / 32 <= 256, else two -- with K split across blocks while
+// that still fits.
+template <int MF>
+static int launch_stream_auto(const Args &a)
 {
     const int tiles = a.N / 32;
-    if (tiles <= 256) return launch_stream_as<1, 8, 2>(a, std::min(4, 256 / tiles), false);
-    return launch_stream_as<2, 8, 2>(a, std::min(4, 512 / tiles), false);
+    if (tiles <= 256) return launch_stream_as<1, 8, MF>(a, std::min(4, 256 / tiles), false);
+    return launch_stream_as<2, 8, MF>(a, std::min(4, 512 / tiles), false);
 }
 
 template <int F, int NW, int SPLIT, int ABL = 0, int UU = 1>
@@ -1339,7 +1340,11 @@ static const Variant kVariants[] = {
     {"stream_f2_w8_s1", &launch_stream<2, 8, 1>, 32, 2, 1},
     {"stream_f2_w8_s2", &launch_stream<2, 8, 2>, 32, 2, 1},
     {"stream_f2_w8_s4", &launch_stream<2, 8, 4>, 32, 2, 1},
-    {"stream_m64", &launch_stream_m64, 64, 2, 1},
+    {"stream_f1_w8_s1", &launch_stream<1, 8, 1>, 32, 1, 1},
+    {"stream_f1_w8_s2", &launch_stream<1, 8, 2>, 32, 1, 1},
+    {"stream_f1_w8_s4", &launch_stream<1, 8, 4>, 32, 1, 1},
+    {"stream_m32", &launch_stream_auto<1>, 32, 2, 1},
+    {"stream_m64", &launch_stream_auto<2>, 64, 2, 1},
     {"stream_m64_f2_w8", &launch_stream<2, 8, 0, 2>, 64, 2, 1},
     {"stream_m64_f2_w8_s1", &launch_stream<2, 8, 1, 2>, 64, 2, 1},
     {"stream_m64_f2_w8_s2", &launch_stream<2, 8, 2, 2>, 64, 2, 1},
@@ -1408,7 +1413,7 @@ static int select_variant(int M, int N, int K)
         if (K % 512 == 0 && K <= 8192 && N / 32 <= 256) return find_variant("stream16_f1_w8_u4");
         return find_variant(N / 64 >= 384 ? "stream16_f2_w4" : "stream16_f2_w8");
     }
-    if (M <= 32) return find_variant("stream_f2_w8");
+    if (M <= 32) return find_variant("stream_m32");
     // up to 64 rows the weights are still best streamed once per block column unless N alone
     // fills the chip with 128 x 256 tiles
     if (M <= 64 && N / 32 <= 512) return find_variant("stream_m64");

@@ -16,7 +16,7 @@ def test_dispatcher_families_on_the_workloads():
         if s.M <= 16:
             assert name.startswith("stream16_"), (s.name, name)
         elif s.M <= 32:
-            assert name.startswith("stream_f"), (s.name, name)
+            assert name == "stream_m32", (s.name, name)
         elif s.M <= 64 and s.N <= 16384:
             assert name == "stream_m64", (s.name, name)
         else:
@@ -29,7 +29,7 @@ def test_dispatcher_boundaries():
     assert _pick(16, 4096, 4096) == "stream16_f1_w8_u4"        # small matrix: deep prefetch, one tile per block
     assert _pick(16, 4096, 11008) == "stream16_f2_w8"          # K not a multiple of 512
     assert _pick(16, 28672, 8192, 128) == "stream16_f2_w4"     # N alone fills the chip
-    assert _pick(17, 4096, 4096).startswith("stream_f2")
+    assert _pick(17, 4096, 4096) == "stream_m32" and _pick(32, 28672, 8192) == "stream_m32"
     assert _pick(33, 4096, 4096) == "stream_m64" and _pick(64, 16384, 4096) == "stream_m64"
     assert _pick(64, 28672, 8192) == "duo_m128" and _pick(65, 4096, 4096) == "duo_m128"
     with pytest.raises(api.LiquidGemmError):
@@ -42,7 +42,7 @@ def test_variant_table_is_consistent():
     for v, name in enumerate(names):
         # row limits are part of the names' families
         limit = (16 if name.startswith("stream16") else 64 if name.startswith("stream_m64")
-                 else 32 if name.startswith("stream_f") else None)
+                 else 32 if name.startswith(("stream_f", "stream_m32")) else None)
         if limit:
             assert api.w4a8_variant_supports(v, limit, 256, 1024, 64)
             assert not api.w4a8_variant_supports(v, limit + 1, 256, 1024, 64)

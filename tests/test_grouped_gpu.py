@@ -117,3 +117,36 @@ def test_grouped_interface_limits():
     assert raw(1, [1, 4]) == -1             # must start at 0
     assert raw(2, [0, 3, 2]) == -1          # must not decrease
     assert raw(1, [0, 4]) == -1             # no output pointer
+
+
+def test_grouped_full_size_layer_all_families():
+    """A layer of realistic width (N = K = 4096, 8 experts) with expert sizes in every kernel
+    family, checked in full: per expert the float64 BLAS product of the oracle's dequantised
+    weights is exact (|ACC| < 2^53)."""
+    import torch
+
+    E, N, K, g = 8, 4096, 4096, 64
+    rows = [5, 0, 16, 33, 64, 65, 130, 700]
+    _say(f"grouped full size E={E} N={N} K={K} rows={rows}")
+    Ws = [WL.make_weights(N, K, 0.02, seed=900 + e) for e in range(E)]
+    packs = [api.liquidquant_pack_weights(W, g) for W in Ws]
+    d_packed = torch.from_numpy(np.concatenate([p[0] for p in packs])).cuda()
+    d_gparams = torch.from_numpy(np.concatenate([p[1] for p in packs])).cuda()
+    d_sw = torch.from_numpy(np.stack([p[2] for p in packs])).cuda()
+    offs = np.concatenate([[0], np.cumsum(rows)]).astype(int)
+    X, s_x = WL.make_activations(int(offs[-1]), K, outlier_frac=0.001, seed=77)
+    Y, ACC = api.w4a8_grouped_gemm(offs, torch.from_numpy(X).cuda(), torch.from_numpy(s_x).cuda(), d_packed,
+                                   d_gparams, d_sw, N, K, g, want_y=True, want_acc=True)
+    torch.cuda.synchronize()
+    ACC, Y = ACC.cpu().numpy(), Y.cpu().numpy()
+    for e in range(E):
+        r0, r1 = offs[e], offs[e + 1]
+        if r1 == r0:
+            continue
+        q = O.quantize_weights(Ws[e], g)
+        assert np.array_equal(q["s_w"].view(np.uint32), packs[e][2].view(np.uint32))
+        Wd = O.dequant_plain(q["Q_u4"], q["s_u8"], q["mn"], g)
+        ref = X[r0:r1].astype(np.float64) @ Wd.astype(np.float64).T
+        assert np.array_equal(ACC[r0:r1].astype(np.float64), ref), f"expert {e}: accumulators differ"
+        H.assert_fp16_close(Y[r0:r1], ref * s_x[r0:r1, None].astype(np.float64) * q["s_w"][None, :].astype(np.float64),
+                            f"expert {e}")
