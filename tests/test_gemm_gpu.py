@@ -231,3 +231,31 @@ def test_calibration_kernels_run():
         api.w4a8_calib_mfma_i8(0, True)
     with pytest.raises(api.LiquidGemmError):
         api.w4a8_calib_stream_read(buf[8:])  # not 16-byte aligned
+
+
+def test_random_shapes_through_the_dispatcher():
+    """A seeded sweep of legal shapes (every row-count family, ragged tails in M and N, one
+    to many k units, both group sizes) through w4a8_gemm / w4a8_gemm_i32 as a caller would
+    use them, with and without the optional workspace."""
+    import torch
+
+    rng = np.random.default_rng(2024)
+    Ms = [1, 15, 16, 17, 31, 32, 33, 63, 64, 65, 96, 127, 128, 129, 191, 257, 300]
+    for case in range(34):
+        M = Ms[case % len(Ms)]
+        N = 64 * int(rng.integers(1, 13))
+        K = 256 * int(rng.integers(1, 9))
+        g = (64, 128)[case % 2]
+        picked = api.w4a8_variant_name(api.w4a8_select_variant(M, N, K, g))
+        _say(f"random shape {case}: M={M} N={N} K={K} g={g} -> {picked}")
+        P = H.Problem(N, K, g, seed=1000 + case)
+        X, s_x = WL.make_activations(M, K, outlier_frac=0.01, seed=2000 + case)
+        ACC_ref, _ = P.oracle_gemm(X, s_x)
+        ref64 = O.scale_epilogue_f64(ACC_ref, s_x, P.oracle_full()["s_w"])
+        dX, dsx = torch.from_numpy(X).cuda(), torch.from_numpy(s_x).cuda()
+        ws = None if case % 3 else torch.empty(16, dtype=torch.uint8, device="cuda")  # every third: no room to split
+        Y = api.w4a8_gemm(dX, dsx, P.d_packed, P.d_gparams, P.d_w_scales, N, K, g, workspace=ws)
+        ACC = api.w4a8_gemm_i32(dX, P.d_packed, P.d_gparams, N, K, g, workspace=ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(ACC.cpu().numpy(), ACC_ref), f"case {case}: accumulators differ"
+        H.assert_fp16_close(Y.cpu().numpy(), ref64, f"case {case}")
