@@ -259,3 +259,49 @@ def test_random_shapes_through_the_dispatcher():
         torch.cuda.synchronize()
         assert np.array_equal(ACC.cpu().numpy(), ACC_ref), f"case {case}: accumulators differ"
         H.assert_fp16_close(Y.cpu().numpy(), ref64, f"case {case}")
+
+
+def test_maximum_k_and_accumulator_range():
+    """K at the interface limit (131072) with inputs that drive the accumulators to the edge
+    of INT32: |ACC| up to K * 127 * 121 = 2 014 183 424 < 2^31 must come out exactly."""
+    import torch
+
+    N, K, g = 64, 131072, 128
+    _say("maximum K, extreme accumulators")
+    Q = np.full((N, K), 119, dtype=np.int8)
+    Q[1::2] = -119
+    Q[:, ::128] = -119          # every group spans the whole protective range: s = 16, top code 15 -> 121
+    Q[1::2, ::128] = 119
+    P = H.Problem(N, K, g, Q_i8=Q)
+    Wd, _ = P.oracle_wd()
+    assert Wd.max() == 121 and Wd.min() == -119
+    for M in (3, 40, 70):
+        X = np.full((M, K), 127, dtype=np.int8)
+        X[1] = -127
+        X[2, ::2] = -127
+        s_x = np.ones(M, dtype=np.float32)
+        ACC_ref = X.astype(np.float64) @ Wd.astype(np.float64).T   # exact: below 2^53
+        assert np.abs(ACC_ref).max() < 2.0 ** 31
+        dX = torch.from_numpy(X).cuda()
+        ACC = api.w4a8_gemm_i32(dX, P.d_packed, P.d_gparams, N, K, g)
+        torch.cuda.synchronize()
+        assert np.array_equal(ACC.cpu().numpy().astype(np.float64), ACC_ref), f"M={M}"
+    with pytest.raises(api.LiquidGemmError):
+        api.liquidquant_packed_size(64, 131072 + 256, 64)
+
+
+def test_wide_layer_large_grid():
+    """N = 65536: grids of thousands of blocks in the stream kernels and many column tiles in
+    the tiled kernel (one k unit keeps the oracle cheap)."""
+    import torch
+
+    N, K, g = 65536, 256, 64
+    _say("wide layer")
+    P = H.Problem(N, K, g, seed=31)
+    Wd, _ = P.oracle_wd()
+    for M in (2, 20, 50, 130):
+        X, s_x = WL.make_activations(M, K, seed=M)
+        ACC = api.w4a8_gemm_i32(torch.from_numpy(X).cuda(), P.d_packed, P.d_gparams, N, K, g)
+        torch.cuda.synchronize()
+        ref = X.astype(np.float64) @ Wd.astype(np.float64).T
+        assert np.array_equal(ACC.cpu().numpy().astype(np.float64), ref), f"M={M}"
