@@ -718,15 +718,16 @@ __device__ __forceinline__ void lds_barrier()
 // MF = row fragments of 32 that the block computes (4, or 2 for a row tile with at most 64
 // rows below M: a ragged last tile, an expert with few tokens): such a tile pays for half
 // the MFMAs, X staging and fragment reads.  The tile grid is that of 128-row tiles either way.
-template <bool G128, int KG, int MF>
+template <bool G128, int KG, int MF, int TM = 128>
 __device__ __forceinline__ void duo_tile(
     const Place pl, const int bm, const int bn, int M, int N, int K, const int8_t *__restrict__ X,
     const float *__restrict__ sx, const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp,
     const float *__restrict__ sw, __half *__restrict__ Y, int32_t *__restrict__ ACC,
     int32_t *__restrict__ partials)
 {
-    constexpr int WM = 128, XP = MF;
-    constexpr int STAGE = WM * kTilePitch;
+    constexpr int WM = TM, XP = MF;  // TM = rows between consecutive row tiles (128, or 64 with MF = 2)
+    static_assert(32 * MF <= TM, "a tile cannot hold more row fragments than its height");
+    constexpr int STAGE = 128 * kTilePitch;
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     __shared__ int s_last;
 
@@ -1022,20 +1023,22 @@ __device__ __forceinline__ void duo_tile(
         finish(std::integral_constant<int, KG - 1>{});
 }
 
-template <bool G128, int KG>
+template <bool G128, int KG, int TM = 128>
 __device__ __forceinline__ void duo_block(
     const Place pl, const int bm, const int bn, int M, int N, int K, const int8_t *__restrict__ X,
     const float *__restrict__ sx, const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp,
     const float *__restrict__ sw, __half *__restrict__ Y, int32_t *__restrict__ ACC,
     int32_t *__restrict__ partials)
 {
-    if (M - 128 * bm <= 64)  // block-uniform
+    if (TM == 64)
+        duo_tile<G128, KG, 2, 64>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+    else if (M - 128 * bm <= 64)  // block-uniform
         duo_tile<G128, KG, 2>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
     else
         duo_tile<G128, KG, 4>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
 }
 
-template <bool G128, int KG>
+template <bool G128, int KG, int TM = 128>
 __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
     int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
@@ -1044,7 +1047,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
 {
     int bm, bn;
     block_coords(blocks_m, blocks_n, bm, bn);
-    duo_block<G128, KG>(grid_place(), bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+    duo_block<G128, KG, TM>(grid_place(), bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
 }
 
 // ------------------------------------------------------------------------------------
@@ -1285,24 +1288,24 @@ static int duo_split(int M, int N, int K)
     s = std::min(std::min(s, 256 / tiles), std::min(units / 2, 8));
     return std::max(1, s);
 }
-static size_t duo_ws_bytes(int M, int N, int S)
+static size_t duo_ws_bytes(int M, int N, int S, int tm = 128)
 {
     if (S <= 1) return 0;
-    const size_t tiles = (size_t)((M + 127) / 128) * ((N + 255) / 256);
-    return tiles * S * 4 * 32 * 256 * sizeof(int32_t);
+    const size_t tiles = (size_t)((M + tm - 1) / tm) * ((N + 255) / 256);
+    return tiles * S * 4 * 32 * 256 * sizeof(int32_t);  // the slot of a tile has the full size whatever its height
 }
 
-template <int SPLIT, int KG>
+template <int SPLIT, int KG, int TM = 128>
 static int launch_duo_as(const Args &a, int S)
 {
-    constexpr int WM = 128;
+    constexpr int WM = TM;
     const int blocks_n = (a.N + 255) / 256, blocks_m = (a.M + WM - 1) / WM;
     if ((long long)a.M * a.K >= (1ll << 32))
         return fail(LQ_ERR_INVALID, "M * K = %lld is beyond the 2^32 - 1 bytes of X one call addresses; split the batch",
                     (long long)a.M * a.K);
     S = std::min(S, a.K / (256 * KG));  // every k group of every slice gets at least one unit
     if (blocks_n * blocks_m > kMaxTicketGroups || S < 1) S = 1;
-    size_t need = duo_ws_bytes(a.M, a.N, S);
+    size_t need = duo_ws_bytes(a.M, a.N, S, TM);
     if (need > 0 && (!a.ws || a.ws_bytes < need)) {
         if (SPLIT)
             return fail(LQ_ERR_WORKSPACE, "split-K needs %zu bytes of workspace, got %zu", need,
@@ -1311,17 +1314,17 @@ static int launch_duo_as(const Args &a, int S)
         need = 0;
     }
     // KG groups x 2 stages of X; the in-block reduction reuses them and needs 64 KiB
-    const size_t lds_bytes = KG == 1 ? 2 * (size_t)WM * kTilePitch
-                                     : std::max<size_t>(KG * 2 * (size_t)WM * kTilePitch, 64 * 1024);
+    const size_t lds_bytes = KG == 1 ? 2 * (size_t)128 * kTilePitch
+                                     : std::max<size_t>(KG * 2 * (size_t)128 * kTilePitch, 64 * 1024);
     const dim3 grid((unsigned)(blocks_n * blocks_m), (unsigned)S), block(256 * KG);
     int32_t *partials = static_cast<int32_t *>(a.ws);
     if (a.group == 128) {
-        if (int rc = allow_lds(w4a8_duo_kernel<true, KG>, lds_bytes)) return rc;
-        hipLaunchKernelGGL((w4a8_duo_kernel<true, KG>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K, a.X,
+        if (int rc = allow_lds(w4a8_duo_kernel<true, KG, TM>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_duo_kernel<true, KG, TM>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K, a.X,
                            a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n, partials);
     } else {
-        if (int rc = allow_lds(w4a8_duo_kernel<false, KG>, lds_bytes)) return rc;
-        hipLaunchKernelGGL((w4a8_duo_kernel<false, KG>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K, a.X,
+        if (int rc = allow_lds(w4a8_duo_kernel<false, KG, TM>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_duo_kernel<false, KG, TM>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K, a.X,
                            a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n, partials);
     }
     return LQ_OK;
@@ -1339,12 +1342,44 @@ static int launch_duo(const Args &a)
     return kg == 2 ? launch_duo_as<SPLIT, 2>(a, S) : launch_duo_as<SPLIT, 1>(a, S);
 }
 
+// The same kernel on a grid of 64-row tiles (two row fragments per wave, two k groups per
+// block): twice the tiles for a given M, half the partial-tile volume per slice.
+static int duo64_split(int M, int N, int K)
+{
+    const int tiles = ((M + 63) / 64) * ((N + 255) / 256);
+    const int units = K / 256;
+    int s = (int)(0.75 * std::sqrt((double)units) + 0.5);
+    s = std::min(std::min(s, 256 / std::max(1, tiles)), std::min(units / 2, 8));
+    return std::max(1, s);
+}
+template <int SPLIT>
+static int launch_duo64(const Args &a)
+{
+    if (a.K < 512) return fail(LQ_ERR_INVALID, "the 64-row tiled variant needs K >= 512");
+    return launch_duo_as<SPLIT, 2, 64>(a, SPLIT ? SPLIT : duo64_split(a.M, a.N, a.K));
+}
+
+// Which tile height for a problem with few tiles.  Fitted to measurements of both forms with
+// two k groups per block (microseconds; u = 256-k units per k group, S = K slices):
+//   128-row tiles: 13.9 + 1.95 u + 2.3 (S - 1)       64-row tiles: 8.1 + 1.76 u + 2.4 (S - 1)
+static bool prefer_64_row_tiles(int M, int N, int K)
+{
+    const int bn = (N + 255) / 256;
+    const int t128 = ((M + 127) / 128) * bn, t64 = ((M + 63) / 64) * bn, units = K / 256;
+    if (K < 512 || t64 > 256 || t128 > 256) return false;
+    const int s128 = duo_split(M, N, K), s64 = duo64_split(M, N, K);
+    const double est128 = 13.9 + 1.95 * units / (2.0 * s128) + 2.3 * (s128 - 1);
+    const double est64 = 8.1 + 1.76 * units / (2.0 * s64) + 2.4 * (s64 - 1);
+    return est64 < est128;
+}
+
 struct Variant {
     const char *name;
     LaunchFn fn;
     int max_m;      // 0 = unlimited
     int tiles_div;  // N/32 must be a multiple of this
     int chunks_div; // K/64 must be a multiple of this
+    int min_k = 256;
 };
 
 // stream_f<F>_w<NW>[_s<S>]: F tiles per block, NW waves splitting the block's K slice,
@@ -1384,6 +1419,11 @@ static const Variant kVariants[] = {
     {"duo_m128_s2", &launch_duo<2, 1>, 0, 1, 1},
     {"duo_m128_s4", &launch_duo<4, 1>, 0, 1, 1},
     {"duo_m128_s8", &launch_duo<8, 1>, 0, 1, 1},
+    {"duo_m64", &launch_duo64<0>, 0, 1, 1, 512},
+    {"duo_m64_s1", &launch_duo64<1>, 0, 1, 1, 512},
+    {"duo_m64_s2", &launch_duo64<2>, 0, 1, 1, 512},
+    {"duo_m64_s3", &launch_duo64<3>, 0, 1, 1, 512},
+    {"duo_m64_s4", &launch_duo64<4>, 0, 1, 1, 512},
     {"duo_m128_g2", &launch_duo<0, 2>, 0, 1, 1},
     {"duo_m128_g2_s1", &launch_duo<1, 2>, 0, 1, 1},
     {"duo_m128_g2_s2", &launch_duo<2, 2>, 0, 1, 1},
@@ -1405,7 +1445,8 @@ constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 static bool variant_supports(int v, int M, int N, int K)
 {
     const Variant &x = kVariants[v];
-    return (x.max_m == 0 || M <= x.max_m) && (N / 32) % x.tiles_div == 0 && (K / 64) % x.chunks_div == 0;
+    return (x.max_m == 0 || M <= x.max_m) && (N / 32) % x.tiles_div == 0 && (K / 64) % x.chunks_div == 0 &&
+           K >= x.min_k;
 }
 
 static int find_variant(const char *name)
@@ -1431,7 +1472,8 @@ static int select_variant(int M, int N, int K)
     // up to 64 rows the weights are still best streamed once per block column unless N alone
     // fills the chip with 128 x 256 tiles
     if (M <= 64 && N / 32 <= 512) return find_variant("stream_m64");
-    return find_variant("duo_m128");
+    // few tiles: a grid of 64-row tiles can fill the chip with half the split-K exchange
+    return find_variant(prefer_64_row_tiles(M, N, K) ? "duo_m64" : "duo_m128");
 }
 
 static int check_device_args(const Args &a)
@@ -1572,7 +1614,7 @@ size_t w4a8_gemm_workspace_size(int M, int N, int K, int group)
     // output has fewer tiles than CUs (at most 8 slices); stream kernels take at most 16
     // slices (the 16-row kernels always exchange 8 values per lane and tile).
     const int tiles = ((M + 127) / 128) * ((N + 255) / 256);
-    size_t need = tiles >= 192 ? 0 : duo_ws_bytes(M, N, 8);
+    size_t need = tiles >= 192 ? 0 : std::max(duo_ws_bytes(M, N, 8), duo_ws_bytes(M, N, 8, 64));
     if (M <= 32) need = std::max(need, stream_ws_bytes(M, N, 16));
     if (M <= 64) need = std::max(need, stream_ws_bytes(M, N, 16, 2));
     if (M <= 16) need = std::max(need, (size_t)16 * (N / 32) * 8 * 64 * sizeof(int32_t));
