@@ -1348,7 +1348,7 @@ static int duo64_split(int M, int N, int K)
 {
     const int tiles = ((M + 63) / 64) * ((N + 255) / 256);
     const int units = K / 256;
-    int s = (int)(0.75 * std::sqrt((double)units) + 0.5);
+    int s = (int)(0.6 * std::sqrt((double)units) + 0.5);  // minimum of the fitted cost below
     s = std::min(std::min(s, 256 / std::max(1, tiles)), std::min(units / 2, 8));
     return std::max(1, s);
 }
