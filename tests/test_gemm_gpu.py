@@ -305,3 +305,39 @@ def test_wide_layer_large_grid():
         torch.cuda.synchronize()
         ref = X.astype(np.float64) @ Wd.astype(np.float64).T
         assert np.array_equal(ACC.cpu().numpy().astype(np.float64), ref), f"M={M}"
+
+
+def test_hip_graph_replays_of_split_k_kernels():
+    """Split-K launches (arrival tickets that reset themselves, partial tiles in the workspace)
+    captured in a HIP graph: every replay, with eager work of the same kind in between, must
+    reproduce the eager result."""
+    import torch
+
+    cases = [(8, 2048, 4096, 64), (48, 4096, 2048, 64), (200, 1024, 4096, 128)]   # stream16 / stream_m64 / duo_m64
+    stream = torch.cuda.Stream()
+    for M, N, K, g in cases:
+        picked = api.w4a8_variant_name(api.w4a8_select_variant(M, N, K, g))
+        _say(f"graph replay M={M} N={N} K={K} -> {picked}")
+        P = H.Problem(N, K, g, seed=M)
+        X, s_x = WL.make_activations(M, K, seed=M + 1)
+        X2, s_x2 = WL.make_activations(M, K, seed=M + 2)
+        dX, dsx = torch.from_numpy(X).cuda(), torch.from_numpy(s_x).cuda()
+        dX2, dsx2 = torch.from_numpy(X2).cuda(), torch.from_numpy(s_x2).cuda()
+        ws = torch.empty(api.w4a8_gemm_workspace_size(M, N, K, g) + 16, dtype=torch.uint8, device="cuda")
+        out = torch.empty((M, N), dtype=torch.int32, device="cuda")
+        eager = api.w4a8_gemm_i32(dX, P.d_packed, P.d_gparams, N, K, g, workspace=ws).clone()
+        eager2 = api.w4a8_gemm_i32(dX2, P.d_packed, P.d_gparams, N, K, g, workspace=ws).clone()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(stream):
+            with torch.cuda.graph(graph, stream=stream):
+                api.w4a8_gemm_i32(dX, P.d_packed, P.d_gparams, N, K, g, out=out, workspace=ws,
+                                  stream=stream.cuda_stream)
+        for rep in range(3):
+            out.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, eager), f"replay {rep} differs from the eager result"
+            other = api.w4a8_gemm_i32(dX2, P.d_packed, P.d_gparams, N, K, g, workspace=ws)   # eager work in between
+            torch.cuda.synchronize()
+            assert torch.equal(other, eager2)
