@@ -141,6 +141,11 @@ def is_tiny(shape, M):
 def time_median(prob, M, torch, api, stream, rotate=True, batches=5, est_ms=None):
     """Median over `batches` of the per-launch average of a batch of back-to-back launches."""
     graph = is_tiny(prob.shape, M)
+    # about 50 ms of untimed launches first: the first batches after a change of kernel run at
+    # unsettled clocks (measured: up to 15 % slower)
+    t_end = time.perf_counter() + 0.05
+    while time.perf_counter() < t_end:
+        time_steps(prob, M, 20, 0, torch, api, stream, graph=False, rotate=rotate)
     if est_ms is None:
         est_ms = time_steps(prob, M, 10, 3, torch, api, stream, graph=False, rotate=rotate)
     steps = max(20, min(200, int(8.0 / max(est_ms, 1e-3))))
