@@ -93,15 +93,23 @@ int liquidquant_unpack_weights(const void *W_packed, const uint8_t *gparams, int
  * W4A8 GEMM (device, Sec. 5: load, unpack, LQQ dequantisation, INT8 MFMA, epilogue)
  * ------------------------------------------------------------------------------------ */
 
-/* Bytes of device workspace w4a8_gemm* can use for this shape: room for the INT32 partial
- * tiles of the grid-level split-K (0 when no kernel that can run the shape splits K across
- * blocks).  No initialisation is required.  With a smaller (or NULL) workspace the
- * dispatcher runs the same kernels without the split, which is slower for small N but gives
- * the same result; a variant that names its split (w4a8_gemm_variant) fails with
- * LQ_ERR_WORKSPACE instead.  Split-K calls also share a small library-owned ticket array
- * on the device: two such calls that overlap in time on one GPU (different streams) race,
- * calls on one stream are safe. */
+/* Bytes of device workspace w4a8_gemm* can use for this shape (0 when no kernel that can run
+ * the shape splits K across blocks): 32 KiB of arrival tickets followed by room for the INT32
+ * partial tiles of the grid-level split-K.
+ *   - The first 32 KiB (or the whole buffer if smaller) must be zero before the first call
+ *     that uses the buffer: zero it yourself or enqueue w4a8_workspace_init() once.  The
+ *     kernels leave the tickets zero again, so one initialisation serves any number of calls,
+ *     shapes and HIP graph replays.  The rest needs no initialisation.
+ *   - One workspace serves one call at a time: calls that may overlap in time on one GPU
+ *     (different streams) need different workspaces; calls on one stream can share one.
+ *   - With a smaller (or NULL) workspace the dispatcher runs the same kernels without the
+ *     split, which is slower for small N but gives the same result; a variant that names its
+ *     split (w4a8_gemm_variant) fails with LQ_ERR_WORKSPACE instead. */
 size_t w4a8_gemm_workspace_size(int M, int N, int K, int group);
+
+/* Enqueue the zeroing of a workspace's ticket area on `hip_stream` (a small fill kernel; safe
+ * under HIP graph capture).  NULL or empty workspaces are a successful no-op. */
+int w4a8_workspace_init(void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Y[M,N] (device, FP16 bits, row-major) = epilogue(X . dequant(W)^T).
  *   X           device [M,K] INT8 row-major

@@ -56,6 +56,8 @@ def lib() -> ctypes.CDLL:
     L.liquidquant_unpack_weights.argtypes = [vp, vp, i, i, i, vp, vp, vp]
     L.w4a8_gemm_workspace_size.restype = sz
     L.w4a8_gemm_workspace_size.argtypes = [i, i, i, i]
+    L.w4a8_workspace_init.restype = i
+    L.w4a8_workspace_init.argtypes = [vp, sz, vp]
     L.w4a8_gemm.restype = i
     L.w4a8_gemm.argtypes = [i, i, i, i, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.w4a8_gemm_i32.restype = i
@@ -182,19 +184,29 @@ def w4a8_gemm_workspace_size(M: int, N: int, K: int, group: int) -> int:
 _ws_cache = {}
 
 
-def _ws(workspace, M=0, N=0, K=0, group=64, device=None):
-    """Workspace pointer and size.  With workspace=None a buffer of the size the library asks
-    for is allocated once per device and reused (device memory plumbing, nothing else)."""
+def w4a8_workspace_init(workspace, stream=None) -> None:
+    """Zero the ticket area at the head of a workspace tensor (uint8, on the GPU)."""
+    import torch
+
+    _check(lib().w4a8_workspace_init(_dev(workspace, torch.uint8, name="workspace"), workspace.numel(),
+                                     _stream(stream)))
+
+
+def _ws(workspace, M=0, N=0, K=0, group=64, device=None, stream=None):
+    """Workspace pointer and size.  With workspace=None a zero-initialised buffer of the size
+    the library asks for is allocated once per (device, stream) and reused: calls on different
+    streams may overlap and must not share one (device memory plumbing, nothing else)."""
     import torch
 
     if workspace is None:
         need = w4a8_gemm_workspace_size(M, N, K, group) if M > 0 else 0
         if need == 0:
             return None, 0
-        key = str(device)
+        key = (str(device), int(stream) if stream is not None else int(torch.cuda.current_stream().cuda_stream))
         buf = _ws_cache.get(key)
         if buf is None or buf.numel() < need:
-            buf = torch.empty(need, dtype=torch.uint8, device=device)
+            buf = torch.zeros(need, dtype=torch.uint8, device=device)
+            torch.cuda.current_stream().synchronize()  # zeroed before any other stream can use it
             _ws_cache[key] = buf
         workspace = buf
     return _dev(workspace, torch.uint8, name="workspace"), workspace.numel()
@@ -208,7 +220,7 @@ def w4a8_gemm(X, act_scales, W_packed, gparams, w_scales, N: int, K: int, group:
     M = X.shape[0]
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
-    wsp, wsb = _ws(workspace, M, N, K, group, X.device)
+    wsp, wsb = _ws(workspace, M, N, K, group, X.device, stream)
     cb, gb = liquidquant_packed_size(N, K, group)
     _check(lib().w4a8_gemm(M, N, K, group, _dev(X, torch.int8, (M, K), "X"),
                            _dev(act_scales, torch.float32, (M,), "act_scales"),
@@ -227,7 +239,7 @@ def w4a8_gemm_i32(X, W_packed, gparams, N: int, K: int, group: int, out=None, wo
     M = X.shape[0]
     if out is None:
         out = torch.empty((M, N), dtype=torch.int32, device=X.device)
-    wsp, wsb = _ws(workspace, M, N, K, group, X.device)
+    wsp, wsb = _ws(workspace, M, N, K, group, X.device, stream)
     cb, gb = liquidquant_packed_size(N, K, group)
     _check(lib().w4a8_gemm_i32(M, N, K, group, _dev(X, torch.int8, (M, K), "X"),
                                _dev(W_packed, torch.uint8, (cb,), "W_packed"),
@@ -247,7 +259,7 @@ def w4a8_gemm_variant(variant: int, X, act_scales, W_packed, gparams, w_scales, 
         out_y = torch.empty((M, N), dtype=torch.float16, device=X.device)
     if want_acc and out_acc is None:
         out_acc = torch.empty((M, N), dtype=torch.int32, device=X.device)
-    wsp, wsb = _ws(workspace, M, N, K, group, X.device)
+    wsp, wsb = _ws(workspace, M, N, K, group, X.device, stream)
     cb, gb = liquidquant_packed_size(N, K, group)
     _check(lib().w4a8_gemm_variant(
         variant, M, N, K, group, _dev(X, torch.int8, (M, K), "X"),

@@ -40,6 +40,14 @@
 
 namespace lqq {
 
+// Clears the ticket area at the head of a workspace (a fill kernel rather than a memset, so
+// that it can be captured in a HIP graph like everything else here).
+__global__ __launch_bounds__(256) void workspace_init_kernel(unsigned int *tickets, int n)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) tickets[i] = 0u;
+}
+
 // ------------------------------------------------------------------------------------
 // Layout hook: packed -> INT8 [N,K] with the kernels' own unpack + Eq. 12 path.
 // One wave per 1 KiB chunk (32 channels x 64 k).
@@ -109,11 +117,12 @@ __device__ long long g_dbg_stamps[4 * 16384];
     } while (0)
 #endif
 
-// Arrival tickets of the grid-level split-K, one per tile group (blockIdx.x).  Zero when
-// the library is loaded; the last block of a group resets its ticket, so every call finds
-// zeros again.  Calls that use split-K and overlap in time on one GPU would share them.
+// Arrival tickets of the grid-level split-K, one per tile group, live at the head of the
+// caller's workspace (kTicketBytes, zeroed once by the caller or by w4a8_workspace_init).
+// The last block of a group resets its ticket, so every call finds zeros again; calls that
+// overlap in time are independent as long as they use different workspaces.
 constexpr int kMaxTicketGroups = 8192;
-__device__ unsigned int g_splitk_tickets[kMaxTicketGroups];
+constexpr size_t kTicketBytes = kMaxTicketGroups * sizeof(unsigned int);
 
 // Device-scope (write-through / cache-bypassing) 16-byte accesses for the exchange of
 // split-K partial tiles between blocks that may sit on different XCDs: the sc1 forms of
@@ -144,10 +153,11 @@ __device__ __forceinline__ void wait_vmcnt0(v4i &a, v4i &b, v4i &c, v4i &d)
 // gridDim.y); grouped launches compute them per expert.
 struct Place {
     int gx, gnx, ks, S;
+    unsigned int *tickets;  // arrival tickets of the split-K groups (unused when S == 1)
 };
-__device__ __forceinline__ Place grid_place()
+__device__ __forceinline__ Place grid_place(unsigned int *tickets)
 {
-    return Place{(int)blockIdx.x, (int)gridDim.x, (int)blockIdx.y, (int)gridDim.y};
+    return Place{(int)blockIdx.x, (int)gridDim.x, (int)blockIdx.y, (int)gridDim.y, tickets};
 }
 
 template <int F, int MF, bool G128>
@@ -280,7 +290,7 @@ __device__ __forceinline__ void stream_block(
             __hip_atomic_store(mine + idx, block_sum(idx), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();  // includes s_waitcnt vmcnt(0): every store above has been acknowledged
         if (threadIdx.x == 0) {
-            const unsigned t = __hip_atomic_fetch_add(&g_splitk_tickets[pl.gx], 1u, __ATOMIC_RELAXED,
+            const unsigned t = __hip_atomic_fetch_add(&pl.tickets[pl.gx], 1u, __ATOMIC_RELAXED,
                                                       __HIP_MEMORY_SCOPE_AGENT);
             s_last = (t == (unsigned)(S - 1));
         }
@@ -295,7 +305,7 @@ __device__ __forceinline__ void stream_block(
                 finish(idx, sum);
             }
             if (threadIdx.x == 0)  // ready for the next call
-                __hip_atomic_store(&g_splitk_tickets[pl.gx], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&pl.tickets[pl.gx], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     LQ_STAMP(3);
@@ -305,9 +315,10 @@ template <int F, int NW, int MF, bool G128>
 __global__ __launch_bounds__(NW * 64) void w4a8_stream_kernel(
     int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
-    __half *__restrict__ Y, int32_t *__restrict__ ACC, int32_t *__restrict__ partials)
+    __half *__restrict__ Y, int32_t *__restrict__ ACC, int32_t *__restrict__ partials,
+    unsigned int *__restrict__ tickets)
 {
-    stream_block<F, NW, MF, G128>(grid_place(), M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+    stream_block<F, NW, MF, G128>(grid_place(tickets), M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
 }
 
 // ------------------------------------------------------------------------------------
@@ -466,7 +477,7 @@ __device__ __forceinline__ void stream16_block(
             __hip_atomic_store(mine + idx, block_sum(idx), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
         if (threadIdx.x == 0) {
-            const unsigned t = __hip_atomic_fetch_add(&g_splitk_tickets[pl.gx], 1u, __ATOMIC_RELAXED,
+            const unsigned t = __hip_atomic_fetch_add(&pl.tickets[pl.gx], 1u, __ATOMIC_RELAXED,
                                                       __HIP_MEMORY_SCOPE_AGENT);
             s_last = (t == (unsigned)(S - 1));
         }
@@ -484,7 +495,7 @@ __device__ __forceinline__ void stream16_block(
                 finish(i, idx, sum);
             }
             if (threadIdx.x == 0)
-                __hip_atomic_store(&g_splitk_tickets[pl.gx], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&pl.tickets[pl.gx], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }
@@ -493,9 +504,10 @@ template <int F, int NW, int UU, bool G128, int ABL = 0>
 __global__ __launch_bounds__(NW * 64) void w4a8_stream16_kernel(
     int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
-    __half *__restrict__ Y, int32_t *__restrict__ ACC, int32_t *__restrict__ partials)
+    __half *__restrict__ Y, int32_t *__restrict__ ACC, int32_t *__restrict__ partials,
+    unsigned int *__restrict__ tickets)
 {
-    stream16_block<F, NW, UU, G128, ABL>(grid_place(), M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+    stream16_block<F, NW, UU, G128, ABL>(grid_place(tickets), M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
 }
 
 // ------------------------------------------------------------------------------------
@@ -973,7 +985,7 @@ __device__ __forceinline__ void duo_tile(
             LQ_DSTAMP(4);
             __syncthreads();
             if (threadIdx.x == 0) {
-                const unsigned tk = __hip_atomic_fetch_add(&g_splitk_tickets[tile], 1u, __ATOMIC_RELAXED,
+                const unsigned tk = __hip_atomic_fetch_add(&pl.tickets[tile], 1u, __ATOMIC_RELAXED,
                                                            __HIP_MEMORY_SCOPE_AGENT);
                 s_last = (tk == (unsigned)(S - 1));
             }
@@ -1010,7 +1022,7 @@ __device__ __forceinline__ void duo_tile(
             }
             LQ_DSTAMP(6);
             if (threadIdx.x == 0)
-                __hip_atomic_store(&g_splitk_tickets[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&pl.tickets[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (!active) return;
         store_tile<MFK>(*reinterpret_cast<const v16i(*)[MFK][2]>(&acc[MF0]), M, N, m0 + 32 * MF0,
@@ -1043,11 +1055,11 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
     int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
     __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n,
-    int32_t *__restrict__ partials)
+    int32_t *__restrict__ partials, unsigned int *__restrict__ tickets)
 {
     int bm, bn;
     block_coords(blocks_m, blocks_n, bm, bn);
-    duo_block<G128, KG, TM>(grid_place(), bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+    duo_block<G128, KG, TM>(grid_place(tickets), bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
 }
 
 // ------------------------------------------------------------------------------------
@@ -1083,7 +1095,7 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream16_grouped_kernel(const Gr
 {
     const int i = blockIdx.x / groups, gx = blockIdx.x % groups;
     const int e = g.expert[i], r0 = g.row_off[i];
-    stream16_block<2, NW, UU, G128>(Place{gx, groups, 0, 1}, g.rows[i], N, K, p.X + (size_t)r0 * K, p.sx + r0,
+    stream16_block<2, NW, UU, G128>(Place{gx, groups, 0, 1, nullptr}, g.rows[i], N, K, p.X + (size_t)r0 * K, p.sx + r0,
                                     p.Wp + e * p.w_stride, p.gp + e * p.gp_stride, p.sw + (size_t)e * N,
                                     p.Y ? p.Y + (size_t)r0 * N : nullptr, p.ACC ? p.ACC + (size_t)r0 * N : nullptr,
                                     nullptr);
@@ -1095,7 +1107,7 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream_grouped_kernel(const Grou
 {
     const int i = blockIdx.x / groups, gx = blockIdx.x % groups;
     const int e = g.expert[i], r0 = g.row_off[i];
-    stream_block<2, NW, 1, G128>(Place{gx, groups, 0, 1}, g.rows[i], N, K, p.X + (size_t)r0 * K, p.sx + r0,
+    stream_block<2, NW, 1, G128>(Place{gx, groups, 0, 1, nullptr}, g.rows[i], N, K, p.X + (size_t)r0 * K, p.sx + r0,
                               p.Wp + e * p.w_stride, p.gp + e * p.gp_stride, p.sw + (size_t)e * N,
                               p.Y ? p.Y + (size_t)r0 * N : nullptr, p.ACC ? p.ACC + (size_t)r0 * N : nullptr,
                               nullptr);
@@ -1113,7 +1125,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_grouped_ke
     // row tiles of one column block are neighbours, so they meet on the expert's W columns
     const int blocks_m = (M + 127) >> 7;
     const int bm = local % blocks_m, bn = local / blocks_m;
-    duo_block<G128, KG>(Place{0, 1, 0, 1}, bm, bn, M, N, K, p.X + (size_t)r0 * K, p.sx + r0,
+    duo_block<G128, KG>(Place{0, 1, 0, 1, nullptr}, bm, bn, M, N, K, p.X + (size_t)r0 * K, p.sx + r0,
                         p.Wp + e * p.w_stride, p.gp + e * p.gp_stride, p.sw + (size_t)e * N,
                         p.Y ? p.Y + (size_t)r0 * N : nullptr, p.ACC ? p.ACC + (size_t)r0 * N : nullptr, nullptr);
 }
@@ -1164,7 +1176,7 @@ static size_t stream_ws_bytes(int M, int N, int S, int MF = 1)
 {
     if (S <= 1) return 0;
     const int rmax = MF == 1 ? 4 * ((M + 7) / 8) : 16;
-    return (size_t)S * (N / 32) * MF * rmax * 64 * sizeof(int32_t);
+    return kTicketBytes + (size_t)S * (N / 32) * MF * rmax * 64 * sizeof(int32_t);
 }
 
 // S = requested number of K slices; `named` = the variant names its split (then a missing
@@ -1188,15 +1200,16 @@ static int launch_stream_as(const Args &a, int S, bool named)
     const dim3 grid(groups, S), block(NW * 64);
     const int rmax = MF == 1 ? 4 * ((a.M + 7) / 8) : 16;
     const size_t lds_bytes = (size_t)NW * F * MF * rmax * 64 * sizeof(int);
-    int32_t *partials = static_cast<int32_t *>(a.ws);
+    unsigned int *tickets = static_cast<unsigned int *>(a.ws);
+    int32_t *partials = a.ws ? reinterpret_cast<int32_t *>(static_cast<char *>(a.ws) + kTicketBytes) : nullptr;
     if (a.group == 128) {
         if (int rc = allow_lds(&w4a8_stream_kernel<F, NW, MF, true>, lds_bytes)) return rc;
         hipLaunchKernelGGL((w4a8_stream_kernel<F, NW, MF, true>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
-                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials);
+                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials, tickets);
     } else {
         if (int rc = allow_lds(&w4a8_stream_kernel<F, NW, MF, false>, lds_bytes)) return rc;
         hipLaunchKernelGGL((w4a8_stream_kernel<F, NW, MF, false>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
-                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials);
+                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials, tickets);
     }
     return LQ_OK;
 }
@@ -1232,7 +1245,7 @@ static int launch_stream16(const Args &a)
     if ((a.K / 128) % UU != 0) return fail(LQ_ERR_INVALID, "K/128 not a multiple of UU=%d", UU);
     S = std::min(S, a.K / (128 * UU));
     if (S > 1 && groups > kMaxTicketGroups) S = 1;
-    size_t need = S > 1 ? (size_t)S * (a.N / 32) * 8 * 64 * sizeof(int32_t) : 0;
+    size_t need = S > 1 ? kTicketBytes + (size_t)S * (a.N / 32) * 8 * 64 * sizeof(int32_t) : 0;
     if (need > 0 && (!a.ws || a.ws_bytes < need)) {
         if (SPLIT)
             return fail(LQ_ERR_WORKSPACE, "split-K needs %zu bytes of workspace, got %zu", need,
@@ -1242,15 +1255,16 @@ static int launch_stream16(const Args &a)
     }
     const dim3 grid(groups, S), block(NW * 64);
     const size_t lds_bytes = (size_t)NW * F * 8 * 64 * sizeof(int);
-    int32_t *partials = static_cast<int32_t *>(a.ws);
+    unsigned int *tickets = static_cast<unsigned int *>(a.ws);
+    int32_t *partials = a.ws ? reinterpret_cast<int32_t *>(static_cast<char *>(a.ws) + kTicketBytes) : nullptr;
     if (a.group == 128) {
         if (int rc = allow_lds(&w4a8_stream16_kernel<F, NW, UU, true, ABL>, lds_bytes)) return rc;
         hipLaunchKernelGGL((w4a8_stream16_kernel<F, NW, UU, true, ABL>), grid, block, lds_bytes, a.stream, a.M, a.N,
-                           a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials);
+                           a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials, tickets);
     } else {
         if (int rc = allow_lds(&w4a8_stream16_kernel<F, NW, UU, false, ABL>, lds_bytes)) return rc;
         hipLaunchKernelGGL((w4a8_stream16_kernel<F, NW, UU, false, ABL>), grid, block, lds_bytes, a.stream, a.M, a.N,
-                           a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials);
+                           a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials, tickets);
     }
     return LQ_OK;
 }
@@ -1292,7 +1306,7 @@ static size_t duo_ws_bytes(int M, int N, int S, int tm = 128)
 {
     if (S <= 1) return 0;
     const size_t tiles = (size_t)((M + tm - 1) / tm) * ((N + 255) / 256);
-    return tiles * S * 4 * 32 * 256 * sizeof(int32_t);  // the slot of a tile has the full size whatever its height
+    return kTicketBytes + tiles * S * 4 * 32 * 256 * sizeof(int32_t);  // a tile's slot has the full size whatever its height
 }
 
 template <int SPLIT, int KG, int TM = 128>
@@ -1317,15 +1331,16 @@ static int launch_duo_as(const Args &a, int S)
     const size_t lds_bytes = KG == 1 ? 2 * (size_t)128 * kTilePitch
                                      : std::max<size_t>(KG * 2 * (size_t)128 * kTilePitch, 64 * 1024);
     const dim3 grid((unsigned)(blocks_n * blocks_m), (unsigned)S), block(256 * KG);
-    int32_t *partials = static_cast<int32_t *>(a.ws);
+    unsigned int *tickets = static_cast<unsigned int *>(a.ws);
+    int32_t *partials = a.ws ? reinterpret_cast<int32_t *>(static_cast<char *>(a.ws) + kTicketBytes) : nullptr;
     if (a.group == 128) {
         if (int rc = allow_lds(w4a8_duo_kernel<true, KG, TM>, lds_bytes)) return rc;
         hipLaunchKernelGGL((w4a8_duo_kernel<true, KG, TM>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K, a.X,
-                           a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n, partials);
+                           a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n, partials, tickets);
     } else {
         if (int rc = allow_lds(w4a8_duo_kernel<false, KG, TM>, lds_bytes)) return rc;
         hipLaunchKernelGGL((w4a8_duo_kernel<false, KG, TM>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K, a.X,
-                           a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n, partials);
+                           a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n, partials, tickets);
     }
     return LQ_OK;
 }
@@ -1617,8 +1632,22 @@ size_t w4a8_gemm_workspace_size(int M, int N, int K, int group)
     size_t need = tiles >= 192 ? 0 : std::max(duo_ws_bytes(M, N, 8), duo_ws_bytes(M, N, 8, 64));
     if (M <= 32) need = std::max(need, stream_ws_bytes(M, N, 16));
     if (M <= 64) need = std::max(need, stream_ws_bytes(M, N, 16, 2));
-    if (M <= 16) need = std::max(need, (size_t)16 * (N / 32) * 8 * 64 * sizeof(int32_t));
+    if (M <= 16) need = std::max(need, kTicketBytes + (size_t)16 * (N / 32) * 8 * 64 * sizeof(int32_t));
     return need;
+}
+
+int w4a8_workspace_init(void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!workspace || workspace_bytes == 0) return LQ_OK;
+    if ((uintptr_t)workspace & 15) return fail(LQ_ERR_ALIGN, "device pointers must be 16-byte aligned");
+    const int n = (int)(std::min(workspace_bytes, kTicketBytes) / sizeof(unsigned int));
+    if (n == 0) return LQ_OK;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(workspace_init_kernel, dim3((n + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<unsigned int *>(workspace), n);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(LQ_ERR_HIP, "workspace init launch failed: %s", hipGetErrorString(e));
+    return LQ_OK;
 }
 
 int w4a8_gemm(int M, int N, int K, int group, const int8_t *X, const float *act_scales,

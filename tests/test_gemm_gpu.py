@@ -323,7 +323,7 @@ def test_hip_graph_replays_of_split_k_kernels():
         X2, s_x2 = WL.make_activations(M, K, seed=M + 2)
         dX, dsx = torch.from_numpy(X).cuda(), torch.from_numpy(s_x).cuda()
         dX2, dsx2 = torch.from_numpy(X2).cuda(), torch.from_numpy(s_x2).cuda()
-        ws = torch.empty(api.w4a8_gemm_workspace_size(M, N, K, g) + 16, dtype=torch.uint8, device="cuda")
+        ws = torch.zeros(api.w4a8_gemm_workspace_size(M, N, K, g) + 16, dtype=torch.uint8, device="cuda")
         out = torch.empty((M, N), dtype=torch.int32, device="cuda")
         eager = api.w4a8_gemm_i32(dX, P.d_packed, P.d_gparams, N, K, g, workspace=ws).clone()
         eager2 = api.w4a8_gemm_i32(dX2, P.d_packed, P.d_gparams, N, K, g, workspace=ws).clone()
@@ -341,3 +341,39 @@ def test_hip_graph_replays_of_split_k_kernels():
             other = api.w4a8_gemm_i32(dX2, P.d_packed, P.d_gparams, N, K, g, workspace=ws)   # eager work in between
             torch.cuda.synchronize()
             assert torch.equal(other, eager2)
+
+
+def test_workspace_init_and_concurrent_streams():
+    """The split-K state lives in the caller's workspace: a dirty buffer works after
+    w4a8_workspace_init, and calls that overlap on two streams, each with its own workspace,
+    do not disturb each other."""
+    import torch
+
+    M, N, K, g = 8, 1024, 8192, 64          # stream16 with grid split-K
+    assert api.w4a8_variant_name(api.w4a8_select_variant(M, N, K, g)).startswith("stream16")
+    P = H.Problem(N, K, g, seed=77)
+    X, s_x = WL.make_activations(M, K, seed=78)
+    ACC_ref, _ = P.oracle_gemm(X, s_x)
+    ref = torch.from_numpy(ACC_ref).cuda()
+    dX = torch.from_numpy(X).cuda()
+    need = api.w4a8_gemm_workspace_size(M, N, K, g)
+    assert need > 32768
+    _say("dirty workspace + init")
+    dirty = torch.full((need,), 0xFF, dtype=torch.uint8, device="cuda")
+    api.w4a8_workspace_init(dirty)
+    for _ in range(3):
+        out = api.w4a8_gemm_i32(dX, P.d_packed, P.d_gparams, N, K, g, workspace=dirty)
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref)
+    _say("two streams")
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    spaces = [torch.zeros(need, dtype=torch.uint8, device="cuda") for _ in streams]
+    outs = [[torch.empty((M, N), dtype=torch.int32, device="cuda") for _ in range(40)] for _ in streams]
+    torch.cuda.synchronize()
+    for i in range(40):
+        for s, ws, o in zip(streams, spaces, outs):
+            api.w4a8_gemm_i32(dX, P.d_packed, P.d_gparams, N, K, g, out=o[i], workspace=ws, stream=s.cuda_stream)
+    torch.cuda.synchronize()
+    for o in outs:
+        for t in o:
+            assert torch.equal(t, ref)
