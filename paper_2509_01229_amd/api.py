@@ -14,7 +14,8 @@ import os
 import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libliquidgemm.so")
+# LIQUIDGEMM_LIB lets tools load another build of the same library (e.g. an experiment build)
+LIB_PATH = os.environ.get("LIQUIDGEMM_LIB") or os.path.join(_PKG, "libliquidgemm.so")
 _lib = None
 
 LQ_OK = 0
