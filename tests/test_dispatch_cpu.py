@@ -20,8 +20,11 @@ def test_dispatcher_families_on_the_workloads():
         elif s.M <= 64 and s.N <= 16384:
             assert name == "stream_m64", (s.name, name)
         else:
-            assert name in ("duo_m64", "duo_m128"), (s.name, name)
-            if -(-s.M // 64) * -(-s.N // 256) > 256:
+            assert name in ("duo_m64", "duo_m128", "duo_dl_m128"), (s.name, name)
+            tiles128 = -(-s.M // 128) * -(-s.N // 256)
+            if tiles128 >= 512:       # two tiles per CU: the direct-to-LDS pipeline
+                assert name == "duo_dl_m128", (s.name, name)
+            elif -(-s.M // 64) * -(-s.N // 256) > 256:
                 assert name == "duo_m128", (s.name, name)
         v = api.w4a8_select_variant(s.M, s.N, s.K, s.group)
         assert api.w4a8_variant_supports(v, s.M, s.N, s.K, s.group)
@@ -39,6 +42,8 @@ def test_dispatcher_boundaries():
     assert _pick(256, 8192, 28672, 128) == "duo_m128"          # long K: more slices of 128-row tiles win
     assert _pick(256, 8192, 8192) == "duo_m64" and _pick(256, 10240, 8192, 128) == "duo_m128"
     assert _pick(128, 4096, 256) == "duo_m128"                 # one k unit: no room for two k groups
+    assert _pick(2048, 8192, 8192) == "duo_dl_m128" and _pick(2047 - 127, 8192, 8192) == "duo_m128"   # 512 tiles or fewer
+    assert _pick(4096, 8192, 8192) == "duo_dl_m128" and _pick(1024, 28672, 8192, 128) == "duo_dl_m128"
     with pytest.raises(api.LiquidGemmError):
         api.w4a8_select_variant(8, 100, 512, 64)                # bad shape
 

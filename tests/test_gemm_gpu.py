@@ -75,6 +75,7 @@ SMALL = [
     (128, 64, 512, 64),      # exactly 128 rows: four row fragments of the stream kernel
     (200, 256, 256, 64),     # one k unit only
     (130, 576, 1280, 128),
+    (300, 320, 1792, 64),    # 14 stages of 128 k; last row tile with 44 rows, N tail
 ]
 
 
