@@ -45,7 +45,7 @@ ROTATE_BYTES = 512 << 20
 # and raw figures are in profiles/.  Counters cannot be read from inside a timed run, so
 # the figure is carried here per (workload, kernel) and is null for anything not profiled.
 MEASURED_TRAFFIC_BYTES = {
-    ("prefill_M4096_N8192_K8192", "duo_m128"): 477.4e6,
+    ("prefill_M4096_N8192_K8192", "duo_dl_m128"): 478.4e6,
     ("l70b_up_M16_N28672_K8192", "stream16_f2_w4"): 123.3e6,
 }
 

@@ -718,11 +718,12 @@ __device__ __forceinline__ void lds_barrier()
 // ------------------------------------------------------------------------------------
 // duo kernel: two waves per SIMD.
 //
-// On CDNA a wave issues in order and its own MFMA keeps it busy for the whole instruction,
-// so the VALU work of the dequantisation only overlaps with matrix work of ANOTHER wave on
-// the same SIMD -- exactly the observation behind the paper's implicit fine-grained
-// pipeline (Sec. 5.1: dequantisation in one compute group overlaps MMA in another, with
-// the hardware arbitrating).  This kernel therefore keeps every wave at <= 256 registers
+// On CDNA a wave issues in order and an MFMA holds the SIMD's vector issue for part of its
+// duration (8 to 16 of the 32 cycles of a 32x32x32 INT8 MFMA, measured), so the VALU work of
+// the dequantisation overlaps best with matrix work of ANOTHER wave on the same SIMD --
+// the observation behind the paper's implicit fine-grained pipeline (Sec. 5.1:
+// dequantisation in one compute group overlaps MMA in another, with the hardware
+// arbitrating).  This kernel therefore keeps every wave at <= 256 registers
 // (wave tile 128 x 64, block tile 128 x 256, two blocks per CU) and software-pipelines each
 // wave at the granularity of one k-step (32 k): while the 8 MFMAs of a k-step run, the
 // B operand of the next k-step is dequantised and its X fragments are read from LDS.
