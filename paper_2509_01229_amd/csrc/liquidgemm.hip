@@ -1815,7 +1815,18 @@ static int select_variant(int M, int N, int K)
     if (M <= 32) return find_variant("stream_m32");
     // up to 64 rows the weights are still best streamed once per block column unless N alone
     // fills the chip with 128 x 256 tiles
-    if (M <= 64 && N / 32 <= 512) return find_variant("stream_m64");
+    if (M <= 64 && N / 32 <= 512) {
+        // ... except when N alone gives the stream kernel its 256 blocks (no K slices) and K is
+        // long: each wave then walks K / 1024 units of 128 k at about 0.027 us per row, against
+        // the tiled kernel's split-K grid (fits of measured times, microseconds)
+        if (N / 32 >= 256 && K >= 8192) {
+            const double est_stream = 7.5 + 0.027 * M * (K / 1024) * (N / 32 > 256 ? 1.15 : 1.0);
+            const int S = duo_split(M, N, K);
+            const double est_tiled = 0.85 * (8.1 + 1.76 * (K / 256) / (2.0 * S) + 2.4 * (S - 1));
+            if (est_tiled < est_stream) return find_variant("duo_m128");
+        }
+        return find_variant("stream_m64");
+    }
     // two or more 128 x 256 tiles per CU: the deeper memory pipeline of the direct-to-LDS form
     // pays (3 to 4 % measured); with fewer tiles the two k groups per block of the other form do
     if (((M + 127) / 128) * ((N + 255) / 256) >= 512 && (long long)M * K < (1ll << 32))
