@@ -1526,6 +1526,9 @@ template <int MF>
 static int launch_stream_auto(const Args &a)
 {
     const int tiles = a.N / 32;
+    // long K with no room for K slices: two tiles per block share the X fragments and two
+    // K slices halve each wave's walk (27 vs 31 us at 24 rows on 8192 x 28672)
+    if (tiles > 128 && tiles <= 256 && a.K >= 16384) return launch_stream_as<2, 8, MF>(a, 2, false);
     if (tiles <= 256) return launch_stream_as<1, 8, MF>(a, std::min(4, 256 / tiles), false);
     return launch_stream_as<2, 8, MF>(a, std::min(4, 512 / tiles), false);
 }
@@ -1746,6 +1749,7 @@ static const Variant kVariants[] = {
     {"stream16_f2_w8_s1", &launch_stream16<2, 8, 1>, 16, 2, 1},
     {"stream16_f2_w8_s2", &launch_stream16<2, 8, 2>, 16, 2, 1},
     {"stream16_f2_w8_s4", &launch_stream16<2, 8, 4>, 16, 2, 1},
+    {"stream16_f1_w8", &launch_stream16<1, 8, 0>, 16, 1, 1},
     {"stream16_f1_w8_s1", &launch_stream16<1, 8, 1>, 16, 1, 1},
     {"stream16_f2_w16_s1", &launch_stream16<2, 16, 1>, 16, 2, 1},
     {"stream16_f1_w16_s1", &launch_stream16<1, 16, 1>, 16, 1, 1},
@@ -1809,7 +1813,10 @@ static int select_variant(int M, int N, int K)
     if (M <= 16) {
         // small weight matrices are bound by launch and first-load latency: one tile per
         // block and all of a wave's loads (512 k) in flight at once
-        if (K % 512 == 0 && K <= 8192 && N / 32 <= 256) return find_variant("stream16_f1_w8_u4");
+        if (K % 512 == 0 && K <= 8192 && N / 32 <= 256)
+            return find_variant(M > 8 && K >= 4096 ? "stream16_f1_w16_s1" : "stream16_f1_w8_u4");
+        // other matrices of up to 256 tiles: still one tile per block, and K slices across blocks
+        if (N / 32 <= 256) return find_variant("stream16_f1_w8");
         return find_variant(N / 64 >= 384 ? "stream16_f2_w4" : "stream16_f2_w8");
     }
     if (M <= 32) return find_variant("stream_m32");
