@@ -1693,6 +1693,8 @@ static int duo64_split(int M, int N, int K)
     const int tiles = ((M + 63) / 64) * ((N + 255) / 256);
     const int units = K / 256;
     int s = (int)(0.6 * std::sqrt((double)units) + 0.5);  // minimum of the fitted cost below
+    // with few tiles the exchange of a slice is cheap (few blocks share the memory system)
+    s = std::max(s, tiles <= 40 ? 4 : tiles <= 64 ? 3 : 1);
     s = std::min(std::min(s, 256 / std::max(1, tiles)), std::min(units / 2, 8));
     return std::max(1, s);
 }
@@ -1705,7 +1707,8 @@ static int launch_duo64(const Args &a)
 
 // Which tile height for a problem with few tiles.  Fitted to measurements of both forms with
 // two k groups per block (microseconds; u = 256-k units per k group, S = K slices):
-//   128-row tiles: 13.9 + 1.95 u + 2.3 (S - 1)       64-row tiles: 8.1 + 1.76 u + 2.4 (S - 1)
+//   128-row tiles: 13.9 + 1.95 u + 2.3 (S - 1)       64-row tiles: 8.1 + 1.76 u + c (S - 1),
+//   c = 0.8 + 1.6 * blocks / 256 (a slice costs less when few blocks exchange at once)
 static bool prefer_64_row_tiles(int M, int N, int K)
 {
     const int bn = (N + 255) / 256;
@@ -1713,7 +1716,7 @@ static bool prefer_64_row_tiles(int M, int N, int K)
     if (K < 512 || t64 > 256 || t128 > 256) return false;
     const int s128 = duo_split(M, N, K), s64 = duo64_split(M, N, K);
     const double est128 = 13.9 + 1.95 * units / (2.0 * s128) + 2.3 * (s128 - 1);
-    const double est64 = 8.1 + 1.76 * units / (2.0 * s64) + 2.4 * (s64 - 1);
+    const double est64 = 8.1 + 1.76 * units / (2.0 * s64) + (0.8 + 1.6 * t64 * s64 / 256.0) * (s64 - 1);
     return est64 < est128;
 }
 
