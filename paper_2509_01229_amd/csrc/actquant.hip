@@ -10,9 +10,13 @@
 // bit for bit; the kernel reproduces it exactly (see round8 for how the second division is
 // avoided where it cannot matter).
 //
-// One block of 256 threads per token.  A token of up to 16384 elements is read from HBM
-// once and kept in registers between the max pass and the rounding pass; longer tokens
-// are read twice (the second read hits L2).  Traffic: 2 bytes in, 1 byte out per element.
+// One block of 256 threads per token (or per R consecutive tokens, one after the other, so
+// that the reciprocals of the smooth scales are computed once for R tokens).  A token of up
+// to 16384 elements is read from HBM once and kept in registers between the max pass and the
+// rounding pass; longer tokens are read twice (the second read hits L2).  Traffic: 2 bytes
+// in, 1 byte out per element.
+#include <algorithm>
+
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
@@ -57,6 +61,42 @@ __device__ __forceinline__ void convert8(const Raw8 &r, float (&f)[8])
     }
 }
 
+// x / s, correctly rounded, from a reciprocal refined once per smooth scale.  This is the
+// instruction sequence of the IEEE division without its scaling and special-case steps
+// (y1 = rcp refined by one Newton step; quotient x * y1 corrected twice with exact
+// residuals), which change nothing while s is within [2^-40, 2^40] and x is zero or an FP16
+// magnitude (2^-24 .. 65504): no intermediate leaves the normal range.  Callers check s.
+struct Recip {
+    float s, y1;
+};
+__device__ __forceinline__ Recip refine_recip(float s)
+{
+    const float y0 = __builtin_amdgcn_rcpf(s);
+    const float e = __builtin_fmaf(-s, y0, 1.0f);
+    return Recip{s, __builtin_fmaf(e, y0, y0)};
+}
+__device__ __forceinline__ float div_by(float x, const Recip r)
+{
+    const float q0 = x * r.y1;
+    const float r0 = __builtin_fmaf(-r.s, q0, x);
+    const float q1 = __builtin_fmaf(r0, r.y1, q0);
+    const float r1 = __builtin_fmaf(-r.s, q1, x);
+    return __builtin_fmaf(r1, r.y1, q1);
+}
+__device__ __forceinline__ bool recip_is_safe(float s) { return s >= 0x1p-40f && s <= 0x1p40f; }
+
+// 8 FP16 values -> FP32 (no smooth divide)
+__device__ __forceinline__ void widen8(const u32x4 x, float (&f)[8])
+{
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const uint32_t w = x[d];
+        const f16x2 h = __builtin_bit_cast(f16x2, w);
+        f[2 * d] = (float)h[0];
+        f[2 * d + 1] = (float)h[1];
+    }
+}
+
 __device__ __forceinline__ float max_abs8(const float (&f)[8], float m)
 {
 #pragma unroll
@@ -93,22 +133,25 @@ __device__ __forceinline__ uint2 round8(const float (&f)[8], float s, float rcp_
     return uint2{w[0], w[1]};
 }
 
-// maximum over the block; every thread gets the result
+// maximum over the block of NWAVES waves; every thread gets the result
+template <int NWAVES = 4>
 __device__ __forceinline__ float block_max(float m, float *s_part)
 {
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
     if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = m;
     __syncthreads();
-    return fmaxf(fmaxf(s_part[0], s_part[1]), fmaxf(s_part[2], s_part[3]));
+    float r = s_part[0];
+#pragma unroll
+    for (int w = 1; w < NWAVES; ++w) r = fmaxf(r, s_part[w]);
+    return r;
 }
 
-// ITERS > 0: the token fits in ITERS x 256 x 8 elements and stays in registers between the
-// two passes; ITERS = 0: any length, read twice.  Loads of a pass are issued together, with
-// indices past the end clamped to the last piece and their values ignored, so that no load
-// waits behind a branch.
-template <bool SMOOTH, int ITERS>
-__global__ __launch_bounds__(kQuantThreads) void quantize_act_kernel(
+// Tokens of any length, one per block, read twice.  Loads of a pass are issued four pieces at
+// a time, with indices past the end clamped to the last piece and their values ignored, so
+// that no load waits behind a branch.
+template <bool SMOOTH>
+__global__ __launch_bounds__(kQuantThreads) void quantize_act_long_kernel(
     int K, const __half *__restrict__ X, const float *__restrict__ smooth, int8_t *__restrict__ Q,
     float *__restrict__ sx)
 {
@@ -117,52 +160,108 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_kernel(
     const u32x4 *xrow = reinterpret_cast<const u32x4 *>(X + (size_t)m * K);
     uint2 *qrow = reinterpret_cast<uint2 *>(Q + (size_t)m * K);
     const int n8 = K >> 3;
-    constexpr int U = 4;  // pieces in flight per thread in the two-pass form
+    constexpr int U = 4;  // pieces in flight per thread
 
     float amax = 0.0f;
-    float f[ITERS > 0 ? ITERS : U][8];
-    if (ITERS > 0) {
-        Raw8 raw[ITERS > 0 ? ITERS : 1];
+    float f[U][8];
+    for (int i0 = tid; i0 < n8; i0 += U * kQuantThreads) {
+        Raw8 raw[U];
 #pragma unroll
-        for (int it = 0; it < ITERS; ++it) raw[it] = load8<SMOOTH>(xrow, smooth, min(it * kQuantThreads + tid, n8 - 1));
+        for (int u = 0; u < U; ++u) raw[u] = load8<SMOOTH>(xrow, smooth, min(i0 + u * kQuantThreads, n8 - 1));
 #pragma unroll
-        for (int it = 0; it < ITERS; ++it) {
-            convert8<SMOOTH>(raw[it], f[it]);
-            if (it * kQuantThreads + tid < n8) amax = max_abs8(f[it], amax);
-        }
-    } else {
-        for (int i0 = tid; i0 < n8; i0 += U * kQuantThreads) {
-            Raw8 raw[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) raw[u] = load8<SMOOTH>(xrow, smooth, min(i0 + u * kQuantThreads, n8 - 1));
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                convert8<SMOOTH>(raw[u], f[u]);
-                if (i0 + u * kQuantThreads < n8) amax = max_abs8(f[u], amax);
-            }
+        for (int u = 0; u < U; ++u) {
+            convert8<SMOOTH>(raw[u], f[u]);
+            if (i0 + u * kQuantThreads < n8) amax = max_abs8(f[u], amax);
         }
     }
     amax = block_max(amax, s_part);
     const float s = amax > 0.0f ? amax / 127.0f : 1.0f;
     if (tid == 0) sx[m] = s;
     const float rcp_s = __builtin_amdgcn_rcpf(s);
-    if (ITERS > 0) {
+    for (int i0 = tid; i0 < n8; i0 += U * kQuantThreads) {
+        Raw8 raw[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) raw[u] = load8<SMOOTH>(xrow, smooth, min(i0 + u * kQuantThreads, n8 - 1));
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            convert8<SMOOTH>(raw[u], f[u]);
+            const int i = i0 + u * kQuantThreads;
+            if (i < n8) qrow[i] = round8(f[u], s, rcp_s);
+        }
+    }
+}
+
+// Register-resident tokens (K <= ITERS x 2048), R consecutive tokens per block.  Thread t owns
+// the 16-byte pieces t, t + 256, ... of every token of its block, i.e. fixed columns: their
+// smooth scales and refined reciprocals are loaded and computed once.
+template <bool SMOOTH, int ITERS, int NT>
+__global__ __launch_bounds__(NT) void quantize_act_rows_kernel(
+    int M, int K, int R, const __half *__restrict__ X, const float *__restrict__ smooth,
+    int8_t *__restrict__ Q, float *__restrict__ sx)
+{
+    __shared__ float s_part[2][NT / 64];
+    const int tid = threadIdx.x;
+    const int n8 = K >> 3;
+    int piece[ITERS];
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) piece[it] = min(it * NT + tid, n8 - 1);
+
+    // the first token's loads go out before anything waits for the smooth scales
+    const int m_begin = blockIdx.x * R, m_end = min(M, m_begin + R);
+    u32x4 raw[ITERS];
+    if (m_begin < m_end) {
+        const u32x4 *xrow = reinterpret_cast<const u32x4 *>(X + (size_t)m_begin * K);
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) raw[it] = xrow[piece[it]];
+    }
+
+    Recip rc[SMOOTH ? ITERS : 1][8];
+    bool safe = true;  // every smooth scale of this thread allows the short division
+    if (SMOOTH) {
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
-            const int i = it * kQuantThreads + tid;
-            if (i < n8) qrow[i] = round8(f[it], s, rcp_s);
-        }
-    } else {
-        for (int i0 = tid; i0 < n8; i0 += U * kQuantThreads) {
-            Raw8 raw[U];
+            const float4 a = *reinterpret_cast<const float4 *>(smooth + 8 * (size_t)piece[it]);
+            const float4 b = *reinterpret_cast<const float4 *>(smooth + 8 * (size_t)piece[it] + 4);
+            const float sm[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
-            for (int u = 0; u < U; ++u) raw[u] = load8<SMOOTH>(xrow, smooth, min(i0 + u * kQuantThreads, n8 - 1));
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                convert8<SMOOTH>(raw[u], f[u]);
-                const int i = i0 + u * kQuantThreads;
-                if (i < n8) qrow[i] = round8(f[u], s, rcp_s);
+            for (int e = 0; e < 8; ++e) {
+                rc[it][e] = refine_recip(sm[e]);
+                safe &= recip_is_safe(sm[e]);
             }
+        }
+    }
+
+    for (int m = m_begin; m < m_end; ++m) {
+        uint2 *qrow = reinterpret_cast<uint2 *>(Q + (size_t)m * K);
+        float f[ITERS][8];
+        float amax = 0.0f;
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            widen8(raw[it], f[it]);
+            if (SMOOTH) {
+                if (safe) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) f[it][e] = div_by(f[it][e], rc[it][e]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) f[it][e] = f[it][e] / rc[it][e].s;
+                }
+            }
+            if (it * NT + tid < n8) amax = max_abs8(f[it], amax);
+        }
+        if (m + 1 < m_end) {  // the next token's loads fly while this one is reduced, rounded and stored
+            const u32x4 *xrow = reinterpret_cast<const u32x4 *>(X + (size_t)(m + 1) * K);
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) raw[it] = xrow[piece[it]];
+        }
+        amax = block_max<NT / 64>(amax, s_part[(m - m_begin) & 1]);
+        const float s = amax > 0.0f ? amax / 127.0f : 1.0f;
+        if (tid == 0) sx[m] = s;
+        const float rcp_s = __builtin_amdgcn_rcpf(s);
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int i = it * NT + tid;
+            if (i < n8) qrow[i] = round8(f[it], s, rcp_s);
         }
     }
 }
@@ -171,10 +270,15 @@ template <bool SMOOTH>
 static void launch_quantize(int M, int K, const __half *X, const float *smooth, int8_t *Q, float *sx,
                             hipStream_t st)
 {
-    const dim3 grid((unsigned)M), block(kQuantThreads);
+    const dim3 block(kQuantThreads);
     const int pieces = (K / 8 + kQuantThreads - 1) / kQuantThreads;  // 16-byte pieces per thread
+    // tokens per block: as many as leave two blocks per CU (with smooth scales only: without
+    // them there is nothing to share between tokens)
+    const int R = !SMOOTH ? 1 : std::max(1, (M + 511) / 512);
+    const dim3 grid((unsigned)((M + R - 1) / R));
 #define LQ_LAUNCH_Q(ITERS) \
-    hipLaunchKernelGGL((quantize_act_kernel<SMOOTH, ITERS>), grid, block, 0, st, K, X, smooth, Q, sx)
+    hipLaunchKernelGGL((quantize_act_rows_kernel<SMOOTH, ITERS, kQuantThreads>), grid, block, 0, st, M, K, R, X, \
+                       smooth, Q, sx)
     if (pieces <= 1)
         LQ_LAUNCH_Q(1);
     else if (pieces <= 2)
@@ -186,7 +290,7 @@ static void launch_quantize(int M, int K, const __half *X, const float *smooth, 
     else if (pieces <= 8)
         LQ_LAUNCH_Q(8);
     else
-        LQ_LAUNCH_Q(0);
+        hipLaunchKernelGGL((quantize_act_long_kernel<SMOOTH>), dim3((unsigned)M), block, 0, st, K, X, smooth, Q, sx);
 #undef LQ_LAUNCH_Q
 }
 

@@ -50,6 +50,49 @@ def test_quantize_activations_bit_exact(M, K, with_smooth):
     assert np.array_equal(q, q_ref), f"{np.count_nonzero(q != q_ref)} codes differ"
 
 
+@pytest.mark.parametrize("M,K", [(1027, 2048), (2051, 4096), (4096, 512)])
+def test_several_tokens_per_block(M, K):
+    """From 1024 tokens on a block quantises 2 or 4 consecutive tokens (ragged last block) and
+    shares the reciprocals of the smooth scales between them."""
+    _say(f"actquant rows per block M={M} K={K}")
+    X16 = WL.make_activations_f16(M, K, outlier_frac=0.001, seed=M)
+    smooth = WL.make_smooth(K, seed=K + 1)
+    q_ref, s_ref = O.quantize_activations(X16, smooth)
+    q, s = _run(X16, smooth)
+    assert np.array_equal(s.view(np.uint32), s_ref.view(np.uint32)), "per-token scales differ"
+    assert np.array_equal(q, q_ref), f"{np.count_nonzero(q != q_ref)} codes differ"
+
+
+def test_smooth_scales_outside_the_short_division_range():
+    """Smooth scales below 2^-40 or above 2^40 (and FP32 subnormals) take the full IEEE
+    division; scales at the edges of the range and powers of two take the short one."""
+    _say("actquant extreme smooth scales")
+    K = 2048
+    rng = np.random.default_rng(5)
+    X16 = (rng.standard_normal((5, K)) * 3).astype(np.float16)
+    X16[1] = (rng.standard_normal(K) * 1e-4).astype(np.float16)       # FP16 subnormals among them
+    smooth = np.exp2(rng.integers(-45, 46, size=K)).astype(np.float32)
+    smooth[::7] *= np.float32(1.2345)
+    smooth[3] = np.float32(2.0 ** -40)
+    smooth[4] = np.float32(2.0 ** 40)
+    smooth[5] = np.float32(1e-38)      # the quotients overflow or are huge: codes saturate
+    smooth[6] = np.float32(1e-44)      # FP32 subnormal
+    X16[:3, 5:7] = 0                   # tokens 0..2 stay finite; 3 and 4 overflow (unspecified codes)
+    with np.errstate(over="ignore", invalid="ignore"):
+        q_ref, s_ref = O.quantize_activations(X16, smooth)
+    finite = np.isfinite(s_ref)
+    assert finite[:3].all() and not finite[3:].any()
+    q, s = _run(X16, smooth)
+    assert np.array_equal(s.view(np.uint32)[finite], s_ref.view(np.uint32)[finite])
+    assert np.array_equal(q[finite], q_ref[finite])
+    # and a moderate range, where every token stays finite and every thread takes the short division
+    smooth = np.exp2(rng.uniform(-12, 12, size=K)).astype(np.float32)
+    q_ref, s_ref = O.quantize_activations(X16, smooth)
+    q, s = _run(X16, smooth)
+    assert np.array_equal(s.view(np.uint32), s_ref.view(np.uint32))
+    assert np.array_equal(q, q_ref)
+
+
 def test_quantize_activations_edge_values():
     _say("actquant edge values")
     K = 512
