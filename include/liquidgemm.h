@@ -166,6 +166,24 @@ int w4a8_grouped_gemm(int E, const int *row_offsets, int N, int K, int group, co
                       const float *w_scales, uint16_t *Y, int32_t *ACC, void *hip_stream);
 
 /* ------------------------------------------------------------------------------------
+ * W8A8 reference (Sec. 3.2, Sec. 7.3: the baseline without dequantisation that W4A8 is
+ * measured against): the same tiled kernel skeleton with INT8 weights fed to the MFMA as
+ * loaded.  A measuring stick, not a product path: no split-K, meant for M >= 128.
+ * ------------------------------------------------------------------------------------ */
+
+/* Host.  W_i8 [N,K] INT8 row-major -> W8_packed, N*K bytes in the kernel's operand order
+ * (opaque).  N % 64 == 0, K % 256 == 0, K <= 131072. */
+int w8a8_pack_weights(const int8_t *W_i8, int N, int K, void *W8_packed);
+
+/* Device, asynchronous on hip_stream.  ACC[m,n] = sum_k X[m,k] * W[n,k] (INT32, exact),
+ * Y[m,n] = fp16(ACC * act_scales[m] * w_scales[n]) as in w4a8_gemm.  Y or ACC may be NULL
+ * (not both); the scales may be NULL when Y is.  All pointers device, 16-byte aligned,
+ * caller-owned; M * K < 2^32.  With W_i8 = the dequantised LiquidQuant weights
+ * (w4a8_dequant_dump) the results equal those of w4a8_gemm / w4a8_gemm_i32 bit for bit. */
+int w8a8_gemm(int M, int N, int K, const int8_t *X, const float *act_scales, const void *W8_packed,
+              const float *w_scales, uint16_t *Y, int32_t *ACC, void *hip_stream);
+
+/* ------------------------------------------------------------------------------------
  * Activation quantisation (device, Sec. 6 "Serving System": dynamic per-token INT8 after
  * dividing by the smooth scale) -- produces the X and act_scales that w4a8_gemm consumes.
  * ------------------------------------------------------------------------------------ */

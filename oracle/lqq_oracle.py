@@ -28,6 +28,8 @@ Pinning status (tests/test_oracle_pins.py):
                      invariance, reconstruction error <= s_x / 2, smooth divide
                      against exact rational arithmetic.
 
+  w8a8_gemm          matmul_i64 + scale_epilogue on INT8 weights: pinned through them.
+
   grouped_w4a8_gemm  pinned: brute force in Python integers on a tiny case, independence of
                      every expert's rows from the other experts' weights, empty experts,
                      the single-expert case.
@@ -221,6 +223,13 @@ def w4a8_gemm(X_i8, s_x, packed, s_u8, a, s_w, g):
     Wd = dequant_plain(Q_u4, s_u8, mn, g)
     assert np.array_equal(Wd, dequant_bits(Q_u4, s_u8, a, g)), "Eq. 8 and Eq. 12 disagree"
     ACC = matmul_i64(X_i8, Wd)
+    return ACC, scale_epilogue(ACC, s_x, s_w)
+
+
+def w8a8_gemm(X_i8, s_x, W_i8, s_w):
+    """The W8A8 baseline of Sec. 3.2 / 7.3 (INT8 weights, no second-level dequantization):
+    the same main loop and epilogue on the level-1 weights.  Returns (ACC int32, Y float16)."""
+    ACC = matmul_i64(X_i8, W_i8)
     return ACC, scale_epilogue(ACC, s_x, s_w)
 
 

@@ -78,6 +78,10 @@ def lib() -> ctypes.CDLL:
     L.w4a8_grouped_gemm.argtypes = [i, ctypes.POINTER(ctypes.c_int), i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
     L.w4a8_quantize_activations.restype = i
     L.w4a8_quantize_activations.argtypes = [i, i, vp, vp, vp, vp, vp]
+    L.w8a8_pack_weights.restype = i
+    L.w8a8_pack_weights.argtypes = [vp, i, i, vp]
+    L.w8a8_gemm.restype = i
+    L.w8a8_gemm.argtypes = [i, i, i, vp, vp, vp, vp, vp, vp, vp]
     L.w4a8_calib_stream_read.restype = i
     L.w4a8_calib_stream_read.argtypes = [vp, sz, vp]
     L.w4a8_calib_mfma_i8.restype = i
@@ -136,6 +140,17 @@ def liquidquant_pack_from_i8(Q_i8, group: int):
     packed, gparams = _alloc_packed(N, K, group)
     _check(lib().liquidquant_pack_from_i8(_np(Q), N, K, group, _np(packed), _np(gparams)))
     return packed, gparams
+
+
+def w8a8_pack_weights(W_i8):
+    """INT8 weights [N,K] (numpy) in the order the W8A8 reference kernel consumes them: uint8 [N*K]."""
+    W = np.ascontiguousarray(W_i8, dtype=np.int8)
+    if W.ndim != 2:
+        raise ValueError("W must be [N, K]")
+    N, K = W.shape
+    packed = np.empty(N * K, dtype=np.uint8)
+    _check(lib().w8a8_pack_weights(_np(W), N, K, _np(packed)))
+    return packed
 
 
 def liquidquant_unpack_weights(W_packed, gparams, N: int, K: int, group: int):
@@ -307,6 +322,26 @@ def w4a8_dequant_dump(W_packed, gparams, N: int, K: int, group: int, out=None, s
                                    _dev(gparams, torch.uint8, (gb,), "gparams"), N, K, group,
                                    _dev(out, torch.int8, (N, K), "out"), _stream(stream)))
     return out
+
+
+def w8a8_gemm(X, act_scales, W8_packed, w_scales, N: int, K: int, want_y=True, want_acc=False, stream=None):
+    """The W8A8 reference GEMM (no dequantisation): returns Y [M,N] float16, raw INT32
+    accumulators [M,N], or both (in that order), as asked."""
+    import torch
+
+    M = int(X.shape[0])
+    dx = _dev(X, torch.int8, (M, K), "X")
+    dw = _dev(W8_packed, torch.uint8, (N * K,), "W8_packed")
+    Y = torch.empty((M, N), dtype=torch.float16, device=X.device) if want_y else None
+    ACC = torch.empty((M, N), dtype=torch.int32, device=X.device) if want_acc else None
+    dsx = _dev(act_scales, torch.float32, (M,), "act_scales") if want_y else None
+    dsw = _dev(w_scales, torch.float32, (N,), "w_scales") if want_y else None
+    _check(lib().w8a8_gemm(M, N, K, dx, dsx, dw, dsw,
+                           _dev(Y, torch.float16, (M, N), "Y") if want_y else None,
+                           _dev(ACC, torch.int32, (M, N), "ACC") if want_acc else None, _stream(stream)))
+    if want_y and want_acc:
+        return Y, ACC
+    return Y if want_y else ACC
 
 
 def w4a8_calib_stream_read(buf, stream=None) -> int:

@@ -1148,7 +1148,8 @@ __device__ __forceinline__ void duo_dl_tile(
     const char *pbase = reinterpret_cast<const char *>(gp) + ((size_t)t0 * stages_total + s_begin) * 32 * (G128 ? 2 : 4);
     const size_t wg_stride = (size_t)chunks_per_tile * 1024;
     const size_t pg_stride = (size_t)stages_total * 32 * (G128 ? 2 : 4);
-    const uint32_t wl = lane * 16, pl_off = j * (G128 ? 2 : 4);
+    uint32_t wl = lane * 16;  // (not const: see issue_x)
+    const uint32_t pl_off = j * (G128 ? 2 : 4);
     // fragment row j sits in 1 KiB piece j >> 3 at position 8 (r ^ (piece & 1)) + (c ^ r), r = j & 7
     const int8_t *xs = lds + (j >> 3) * 1024 + 128 * ((j & 7) ^ ((j >> 3) & 1));
     const int jr = j & 7;
@@ -1170,8 +1171,8 @@ __device__ __forceinline__ void duo_dl_tile(
         const uint32_t so = (uint32_t)s * 128;
 #pragma unroll
         for (int i = 0; i < XP; ++i)
-            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                         :
+            asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         : "+v"(wl)  // untouched; makes the W loads that follow depend on this statement
                          : "v"(xg[i] + so), "s"(xbase), "s"(lds0 + buf * STAGE + (4 * i + wave) * 1024)
                          : "memory", "m0");
     };
@@ -1215,6 +1216,11 @@ __device__ __forceinline__ void duo_dl_tile(
     // One stage: w_cur = W(s) on entry and W(s+3) on exit, w_nxt = W(s+1).  Loads in flight
     // when the stage reaches its barrier, oldest first: X(s+1), W(s+1), X(s+2), W(s+2); "at
     // most PER_STAGE in flight" therefore means that this wave's part of X(s+1) is in LDS.
+    // That count holds as long as the compiler leaves the W loads where they are written.  It
+    // may issue them later (never earlier than the X loads of their stage, see issue_x), so
+    // the first use of W(s+1) also sits above the barrier: loads complete in order, and the
+    // wait that the compiler puts in front of that use covers the older X(s+1) whatever it
+    // did with the W loads.
     auto stage = [&](int s, u32x4 (&w_cur)[2][2], UnitParams<G128> (&p_cur)[2], u32x4 (&w_nxt)[2][2],
                      UnitParams<G128> (&p_nxt)[2], auto tail_tag) {
         constexpr bool TAIL = decltype(tail_tag)::value;  // one of the last stages: nothing left to prefetch
@@ -1231,6 +1237,8 @@ __device__ __forceinline__ void duo_dl_tile(
         build_b(w_cur, p_cur, 1, 1, bf[1]);
         mma(af[0], bf[0]);
         __builtin_amdgcn_sched_barrier(0);
+        build_b(w_nxt, p_nxt, 0, 0, bf[0]);
+        asm volatile("" : "+v"(bf[0][0]), "+v"(bf[0][1]));  // (keeps that use above the barrier)
         if (TAIL)
             wait_vmcnt0();
         else
@@ -1238,7 +1246,6 @@ __device__ __forceinline__ void duo_dl_tile(
         lds_barrier_raw();  // X(s+1) is complete and visible; every wave is done reading X(s-1)
         __builtin_amdgcn_sched_barrier(0);
         read_a((s + 1) & 3, 0, 0, af[0]);
-        build_b(w_nxt, p_nxt, 0, 0, bf[0]);
         __builtin_amdgcn_sched_barrier(0);
         if (!TAIL) issue_x(s + 3, (s + 3) & 3);  // into the stage that held X(s-1)
         if (!TAIL) load_w(s + 3, w_cur, p_cur);
@@ -1257,9 +1264,10 @@ __device__ __forceinline__ void duo_dl_tile(
     issue_x(2, 2);
     load_w(2, wr[2], pr[2]);
     __builtin_amdgcn_sched_barrier(0);
+    build_b(wr[0], pr[0], 0, 0, bf[0]);
+    asm volatile("" : "+v"(bf[0][0]), "+v"(bf[0][1]));
     wait_vmcnt<2 * PER_STAGE>();
     lds_barrier_raw();
-    build_b(wr[0], pr[0], 0, 0, bf[0]);
     read_a(0, 0, 0, af[0]);
     __builtin_amdgcn_sched_barrier(0);
 
@@ -1357,6 +1365,153 @@ __global__ __launch_bounds__(256, 2) void w4a8_duo_dl_kernel(
         duo_dl_tile<G128, 2>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
     else
         duo_dl_tile<G128, 4>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+}
+
+// ------------------------------------------------------------------------------------
+// W8A8 reference kernel (Sec. 3.2 / 7.3: the baseline without dequantisation that the paper
+// measures W4A8 against), on the skeleton of the direct-to-LDS tiled kernel: same tiles,
+// wave layout, X pipeline and epilogue; the B operand is the loaded INT8 register itself.
+// A stage of W is 32 registers per wave (8 loads of 16 bytes per lane), so two stages are
+// held instead of three and every load is issued one stage ahead.  No split-K: a reference
+// for grids that fill the chip.
+// ------------------------------------------------------------------------------------
+template <int MF>
+__device__ __forceinline__ void w8a8_tile(const int bm, const int bn, int M, int N, int K,
+                                          const int8_t *__restrict__ X, const float *__restrict__ sx,
+                                          const u32x4 *__restrict__ W8, const float *__restrict__ sw,
+                                          __half *__restrict__ Y, int32_t *__restrict__ ACC)
+{
+    constexpr int XP = MF;
+    constexpr int STAGE = 128 * 128;
+    extern __shared__ __attribute__((aligned(16))) int8_t lds[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int j = lane & 31, kb = lane >> 5;
+    const int m0 = bm * 128;
+    const int ng = bn * 4 + wave;
+    const bool active = ng < (N >> 6);
+    const int t0 = 2 * (active ? ng : (N >> 6) - 1);
+    const int stages = K >> 7;
+
+    v16i acc[MF][2];
+#pragma unroll
+    for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mf][t][r] = 0;
+
+    const int ld_r = (lane >> 3) ^ (wave & 1), ld_c = (lane & 7) ^ ld_r;
+    uint32_t xg[XP];
+#pragma unroll
+    for (int i = 0; i < XP; ++i)
+        xg[i] = (uint32_t)min(m0 + 32 * i + 8 * wave + ld_r, M - 1) * (uint32_t)K + 16 * ld_c;
+    // tile t0 + t: K / 32 k-steps of 1 KiB each
+    const char *wbase = reinterpret_cast<const char *>(W8) + (size_t)t0 * K * 32;
+    const size_t w_stride = (size_t)K * 32;
+    const uint32_t wl = lane * 16;
+    const int8_t *xs = lds + (j >> 3) * 1024 + 128 * ((j & 7) ^ ((j >> 3) & 1));
+    const int jr = j & 7;
+
+    u32x4 wr[2][2][4];  // [stage parity][tile][k-step of the stage]
+    v4i af[2][MF];
+
+    const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) void *)lds;
+    auto issue_x = [&](int s, int buf) {
+        s = min(s, stages - 1);
+        const uint32_t so = (uint32_t)s * 128;
+#pragma unroll
+        for (int i = 0; i < XP; ++i)
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                         :
+                         : "v"(xg[i] + so), "s"(X), "s"(lds0 + buf * STAGE + (4 * i + wave) * 1024)
+                         : "memory", "m0");
+    };
+    auto load_w = [&](int s, u32x4 (&w)[2][4]) {
+        s = min(s, stages - 1);
+        const uint32_t wo = wl + (uint32_t)s * 4096;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const char *wb = wbase + t * w_stride;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) w[t][q] = *reinterpret_cast<const u32x4 *>(wb + wo + q * 1024);
+        }
+    };
+    auto read_a = [&](int buf, int q, v4i (&a)[MF]) {
+#pragma unroll
+        for (int mf = 0; mf < MF; ++mf)
+            a[mf] = *reinterpret_cast<const v4i *>(xs + 16 * ((2 * q + kb) ^ jr) + buf * STAGE + mf * 4096);
+    };
+    auto mma = [&](const v4i (&a)[MF], const u32x4 (&w)[2][4], int q) {
+#pragma unroll
+        for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+                acc[mf][t] = mfma_i8(a[mf], __builtin_bit_cast(v4i, w[t][q]), acc[mf][t]);
+    };
+    // One stage; loads in flight at its barrier: X(s+1), W(s+1) -- waited for completely.
+    auto stage = [&](int s, u32x4 (&w_cur)[2][4], auto tail_tag) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
+        const int buf = s & 3;
+        read_a(buf, 1, af[1]);
+        mma(af[0], w_cur, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_a(buf, 2, af[0]);
+        mma(af[1], w_cur, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_a(buf, 3, af[1]);
+        mma(af[0], w_cur, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        wait_vmcnt0();
+        lds_barrier_raw();
+        __builtin_amdgcn_sched_barrier(0);
+        read_a((s + 1) & 3, 0, af[0]);
+        mma(af[1], w_cur, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        if (!TAIL) issue_x(s + 2, (s + 2) & 3);
+        if (!TAIL) load_w(s + 2, w_cur);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    const std::false_type body{};
+    const std::true_type tail{};
+
+    issue_x(0, 0);
+    load_w(0, wr[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    issue_x(1, 1);
+    load_w(1, wr[1]);
+    __builtin_amdgcn_sched_barrier(0);
+    // (everything, not a count: the compiler is free to issue the W loads above later than
+    // written, which would shift a count)
+    wait_vmcnt0();
+    lds_barrier_raw();
+    read_a(0, 0, af[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    int s = 0;
+    for (; s + 2 <= stages; s += 2) {  // stages is even (K % 256 == 0)
+        stage(s, wr[0], body);
+        stage(s + 1, wr[1], body);
+    }
+    (void)tail;
+    wait_vmcnt0();  // the clamped prefetches past the end write LDS too
+
+    if (!active) return;
+    store_tile<MF>(acc, M, N, m0, 64 * ng + 2 * j, lane, sx, sw, Y, ACC);
+}
+
+__global__ __launch_bounds__(256, 2) void w8a8_kernel(int M, int N, int K, const int8_t *__restrict__ X,
+                                                      const float *__restrict__ sx,
+                                                      const u32x4 *__restrict__ W8,
+                                                      const float *__restrict__ sw, __half *__restrict__ Y,
+                                                      int32_t *__restrict__ ACC, int blocks_m, int blocks_n)
+{
+    int bm, bn;
+    block_coords(blocks_m, blocks_n, bm, bn);
+    if (M - 128 * bm <= 64)  // block-uniform
+        w8a8_tile<2>(bm, bn, M, N, K, X, sx, W8, sw, Y, ACC);
+    else
+        w8a8_tile<4>(bm, bn, M, N, K, X, sx, W8, sw, Y, ACC);
 }
 
 // ------------------------------------------------------------------------------------
@@ -2106,6 +2261,34 @@ int w4a8_grouped_gemm(int E, const int *row_offsets, int N, int K, int group, co
                       reinterpret_cast<__half *>(Y), ACC, (size_t)N * K / 32, (size_t)2 * N * K / group};
     a.stream = static_cast<hipStream_t>(hip_stream);
     return grouped_run(a);
+}
+
+int w8a8_gemm(int M, int N, int K, const int8_t *X, const float *act_scales, const void *W8_packed,
+              const float *w_scales, uint16_t *Y, int32_t *ACC, void *hip_stream)
+{
+    if (M < 0 || !shape_ok(N, K, 64))
+        return fail(LQ_ERR_INVALID, "bad shape M=%d N=%d K=%d (need M>=0, N%%64==0, K%%256==0, K<=131072)", M, N, K);
+    if (M == 0) return LQ_OK;
+    if (!Y && !ACC) return fail(LQ_ERR_INVALID, "no output pointer");
+    if (!X || !W8_packed) return fail(LQ_ERR_INVALID, "null input pointer");
+    if (Y && (!act_scales || !w_scales)) return fail(LQ_ERR_INVALID, "null scale pointer");
+    if (((uintptr_t)X | (uintptr_t)W8_packed | (uintptr_t)act_scales | (uintptr_t)w_scales | (uintptr_t)Y |
+         (uintptr_t)ACC) & 15)
+        return fail(LQ_ERR_ALIGN, "device pointers must be 16-byte aligned");
+    if ((long long)M * K >= (1ll << 32))
+        return fail(LQ_ERR_INVALID, "M * K = %lld is beyond the 2^32 - 1 bytes of X one call addresses; split the batch",
+                    (long long)M * K);
+    const int blocks_n = (N + 255) / 256, blocks_m = (M + 127) / 128;
+    const size_t lds_bytes = 4 * (size_t)128 * 128;
+    if (int rc = allow_lds(w8a8_kernel, lds_bytes)) return rc;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(w8a8_kernel, dim3((unsigned)(blocks_n * blocks_m)), dim3(256), lds_bytes,
+                       static_cast<hipStream_t>(hip_stream), M, N, K, X, act_scales,
+                       static_cast<const u32x4 *>(W8_packed), w_scales, reinterpret_cast<__half *>(Y), ACC,
+                       blocks_m, blocks_n);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(LQ_ERR_HIP, "w8a8 launch failed: %s", hipGetErrorString(e));
+    return LQ_OK;
 }
 
 }  // extern "C"

@@ -225,4 +225,27 @@ int liquidquant_unpack_weights(const void *W_packed, const uint8_t *gparams, int
     return LQ_OK;
 }
 
+// W8A8 reference (Sec. 3.2 / 7.3: the no-dequantisation baseline): INT8 weights in the order in
+// which the reference kernel's lanes consume them.  Per tile of 32 channels and k-step of
+// 32: 64 lanes x 16 bytes, lane = 32 * kb + j holding W[n][32 step + 16 kb + 0..15] with
+// n = 64 (tile / 2) + 2 j + tile % 2: as in the 4-bit layout, the two tiles of a wave
+// interleave their channels so that a lane stores two adjacent outputs.
+int w8a8_pack_weights(const int8_t *W_i8, int N, int K, void *W8_packed)
+{
+    if (!shape_ok(N, K, 64)) return fail(LQ_ERR_INVALID, "bad shape N=%d K=%d", N, K);
+    if (!W_i8 || !W8_packed) return fail(LQ_ERR_INVALID, "null pointer");
+    int8_t *out = static_cast<int8_t *>(W8_packed);
+    const int steps = K / 32;
+    parallel_rows(N / 32, [&](int tb, int te) {
+        for (int tile = tb; tile < te; ++tile)
+            for (int st = 0; st < steps; ++st)
+                for (int lane = 0; lane < 64; ++lane) {
+                    const int j = lane & 31, kb = lane >> 5;
+                    std::memcpy(out + (((size_t)tile * steps + st) * 64 + lane) * 16,
+                                W_i8 + (size_t)(64 * (tile >> 1) + 2 * j + (tile & 1)) * K + 32 * st + 16 * kb, 16);
+                }
+    });
+    return LQ_OK;
+}
+
 }  // extern "C"

@@ -138,3 +138,23 @@ def test_host_argument_checks():
     assert api.w4a8_select_variant(1, 4096, 4096, 64) >= 0
     with pytest.raises(api.LiquidGemmError):
         api.w4a8_select_variant(1, 4000, 4096, 64)
+
+
+def test_w8a8_packer_layout():
+    """INT8 weights of the W8A8 reference: per tile of 32 channels and k-step of 32, lane
+    32*kb + j holds W[n][32*step + 16*kb + 0..15] in 16 consecutive bytes, n = 64*(tile//2) +
+    2*j + tile%2 (the two tiles of a 64-channel group interleave)."""
+    rng = np.random.default_rng(3)
+    N, K = 128, 512
+    W = rng.integers(-128, 128, size=(N, K), dtype=np.int64).astype(np.int8)
+    blob = api.w8a8_pack_weights(W).view(np.int8).reshape(N // 32, K // 32, 2, 32, 16)   # tile, step, kb, j, byte
+    for tile in range(N // 32):
+        for step in (0, 5, K // 32 - 1):
+            for kb in range(2):
+                rows = 64 * (tile // 2) + 2 * np.arange(32) + tile % 2
+                want = W[rows, 32 * step + 16 * kb:32 * step + 16 * kb + 16]
+                assert np.array_equal(blob[tile, step, kb], want)
+    # every weight appears exactly once
+    assert np.array_equal(np.sort(blob.ravel()), np.sort(W.ravel()))
+    with pytest.raises(api.LiquidGemmError):
+        api.w8a8_pack_weights(np.zeros((64, 100), dtype=np.int8))
