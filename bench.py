@@ -264,6 +264,38 @@ def vendor_w8a8_reference(torch, stream):
     return rows
 
 
+def own_w8a8_reference(prob, torch, api, stream):
+    """The W8A8 reference kernel of this library (same tiles and pipeline as the W4A8 kernel,
+    INT8 weights fed to the MFMA as loaded) on the dequantised weights of the headline
+    problem, so that both kernels compute the same integers; W4A8 timed beside it."""
+    s = prob.shape
+    N, K, g = s.N, s.K, s.group
+    rows = []
+    Wd = api.w4a8_dequant_dump(prob.d_packed[0], prob.d_gparams[0], N, K, g)
+    torch.cuda.synchronize()
+    packed = torch.from_numpy(api.w8a8_pack_weights(Wd.cpu().numpy()))
+    del Wd
+    copies = max(1, math.ceil(ROTATE_BYTES / (N * K)))
+    dW = [packed.to("cuda:0") for _ in range(copies)]
+    for M in (256, 1024, 4096):
+        if M not in prob.dX:
+            continue
+
+        def launch(i):
+            api.w8a8_gemm(prob.dX[M], prob.dsx[M], dW[i % copies], prob.d_w_scales, N, K, out_y=prob.dY[M],
+                          stream=stream.cuda_stream)
+
+        ms8 = statistics.median(time_launches(launch, 30, 5, torch, stream) for _ in range(3))
+        ms4 = statistics.median(time_steps(prob, M, 30, 5, torch, api, stream) for _ in range(3))
+        rows.append({"M": M, "N": N, "K": K, "w8a8_us": round(ms8 * 1e3, 2),
+                     "w8a8_tops": round(algorithmic_ops(M, N, K) / (ms8 * 1e-3) / 1e12, 1),
+                     "w4a8_us": round(ms4 * 1e3, 2),
+                     "w4a8_tops": round(algorithmic_ops(M, N, K) / (ms4 * 1e-3) / 1e12, 1)})
+    del dW
+    torch.cuda.empty_cache()
+    return rows
+
+
 def grouped_moe_points(torch, api, WL, stream):
     """Mixture-of-experts layers shaped like Mixtral-8x7B (8 experts, top-2 routing, hidden
     4096, intermediate 14336; Sec. 7.3 of the paper): one grouped call against one
@@ -481,6 +513,7 @@ def main():
 
     if not args.no_configs:
         out["activation_quant"] = activation_quant_points(torch, api, WL, stream, calib)
+        out["reference_w8a8_own"] = own_w8a8_reference(prob, torch, api, stream)
         del prob.d_packed[1:], prob.d_gparams[1:]
         torch.cuda.empty_cache()
         out["reference_w8a8_vendor"] = vendor_w8a8_reference(torch, stream)

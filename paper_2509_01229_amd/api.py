@@ -324,16 +324,19 @@ def w4a8_dequant_dump(W_packed, gparams, N: int, K: int, group: int, out=None, s
     return out
 
 
-def w8a8_gemm(X, act_scales, W8_packed, w_scales, N: int, K: int, want_y=True, want_acc=False, stream=None):
+def w8a8_gemm(X, act_scales, W8_packed, w_scales, N: int, K: int, want_y=True, want_acc=False, out_y=None,
+              out_acc=None, stream=None):
     """The W8A8 reference GEMM (no dequantisation): returns Y [M,N] float16, raw INT32
-    accumulators [M,N], or both (in that order), as asked."""
+    accumulators [M,N], or both (in that order), as asked; out_y / out_acc reuse tensors."""
     import torch
 
     M = int(X.shape[0])
     dx = _dev(X, torch.int8, (M, K), "X")
     dw = _dev(W8_packed, torch.uint8, (N * K,), "W8_packed")
-    Y = torch.empty((M, N), dtype=torch.float16, device=X.device) if want_y else None
-    ACC = torch.empty((M, N), dtype=torch.int32, device=X.device) if want_acc else None
+    want_y, want_acc = want_y or out_y is not None, want_acc or out_acc is not None
+    Y = (out_y if out_y is not None else torch.empty((M, N), dtype=torch.float16, device=X.device)) if want_y else None
+    ACC = (out_acc if out_acc is not None
+           else torch.empty((M, N), dtype=torch.int32, device=X.device)) if want_acc else None
     dsx = _dev(act_scales, torch.float32, (M,), "act_scales") if want_y else None
     dsw = _dev(w_scales, torch.float32, (N,), "w_scales") if want_y else None
     _check(lib().w8a8_gemm(M, N, K, dx, dsx, dw, dsw,
