@@ -514,6 +514,16 @@ def main():
     if not args.no_configs:
         out["activation_quant"] = activation_quant_points(torch, api, WL, stream, calib)
         out["reference_w8a8_own"] = own_w8a8_reference(prob, torch, api, stream)
+        # Fig. 13's pipeline comparison on this chip: the dispatcher's implicit form against the
+        # explicit producer / consumer form (dequantised weights handed over through LDS)
+        names = api.w4a8_variant_names()
+        if "excp_m128" in names:
+            t_im = statistics.median(time_steps(prob, head.M, 30, 5, torch, api, stream) for _ in range(3))
+            t_ex = statistics.median(time_steps(prob, head.M, 30, 5, torch, api, stream, names.index("excp_m128"))
+                                     for _ in range(3))
+            out["ablation_pipeline"] = {"workload": head.name, "implicit_us": round(t_im * 1e3, 2),
+                                        "explicit_lds_round_trip_us": round(t_ex * 1e3, 2),
+                                        "explicit_over_implicit": round(t_ex / t_im, 3)}
         del prob.d_packed[1:], prob.d_gparams[1:]
         torch.cuda.empty_cache()
         out["reference_w8a8_vendor"] = vendor_w8a8_reference(torch, stream)
