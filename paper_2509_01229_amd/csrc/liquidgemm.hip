@@ -2172,9 +2172,10 @@ static int select_variant(int M, int N, int K)
         }
         return find_variant("stream_m64");
     }
-    // two or more 128 x 256 tiles per CU: the deeper memory pipeline of the direct-to-LDS form
-    // pays (3 to 4 % measured); with fewer tiles the two k groups per block of the other form do
-    if (((M + 127) / 128) * ((N + 255) / 256) >= 512 && (long long)M * K < (1ll << 32))
+    // clearly more 128 x 256 tiles than CUs: the deeper memory pipeline of the direct-to-LDS
+    // form pays (3 to 6 % measured from 320 tiles up); with one tile per CU or fewer, the two k
+    // groups per block of the other form do
+    if (((M + 127) / 128) * ((N + 255) / 256) >= 320 && (long long)M * K < (1ll << 32))
         return find_variant("duo_dl_m128");
     // few tiles: a grid of 64-row tiles can fill the chip with half the split-K exchange
     return find_variant(prefer_64_row_tiles(M, N, K) ? "duo_m64" : "duo_m128");
