@@ -28,15 +28,22 @@ pytestmark = pytest.mark.gpu
 # batch sizes on the 7B up-projection cover them at full size
 _M64 = [WL.GemmShape(f"mlp7b_up_M{M}_N11008_K4096", M, 11008, 4096, outlier_frac=0.001, seed=2) for M in (48, 64)]
 
+# 33..64 rows on layers whose N alone fills the stream kernel's grid and whose K is long go to
+# the split-K tile grid instead; 1280 rows on 8192 x 8192 is the smallest prefill batch of the
+# direct-to-LDS kernel (320 tiles)
+_DOWN_MID = [WL.GemmShape(f"l70b_down_M{M}_N8192_K28672", M, 8192, 28672, group=128, sigma_w=0.015, seed=3)
+             for M in (40, 64)]
+_PREFILL_MID = [WL.GemmShape(f"prefill_M{M}_N8192_K8192", M, 8192, 8192, seed=4) for M in (56, 1280)]
+
 FAMILIES = [
     ("decode", WL.DECODE),
     ("mlp7b_up_m64", _M64),
     ("mlp7b_up", WL.MLP_7B[:3]),
     ("mlp7b_down", WL.MLP_7B[3:]),
     ("l70b_up", WL.LAYERS_70B[0:3]),
-    ("l70b_down", WL.LAYERS_70B[3:6]),
+    ("l70b_down", list(WL.LAYERS_70B[3:6]) + _DOWN_MID),
     ("l70b_qkv", WL.LAYERS_70B[6:9]),
-    ("prefill", WL.PREFILL),
+    ("prefill", list(WL.PREFILL) + _PREFILL_MID),
 ]
 
 
