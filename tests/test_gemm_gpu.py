@@ -262,6 +262,37 @@ def test_random_shapes_through_the_dispatcher():
         H.assert_fp16_close(Y.cpu().numpy(), ref64, f"case {case}")
 
 
+def test_random_large_grids_through_the_dispatcher():
+    """Seeded shapes with 320 and more 128 x 256 tiles (the direct-to-LDS tiled kernel: ragged
+    last row tiles, N tails, 2 to 24 stages so that every remainder of its three-stage loop
+    occurs) and a few just below; the accumulators are compared with the exact float64
+    product on the oracle's dequantised weights, the FP16 output with the epilogue definition."""
+    import torch
+
+    rng = np.random.default_rng(11)
+    seen = set()
+    for case in range(14):
+        N = 64 * int(rng.integers(40, 65))
+        K = 256 * int(rng.integers(1, 13))
+        g = (64, 128)[case % 2]
+        M = int(rng.integers(2600, 4600))
+        picked = api.w4a8_variant_name(api.w4a8_select_variant(M, N, K, g))
+        seen.add(picked)
+        _say(f"large grid {case}: M={M} N={N} K={K} g={g} -> {picked}")
+        P = H.Problem(N, K, g, seed=500 + case)
+        X, s_x = WL.make_activations(M, K, outlier_frac=0.01, seed=900 + case)
+        Wd, s_w = P.oracle_wd()
+        ref = X.astype(np.float64) @ Wd.astype(np.float64).T      # exact: |acc| < 2^31 << 2^53
+        dX, dsx = torch.from_numpy(X).cuda(), torch.from_numpy(s_x).cuda()
+        ACC = api.w4a8_gemm_i32(dX, P.d_packed, P.d_gparams, N, K, g)
+        Y = api.w4a8_gemm(dX, dsx, P.d_packed, P.d_gparams, P.d_w_scales, N, K, g)
+        torch.cuda.synchronize()
+        assert np.array_equal(ACC.cpu().numpy().astype(np.float64), ref), f"case {case}: accumulators differ"
+        H.assert_fp16_close(Y.cpu().numpy(), O.scale_epilogue_f64(ref, s_x, s_w), f"case {case}")
+        del P, dX, ACC, Y
+    assert "duo_dl_m128" in seen and "duo_m128" in seen
+
+
 def test_maximum_k_and_accumulator_range():
     """K at the interface limit (131072) with inputs that drive the accumulators to the edge
     of INT32: |ACC| up to K * 127 * 121 = 2 014 183 424 < 2^31 must come out exactly."""
