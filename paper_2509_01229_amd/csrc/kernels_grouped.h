@@ -1,0 +1,72 @@
+// Grouped (mixture-of-experts) launches of the per-block device functions.
+// (part of liquidgemm.hip: included there, inside namespace lqq)
+#pragma once
+
+// ------------------------------------------------------------------------------------
+// Grouped launches (mixture-of-experts layers, Sec. 7.3): one launch runs the same per-block
+// code over several experts that share N, K and the group size.  Expert i of the launch
+// owns rows row_off[i] .. row_off[i] + rows[i] - 1 of X / Y and the expert[i]-th weight
+// blob.  The table travels by value in the kernel arguments (no device copy, nothing to
+// allocate), which bounds a call to 64 experts.
+// ------------------------------------------------------------------------------------
+constexpr int kMaxExperts = 64;
+struct GroupTable {
+    int count;
+    int block_end[kMaxExperts];  // running total of blocks up to and including entry i
+    int expert[kMaxExperts];
+    int row_off[kMaxExperts];
+    int rows[kMaxExperts];
+};
+struct GroupedPtrs {
+    const int8_t *X;
+    const float *sx;
+    const u32x4 *Wp;
+    const uint8_t *gp;
+    const float *sw;
+    __half *Y;
+    int32_t *ACC;
+    size_t w_stride;   // u32x4 elements between the packed codes of consecutive experts
+    size_t gp_stride;  // bytes between their group parameters
+};
+
+template <int NW, int UU, bool G128>
+__global__ __launch_bounds__(NW * 64) void w4a8_stream16_grouped_kernel(const GroupTable g, const GroupedPtrs p,
+                                                                        int N, int K, int groups)
+{
+    const int i = blockIdx.x / groups, gx = blockIdx.x % groups;
+    const int e = g.expert[i], r0 = g.row_off[i];
+    stream16_block<2, NW, UU, G128>(Place{gx, groups, 0, 1, nullptr}, g.rows[i], N, K, p.X + (size_t)r0 * K, p.sx + r0,
+                                    p.Wp + e * p.w_stride, p.gp + e * p.gp_stride, p.sw + (size_t)e * N,
+                                    p.Y ? p.Y + (size_t)r0 * N : nullptr, p.ACC ? p.ACC + (size_t)r0 * N : nullptr,
+                                    nullptr);
+}
+
+template <int NW, bool G128>
+__global__ __launch_bounds__(NW * 64) void w4a8_stream_grouped_kernel(const GroupTable g, const GroupedPtrs p,
+                                                                      int N, int K, int groups)
+{
+    const int i = blockIdx.x / groups, gx = blockIdx.x % groups;
+    const int e = g.expert[i], r0 = g.row_off[i];
+    stream_block<2, NW, 1, G128>(Place{gx, groups, 0, 1, nullptr}, g.rows[i], N, K, p.X + (size_t)r0 * K, p.sx + r0,
+                              p.Wp + e * p.w_stride, p.gp + e * p.gp_stride, p.sw + (size_t)e * N,
+                              p.Y ? p.Y + (size_t)r0 * N : nullptr, p.ACC ? p.ACC + (size_t)r0 * N : nullptr,
+                              nullptr);
+}
+
+template <bool G128, int KG>
+__global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_grouped_kernel(const GroupTable g,
+                                                                                     const GroupedPtrs p, int N,
+                                                                                     int K)
+{
+    int i = 0;
+    while (i < g.count - 1 && (int)blockIdx.x >= g.block_end[i]) ++i;
+    const int local = (int)blockIdx.x - (i ? g.block_end[i - 1] : 0);
+    const int M = g.rows[i], e = g.expert[i], r0 = g.row_off[i];
+    // row tiles of one column block are neighbours, so they meet on the expert's W columns
+    const int blocks_m = (M + 127) >> 7;
+    const int bm = local % blocks_m, bn = local / blocks_m;
+    duo_block<G128, KG>(Place{0, 1, 0, 1, nullptr}, bm, bn, M, N, K, p.X + (size_t)r0 * K, p.sx + r0,
+                        p.Wp + e * p.w_stride, p.gp + e * p.gp_stride, p.sw + (size_t)e * N,
+                        p.Y ? p.Y + (size_t)r0 * N : nullptr, p.ACC ? p.ACC + (size_t)r0 * N : nullptr, nullptr);
+}
+

@@ -1,0 +1,496 @@
+// Tiled kernels (larger M): the plain tile kernel and the duo kernel (two waves per SIMD).
+// (part of liquidgemm.hip: included there, inside namespace lqq)
+#pragma once
+
+// ------------------------------------------------------------------------------------
+// tile kernel.  MF = 32-row fragments per wave; block tile = (32*MF) x 256.
+// ------------------------------------------------------------------------------------
+template <int MF, bool G128>
+__global__ __launch_bounds__(256, 2) void w4a8_tile_kernel(
+    int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
+    const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
+    __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n)
+{
+    constexpr int WM = 32 * MF;
+    constexpr int XP = MF;  // 16-byte X pieces per thread per stage of 128 k
+    constexpr int STAGE = WM * kTilePitch;
+    extern __shared__ __attribute__((aligned(16))) int8_t lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 31, kb = lane >> 5;
+    int bm, bn;
+    block_coords(blocks_m, blocks_n, bm, bn);
+    const int m0 = bm * WM;
+    const int ng = bn * 4 + wave;  // 64-channel group of this wave
+    const bool active = ng < (N >> 6);
+    // A wave past the last group recomputes the last one and stores nothing, so that the
+    // main loop has no divergent path around its barriers.
+    const int t0 = 2 * (active ? ng : (N >> 6) - 1);
+    const int stages = K >> 7;
+    const int chunks_per_tile = K >> 6;
+
+    v16i acc[MF][2];
+#pragma unroll
+    for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mf][t][r] = 0;
+
+    u32x4 xr[XP];
+    u32x4 wc[2][2], wn[2][2];
+    UnitParams<G128> pc[2], pn[2];
+
+    // Rows past M read row M-1: an output row depends only on its own X row, and rows
+    // past M are never stored.
+    auto load_x = [&](int s) {
+#pragma unroll
+        for (int i = 0; i < XP; ++i) {
+            const int q = tid + 256 * i;
+            const int row = q >> 3, col = q & 7;
+            const int m = min(m0 + row, M - 1);
+            xr[i] = *reinterpret_cast<const u32x4 *>(X + (size_t)m * K + (size_t)s * 128 + 16 * col);
+        }
+    };
+    auto store_x = [&](int buf) {
+        int8_t *base = lds + buf * STAGE;
+#pragma unroll
+        for (int i = 0; i < XP; ++i) {
+            const int q = tid + 256 * i;
+            const int row = q >> 3, col = q & 7;
+            *reinterpret_cast<u32x4 *>(base + row * kTilePitch + 16 * col) = xr[i];
+        }
+    };
+    auto load_w = [&](int s, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const u32x4 *base = Wp + ((size_t)(t0 + t) * chunks_per_tile + 2 * (size_t)s) * 64 + lane;
+            w[t][0] = base[0];
+            w[t][1] = base[64];
+            p[t].load(gp, (size_t)(t0 + t) * stages + s, j);
+        }
+    };
+    auto compute = [&](int buf) {
+        const int8_t *xs = lds + buf * STAGE + j * kTilePitch + 16 * kb;
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            v4i blo[2], bhi[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                uint32_t s2, a4;
+                pc[t].get(c, s2, a4);
+                dequant_chunk(wc[t][c], s2, a4, blo[t], bhi[t]);
+            }
+#pragma unroll
+            for (int mf = 0; mf < MF; ++mf) {
+                const v4i a0 = *reinterpret_cast<const v4i *>(xs + mf * 32 * kTilePitch + 64 * c);
+                const v4i a1 = *reinterpret_cast<const v4i *>(xs + mf * 32 * kTilePitch + 64 * c + 32);
+#pragma unroll
+                for (int t = 0; t < 2; ++t) acc[mf][t] = mfma_i8(a0, blo[t], acc[mf][t]);
+#pragma unroll
+                for (int t = 0; t < 2; ++t) acc[mf][t] = mfma_i8(a1, bhi[t], acc[mf][t]);
+            }
+        }
+    };
+
+    load_x(0);
+    load_w(0, wc, pc);
+    store_x(0);
+    __syncthreads();
+
+    // Steady state: the global loads of stage s+1 are issued before the MFMAs of stage s
+    // and land in LDS / registers after them.
+    for (int s = 0; s + 1 < stages; ++s) {
+        load_x(s + 1);
+        load_w(s + 1, wn, pn);
+        __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of the MFMAs
+        compute(s & 1);
+        __builtin_amdgcn_sched_barrier(0);
+        store_x((s + 1) & 1);
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            wc[t][0] = wn[t][0];
+            wc[t][1] = wn[t][1];
+            pc[t] = pn[t];
+        }
+    }
+    compute((stages - 1) & 1);
+
+    if (!active) return;
+    // Epilogue: element r of acc[mf][t] is row m0 + 32*mf + acc_row(r), channel
+    // 64*ng + 2*j + t: the two tiles give 2 adjacent channels per lane.
+    store_tile<MF>(acc, M, N, m0, 64 * ng + 2 * j, lane, sx, sw, Y, ACC);
+}
+
+// Block barrier that orders LDS traffic only: __syncthreads() would also wait for every
+// outstanding global load (vmcnt(0)), which is exactly what the prefetches must not do.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// ------------------------------------------------------------------------------------
+// duo kernel: two waves per SIMD.
+//
+// On CDNA a wave issues in order and an MFMA holds the SIMD's vector issue for part of its
+// duration (8 to 16 of the 32 cycles of a 32x32x32 INT8 MFMA, measured), so the VALU work of
+// the dequantisation overlaps best with matrix work of ANOTHER wave on the same SIMD --
+// the observation behind the paper's implicit fine-grained pipeline (Sec. 5.1:
+// dequantisation in one compute group overlaps MMA in another, with the hardware
+// arbitrating).  This kernel therefore keeps every wave at <= 256 registers
+// (wave tile 128 x 64, block tile 128 x 256, two blocks per CU) and software-pipelines each
+// wave at the granularity of one k-step (32 k): while the 8 MFMAs of a k-step run, the
+// B operand of the next k-step is dequantised and its X fragments are read from LDS.
+// ------------------------------------------------------------------------------------
+//
+// KG = 2 is the variant for grids of at most one block per CU: the block then holds two
+// groups of four waves that work on the same 128 x 256 tile, each on its own half of the
+// block's k range with its own LDS stages, and exchange halves of their accumulators
+// through LDS at the end (in-block split-K).  Every SIMD again has two waves, which a
+// single 4-wave block per CU would not give.
+// MF = row fragments of 32 that the block computes (4, or 2 for a row tile with at most 64
+// rows below M: a ragged last tile, an expert with few tokens): such a tile pays for half
+// the MFMAs, X staging and fragment reads.  The tile grid is that of 128-row tiles either way.
+template <bool G128, int KG, int MF, int TM = 128>
+__device__ __forceinline__ void duo_tile(
+    const Place pl, const int bm, const int bn, int M, int N, int K, const int8_t *__restrict__ X,
+    const float *__restrict__ sx, const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp,
+    const float *__restrict__ sw, __half *__restrict__ Y, int32_t *__restrict__ ACC,
+    int32_t *__restrict__ partials)
+{
+    constexpr int WM = TM, XP = MF;  // TM = rows between consecutive row tiles (128, or 64 with MF = 2)
+    static_assert(32 * MF <= TM, "a tile cannot hold more row fragments than its height");
+    constexpr int STAGE = 128 * kTilePitch;
+    extern __shared__ __attribute__((aligned(16))) int8_t lds[];
+    __shared__ int s_last;
+
+    const int tid = threadIdx.x & 255;  // thread within its k group
+    const int grp = KG == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 8));
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it in an SGPR
+    const int j = lane & 31, kb = lane >> 5;
+    const int m0 = bm * WM;
+    const int ng = bn * 4 + wave;
+    const bool active = ng < (N >> 6);
+    const int t0 = 2 * (active ? ng : (N >> 6) - 1);
+    // grid-level split-K: slice ks of S covers whole units of 256 k ...
+    const int S = pl.S, ks = pl.ks;
+    const int u_begin = (int)((long long)(K >> 8) * ks / S), u_end = (int)((long long)(K >> 8) * (ks + 1) / S);
+    // ... and the in-block split gives group 0 the first ceil(half) of them.  All groups run
+    // the loop of group 0 (the barriers are block-wide); a group with one unit less feeds
+    // zeros as X in its last pass.
+    const int u_first = (u_end - u_begin + KG - 1) / KG;
+    const int s_begin = 2 * (u_begin + (grp ? u_first : 0));
+    const int my_stages = 2 * (grp ? u_end - u_begin - u_first : u_first);
+    const int stages = 2 * u_first;  // loop length in stages of 128 k (even)
+    const int stages_total = K >> 7;
+    const int chunks_per_tile = K >> 6;
+
+    LQ_DSTAMP(0);
+    v16i acc[MF][2];
+#pragma unroll
+    for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mf][t][r] = 0;
+
+    // X piece i of this thread: row (tid>>3) + 32*i, 16-byte column tid&7
+    const int xrow = tid >> 3, xcol = tid & 7;
+    // 32-bit offsets from block-uniform bases instead of one 64-bit pointer per piece: the
+    // kernel runs at the 256-register limit and X has fewer than 2^32 bytes (K <= 131072 and
+    // the host rejects M * K >= 2^32).
+    const int8_t *xbase = X + (size_t)s_begin * 128;
+    uint32_t xg[XP];
+#pragma unroll
+    for (int i = 0; i < XP; ++i) xg[i] = (uint32_t)min(m0 + xrow + 32 * i, M - 1) * (uint32_t)K + 16 * xcol;
+    const int xl = xrow * kTilePitch + 16 * xcol;
+    // tile t0 + 1 lies one tile stream behind t0 (block-uniform strides)
+    const u32x4 *wg0 = Wp + ((size_t)t0 * chunks_per_tile + 2 * (size_t)s_begin) * 64 + lane;
+    const uint8_t *pg0 = gp + (((size_t)t0 * stages_total + s_begin) * 32 + j) * (G128 ? 2 : 4);
+    const size_t wg_stride = (size_t)chunks_per_tile * 64;
+    const size_t pg_stride = (size_t)stages_total * 32 * (G128 ? 2 : 4);
+    int8_t *lds_g = lds + grp * (2 * STAGE);  // the two X stages of this k group
+    const int8_t *xs = lds_g + j * kTilePitch + 16 * kb;
+
+    u32x4 xr[XP];
+    u32x4 wr[2][2][2];  // [stage parity][tile][chunk]
+    UnitParams<G128> pr[2][2];
+    v4i bf[2][2];       // [ping-pong][tile]
+    v4i af[2][MF];      // [ping-pong][m fragment]
+
+    auto load_x = [&](int s) {
+        if (KG > 1 && s >= my_stages) {  // past this group's slice: contributes nothing
+#pragma unroll
+            for (int i = 0; i < XP; ++i) xr[i] = u32x4{0, 0, 0, 0};
+            return;
+        }
+        s = min(s, my_stages - 1);
+#pragma unroll
+        for (int i = 0; i < XP; ++i)
+            xr[i] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)s * 128 + xg[i]);
+    };
+    auto store_x = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < XP; ++i)
+            *reinterpret_cast<u32x4 *>(lds_g + buf * STAGE + xl + i * 32 * kTilePitch) = xr[i];
+    };
+    auto load_w = [&](int s, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
+        s = min(s, my_stages - 1);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const u32x4 *wg = wg0 + t * wg_stride;
+            const uint8_t *pg = pg0 + t * pg_stride;
+            w[t][0] = wg[(size_t)s * 128];
+            w[t][1] = wg[(size_t)s * 128 + 64];
+            if (G128)
+                p[t].raw = *reinterpret_cast<const uint16_t *>(pg + (size_t)s * 64);
+            else
+                p[t].raw = *reinterpret_cast<const uint32_t *>(pg + (size_t)s * 128);
+        }
+    };
+    // B operand of k-step (c, h) for both tiles
+    auto build_b = [&](const u32x4 (&w)[2][2], const UnitParams<G128> (&p)[2], int c, int h, v4i (&b)[2]) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+#if defined(LQ_ABLATE) && (LQ_DUO_ABL & 1)  // experiments only: raw bytes instead of the dequantised operand
+            b[t] = __builtin_bit_cast(v4i, w[t][c]) + h + (int)p[t].raw;
+#elif defined(LQ_ABLATE) && (LQ_DUO_ABL & 4)
+            // experiments only: the overflow-safe dequantisation that LiquidQuant avoids --
+            // code * s + min in signed 16-bit lanes (two codes per register), low bytes
+            // gathered with a byte permute: about twice the instructions, same result
+            uint32_t s2, a4;
+            p[t].get(c, s2, a4);
+            const uint32_t mn2 = (((a4 & 0xffu) - 128u) & 0xffffu) * 0x00010001u;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const uint32_t q = w[t][c][d] >> (4 * h);
+                const uint32_t ra = q & 0x000F000Fu, rb = (q >> 8) & 0x000F000Fu;
+                const uint32_t ma = pk_mad_u16(ra, s2, mn2), mb = pk_mad_u16(rb, s2, mn2);
+                b[t][d] = (int)__builtin_amdgcn_perm(mb, ma, 0x06020400u);
+            }
+#else
+            uint32_t s2, a4;
+            p[t].get(c, s2, a4);
+            dequant_half(w[t][c], s2, a4, h, b[t]);
+#endif
+        }
+    };
+    auto read_a = [&](int buf, int c, int h, v4i (&a)[MF]) {
+#if defined(LQ_ABLATE) && (LQ_DUO_ABL & 2)  // experiments only: no X fragment reads from LDS
+        if (buf + c + h == -1)
+#endif
+#pragma unroll
+        for (int mf = 0; mf < MF; ++mf)
+            a[mf] = *reinterpret_cast<const v4i *>(xs + buf * STAGE + mf * 32 * kTilePitch + 64 * c + 32 * h);
+    };
+    auto mma = [&](const v4i (&a)[MF], const v4i (&b)[2]) {
+#pragma unroll
+        for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) acc[mf][t] = mfma_i8(a[mf], b[t], acc[mf][t]);
+    };
+
+    // One stage: w_cur = W(s) on entry and W(s+2) on exit, w_nxt = W(s+1); af[0], bf[0] hold
+    // k-step (0,0) of this stage on entry and of the next stage on exit; xr holds X(s+1).
+    auto stage = [&](int s, u32x4 (&w_cur)[2][2], UnitParams<G128> (&p_cur)[2], u32x4 (&w_nxt)[2][2],
+                     UnitParams<G128> (&p_nxt)[2], int buf) {
+        // k-step (0,0)
+        store_x(buf ^ 1);  // X(s+1); that buffer was released by the previous barrier
+        read_a(buf, 0, 1, af[1]);
+        build_b(w_cur, p_cur, 0, 1, bf[1]);
+        mma(af[0], bf[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        // k-step (0,1)
+        load_x(s + 2);
+        read_a(buf, 1, 0, af[0]);
+        build_b(w_cur, p_cur, 1, 0, bf[0]);
+        mma(af[1], bf[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        // k-step (1,0)
+        read_a(buf, 1, 1, af[1]);
+        build_b(w_cur, p_cur, 1, 1, bf[1]);
+        mma(af[0], bf[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        // k-step (1,1): W(s) is fully consumed, the next stage's X is complete after the barrier
+        lds_barrier();
+        read_a(buf ^ 1, 0, 0, af[0]);
+        build_b(w_nxt, p_nxt, 0, 0, bf[0]);
+        load_w(s + 2, w_cur, p_cur);
+        mma(af[1], bf[1]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // prologue (the W loads are issued after X(1) so that, as in the steady state, the
+    // only loads younger than an X stage are one stage of W)
+    load_x(0);
+    store_x(0);
+    load_x(1);
+    __builtin_amdgcn_sched_barrier(0);
+    load_w(0, wr[0], pr[0]);
+    load_w(1, wr[1], pr[1]);
+    __builtin_amdgcn_sched_barrier(0);
+    build_b(wr[0], pr[0], 0, 0, bf[0]);
+    lds_barrier();
+    read_a(0, 0, 0, af[0]);
+    __builtin_amdgcn_sched_barrier(0);
+
+    LQ_DSTAMP(1);
+    for (int s = 0; s < stages; s += 2) {
+        stage(s, wr[0], pr[0], wr[1], pr[1], 0);
+        stage(s + 1, wr[1], pr[1], wr[0], pr[0], 1);
+    }
+    LQ_DSTAMP(2);
+
+    // What is left is written once per k group with compile-time fragment indices: group G
+    // finishes the MFK = MF / KG row fragments starting at MF0 = G * MFK.
+    auto finish = [&](auto group_tag) {
+        constexpr int G = decltype(group_tag)::value;
+        constexpr int MFK = MF / KG, MF0 = G * MFK, GIVE0 = (KG - 1 - G) * MFK;
+        if (KG > 1) {
+            // In-block reduction through LDS (the X stages are dead by now), one column tile
+            // at a time so that 64 KiB suffice: every wave hands the fragments it does not
+            // finish to the wave of the other group that owns the same 128 x 64 sub-tile.
+            v4i *ex = reinterpret_cast<v4i *>(lds);
+            lds_barrier();
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+#pragma unroll
+                for (int i = 0; i < MFK; ++i)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        ex[(((G * 4 + wave) * MFK + i) * 4 + q) * 64 + lane] =
+                            v4i{acc[GIVE0 + i][t][4 * q], acc[GIVE0 + i][t][4 * q + 1],
+                                acc[GIVE0 + i][t][4 * q + 2], acc[GIVE0 + i][t][4 * q + 3]};
+                lds_barrier();
+#pragma unroll
+                for (int i = 0; i < MFK; ++i)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const v4i v = ex[((((KG - 1 - G) * 4 + wave) * MFK + i) * 4 + q) * 64 + lane];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[MF0 + i][t][4 * q + e] += v[e];
+                    }
+                if (t == 0) lds_barrier();
+            }
+        }
+        LQ_DSTAMP(3);
+        if (S > 1) {
+            // Grid-level split-K (same protocol as the stream kernels): every block publishes its
+            // INT32 partial tile with device-scope write-through stores, takes a ticket, and the
+            // last one of the S slices adds the others to its registers and runs the epilogue.
+            // Layout: [tile][slice][wave of the block][MFK*8 x (64 lanes x 16 B)], fully coalesced.
+            constexpr int EPW = (4 / KG) * 8;  // slots of a full 4-fragment tile, whatever MF is
+            const size_t tile = pl.gx;
+            const int bw = G * 4 + wave;
+            int32_t *mine = partials + (((tile * S + ks) * (4 * KG) + bw) * EPW) * 256 + lane * 4;
+            // row fragments that lie wholly past M are neither published nor read back
+            auto live = [&](int i) { return m0 + 32 * (MF0 + i) < M; };
+#pragma unroll
+            for (int i = 0; i < MFK; ++i) {
+                if (!live(i)) continue;
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    int32_t *frag = mine + (i * 2 + t) * 4 * 256;
+                    auto part = [&](int q) {
+                        return v4i{acc[MF0 + i][t][4 * q], acc[MF0 + i][t][4 * q + 1], acc[MF0 + i][t][4 * q + 2],
+                                   acc[MF0 + i][t][4 * q + 3]};
+                    };
+                    store_sc1_x4<0>(frag, part(0));
+                    store_sc1_x4<1024>(frag, part(1));
+                    store_sc1_x4<2048>(frag, part(2));
+                    store_sc1_x4<3072>(frag, part(3));
+                }
+            }
+            wait_vmcnt0();
+            LQ_DSTAMP(4);
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                const unsigned tk = __hip_atomic_fetch_add(&pl.tickets[tile], 1u, __ATOMIC_RELAXED,
+                                                           __HIP_MEMORY_SCOPE_AGENT);
+                s_last = (tk == (unsigned)(S - 1));
+            }
+            __syncthreads();
+            LQ_DSTAMP(5);
+            if (!s_last) return;
+            // The 8 loads of one row fragment (2 column tiles x 4 pieces of 16 bytes per lane)
+            // are in flight before the first is waited for: the latency of these device-scope
+            // reads, not their volume, is what this tail costs.
+            for (int k2 = 0; k2 < S; ++k2) {
+                if (k2 == ks) continue;
+                const int32_t *other = partials + (((tile * S + k2) * (4 * KG) + bw) * EPW) * 256 + lane * 4;
+#pragma unroll
+                for (int i = 0; i < MFK; ++i) {
+                    if (!live(i)) continue;
+                    v4i v[2][4];
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        const int32_t *frag = other + (i * 2 + t) * 4 * 256;
+                        v[t][0] = load_sc1_x4<0>(frag);
+                        v[t][1] = load_sc1_x4<1024>(frag);
+                        v[t][2] = load_sc1_x4<2048>(frag);
+                        v[t][3] = load_sc1_x4<3072>(frag);
+                    }
+                    wait_vmcnt0(v[0][0], v[0][1], v[0][2], v[0][3]);
+                    wait_vmcnt0(v[1][0], v[1][1], v[1][2], v[1][3]);
+#pragma unroll
+                    for (int t = 0; t < 2; ++t)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) acc[MF0 + i][t][4 * q + e] += v[t][q][e];
+                }
+            }
+            LQ_DSTAMP(6);
+            if (threadIdx.x == 0)
+                __hip_atomic_store(&pl.tickets[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (!active) return;
+        store_tile<MFK>(*reinterpret_cast<const v16i(*)[MFK][2]>(&acc[MF0]), M, N, m0 + 32 * MF0,
+                        64 * ng + 2 * j, lane, sx, sw, Y, ACC);
+        LQ_DSTAMP(7);
+    };
+    if (KG == 1 || grp == 0)
+        finish(std::integral_constant<int, 0>{});
+    else
+        finish(std::integral_constant<int, KG - 1>{});
+}
+
+template <bool G128, int KG, int TM = 128>
+__device__ __forceinline__ void duo_block(
+    const Place pl, const int bm, const int bn, int M, int N, int K, const int8_t *__restrict__ X,
+    const float *__restrict__ sx, const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp,
+    const float *__restrict__ sw, __half *__restrict__ Y, int32_t *__restrict__ ACC,
+    int32_t *__restrict__ partials)
+{
+    if (TM == 64)
+        duo_tile<G128, KG, 2, 64>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+    else if (M - 128 * bm <= 64)  // block-uniform
+        duo_tile<G128, KG, 2>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+    else
+        duo_tile<G128, KG, 4>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+}
+
+template <bool G128, int KG, int TM = 128>
+__global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
+    int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
+    const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
+    __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n,
+    int32_t *__restrict__ partials, unsigned int *__restrict__ tickets)
+{
+    int bm, bn;
+    block_coords(blocks_m, blocks_n, bm, bn);
+    duo_block<G128, KG, TM>(grid_place(tickets), bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+}
+
+// The same barrier for code that waits for its loads itself: a fence would also wait for
+// every asynchronous load into LDS that is still in flight.
+__device__ __forceinline__ void lds_barrier_raw()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
