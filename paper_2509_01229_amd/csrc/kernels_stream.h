@@ -21,13 +21,22 @@ struct StreamRegs {
 // streamed once; the dequantised operand of a chunk feeds MF MFMAs).  Four fragments were
 // measured too: the X fragments, which every block reads for itself from L2, then outweigh
 // the weights four to one and the 128 x 256 tiles with X shared through LDS are faster.
-template <int F, int NW, int MF, bool G128>
+//
+// XL = the X fragments pass through LDS.  Read straight from global memory, one fragment
+// load touches 32 rows, 16 bytes of each (32 cache lines for 1 KiB); with two row fragments
+// these loads, not the weights, set the pace.  With XL a wave fetches its 32 MF rows x 128 k
+// of a unit with loads that cover 8 whole rows each (8 lines per KiB), stores them to a
+// region of LDS of its own and reads the fragments back from there.  The region is laid out
+// like a stage of the direct-to-LDS tile kernel (1 KiB pieces of 8 rows, the 16-byte columns
+// of a row rotated by an XOR with the row) so that neither the stores nor the fragment reads
+// meet bank conflicts.
+template <int F, int NW, int MF, bool G128, bool XL = false>
 __device__ __forceinline__ void stream_block(
     const Place pl, int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
     __half *__restrict__ Y, int32_t *__restrict__ ACC, int32_t *__restrict__ partials)
 {
-    extern __shared__ __attribute__((aligned(16))) int red[];  // [NW][F * MF * rmax][64]
+    extern __shared__ __attribute__((aligned(16))) int red[];  // [NW][F * MF * rmax][64]; XL: first the X regions
     __shared__ int s_last;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane & 31, kb = lane >> 5;
@@ -52,6 +61,20 @@ __device__ __forceinline__ void stream_block(
     const int8_t *xrow[MF];
 #pragma unroll
     for (int mf = 0; mf < MF; ++mf) xrow[mf] = X + (size_t)min(j + 32 * mf, M - 1) * K + 16 * kb;
+    // XL: load i of a unit (i = 0 .. 4 MF - 1) fills the 1 KiB piece i of the wave's region in
+    // lane order; lane p brings row 8 i + r, 16-byte column c with r = (p >> 3) ^ (i & 1),
+    // c = (p & 7) ^ r.  Fragment row j' = 32 mf + j is then found in piece j' >> 3 at
+    // 128 ((j & 7) ^ (piece & 1)) + 16 (column ^ (j & 7)).
+    int8_t *const xregion = reinterpret_cast<int8_t *>(red) + wave * (MF * 4096);
+    const int8_t *const xfrag = xregion + (j >> 3) * 1024 + 128 * ((j & 7) ^ ((j >> 3) & 1));
+    uint32_t xoff[XL ? 4 * MF : 1];
+    if (XL) {
+#pragma unroll
+        for (int i = 0; i < 4 * MF; ++i) {
+            const int r = (lane >> 3) ^ (i & 1), c = (lane & 7) ^ r;
+            xoff[i] = (uint32_t)min(8 * i + r, M - 1) * (uint32_t)K + 16 * c;
+        }
+    }
 
     auto load_unit = [&](int u, StreamRegs<F, MF, G128> &r) {
 #pragma unroll
@@ -65,9 +88,21 @@ __device__ __forceinline__ void stream_block(
         for (int mf = 0; mf < MF; ++mf)
 #pragma unroll
             for (int ks4 = 0; ks4 < 4; ++ks4)
-                r.x[mf][ks4] = *reinterpret_cast<const u32x4 *>(xrow[mf] + (size_t)u * 128 + 32 * ks4);
+                r.x[mf][ks4] = XL ? *reinterpret_cast<const u32x4 *>(X + ((size_t)xoff[XL ? 4 * mf + ks4 : 0] + (size_t)u * 128))
+                                  : *reinterpret_cast<const u32x4 *>(xrow[mf] + (size_t)u * 128 + 32 * ks4);
     };
     auto compute_unit = [&](const StreamRegs<F, MF, G128> &r) {
+        if (XL) {
+#pragma unroll
+            for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+                for (int ks4 = 0; ks4 < 4; ++ks4)
+                    *reinterpret_cast<u32x4 *>(xregion + (4 * mf + ks4) * 1024 + 16 * lane) = r.x[mf][ks4];
+        }
+        auto frag = [&](int mf, int ks4) {
+            return XL ? *reinterpret_cast<const v4i *>(xfrag + mf * 4096 + 16 * ((2 * ks4 + kb) ^ (j & 7)))
+                      : __builtin_bit_cast(v4i, r.x[mf][ks4]);
+        };
 #pragma unroll
         for (int f = 0; f < F; ++f)
 #pragma unroll
@@ -78,8 +113,8 @@ __device__ __forceinline__ void stream_block(
                 dequant_chunk(r.w[f][c], s2, a4, lo, hi);
 #pragma unroll
                 for (int mf = 0; mf < MF; ++mf) {
-                    acc[f][mf] = mfma_i8(__builtin_bit_cast(v4i, r.x[mf][2 * c]), lo, acc[f][mf]);
-                    acc[f][mf] = mfma_i8(__builtin_bit_cast(v4i, r.x[mf][2 * c + 1]), hi, acc[f][mf]);
+                    acc[f][mf] = mfma_i8(frag(mf, 2 * c), lo, acc[f][mf]);
+                    acc[f][mf] = mfma_i8(frag(mf, 2 * c + 1), hi, acc[f][mf]);
                 }
             }
     };
@@ -103,6 +138,7 @@ __device__ __forceinline__ void stream_block(
     // [8*(r/4), 8*(r/4)+8).  Value v = (f * MF + mf) * rmax + r of lane l is row
     // 32*mf + acc_row(r, l), slot l%32 of tile t0 + f.
     const int rmax = MF == 1 ? 4 * ((M + 7) >> 3) : 16;
+    if (XL) __syncthreads();  // the X regions are done with: the reduction takes the same LDS
 #pragma unroll
     for (int f = 0; f < F; ++f)
 #pragma unroll
@@ -161,14 +197,14 @@ __device__ __forceinline__ void stream_block(
     LQ_STAMP(3);
 }
 
-template <int F, int NW, int MF, bool G128>
+template <int F, int NW, int MF, bool G128, bool XL = false>
 __global__ __launch_bounds__(NW * 64) void w4a8_stream_kernel(
     int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
     __half *__restrict__ Y, int32_t *__restrict__ ACC, int32_t *__restrict__ partials,
     unsigned int *__restrict__ tickets)
 {
-    stream_block<F, NW, MF, G128>(grid_place(tickets), M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+    stream_block<F, NW, MF, G128, XL>(grid_place(tickets), M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
 }
 
 // ------------------------------------------------------------------------------------

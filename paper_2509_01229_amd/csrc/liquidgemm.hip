@@ -141,7 +141,7 @@ static size_t stream_ws_bytes(int M, int N, int S, int MF = 1)
 
 // S = requested number of K slices; `named` = the variant names its split (then a missing
 // workspace is an error instead of a fall-back to one slice).
-template <int F, int NW, int MF>
+template <int F, int NW, int MF, bool XL = false>
 static int launch_stream_as(const Args &a, int S, bool named)
 {
     if (a.M > 32 * MF) return fail(LQ_ERR_INVALID, "this stream variant handles M <= %d, got %d", 32 * MF, a.M);
@@ -159,41 +159,55 @@ static int launch_stream_as(const Args &a, int S, bool named)
     }
     const dim3 grid(groups, S), block(NW * 64);
     const int rmax = MF == 1 ? 4 * ((a.M + 7) / 8) : 16;
-    const size_t lds_bytes = (size_t)NW * F * MF * rmax * 64 * sizeof(int);
+    // reduction buffer; with XL the waves' X regions (32 MF rows x 128 k each) come first in the same memory
+    const size_t lds_bytes = std::max((size_t)NW * F * MF * rmax * 64 * sizeof(int), XL ? (size_t)NW * MF * 4096 : 0);
     unsigned int *tickets = static_cast<unsigned int *>(a.ws);
     int32_t *partials = a.ws ? reinterpret_cast<int32_t *>(static_cast<char *>(a.ws) + kTicketBytes) : nullptr;
     if (a.group == 128) {
-        if (int rc = allow_lds(&w4a8_stream_kernel<F, NW, MF, true>, lds_bytes)) return rc;
-        hipLaunchKernelGGL((w4a8_stream_kernel<F, NW, MF, true>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
+        if (int rc = allow_lds(&w4a8_stream_kernel<F, NW, MF, true, XL>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_stream_kernel<F, NW, MF, true, XL>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
                            a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials, tickets);
     } else {
-        if (int rc = allow_lds(&w4a8_stream_kernel<F, NW, MF, false>, lds_bytes)) return rc;
-        hipLaunchKernelGGL((w4a8_stream_kernel<F, NW, MF, false>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
+        if (int rc = allow_lds(&w4a8_stream_kernel<F, NW, MF, false, XL>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_stream_kernel<F, NW, MF, false, XL>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
                            a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials, tickets);
     }
     return LQ_OK;
 }
 
 // SPLIT: 0 = choose with stream_split(), otherwise the fixed number of K slices.
-template <int F, int NW, int SPLIT, int MF = 1>
+template <int F, int NW, int SPLIT, int MF = 1, bool XL = false>
 static int launch_stream(const Args &a)
 {
-    return launch_stream_as<F, NW, MF>(a, SPLIT ? SPLIT : stream_split(a.N, a.K, F, NW), SPLIT != 0);
+    return launch_stream_as<F, NW, MF, XL>(a, SPLIT ? SPLIT : stream_split(a.N, a.K, F, NW), SPLIT != 0);
 }
 
 // 32-row (MF = 1) and 64-row (MF = 2) stream kernels with the block shape chosen from N.
 // Measured for both: the best grid is the largest one of at most 256 blocks of 8 waves --
 // one tile per block while N / 32 <= 256, else two -- with K split across blocks while
-// that still fits.
-template <int MF>
-static int launch_stream_auto(const Args &a)
+// that still fits and leaves every wave at least four units of 128 k.
+template <int MF, bool XL>
+static int launch_stream_shaped(const Args &a)
 {
     const int tiles = a.N / 32;
     // long K with no room for K slices: two tiles per block share the X fragments and two
-    // K slices halve each wave's walk (27 vs 31 us at 24 rows on 8192 x 28672)
-    if (tiles > 128 && tiles <= 256 && a.K >= 16384) return launch_stream_as<2, 8, MF>(a, 2, false);
-    if (tiles <= 256) return launch_stream_as<1, 8, MF>(a, std::min(4, 256 / tiles), false);
-    return launch_stream_as<2, 8, MF>(a, std::min(4, 512 / tiles), false);
+    // K slices halve each wave's walk (29 vs 31 us at 32 rows, 39 vs 42 at 64 rows on 8192 x 28672)
+    if (tiles > 128 && tiles <= 256 && a.K >= 24576) return launch_stream_as<2, 8, MF, XL>(a, 2, false);
+    if (tiles <= 256) {
+        const int s_units = std::max(1, a.K / (128 * 8 * 4));
+        return launch_stream_as<1, 8, MF, XL>(a, std::min({4, 256 / tiles, s_units}), false);
+    }
+    return launch_stream_as<2, 8, MF, XL>(a, 1, false);
+}
+
+// X through LDS (XL) pays whenever a wave holds two row fragments; with one it is worth
+// 4-9 % once most of the 32 rows exist and N is small enough for one tile per block, and
+// costs a few per cent otherwise (measured at 24 and 32 rows on thirteen weight shapes).
+template <int MF>
+static int launch_stream_auto(const Args &a)
+{
+    if (MF == 2) return launch_stream_shaped<2, true>(a);
+    return a.M > 24 && a.N / 32 <= 256 ? launch_stream_shaped<1, true>(a) : launch_stream_shaped<1, false>(a);
 }
 
 template <int F, int NW, int SPLIT, int ABL = 0, int UU = 1>
@@ -431,6 +445,18 @@ static const Variant kVariants[] = {
     {"stream_m64_f2_w8_s4", &launch_stream<2, 8, 4, 2>, 64, 2, 1},
     {"stream_m64_f1_w8_s1", &launch_stream<1, 8, 1, 2>, 64, 1, 1},
     {"stream_m64_f1_w8_s2", &launch_stream<1, 8, 2, 2>, 64, 1, 1},
+    {"stream_m64x_f1_w8_s1", &launch_stream<1, 8, 1, 2, true>, 64, 1, 1},
+    {"stream_m64x_f1_w8_s2", &launch_stream<1, 8, 2, 2, true>, 64, 1, 1},
+    {"stream_m64x_f2_w8_s1", &launch_stream<2, 8, 1, 2, true>, 64, 2, 1},
+    {"stream_m64x_f2_w8_s2", &launch_stream<2, 8, 2, 2, true>, 64, 2, 1},
+    {"stream_m64x_f1_w8_s4", &launch_stream<1, 8, 4, 2, true>, 64, 1, 1},
+    {"stream_m64x_f2_w8_s4", &launch_stream<2, 8, 4, 2, true>, 64, 2, 1},
+    {"stream_x_f1_w8_s1", &launch_stream<1, 8, 1, 1, true>, 32, 1, 1},
+    {"stream_x_f1_w8_s2", &launch_stream<1, 8, 2, 1, true>, 32, 1, 1},
+    {"stream_x_f1_w8_s4", &launch_stream<1, 8, 4, 1, true>, 32, 1, 1},
+    {"stream_x_f2_w8_s1", &launch_stream<2, 8, 1, 1, true>, 32, 2, 1},
+    {"stream_x_f2_w8_s2", &launch_stream<2, 8, 2, 1, true>, 32, 2, 1},
+    {"stream_x_f2_w8_s4", &launch_stream<2, 8, 4, 1, true>, 32, 2, 1},
     {"stream16_f2_w8", &launch_stream16<2, 8, 0>, 16, 2, 1},
     {"stream16_f2_w4", &launch_stream16<2, 4, 0>, 16, 2, 1},
     {"stream16_f2_w8_s1", &launch_stream16<2, 8, 1>, 16, 2, 1},
@@ -508,20 +534,9 @@ static int select_variant(int M, int N, int K)
         return find_variant(N / 64 >= 384 ? "stream16_f2_w4" : "stream16_f2_w8");
     }
     if (M <= 32) return find_variant("stream_m32");
-    // up to 64 rows the weights are still best streamed once per block column unless N alone
-    // fills the chip with 128 x 256 tiles
-    if (M <= 64 && N / 32 <= 512) {
-        // ... except when N alone gives the stream kernel its 256 blocks (no K slices) and K is
-        // long: each wave then walks K / 1024 units of 128 k at about 0.027 us per row, against
-        // the tiled kernel's split-K grid (fits of measured times, microseconds)
-        if (N / 32 >= 256 && K >= 8192) {
-            const double est_stream = 7.5 + 0.027 * M * (K / 1024) * (N / 32 > 256 ? 1.15 : 1.0);
-            const int S = duo_split(M, N, K);
-            const double est_tiled = 0.85 * (8.1 + 1.76 * (K / 256) / (2.0 * S) + 2.4 * (S - 1));
-            if (est_tiled < est_stream) return find_variant("duo_m128");
-        }
-        return find_variant("stream_m64");
-    }
+    // up to 64 rows the weights are still best streamed once per block column (X through LDS)
+    // unless N alone fills the chip with 128 x 256 tiles
+    if (M <= 64 && N / 32 <= 512) return find_variant("stream_m64");
     // clearly more 128 x 256 tiles than CUs: the deeper memory pipeline of the direct-to-LDS
     // form pays (3 to 6 % measured from 320 tiles up); with one tile per CU or fewer, the two k
     // groups per block of the other form do

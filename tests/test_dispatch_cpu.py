@@ -17,7 +17,7 @@ def test_dispatcher_families_on_the_workloads():
             assert name.startswith("stream16_"), (s.name, name)
         elif s.M <= 32:
             assert name == "stream_m32", (s.name, name)
-        elif s.M <= 64 and s.N <= 16384 and s.K < 8192:
+        elif s.M <= 64 and s.N <= 16384:
             assert name == "stream_m64", (s.name, name)
         else:
             assert name in ("duo_m64", "duo_m128", "duo_dl_m128"), (s.name, name)
@@ -39,9 +39,9 @@ def test_dispatcher_boundaries():
     assert _pick(16, 28672, 8192, 128) == "stream16_f2_w4"     # N alone fills the chip
     assert _pick(17, 4096, 4096) == "stream_m32" and _pick(32, 28672, 8192) == "stream_m32"
     assert _pick(33, 4096, 4096) == "stream_m64" and _pick(64, 16384, 4096) == "stream_m64"
-    # 33..64 rows, N alone fills the stream kernel's grid and K is long: the tiled kernel's split-K grid
-    assert _pick(64, 8192, 8192) == "duo_m128" and _pick(48, 8192, 8192) == "stream_m64"
-    assert _pick(40, 8192, 28672, 128) == "duo_m128" and _pick(64, 4096, 11008) == "stream_m64"
+    # 33..64 rows: streamed (X through LDS) up to 512 tiles of 32 channels, whatever K
+    assert _pick(64, 8192, 8192) == "stream_m64" and _pick(48, 8192, 8192) == "stream_m64"
+    assert _pick(40, 8192, 28672, 128) == "stream_m64" and _pick(64, 4096, 11008) == "stream_m64"
     assert _pick(64, 28672, 8192) == "duo_m64" and _pick(65, 4096, 4096) == "duo_m64"
     assert _pick(256, 28672, 8192) == "duo_m128"
     assert _pick(512, 4096, 4096) == "duo_m64" and _pick(1025, 4096, 4096) == "duo_m128"
@@ -60,7 +60,7 @@ def test_variant_table_is_consistent():
     for v, name in enumerate(names):
         # row limits are part of the names' families
         limit = (16 if name.startswith("stream16") else 64 if name.startswith("stream_m64")
-                 else 32 if name.startswith(("stream_f", "stream_m32")) else None)
+                 else 32 if name.startswith(("stream_f", "stream_x_", "stream_m32")) else None)
         if limit:
             assert api.w4a8_variant_supports(v, limit, 256, 1024, 64)
             assert not api.w4a8_variant_supports(v, limit + 1, 256, 1024, 64)
