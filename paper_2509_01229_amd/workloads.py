@@ -49,10 +49,17 @@ ALL_SHAPES = TINY + DECODE + MLP_7B + LAYERS_70B + PREFILL
 
 
 def by_name(name: str) -> GemmShape:
+    """A shape of ALL_SHAPES, or any other one spelled `<label>_M<M>_N<N>_K<K>[_g<group>]`
+    (group 64 unless given; the recipe of the prefill sweep)."""
     for s in ALL_SHAPES:
         if s.name == name:
             return s
-    raise KeyError(name)
+    import re
+
+    m = re.fullmatch(r"[A-Za-z0-9]+_M(\d+)_N(\d+)_K(\d+)(?:_g(64|128))?", name)
+    if not m:
+        raise KeyError(name)
+    return GemmShape(name, int(m.group(1)), int(m.group(2)), int(m.group(3)), group=int(m.group(4) or 64), seed=4)
 
 
 def quantize_activations(X):
