@@ -82,3 +82,15 @@ def test_workspace_sizes():
     # the tiled kernel's partial tiles (128 x 256 INT32 per tile and slice, up to 8 slices)
     assert ws(128, 4096, 4096, 64) >= 16 * 8 * 128 * 256 * 4
     assert ws(128, 4096, 4096, 64) <= 1 << 30
+
+
+def test_workload_names():
+    # the listed shapes by name, and any other shape spelled <label>_M.._N.._K..[_g..]
+    s = WL.by_name("l70b_up_M16_N28672_K8192")
+    assert (s.M, s.N, s.K, s.group) == (16, 28672, 8192, 128)
+    s = WL.by_name("curve_M64_N8192_K8192_g128")
+    assert (s.M, s.N, s.K, s.group) == (64, 8192, 8192, 128)
+    assert WL.by_name("x_M3_N64_K256").group == 64
+    for bad in ("bogus", "x_M3_N64", "x_M3_N64_K256_g32", "_M3_N64_K256"):
+        with pytest.raises(KeyError):
+            WL.by_name(bad)
