@@ -12,9 +12,9 @@
 //
 // One block of 256 threads per token (or per R consecutive tokens, one after the other, so
 // that the reciprocals of the smooth scales are computed once for R tokens).  A token of up
-// to 16384 elements is read from HBM once and kept in registers between the max pass and the
-// rounding pass; longer tokens are read twice (the second read hits L2).  Traffic: 2 bytes
-// in, 1 byte out per element.
+// to 32768 elements is read from HBM once and kept in registers between the max pass and the
+// rounding pass (from 16392 elements on, on blocks of 512 or 1024 threads); longer tokens are
+// read twice (the second read hits L2).  Traffic: 2 bytes in, 1 byte out per element.
 #include <algorithm>
 
 #include <hip/hip_fp16.h>
@@ -191,10 +191,13 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_act_long_kernel(
     }
 }
 
-// Register-resident tokens (K <= ITERS x 2048), R consecutive tokens per block.  Thread t owns
-// the 16-byte pieces t, t + 256, ... of every token of its block, i.e. fixed columns: their
+// Register-resident tokens (K <= ITERS x NT x 8), R consecutive tokens per block.  Thread t owns
+// the 16-byte pieces t, t + NT, ... of every token of its block, i.e. fixed columns: their
 // smooth scales and refined reciprocals are loaded and computed once.
-template <bool SMOOTH, int ITERS, int NT>
+// KEEP = false (tokens of 16392..32768 elements, on 512 or 1024 threads): what would not fit in
+// registers is not kept -- with smooth scales the reciprocals (the scales are re-read for
+// every token and divided by with the IEEE division), without them the widened values.
+template <bool SMOOTH, int ITERS, int NT, bool KEEP = true>
 __global__ __launch_bounds__(NT) void quantize_act_rows_kernel(
     int M, int K, int R, const __half *__restrict__ X, const float *__restrict__ smooth,
     int8_t *__restrict__ Q, float *__restrict__ sx)
@@ -215,9 +218,9 @@ __global__ __launch_bounds__(NT) void quantize_act_rows_kernel(
         for (int it = 0; it < ITERS; ++it) raw[it] = xrow[piece[it]];
     }
 
-    Recip rc[SMOOTH ? ITERS : 1][8];
+    Recip rc[SMOOTH && KEEP ? ITERS : 1][8];
     bool safe = true;  // every smooth scale of this thread allows the short division
-    if (SMOOTH) {
+    if (SMOOTH && KEEP) {
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
             const float4 a = *reinterpret_cast<const float4 *>(smooth + 8 * (size_t)piece[it]);
@@ -233,19 +236,58 @@ __global__ __launch_bounds__(NT) void quantize_act_rows_kernel(
 
     for (int m = m_begin; m < m_end; ++m) {
         uint2 *qrow = reinterpret_cast<uint2 *>(Q + (size_t)m * K);
+        if (!SMOOTH && !KEEP) {
+            // Long tokens without smooth scales: only the FP16 token itself stays in registers
+            // between the two passes (4 registers per piece instead of 12) and widening is
+            // repeated, so that several blocks still share a CU (34 instead of 41 us for
+            // 2048 x 28672; shorter tokens are 5 % faster with the widened values kept).
+            if (m > m_begin) {
+                const u32x4 *xrow = reinterpret_cast<const u32x4 *>(X + (size_t)m * K);
+#pragma unroll
+                for (int it = 0; it < ITERS; ++it) raw[it] = xrow[piece[it]];
+            }
+            float amax = 0.0f;
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) {
+                float f[8];
+                widen8(raw[it], f);
+                if (it * NT + tid < n8) amax = max_abs8(f, amax);
+            }
+            amax = block_max<NT / 64>(amax, s_part[(m - m_begin) & 1]);
+            const float s = amax > 0.0f ? amax / 127.0f : 1.0f;
+            if (tid == 0) sx[m] = s;
+            const float rcp_s = __builtin_amdgcn_rcpf(s);
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) {
+                // (opaque to the compiler, so that it widens again instead of keeping the first pass's values)
+                asm volatile("" : "+v"(raw[it]));
+                float f[8];
+                widen8(raw[it], f);
+                const int i = it * NT + tid;
+                if (i < n8) qrow[i] = round8(f, s, rcp_s);
+            }
+            continue;
+        }
         float f[ITERS][8];
         float amax = 0.0f;
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
             widen8(raw[it], f[it]);
-            if (SMOOTH) {
+            if (!SMOOTH) {
+            } else if (KEEP) {
                 if (safe) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) f[it][e] = div_by(f[it][e], rc[it][e]);
+                    for (int e = 0; e < 8; ++e) f[it][e] = div_by(f[it][e], rc[KEEP ? it : 0][e]);
                 } else {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) f[it][e] = f[it][e] / rc[it][e].s;
+                    for (int e = 0; e < 8; ++e) f[it][e] = f[it][e] / rc[KEEP ? it : 0][e].s;
                 }
+            } else {
+                const float4 a = *reinterpret_cast<const float4 *>(smooth + 8 * (size_t)piece[it]);
+                const float4 b = *reinterpret_cast<const float4 *>(smooth + 8 * (size_t)piece[it] + 4);
+                const float sm[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) f[it][e] = f[it][e] / sm[e];
             }
             if (it * NT + tid < n8) amax = max_abs8(f[it], amax);
         }
@@ -285,11 +327,31 @@ static void launch_quantize(int M, int K, const __half *X, const float *smooth, 
         LQ_LAUNCH_Q(2);
     else if (pieces <= 4)
         LQ_LAUNCH_Q(4);
-    else if (pieces <= 6)
-        LQ_LAUNCH_Q(6);
-    else if (pieces <= 8)
-        LQ_LAUNCH_Q(8);
-    else
+    else if (pieces <= 8) {
+        // 8193..16384 columns.  With smooth scales the reciprocals triple the registers per
+        // piece: blocks of 512 threads keep twice the waves on a CU (64 instead of 72 us for
+        // 4096 x 16384, 32 instead of 38 for 2048 x 14336).
+        if constexpr (SMOOTH) {
+            if (pieces <= 6)
+                hipLaunchKernelGGL((quantize_act_rows_kernel<SMOOTH, 3, 512>), grid, dim3(512), 0, st, M, K, R, X,
+                                   smooth, Q, sx);
+            else
+                hipLaunchKernelGGL((quantize_act_rows_kernel<SMOOTH, 4, 512>), grid, dim3(512), 0, st, M, K, R, X,
+                                   smooth, Q, sx);
+        } else {
+            if (pieces <= 6)
+                LQ_LAUNCH_Q(6);
+            else
+                LQ_LAUNCH_Q(8);
+        }
+    } else if (pieces <= 16) {  // up to 32768 columns: still register-resident, on larger blocks
+        if constexpr (SMOOTH)
+            hipLaunchKernelGGL((quantize_act_rows_kernel<SMOOTH, 4, 1024, false>), dim3((unsigned)M), dim3(1024), 0, st,
+                               M, K, 1, X, smooth, Q, sx);
+        else
+            hipLaunchKernelGGL((quantize_act_rows_kernel<false, 8, 512, false>), dim3((unsigned)M), dim3(512), 0, st, M,
+                               K, 1, X, smooth, Q, sx);
+    } else
         hipLaunchKernelGGL((quantize_act_long_kernel<SMOOTH>), dim3((unsigned)M), block, 0, st, K, X, smooth, Q, sx);
 #undef LQ_LAUNCH_Q
 }

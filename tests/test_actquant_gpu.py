@@ -33,7 +33,8 @@ def _run(X16, smooth):
 
 SHAPES = [
     (1, 8), (1, 256), (7, 4096), (33, 11008), (16, 8192), (3, 16384),  # register-resident tokens
-    (2, 16392), (5, 28672), (2, 131072),                              # two-pass tokens, ragged tail
+    (2, 16392), (5, 28672), (3, 32768),                               # register-resident on 1024 threads, ragged tail
+    (2, 32776), (2, 131072),                                          # two-pass tokens
     (300, 512),                                                       # many short tokens
 ]
 
@@ -50,7 +51,7 @@ def test_quantize_activations_bit_exact(M, K, with_smooth):
     assert np.array_equal(q, q_ref), f"{np.count_nonzero(q != q_ref)} codes differ"
 
 
-@pytest.mark.parametrize("M,K", [(1027, 2048), (2051, 4096), (4096, 512)])
+@pytest.mark.parametrize("M,K", [(1027, 2048), (2051, 4096), (4096, 512), (1027, 12288), (600, 16384)])
 def test_several_tokens_per_block(M, K):
     """From 1024 tokens on a block quantises 2 or 4 consecutive tokens (ragged last block) and
     shares the reciprocals of the smooth scales between them."""
