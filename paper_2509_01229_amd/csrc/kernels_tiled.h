@@ -218,8 +218,11 @@ __device__ __forceinline__ void duo_tile(
     const int8_t *xs = lds_g + j * kTilePitch + 16 * kb;
 
     u32x4 xr[XP];
-    u32x4 wr[2][2][2];  // [stage parity][tile][chunk]
-    UnitParams<G128> pr[2][2];
+    // W register stages: two, or three where the accumulators leave room (two row fragments):
+    // the loads of a stage are then in flight for two stages instead of one
+    constexpr int WS = MF <= 2 ? 3 : 2;
+    u32x4 wr[WS][2][2];  // [stage mod WS][tile][chunk]
+    UnitParams<G128> pr[WS][2];
     v4i bf[2][2];       // [ping-pong][tile]
     v4i af[2][MF];      // [ping-pong][m fragment]
 
@@ -295,7 +298,7 @@ __device__ __forceinline__ void duo_tile(
             for (int t = 0; t < 2; ++t) acc[mf][t] = mfma_i8(a[mf], b[t], acc[mf][t]);
     };
 
-    // One stage: w_cur = W(s) on entry and W(s+2) on exit, w_nxt = W(s+1); af[0], bf[0] hold
+    // One stage: w_cur = W(s) on entry and W(s+WS) on exit, w_nxt = W(s+1); af[0], bf[0] hold
     // k-step (0,0) of this stage on entry and of the next stage on exit; xr holds X(s+1).
     auto stage = [&](int s, u32x4 (&w_cur)[2][2], UnitParams<G128> (&p_cur)[2], u32x4 (&w_nxt)[2][2],
                      UnitParams<G128> (&p_nxt)[2], int buf) {
@@ -320,7 +323,7 @@ __device__ __forceinline__ void duo_tile(
         lds_barrier();
         read_a(buf ^ 1, 0, 0, af[0]);
         build_b(w_nxt, p_nxt, 0, 0, bf[0]);
-        load_w(s + 2, w_cur, p_cur);
+        load_w(s + WS, w_cur, p_cur);
         mma(af[1], bf[1]);
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -333,6 +336,7 @@ __device__ __forceinline__ void duo_tile(
     __builtin_amdgcn_sched_barrier(0);
     load_w(0, wr[0], pr[0]);
     load_w(1, wr[1], pr[1]);
+    if (WS == 3) load_w(2, wr[WS - 1], pr[WS - 1]);
     __builtin_amdgcn_sched_barrier(0);
     build_b(wr[0], pr[0], 0, 0, bf[0]);
     lds_barrier();
@@ -340,9 +344,32 @@ __device__ __forceinline__ void duo_tile(
     __builtin_amdgcn_sched_barrier(0);
 
     LQ_DSTAMP(1);
-    for (int s = 0; s < stages; s += 2) {
-        stage(s, wr[0], pr[0], wr[1], pr[1], 0);
-        stage(s + 1, wr[1], pr[1], wr[0], pr[0], 1);
+    if (WS == 2) {
+        for (int s = 0; s < stages; s += 2) {
+            stage(s, wr[0], pr[0], wr[1], pr[1], 0);
+            stage(s + 1, wr[1], pr[1], wr[0], pr[0], 1);
+        }
+    } else {
+        // three W stages against two X stages: the pattern repeats every six stages.  The
+        // loop has one exit (with more the register allocator spills); the two or four
+        // stages that may remain (the number of stages is even) follow it.
+        int s = 0;
+        for (; s + 6 <= stages; s += 6) {
+            stage(s, wr[0], pr[0], wr[1], pr[1], 0);
+            stage(s + 1, wr[1], pr[1], wr[WS - 1], pr[WS - 1], 1);
+            stage(s + 2, wr[WS - 1], pr[WS - 1], wr[0], pr[0], 0);
+            stage(s + 3, wr[0], pr[0], wr[1], pr[1], 1);
+            stage(s + 4, wr[1], pr[1], wr[WS - 1], pr[WS - 1], 0);
+            stage(s + 5, wr[WS - 1], pr[WS - 1], wr[0], pr[0], 1);
+        }
+        if (s < stages) {
+            stage(s, wr[0], pr[0], wr[1], pr[1], 0);
+            stage(s + 1, wr[1], pr[1], wr[WS - 1], pr[WS - 1], 1);
+            if (s + 2 < stages) {
+                stage(s + 2, wr[WS - 1], pr[WS - 1], wr[0], pr[0], 0);
+                stage(s + 3, wr[0], pr[0], wr[1], pr[1], 1);
+            }
+        }
     }
     LQ_DSTAMP(2);
 
