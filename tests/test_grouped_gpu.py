@@ -63,6 +63,7 @@ CASES = [
     (4, 16384, 256, 64, [20, 64, 33, 50]),
     (8, 16384, 256, 128, [17, 32, 25, 30, 64, 40, 50, 60]),
     (16, 16384, 256, 64, [18, 33] * 8),
+    (6, 16384, 512, 128, [70, 96, 65, 80, 128, 90]),   # one k group per block, tiles of three row fragments
 ]
 
 
