@@ -529,6 +529,11 @@ static int select_variant(int M, int N, int K)
         // block and all of a wave's loads (512 k) in flight at once
         if (K % 512 == 0 && K <= 8192 && N / 32 <= 256)
             return find_variant(M > 8 && K >= 4096 ? "stream16_f1_w16_s1" : "stream16_f1_w8_u4");
+        // 129..256 tiles and long K (no room for K slices across blocks): up to 8 rows, sixteen
+        // waves per block split K (21.5 instead of 26 us on 8192 x 28672, 12.4 / 17.8 on
+        // 6144 x 16384); above, two tiles per block and two K slices (23.3 / 25.9, 14.8 / 15.7)
+        if (N / 32 > 128 && N / 32 <= 256 && M <= 8 && K >= 12288) return find_variant("stream16_f1_w16_s1");
+        if (N / 32 > 128 && N / 32 <= 256 && M > 8 && K >= 16384) return find_variant("stream16_f2_w8");
         // other matrices of up to 256 tiles: still one tile per block, and K slices across blocks
         if (N / 32 <= 256) return find_variant("stream16_f1_w8");
         return find_variant(N / 64 >= 384 ? "stream16_f2_w4" : "stream16_f2_w8");
