@@ -525,18 +525,30 @@ static int find_variant(const char *name)
 static int select_variant(int M, int N, int K)
 {
     if (M <= 16) {
-        // small weight matrices are bound by launch and first-load latency: one tile per
-        // block and all of a wave's loads (512 k) in flight at once
-        if (K % 512 == 0 && K <= 8192 && N / 32 <= 256)
-            return find_variant(M > 8 && K >= 4096 ? "stream16_f1_w16_s1" : "stream16_f1_w8_u4");
-        // 129..256 tiles and long K (no room for K slices across blocks): up to 8 rows, sixteen
-        // waves per block split K (21.5 instead of 26 us on 8192 x 28672, 12.4 / 17.8 on
-        // 6144 x 16384); above, two tiles per block and two K slices (23.3 / 25.9, 14.8 / 15.7)
-        if (N / 32 > 128 && N / 32 <= 256 && M <= 8 && K >= 12288) return find_variant("stream16_f1_w16_s1");
-        if (N / 32 > 128 && N / 32 <= 256 && M > 8 && K >= 16384) return find_variant("stream16_f2_w8");
-        // other matrices of up to 256 tiles: still one tile per block, and K slices across blocks
-        if (N / 32 <= 256) return find_variant("stream16_f1_w8");
-        return find_variant(N / 64 >= 384 ? "stream16_f2_w4" : "stream16_f2_w8");
+        // Measured over 36 weight shapes (N, K from 2048 to 28672) at 1, 8 and 16 rows.
+        const int tiles = N / 32;
+        if (tiles <= 256) {
+            // one tile per block.  Short K is bound by launch and first-load latency: sixteen
+            // waves per block take one or two units of 128 k each ...
+            if (K <= 4096) return find_variant("stream16_f1_w16_s1");
+            if (K <= 8192 && K % 512 == 0) {
+                // ... up to 8192, all of a wave's loads (512 k) in flight at once; from 9 rows
+                // K slices across blocks while N leaves room for them, else sixteen waves again
+                if (M <= 8) return find_variant("stream16_f1_w8_u4");
+                return find_variant(tiles <= 128 ? "stream16_f1_w8" : "stream16_f1_w16_s1");
+            }
+            // 129..256 tiles and long K (no room for K slices across blocks): up to 8 rows, sixteen
+            // waves per block split K (21.5 instead of 26 us on 8192 x 28672, 12.4 / 17.8 on
+            // 6144 x 16384); above, two tiles per block and two K slices (23.3 / 25.9, 14.8 / 15.7)
+            if (tiles > 128 && M <= 8 && K >= 12288) return find_variant("stream16_f1_w16_s1");
+            if (tiles > 128 && M > 8 && K >= 16384) return find_variant("stream16_f2_w8");
+            // otherwise 2 or 4 K slices across blocks
+            return find_variant("stream16_f1_w8");
+        }
+        // up to 512 tiles with short K: sixteen waves again (8.1 instead of 9.1 us on 16384 x 4096)
+        if (tiles <= 512 && K <= 4096) return find_variant(M <= 8 ? "stream16_f1_w16_s1" : "stream16_f2_w16_s1");
+        if (N / 64 >= 384) return find_variant(K <= 2048 ? "stream16_f2_w8" : "stream16_f2_w4");
+        return find_variant("stream16_f2_w8");
     }
     if (M <= 32) return find_variant("stream_m32");
     // up to 64 rows the weights are still best streamed once per block column (X through LDS)

@@ -31,14 +31,17 @@ def test_dispatcher_families_on_the_workloads():
 
 
 def test_dispatcher_boundaries():
-    assert _pick(8, 4096, 4096) == "stream16_f1_w8_u4"         # small matrix: deep prefetch, one tile per block
-    assert _pick(16, 4096, 4096) == "stream16_f1_w16_s1"       # ... 9..16 rows: sixteen waves share K
-    assert _pick(16, 4096, 2048) == "stream16_f1_w8_u4"
-    assert _pick(16, 4096, 11008) == "stream16_f1_w8"          # K not a multiple of 512: K slices across blocks
+    assert _pick(8, 4096, 4096) == "stream16_f1_w16_s1"        # short K: sixteen waves per block, one tile
+    assert _pick(16, 4096, 4096) == "stream16_f1_w16_s1" and _pick(16, 4096, 2048) == "stream16_f1_w16_s1"
+    assert _pick(8, 8192, 8192) == "stream16_f1_w8_u4"         # K to 8192: deep prefetch, whole K in the block
+    assert _pick(16, 8192, 8192) == "stream16_f1_w16_s1" and _pick(16, 4096, 8192) == "stream16_f1_w8"
+    assert _pick(16, 4096, 11008) == "stream16_f1_w8"          # longer K: K slices across blocks
     assert _pick(16, 8192, 28672, 128) == "stream16_f2_w8"     # 129..256 tiles, long K: two tiles per block
     assert _pick(4, 8192, 28672, 128) == "stream16_f1_w16_s1"  # ... up to 8 rows: sixteen waves split K
     assert _pick(4, 4096, 16384) == "stream16_f1_w8" and _pick(16, 8192, 14336) == "stream16_f1_w8"
-    assert _pick(16, 11008, 4096) == "stream16_f2_w8"          # more than 256 tiles: two per block
+    assert _pick(16, 11008, 4096) == "stream16_f2_w16_s1"      # more than 256 tiles: two per block
+    assert _pick(4, 16384, 4096) == "stream16_f1_w16_s1" and _pick(16, 16384, 8192) == "stream16_f2_w8"
+    assert _pick(16, 28672, 2048) == "stream16_f2_w8"
     assert _pick(16, 28672, 8192, 128) == "stream16_f2_w4"     # N alone fills the chip
     assert _pick(17, 4096, 4096) == "stream_m32" and _pick(32, 28672, 8192) == "stream_m32"
     assert _pick(33, 4096, 4096) == "stream_m64" and _pick(64, 16384, 4096) == "stream_m64"
