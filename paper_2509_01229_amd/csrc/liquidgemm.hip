@@ -201,13 +201,16 @@ static int launch_stream_shaped(const Args &a)
 }
 
 // X through LDS (XL) pays whenever a wave holds two row fragments; with one it is worth
-// 4-9 % once most of the 32 rows exist and N is small enough for one tile per block, and
-// costs a few per cent otherwise (measured at 24 and 32 rows on thirteen weight shapes).
+// 4-9 % once most of the 32 rows exist and N is small enough for one tile per block (or, with
+// two tiles per block, K is long: 21.5 against 22.8 us at 32 rows on 12288 x 12288), and
+// costs a few per cent otherwise (measured at 20..32 rows on 36 weight shapes).
 template <int MF>
 static int launch_stream_auto(const Args &a)
 {
     if (MF == 2) return launch_stream_shaped<2, true>(a);
-    return a.M > 24 && a.N / 32 <= 256 ? launch_stream_shaped<1, true>(a) : launch_stream_shaped<1, false>(a);
+    const int tiles = a.N / 32;
+    const bool xl = a.M > 24 && (tiles <= 256 || (tiles <= 512 && a.K >= 12288));
+    return xl ? launch_stream_shaped<1, true>(a) : launch_stream_shaped<1, false>(a);
 }
 
 template <int F, int NW, int SPLIT, int ABL = 0, int UU = 1>
@@ -553,7 +556,10 @@ static int select_variant(int M, int N, int K)
     if (M <= 32) return find_variant("stream_m32");
     // up to 64 rows the weights are still best streamed once per block column (X through LDS)
     // unless N alone fills the chip with 128 x 256 tiles
-    if (M <= 64 && N / 32 <= 512) return find_variant("stream_m64");
+    // (except 129..256 tiles with very long K from 48 rows on: no room for K slices across blocks,
+    // and the tiles' split-K grid is 8-16 % ahead, 32.8 against 38.1 us at 64 rows on 6144 x 28672)
+    if (M <= 64 && N / 32 <= 512 && !(M >= 48 && N / 32 > 128 && N / 32 <= 256 && K >= 24576))
+        return find_variant("stream_m64");
     // clearly more 128 x 256 tiles than CUs: the deeper memory pipeline of the direct-to-LDS
     // form pays (3 to 6 % measured from 320 tiles up); with one tile per CU or fewer, the two k
     // groups per block of the other form do

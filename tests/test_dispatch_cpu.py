@@ -48,6 +48,9 @@ def test_dispatcher_boundaries():
     # 33..64 rows: streamed (X through LDS) up to 512 tiles of 32 channels, whatever K
     assert _pick(64, 8192, 8192) == "stream_m64" and _pick(48, 8192, 8192) == "stream_m64"
     assert _pick(40, 8192, 28672, 128) == "stream_m64" and _pick(64, 4096, 11008) == "stream_m64"
+    # ... except 129..256 tiles with very long K from 48 rows on: the tiles' split-K grid
+    assert _pick(64, 8192, 28672, 128) in ("duo_m64", "duo_m128") and _pick(48, 6144, 28672, 128) in ("duo_m64", "duo_m128")
+    assert _pick(64, 4096, 28672, 128) == "stream_m64" and _pick(64, 8192, 16384, 128) == "stream_m64"
     assert _pick(64, 28672, 8192) == "duo_m64" and _pick(65, 4096, 4096) == "duo_m64"
     assert _pick(256, 28672, 8192) == "duo_m128"
     assert _pick(512, 4096, 4096) == "duo_m64" and _pick(1025, 4096, 4096) == "duo_m128"
