@@ -157,14 +157,16 @@ __device__ __forceinline__ void lds_barrier()
 // the MFMAs, X staging and fragment reads.  The tile grid is that of 128-row tiles either way.
 // With one k group a tile of 65..96 rows takes 3 fragments (8 experts of 58..71 tokens on
 // 14336 x 4096: 65 instead of 72 us).
-template <bool G128, int KG, int MF, int TM = 128>
+template <bool G128, int KG, int MF, int TM = 128, int MFC = MF>
 __device__ __forceinline__ void duo_tile(
     const Place pl, const int bm, const int bn, int M, int N, int K, const int8_t *__restrict__ X,
     const float *__restrict__ sx, const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp,
     const float *__restrict__ sw, __half *__restrict__ Y, int32_t *__restrict__ ACC,
     int32_t *__restrict__ partials)
 {
-    constexpr int WM = TM, XP = MF;  // TM = rows between consecutive row tiles (128, or 64 with MF = 2)
+    // MFC = fragments the K loop computes: MF, or 3 of 4 for a tile of 65..96 rows where two k
+    // groups must share out an even number (the fourth stays zero through the exchange)
+    constexpr int WM = TM, XP = MFC;  // TM = rows between consecutive row tiles (128, or 64 with MF = 2)
     static_assert(32 * MF <= TM, "a tile cannot hold more row fragments than its height");
     constexpr int STAGE = 128 * kTilePitch;
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
@@ -195,7 +197,7 @@ __device__ __forceinline__ void duo_tile(
     LQ_DSTAMP(0);
     v16i acc[MF][2];
 #pragma unroll
-    for (int mf = 0; mf < MF; ++mf)
+    for (int mf = 0; mf < MFC; ++mf)
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -226,7 +228,7 @@ __device__ __forceinline__ void duo_tile(
     u32x4 wr[WS][2][2];  // [stage mod WS][tile][chunk]
     UnitParams<G128> pr[WS][2];
     v4i bf[2][2];       // [ping-pong][tile]
-    v4i af[2][MF];      // [ping-pong][m fragment]
+    v4i af[2][MFC];     // [ping-pong][m fragment]
 
     auto load_x = [&](int s) {
         if (KG > 1 && s >= my_stages) {  // past this group's slice: contributes nothing
@@ -285,17 +287,17 @@ __device__ __forceinline__ void duo_tile(
 #endif
         }
     };
-    auto read_a = [&](int buf, int c, int h, v4i (&a)[MF]) {
+    auto read_a = [&](int buf, int c, int h, v4i (&a)[MFC]) {
 #if defined(LQ_ABLATE) && (LQ_DUO_ABL & 2)  // experiments only: no X fragment reads from LDS
         if (buf + c + h == -1)
 #endif
 #pragma unroll
-        for (int mf = 0; mf < MF; ++mf)
+        for (int mf = 0; mf < MFC; ++mf)
             a[mf] = *reinterpret_cast<const v4i *>(xs + buf * STAGE + mf * 32 * kTilePitch + 64 * c + 32 * h);
     };
-    auto mma = [&](const v4i (&a)[MF], const v4i (&b)[2]) {
+    auto mma = [&](const v4i (&a)[MFC], const v4i (&b)[2]) {
 #pragma unroll
-        for (int mf = 0; mf < MF; ++mf)
+        for (int mf = 0; mf < MFC; ++mf)
 #pragma unroll
             for (int t = 0; t < 2; ++t) acc[mf][t] = mfma_i8(a[mf], b[t], acc[mf][t]);
     };
@@ -374,6 +376,13 @@ __device__ __forceinline__ void duo_tile(
         }
     }
     LQ_DSTAMP(2);
+    // fragments that the loop did not compute come into being only here (no registers before)
+#pragma unroll
+    for (int mf = MFC; mf < MF; ++mf)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mf][t][r] = 0;
 
     // What is left is written once per k group with compile-time fragment indices: group G
     // finishes the MFK = MF / KG row fragments starting at MF0 = G * MFK.
@@ -489,19 +498,23 @@ __device__ __forceinline__ void duo_tile(
         finish(std::integral_constant<int, KG - 1>{});
 }
 
-template <bool G128, int KG, int TM = 128>
+// ALL3 = every row tile of the launch has 65..96 rows (M itself has): the kernel holds that
+// path only.  (Inside the general two-k-group kernel it would be a third copy of the tile code,
+// and the register allocation of the four-fragment copy, which has none to spare, then spills.)
+template <bool G128, int KG, int TM = 128, bool ALL3 = false>
 __device__ __forceinline__ void duo_block(
     const Place pl, const int bm, const int bn, int M, int N, int K, const int8_t *__restrict__ X,
     const float *__restrict__ sx, const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp,
     const float *__restrict__ sw, __half *__restrict__ Y, int32_t *__restrict__ ACC,
     int32_t *__restrict__ partials)
 {
-    if (TM == 64)
+    if (ALL3)
+        duo_tile<G128, KG, 4, 128, 3>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+    else if (TM == 64)
         duo_tile<G128, KG, 2, 64>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
     else if (M - 128 * bm <= 64)  // block-uniform
         duo_tile<G128, KG, 2>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
     else {
-        // (one k group only: two groups share out the fragments evenly)
         if constexpr (KG == 1) {
             if (M - 128 * bm <= 96) {
                 duo_tile<G128, KG, 3>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
@@ -512,7 +525,7 @@ __device__ __forceinline__ void duo_block(
     }
 }
 
-template <bool G128, int KG, int TM = 128>
+template <bool G128, int KG, int TM = 128, bool ALL3 = false>
 __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
     int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
@@ -521,7 +534,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
 {
     int bm, bn;
     block_coords(blocks_m, blocks_n, bm, bn);
-    duo_block<G128, KG, TM>(grid_place(tickets), bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+    duo_block<G128, KG, TM, ALL3>(grid_place(tickets), bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
 }
 
 // The same barrier for code that waits for its loads itself: a fence would also wait for

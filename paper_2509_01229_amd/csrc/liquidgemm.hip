@@ -313,6 +313,22 @@ static int launch_duo_as(const Args &a, int S)
     const dim3 grid((unsigned)(blocks_n * blocks_m), (unsigned)S), block(256 * KG);
     unsigned int *tickets = static_cast<unsigned int *>(a.ws);
     int32_t *partials = a.ws ? reinterpret_cast<int32_t *>(static_cast<char *>(a.ws) + kTicketBytes) : nullptr;
+    if constexpr (KG == 2 && TM == 128) {
+      // one row tile of 65..96 rows: the kernel that computes three of its four row fragments
+      if (a.M > 64 && a.M <= 96) {
+        constexpr int KG3 = 2;
+        if (a.group == 128) {
+            if (int rc = allow_lds(w4a8_duo_kernel<true, KG3, 128, true>, lds_bytes)) return rc;
+            hipLaunchKernelGGL((w4a8_duo_kernel<true, KG3, 128, true>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
+                               a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n, partials, tickets);
+        } else {
+            if (int rc = allow_lds(w4a8_duo_kernel<false, KG3, 128, true>, lds_bytes)) return rc;
+            hipLaunchKernelGGL((w4a8_duo_kernel<false, KG3, 128, true>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
+                               a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n, partials, tickets);
+        }
+        return LQ_OK;
+      }
+    }
     if (a.group == 128) {
         if (int rc = allow_lds(w4a8_duo_kernel<true, KG, TM>, lds_bytes)) return rc;
         hipLaunchKernelGGL((w4a8_duo_kernel<true, KG, TM>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K, a.X,
