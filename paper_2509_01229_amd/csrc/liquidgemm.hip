@@ -576,10 +576,10 @@ static int select_variant(int M, int N, int K)
     // and the tiles' split-K grid is 8-16 % ahead, 32.8 against 38.1 us at 64 rows on 6144 x 28672)
     if (M <= 64 && N / 32 <= 512 && !(M >= 48 && N / 32 > 128 && N / 32 <= 256 && K >= 24576))
         return find_variant("stream_m64");
-    // clearly more 128 x 256 tiles than CUs: the deeper memory pipeline of the direct-to-LDS
-    // form pays (3 to 6 % measured from 320 tiles up); with one tile per CU or fewer, the two k
-    // groups per block of the other form do
-    if (((M + 127) / 128) * ((N + 255) / 256) >= 320 && (long long)M * K < (1ll << 32))
+    // more 128 x 256 tiles than CUs (blocks of one k group): the deeper memory pipeline of the
+    // direct-to-LDS form pays (3 to 6 % measured from 320 tiles up, 1 to 5 % at 264..288); with
+    // one tile per CU or fewer, the two k groups per block of the other form do
+    if (((M + 127) / 128) * ((N + 255) / 256) > 256 && (long long)M * K < (1ll << 32))
         return find_variant("duo_dl_m128");
     // few tiles: a grid of 64-row tiles can fill the chip with half the split-K exchange
     return find_variant(prefer_64_row_tiles(M, N, K) ? "duo_m64" : "duo_m128");
