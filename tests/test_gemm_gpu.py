@@ -293,6 +293,47 @@ def test_random_large_grids_through_the_dispatcher():
     assert "duo_dl_m128" in seen and seen & {"duo_m128", "duo_m64"}
 
 
+def test_random_small_batches_through_the_dispatcher():
+    """Seeded shapes with 1..64 rows over weight matrices of every aspect (the stream kernels as
+    the dispatcher launches them: 16-, 32- and 64-row forms, one or two tiles per block, 4 to 16
+    waves, K slices across blocks, X fragments direct or through LDS), with and without a
+    workspace; accumulators against the exact float64 product on the oracle's dequantised
+    weights, FP16 output against the epilogue definition."""
+    import torch
+
+    rng = np.random.default_rng(23)
+    seen = set()
+    for case in range(16):
+        aspect = case // 4                      # generic / wide and short / narrow and long / wide
+        if aspect == 0:
+            N, K = 64 * int(rng.integers(1, 129)), 256 * int(rng.integers(1, 33))
+        elif aspect == 1:
+            N, K = 64 * int(rng.integers(100, 201)), 256 * int(rng.integers(1, 5))
+        elif aspect == 2:
+            N, K = 64 * int(rng.integers(4, 41)), 256 * int(rng.integers(48, 81))
+        else:
+            N, K = 64 * int(rng.integers(128, 257)), 256 * int(rng.integers(8, 17))
+        g = (64, 128)[case % 2]
+        lo, hi = ((1, 9), (9, 17), (17, 33), (33, 65))[case % 4]
+        M = int(rng.integers(lo, hi))
+        picked = api.w4a8_variant_name(api.w4a8_select_variant(M, N, K, g))
+        seen.add(picked)
+        _say(f"small batch {case}: M={M} N={N} K={K} g={g} -> {picked}")
+        P = H.Problem(N, K, g, seed=700 + case)
+        X, s_x = WL.make_activations(M, K, outlier_frac=0.01, seed=1100 + case)
+        Wd, s_w = P.oracle_wd()
+        ref = X.astype(np.float64) @ Wd.astype(np.float64).T      # exact: |acc| < 2^31 << 2^53
+        dX, dsx = torch.from_numpy(X).cuda(), torch.from_numpy(s_x).cuda()
+        ws = None if case % 4 else torch.empty(16, dtype=torch.uint8, device="cuda")  # every fourth: no room to split
+        ACC = api.w4a8_gemm_i32(dX, P.d_packed, P.d_gparams, N, K, g, workspace=ws)
+        Y = api.w4a8_gemm(dX, dsx, P.d_packed, P.d_gparams, P.d_w_scales, N, K, g, workspace=ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(ACC.cpu().numpy().astype(np.float64), ref), f"case {case}: accumulators differ"
+        H.assert_fp16_close(Y.cpu().numpy(), O.scale_epilogue_f64(ref, s_x, s_w), f"case {case}")
+        del P, dX, ACC, Y
+    assert len(seen) >= 5, seen
+
+
 def test_maximum_k_and_accumulator_range():
     """K at the interface limit (131072) with inputs that drive the accumulators to the edge
     of INT32: |ACC| up to K * 127 * 121 = 2 014 183 424 < 2^31 must come out exactly."""
