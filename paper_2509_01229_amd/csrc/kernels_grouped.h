@@ -53,7 +53,8 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream_grouped_kernel(const Grou
                               nullptr);
 }
 
-template <bool G128, int KG>
+// TM = rows per row tile (128, or 64: twice the blocks for launches that would leave CUs idle)
+template <bool G128, int KG, int TM = 128>
 __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_grouped_kernel(const GroupTable g,
                                                                                      const GroupedPtrs p, int N,
                                                                                      int K)
@@ -63,10 +64,11 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_grouped_ke
     const int local = (int)blockIdx.x - (i ? g.block_end[i - 1] : 0);
     const int M = g.rows[i], e = g.expert[i], r0 = g.row_off[i];
     // row tiles of one column block are neighbours, so they meet on the expert's W columns
-    const int blocks_m = (M + 127) >> 7;
+    const int blocks_m = (M + TM - 1) / TM;
     const int bm = local % blocks_m, bn = local / blocks_m;
-    duo_block<G128, KG>(Place{0, 1, 0, 1, nullptr}, bm, bn, M, N, K, p.X + (size_t)r0 * K, p.sx + r0,
-                        p.Wp + e * p.w_stride, p.gp + e * p.gp_stride, p.sw + (size_t)e * N,
-                        p.Y ? p.Y + (size_t)r0 * N : nullptr, p.ACC ? p.ACC + (size_t)r0 * N : nullptr, nullptr);
+    duo_block<G128, KG, TM>(Place{0, 1, 0, 1, nullptr}, bm, bn, M, N, K, p.X + (size_t)r0 * K, p.sx + r0,
+                            p.Wp + e * p.w_stride, p.gp + e * p.gp_stride, p.sw + (size_t)e * N,
+                            p.Y ? p.Y + (size_t)r0 * N : nullptr, p.ACC ? p.ACC + (size_t)r0 * N : nullptr,
+                            nullptr);
 }
 

@@ -645,7 +645,7 @@ static int launch_checked(const char *what, Kernel kernel, dim3 grid, dim3 block
 static int grouped_run(const GroupedArgs &a)
 {
     GroupTable small{}, mid{}, big{};
-    long long big_blocks = 0;
+    long long big_blocks = 0, big_blocks64 = 0;
     const int blocks_n = (a.N + 255) / 256;
     for (int e = 0; e < a.E; ++e) {
         const int r0 = a.row_offsets[e], rows = a.row_offsets[e + 1] - r0;
@@ -655,6 +655,7 @@ static int grouped_run(const GroupedArgs &a)
         t.expert[i] = e, t.row_off[i] = r0, t.rows[i] = rows;
         if (&t == &big) {
             big_blocks += (long long)((rows + 127) / 128) * blocks_n;
+            big_blocks64 += (long long)((rows + 63) / 64) * blocks_n;
             if (big_blocks > 0x7fffffff) return fail(LQ_ERR_INVALID, "grouped GEMM too large for one launch");
             t.block_end[i] = (int)big_blocks;
         }
@@ -688,7 +689,22 @@ static int grouped_run(const GroupedArgs &a)
                                              lds, a.stream, mid, a.p, a.N, a.K, groups);
         if (rc) return rc;
     }
-    if (big.count) {
+    if (big.count && big_blocks64 <= 256 && big_blocks64 > big_blocks && a.K >= 512) {
+        // few blocks and experts of more than 64 rows: a grid of 64-row tiles has up to twice the
+        // blocks, still at most one per CU (8 experts of 72 rows on 4096 x 14336: 128 -> 256 blocks)
+        long long end = 0;
+        for (int i = 0; i < big.count; ++i) {
+            end += (long long)((big.rows[i] + 63) / 64) * blocks_n;
+            big.block_end[i] = (int)end;
+        }
+        const dim3 grid((unsigned)big_blocks64);
+        const size_t lds2 = std::max<size_t>(4 * (size_t)128 * kTilePitch, 64 * 1024);
+        const int rc = g128 ? launch_checked("grouped duo", w4a8_duo_grouped_kernel<true, 2, 64>, grid, dim3(512), lds2,
+                                             a.stream, big, a.p, a.N, a.K)
+                            : launch_checked("grouped duo", w4a8_duo_grouped_kernel<false, 2, 64>, grid, dim3(512), lds2,
+                                             a.stream, big, a.p, a.N, a.K);
+        if (rc) return rc;
+    } else if (big.count) {
         const dim3 grid((unsigned)big_blocks);
         // as for single GEMMs: two k groups per block while the grid gives at most one block per CU
         const bool kg2 = big_blocks <= 256 && a.K >= 512;
