@@ -72,3 +72,30 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_grouped_ke
                             nullptr);
 }
 
+// The direct-to-LDS form of the tiles for launches with more blocks than CUs (one k group per
+// block, two blocks per CU).
+template <bool G128>
+__global__ __launch_bounds__(256, 2) void w4a8_duo_dl_grouped_kernel(const GroupTable g, const GroupedPtrs p, int N,
+                                                                     int K)
+{
+    int i = 0;
+    while (i < g.count - 1 && (int)blockIdx.x >= g.block_end[i]) ++i;
+    const int local = (int)blockIdx.x - (i ? g.block_end[i - 1] : 0);
+    const int M = g.rows[i], e = g.expert[i], r0 = g.row_off[i];
+    const int blocks_m = (M + 127) >> 7;
+    const int bm = local % blocks_m, bn = local / blocks_m;
+    const Place pl{0, 1, 0, 1, nullptr};
+    const int8_t *X = p.X + (size_t)r0 * K;
+    const float *sx = p.sx + r0, *sw = p.sw + (size_t)e * N;
+    const u32x4 *Wp = p.Wp + e * p.w_stride;
+    const uint8_t *gp = p.gp + e * p.gp_stride;
+    __half *Y = p.Y ? p.Y + (size_t)r0 * N : nullptr;
+    int32_t *ACC = p.ACC ? p.ACC + (size_t)r0 * N : nullptr;
+    const int left = M - 128 * bm;  // block-uniform
+    if (left <= 64)
+        duo_dl_tile<G128, 2>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, nullptr);
+    else if (left <= 96)
+        duo_dl_tile<G128, 3>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, nullptr);
+    else
+        duo_dl_tile<G128, 4>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, nullptr);
+}

@@ -711,7 +711,23 @@ static int grouped_run(const GroupedArgs &a)
         const size_t lds1 = 2 * (size_t)128 * kTilePitch;
         const size_t lds2 = std::max<size_t>(2 * lds1, 64 * 1024);
         int rc;
-        if (kg2)
+        // more blocks than CUs: the direct-to-LDS form, as for single GEMMs (its X offsets have 32
+        // bits) -- unless the experts are so small that most tiles have two row fragments, which
+        // the other form runs with a deeper W pipeline (8 experts of 58..71 rows: 63 against 67 us;
+        // of 128 rows: 91 against 79; of about 1000: 531 against 513)
+        bool dl = !kg2 && a.K >= 512;
+        long long big_rows = 0;
+        for (int i = 0; i < big.count; ++i) {
+            dl = dl && (long long)big.rows[i] * a.K < (1ll << 32);
+            big_rows += big.rows[i];
+        }
+        dl = dl && big_rows > 96ll * big.count;
+        if (dl)
+            rc = g128 ? launch_checked("grouped duo", w4a8_duo_dl_grouped_kernel<true>, grid, dim3(256),
+                                       4 * (size_t)128 * 128, a.stream, big, a.p, a.N, a.K)
+                      : launch_checked("grouped duo", w4a8_duo_dl_grouped_kernel<false>, grid, dim3(256),
+                                       4 * (size_t)128 * 128, a.stream, big, a.p, a.N, a.K);
+        else if (kg2)
             rc = g128 ? launch_checked("grouped duo", w4a8_duo_grouped_kernel<true, 2>, grid, dim3(512), lds2, a.stream,
                                        big, a.p, a.N, a.K)
                       : launch_checked("grouped duo", w4a8_duo_grouped_kernel<false, 2>, grid, dim3(512), lds2, a.stream,

@@ -64,6 +64,9 @@ CASES = [
     (8, 16384, 256, 128, [17, 32, 25, 30, 64, 40, 50, 60]),
     (16, 16384, 256, 64, [18, 33] * 8),
     (6, 16384, 512, 128, [70, 96, 65, 80, 128, 90]),   # one k group per block, tiles of three row fragments
+    # more blocks than CUs and larger experts: the direct-to-LDS tiles (2, 3 and 4 row fragments; 6 and 10 stages)
+    (4, 16384, 768, 64, [200, 130, 75, 300]),
+    (3, 16384, 1280, 128, [129, 260, 100]),
 ]
 
 
