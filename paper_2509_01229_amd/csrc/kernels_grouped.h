@@ -47,6 +47,13 @@ __global__ __launch_bounds__(NW * 64) void w4a8_stream_grouped_kernel(const Grou
 {
     const int i = blockIdx.x / groups, gx = blockIdx.x % groups;
     const int e = g.expert[i], r0 = g.row_off[i];
+    if (g.rows[i] > 24) {  // block-uniform: X through LDS once most of the 32 rows exist (57 -> 51 us for 8 x 32 rows on 4096 x 14336)
+        stream_block<2, NW, 1, G128, true>(Place{gx, groups, 0, 1, nullptr}, g.rows[i], N, K, p.X + (size_t)r0 * K,
+                                           p.sx + r0, p.Wp + e * p.w_stride, p.gp + e * p.gp_stride,
+                                           p.sw + (size_t)e * N, p.Y ? p.Y + (size_t)r0 * N : nullptr,
+                                           p.ACC ? p.ACC + (size_t)r0 * N : nullptr, nullptr);
+        return;
+    }
     stream_block<2, NW, 1, G128>(Place{gx, groups, 0, 1, nullptr}, g.rows[i], N, K, p.X + (size_t)r0 * K, p.sx + r0,
                               p.Wp + e * p.w_stride, p.gp + e * p.gp_stride, p.sw + (size_t)e * N,
                               p.Y ? p.Y + (size_t)r0 * N : nullptr, p.ACC ? p.ACC + (size_t)r0 * N : nullptr,
