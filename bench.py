@@ -76,13 +76,14 @@ class DeviceProblem:
         self.d_packed = [hp.to(dev) for _ in range(self.copies)]
         self.d_gparams = [hg.to(dev) for _ in range(self.copies)]
         self.d_w_scales = torch.from_numpy(self.w_scales).to(dev)
-        self.X, self.sx, self.dX, self.dsx, self.dY = {}, {}, {}, {}, {}
+        # FP16 activations from the seeded generator; their INT8 form and per-token scales come
+        # from the library's own quantisation kernel (outside every timed region)
+        self.X16, self.dX, self.dsx, self.dY = {}, {}, {}, {}
         for M in Ms:
-            X, sx = WL.make_activations(M, K, shape.outlier_frac, seed=shape.seed + 1000 + M)
-            self.X[M], self.sx[M] = X, sx
-            self.dX[M] = torch.from_numpy(X).to(dev)
-            self.dsx[M] = torch.from_numpy(sx).to(dev)
+            self.X16[M] = WL.make_activations_f16(M, K, shape.outlier_frac, seed=shape.seed + 1000 + M)
+            self.dX[M], self.dsx[M] = api.w4a8_quantize_activations(torch.from_numpy(self.X16[M]).to(dev))
             self.dY[M] = torch.empty((M, N), dtype=torch.float16, device=dev)
+        torch.cuda.synchronize()
 
     def launch(self, M, i, api, stream, variant=-1, rotate=True):
         c = i % self.copies if rotate else 0
@@ -319,8 +320,7 @@ def grouped_moe_points(torch, api, WL, stream):
             rows = rng.multinomial(2 * B, [1.0 / E] * E)
             offs = np.concatenate([[0], np.cumsum(rows)]).astype(int)
             M = int(offs[-1])
-            X, sx = WL.make_activations(M, K, 0.0, seed=B)
-            dX, dsx = torch.from_numpy(X).to("cuda:0"), torch.from_numpy(sx).to("cuda:0")
+            dX, dsx = api.w4a8_quantize_activations(torch.from_numpy(WL.make_activations_f16(M, K, 0.0, seed=B)).to("cuda:0"))
             Y = torch.empty((M, N), dtype=torch.float16, device="cuda:0")
             Xe = [dX[offs[e]:offs[e + 1]] for e in range(E)]
             sxe = [dsx[offs[e]:offs[e + 1]].clone() for e in range(E)]  # own allocations: 16-byte aligned
@@ -352,7 +352,7 @@ def grouped_moe_points(torch, api, WL, stream):
     return rows_out
 
 
-def cpu_baseline(prob, M, budget_s=15.0):
+def cpu_baseline(prob, M, budget_s=12.0):
     """The C oracle (as it stands) on a bounded row sample of the same workload."""
     from oracle import c_oracle
     from oracle import lqq_oracle as O
@@ -362,23 +362,24 @@ def cpu_baseline(prob, M, budget_s=15.0):
     codes, s_u8, a = api.liquidquant_unpack_weights(prob.packed, prob.gparams, s.N, s.K, s.group)
     canon = O.pack_canonical(codes)
     del codes
-    X, sx = prob.X[M], prob.sx[M]
+    X, sx = O.quantize_activations(prob.X16[M][:min(M, 4096)])  # the oracle's own per-token quantisation
     t0 = time.perf_counter()
     c_oracle.w4a8_gemm(X[:1], sx[:1], canon, s_u8, a, prob.w_scales, s.group)
     t_one = time.perf_counter() - t0                       # dominated by the dequantisation
+    n3 = min(3, len(X))
     t0 = time.perf_counter()
-    c_oracle.w4a8_gemm(X[:3], sx[:3], canon, s_u8, a, prob.w_scales, s.group)
+    c_oracle.w4a8_gemm(X[:n3], sx[:n3], canon, s_u8, a, prob.w_scales, s.group)
     t_three = time.perf_counter() - t0
     per_row = max((t_three - t_one) / 2, 1e-6)
-    rows = int(max(1, min(M, (budget_s - t_one) / per_row)))
+    rows = int(max(1, min(len(X), (budget_s - t_one) / per_row)))
     t0 = time.perf_counter()
     c_oracle.w4a8_gemm(X[:rows], sx[:rows], canon, s_u8, a, prob.w_scales, s.group)
     dt = time.perf_counter() - t0
     return {
         "value": round(algorithmic_ops(rows, s.N, s.K) / dt / 1e12, 6), "unit": "TOPS",
         "cores": c_oracle.threads(), "kind": "oracle",
-        "sample": f"rows 0..{rows} of X (of M={M}), all N={s.N} K={s.K}; one full dequantisation "
-                  f"included; {dt:.1f} s",
+        "sample": f"rows 0..{rows} of X (of M={M}), all N={s.N} K={s.K} group={s.group}; one full "
+                  f"dequantisation included; {dt:.1f} s",
     }
 
 
@@ -488,6 +489,10 @@ def main():
                     out["curve_N4096_K4096"] = [
                         point(shapes[0], M, time_median(p2, M, torch, api, stream, batches=3), api, calib)
                         for M in extra_Ms]
+            # the oracle beside every family of configs: a bounded row sample of its largest batch
+            fam_cpu = None
+            if not args.no_cpu and p2 is not prob:
+                fam_cpu = cpu_baseline(p2, max(s.M for s in shapes if s.M in p2.dX), budget_s=2.5)
             for s in shapes:
                 if s.M not in p2.dX:
                     continue
@@ -495,6 +500,8 @@ def main():
                 warm = time_median(p2, s.M, torch, api, stream, rotate=False, est_ms=cold)
                 r = point(s, s.M, cold, api, calib, ms_same=warm)
                 r["workload"] = s.name
+                if fam_cpu:
+                    r["cpu_oracle"] = fam_cpu
                 rows.append(r)
             if p2 is not prob:
                 del p2
@@ -524,6 +531,17 @@ def main():
             out["ablation_pipeline"] = {"workload": head.name, "implicit_us": round(t_im * 1e3, 2),
                                         "explicit_lds_round_trip_us": round(t_ex * 1e3, 2),
                                         "explicit_over_implicit": round(t_ex / t_im, 3)}
+        # Fig. 13's other half: the same tiled kernel (two waves per SIMD, X through LDS by
+        # registers) with LiquidQuant's 7-instruction dequantisation and with the widened
+        # overflow-safe form it replaces
+        if "widened_dq_m128" in names and "duo_m128_s1" in names:
+            t_lq = statistics.median(time_steps(prob, head.M, 30, 5, torch, api, stream, names.index("duo_m128_s1"))
+                                     for _ in range(3))
+            t_wd = statistics.median(time_steps(prob, head.M, 30, 5, torch, api, stream, names.index("widened_dq_m128"))
+                                     for _ in range(3))
+            out["ablation_dequant"] = {"workload": head.name, "kernel": "duo_m128_s1",
+                                       "liquidquant_us": round(t_lq * 1e3, 2), "widened_us": round(t_wd * 1e3, 2),
+                                       "widened_over_liquidquant": round(t_wd / t_lq, 3)}
         del prob.d_packed[1:], prob.d_gparams[1:]
         torch.cuda.empty_cache()
         out["reference_w8a8_vendor"] = vendor_w8a8_reference(torch, stream)
@@ -531,6 +549,8 @@ def main():
 
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(prob, head.M)
+        for r in out.get("configs", []):
+            r.setdefault("cpu_oracle", out["cpu_baseline"])  # rows of the headline's own family
 
     print(json.dumps(out), flush=True)
 

@@ -23,6 +23,11 @@
  *     stream) and return without synchronising.
  *   - Shapes: N % 64 == 0, K % 256 == 0, group in {64, 128}, 0 <= M, K <= 131072
  *     (so that |ACC| <= K * 127 * 127 stays below 2^31).  M = 0 is a successful no-op.
+ *     M itself is only bounded by int: the kernels address X with 32-bit byte offsets, and
+ *     w4a8_gemm / w4a8_gemm_i32 / w4a8_gemm_variant run a batch with M * K >= 2^32 as
+ *     consecutive launches over chunks of rows on the same stream (same result).  The
+ *     grouped and W8A8 entry points do not chunk: there an expert (resp. the call) with
+ *     rows * K >= 2^32 is rejected with LQ_ERR_INVALID.
  *   - The packed weight blob (W_packed, gparams) is opaque, position independent and
  *     specific to this library version (w4a8_version()); it can be stored and reloaded
  *     byte for byte.  Its size is given by liquidquant_packed_size().
@@ -159,8 +164,9 @@ int w4a8_dequant_dump(const void *W_packed, const uint8_t *gparams, int N, int K
  *               order); gparams likewise (gparams_bytes each); w_scales device [E, N] FP32
  *   Y           device [row_offsets[E], N] FP16 bits, or NULL
  *   ACC         device [row_offsets[E], N] raw INT32 accumulators (parity hook), or NULL
- * 1 <= E <= 64.  Per expert the result is exactly that of w4a8_gemm / w4a8_gemm_i32 on its
- * rows.  No workspace: the grid over all experts replaces the split of K. */
+ * 1 <= E <= 64; every expert's rows * K < 2^32 (else LQ_ERR_INVALID: split the expert).
+ * Per expert the result is exactly that of w4a8_gemm / w4a8_gemm_i32 on its rows.  No
+ * workspace: the grid over all experts replaces the split of K. */
 int w4a8_grouped_gemm(int E, const int *row_offsets, int N, int K, int group, const int8_t *X,
                       const float *act_scales, const void *W_packed, const uint8_t *gparams,
                       const float *w_scales, uint16_t *Y, int32_t *ACC, void *hip_stream);

@@ -198,6 +198,7 @@ def w4a8_gemm_workspace_size(M: int, N: int, K: int, group: int) -> int:
 
 
 _ws_cache = {}
+_ws_retired = []
 
 
 def w4a8_workspace_init(workspace, stream=None) -> None:
@@ -221,8 +222,13 @@ def _ws(workspace, M=0, N=0, K=0, group=64, device=None, stream=None):
         key = (str(device), int(stream) if stream is not None else int(torch.cuda.current_stream().cuda_stream))
         buf = _ws_cache.get(key)
         if buf is None or buf.numel() < need:
+            # A raw stream is unknown to torch's allocator, so a superseded buffer is kept
+            # alive (earlier launches on that stream may still use it) and the new one is
+            # zeroed under a device-wide synchronisation before any stream can see it.
+            if buf is not None:
+                _ws_retired.append(buf)
             buf = torch.zeros(need, dtype=torch.uint8, device=device)
-            torch.cuda.current_stream().synchronize()  # zeroed before any other stream can use it
+            torch.cuda.synchronize(device)
             _ws_cache[key] = buf
         workspace = buf
     return _dev(workspace, torch.uint8, name="workspace"), workspace.numel()

@@ -38,7 +38,7 @@ def build_library(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
         raise RuntimeError("hipcc failed building libliquidgemm.so")
     usage = kernel_resource_usage(res.stderr)
     spilling = {k: v for k, v in usage.items() if v.get("ScratchSize [bytes/lane]", 0) > 0}
-    if spilling and "-DLQ_ABLATE" not in extra_flags:
+    if spilling:
         raise RuntimeError("kernels must not use scratch memory, but these do: "
                            + ", ".join(f"{k} ({v['ScratchSize [bytes/lane]']} B/lane)" for k, v in spilling.items()))
     if verbose:

@@ -1,32 +1,6 @@
-// Pieces shared by the GEMM kernels: experiment hooks, split-K tickets and device-scope accesses, block placement, epilogue of the tiled kernels.
+// Pieces shared by the GEMM kernels: split-K tickets and device-scope accesses, block placement, epilogue of the tiled kernels.
 // (part of liquidgemm.hip: included there, inside namespace lqq)
 #pragma once
-
-#ifndef LQ_DUO_ABL
-#define LQ_DUO_ABL 0
-#endif
-#ifdef LQ_ABLATE
-// experiments only: per-wave wall-clock stamps (start, first unit done, loop done, end)
-__device__ long long g_dbg_stamps[4 * 16384];
-#define LQ_STAMP(slot)                                                                          \
-    do {                                                                                        \
-        const unsigned w_ = (blockIdx.y * gridDim.x + blockIdx.x) * NW + wave;                  \
-        if (lane == 0 && w_ < 16384) g_dbg_stamps[4 * w_ + (slot)] = wall_clock64();            \
-    } while (0)
-// same for the duo kernel: 8 slots per wave
-#define LQ_DSTAMP(slot)                                                                         \
-    do {                                                                                        \
-        const unsigned w_ = (blockIdx.y * gridDim.x + blockIdx.x) * (4 * KG) + (threadIdx.x >> 6); \
-        if ((threadIdx.x & 63) == 0 && w_ < 8192) g_dbg_stamps[8 * w_ + (slot)] = wall_clock64(); \
-    } while (0)
-#else
-#define LQ_STAMP(slot) \
-    do {               \
-    } while (0)
-#define LQ_DSTAMP(slot) \
-    do {                \
-    } while (0)
-#endif
 
 // Arrival tickets of the grid-level split-K, one per tile group, live at the head of the
 // caller's workspace (kTicketBytes, zeroed once by the caller or by w4a8_workspace_init).
@@ -135,10 +109,7 @@ __device__ __forceinline__ void block_coords(int blocks_m, int blocks_n, int &bm
     const int total = blocks_m * blocks_n;
     int lid = blockIdx.x;
     if ((total & 7) == 0) lid = (lid & 7) * (total >> 3) + (lid >> 3);
-#ifndef LQ_GM
-#define LQ_GM 4
-#endif
-    constexpr int GM = LQ_GM;
+    constexpr int GM = 4;
     const int per_group = GM * blocks_n;
     const int first = (lid / per_group) * GM;
     const int gsz = min(blocks_m - first, GM);

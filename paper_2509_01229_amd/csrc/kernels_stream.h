@@ -121,7 +121,6 @@ __device__ __forceinline__ void stream_block(
 
     // Register double buffering: the loads of the next unit are in flight while the
     // current one is dequantised and multiplied.
-    LQ_STAMP(0);
     StreamRegs<F, MF, G128> cur, nxt;
     int u = u_begin + wave;
     if (u < u_end) load_unit(u, cur);
@@ -131,7 +130,6 @@ __device__ __forceinline__ void stream_block(
         compute_unit(cur);
         if (more) cur = nxt;
     }
-    LQ_STAMP(2);
 
     // In-block split-K reduction (integer, order independent).  With one row fragment only
     // the accumulator elements that hold rows < M take part: rows of element r lie in
@@ -169,12 +167,15 @@ __device__ __forceinline__ void stream_block(
     } else {
         // Partial tile of this slice: [ks][blockIdx.x][vals * 64], coalesced.  The tiles are
         // written and read with device-scope atomics, which act at the memory side common to
-        // all XCDs, so no cache has to be flushed or invalidated; the barrier's wait for
-        // outstanding memory operations orders them before the ticket.
+        // all XCDs, so no cache has to be flushed or invalidated.  Every wave waits for the
+        // acknowledgement of its own stores (a block barrier alone does not: it orders LDS
+        // traffic only) before the barrier that precedes the ticket, so a block that sees
+        // the last ticket also sees every partial tile.
         int32_t *mine = partials + ((size_t)ks * pl.gnx + pl.gx) * (size_t)(vals * 64);
         for (int idx = threadIdx.x; idx < vals * 64; idx += NW * 64)
             __hip_atomic_store(mine + idx, block_sum(idx), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __syncthreads();  // includes s_waitcnt vmcnt(0): every store above has been acknowledged
+        wait_vmcnt0();
+        __syncthreads();
         if (threadIdx.x == 0) {
             const unsigned t = __hip_atomic_fetch_add(&pl.tickets[pl.gx], 1u, __ATOMIC_RELAXED,
                                                       __HIP_MEMORY_SCOPE_AGENT);
@@ -194,7 +195,6 @@ __device__ __forceinline__ void stream_block(
                 __hip_atomic_store(&pl.tickets[pl.gx], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    LQ_STAMP(3);
 }
 
 template <int F, int NW, int MF, bool G128, bool XL = false>
@@ -225,9 +225,7 @@ struct Stream16Regs {
     u32x4 x[2 * UU];
 };
 
-// ABL (experiments only, 0 in shipped variants): 1 = no X loads, 2 = no parameter loads,
-// 4 = no dequantisation, 8 = no reduction / epilogue.  Results are wrong for ABL != 0.
-template <int F, int NW, int UU, bool G128, int ABL = 0>
+template <int F, int NW, int UU, bool G128>
 __device__ __forceinline__ void stream16_block(
     const Place pl, int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
@@ -277,16 +275,12 @@ __device__ __forceinline__ void stream16_block(
             for (int c = 0; c < 2 * UU; ++c) r.w[f][c] = __builtin_nontemporal_load(base + 64 * c);
 #pragma unroll
             for (int q = 0; q < UU; ++q) {
-                if (ABL & 2)
-                    r.p[f][q].raw = 0x01800180u;
-                else
-                    r.p[f][q].load(gp, (size_t)(t0 + f) * units + (size_t)u * UU + q, j);
+                r.p[f][q].load(gp, (size_t)(t0 + f) * units + (size_t)u * UU + q, j);
             }
         }
 #pragma unroll
         for (int c = 0; c < 2 * UU; ++c)
-            r.x[c] = (ABL & 1) ? u32x4{1u, 2u, 3u, (unsigned)u}
-                               : *reinterpret_cast<const u32x4 *>(xrow + (size_t)u * (128 * UU) + 64 * c);
+            r.x[c] = *reinterpret_cast<const u32x4 *>(xrow + (size_t)u * (128 * UU) + 64 * c);
     };
     auto compute_unit = [&](const Stream16Regs<F, UU, G128> &r) {
 #pragma unroll
@@ -296,12 +290,7 @@ __device__ __forceinline__ void stream16_block(
                 uint32_t s2, a4;
                 r.p[f][c >> 1].get(c & 1, s2, a4);
                 v4i lo, hi, b1, b2;
-                if (ABL & 4) {
-                    lo = __builtin_bit_cast(v4i, r.w[f][c]);
-                    hi = lo + (int)s2;
-                } else {
-                    dequant_chunk(r.w[f][c], s2, a4, lo, hi);
-                }
+                dequant_chunk(r.w[f][c], s2, a4, lo, hi);
                 regroup_16x16(lo, hi, b1, b2);
                 const v4i xa = __builtin_bit_cast(v4i, r.x[c]);
                 acc[f][0] = mfma16_i8(xa, b1, acc[f][0]);
@@ -319,13 +308,6 @@ __device__ __forceinline__ void stream16_block(
         if (more) cur = nxt;
     }
 
-    if (ABL & 8) {
-        int sum = 0;
-#pragma unroll
-        for (int f = 0; f < F; ++f) sum += acc[f][0][0] + acc[f][1][1] + acc[f][0][2] + acc[f][1][3];
-        if (sum == 0x12345678) ACC[0] = sum;
-        return;
-    }
     // in-block split-K reduction: value v = (f*2 + h)*4 + r of lane l is row 4*(l/16) + r,
     // slot 16*h + l%16 of tile t0 + f
 #pragma unroll
@@ -357,10 +339,12 @@ __device__ __forceinline__ void stream16_block(
             if (idx < VALS * 64) finish(i, idx, block_sum(idx));
         }
     } else {
-        // grid-level split-K: same protocol as w4a8_stream_kernel
+        // grid-level split-K: same protocol as w4a8_stream_kernel (stores acknowledged, then
+        // the barrier, then the ticket)
         int32_t *mine = partials + ((size_t)ks * pl.gnx + pl.gx) * (size_t)(VALS * 64);
         for (int idx = threadIdx.x; idx < VALS * 64; idx += NW * 64)
             __hip_atomic_store(mine + idx, block_sum(idx), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        wait_vmcnt0();
         __syncthreads();
         if (threadIdx.x == 0) {
             const unsigned t = __hip_atomic_fetch_add(&pl.tickets[pl.gx], 1u, __ATOMIC_RELAXED,
@@ -386,13 +370,13 @@ __device__ __forceinline__ void stream16_block(
     }
 }
 
-template <int F, int NW, int UU, bool G128, int ABL = 0>
+template <int F, int NW, int UU, bool G128>
 __global__ __launch_bounds__(NW * 64) void w4a8_stream16_kernel(
     int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
     __half *__restrict__ Y, int32_t *__restrict__ ACC, int32_t *__restrict__ partials,
     unsigned int *__restrict__ tickets)
 {
-    stream16_block<F, NW, UU, G128, ABL>(grid_place(tickets), M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+    stream16_block<F, NW, UU, G128>(grid_place(tickets), M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
 }
 

@@ -157,7 +157,9 @@ __device__ __forceinline__ void lds_barrier()
 // the MFMAs, X staging and fragment reads.  The tile grid is that of 128-row tiles either way.
 // With one k group a tile of 65..96 rows takes 3 fragments (8 experts of 58..71 tokens on
 // 14336 x 4096: 65 instead of 72 us).
-template <bool G128, int KG, int MF, int TM = 128, int MFC = MF>
+// DQ = how the B operand is dequantised: 0 = LiquidQuant (Eq. 12, the product path), 1 = the
+// overflow-safe widened form it replaces (ablation variant only, never dispatched).
+template <bool G128, int KG, int MF, int TM = 128, int MFC = MF, int DQ = 0>
 __device__ __forceinline__ void duo_tile(
     const Place pl, const int bm, const int bn, int M, int N, int K, const int8_t *__restrict__ X,
     const float *__restrict__ sx, const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp,
@@ -194,7 +196,6 @@ __device__ __forceinline__ void duo_tile(
     const int stages_total = K >> 7;
     const int chunks_per_tile = K >> 6;
 
-    LQ_DSTAMP(0);
     v16i acc[MF][2];
 #pragma unroll
     for (int mf = 0; mf < MFC; ++mf)
@@ -264,33 +265,30 @@ __device__ __forceinline__ void duo_tile(
     auto build_b = [&](const u32x4 (&w)[2][2], const UnitParams<G128> (&p)[2], int c, int h, v4i (&b)[2]) {
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-#if defined(LQ_ABLATE) && (LQ_DUO_ABL & 1)  // experiments only: raw bytes instead of the dequantised operand
-            b[t] = __builtin_bit_cast(v4i, w[t][c]) + h + (int)p[t].raw;
-#elif defined(LQ_ABLATE) && (LQ_DUO_ABL & 4)
-            // experiments only: the overflow-safe dequantisation that LiquidQuant avoids --
-            // code * s + min in signed 16-bit lanes (two codes per register), low bytes
-            // gathered with a byte permute: about twice the instructions, same result
             uint32_t s2, a4;
             p[t].get(c, s2, a4);
-            const uint32_t mn2 = (((a4 & 0xffu) - 128u) & 0xffffu) * 0x00010001u;
+            if constexpr (DQ == 0) {
+                dequant_half(w[t][c], s2, a4, h, b[t]);
+            } else {
+                // The overflow-safe form that LiquidQuant avoids (Sec. 4 "Dequantization",
+                // Sec. 7.3 ablation): code * s + min in signed 16-bit lanes, two codes per
+                // register, low bytes gathered with a byte permute -- the same integers for
+                // about twice the instructions.
+                const uint32_t mn2 = (((a4 & 0xffu) - 128u) & 0xffffu) * 0x00010001u;
 #pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                const uint32_t q = w[t][c][d] >> (4 * h);
-                const uint32_t ra = q & 0x000F000Fu, rb = (q >> 8) & 0x000F000Fu;
-                const uint32_t ma = pk_mad_u16(ra, s2, mn2), mb = pk_mad_u16(rb, s2, mn2);
-                b[t][d] = (int)__builtin_amdgcn_perm(mb, ma, 0x06020400u);
+                for (int d = 0; d < 4; ++d) {
+                    const uint32_t q = w[t][c][d] >> (4 * h);
+                    const uint32_t ra = q & 0x000F000Fu, rb = (q >> 8) & 0x000F000Fu;
+                    const uint32_t ma = pk_mad_u16(ra, s2, mn2), mb = pk_mad_u16(rb, s2, mn2);
+                    b[t][d] = (int)__builtin_amdgcn_perm(mb, ma, 0x06020400u);
+                    // one register at a time: the kernel has no registers to spare for four
+                    // chains of temporaries in flight at once
+                    asm volatile("" : "+v"(b[t][d]));
+                }
             }
-#else
-            uint32_t s2, a4;
-            p[t].get(c, s2, a4);
-            dequant_half(w[t][c], s2, a4, h, b[t]);
-#endif
         }
     };
     auto read_a = [&](int buf, int c, int h, v4i (&a)[MFC]) {
-#if defined(LQ_ABLATE) && (LQ_DUO_ABL & 2)  // experiments only: no X fragment reads from LDS
-        if (buf + c + h == -1)
-#endif
 #pragma unroll
         for (int mf = 0; mf < MFC; ++mf)
             a[mf] = *reinterpret_cast<const v4i *>(xs + buf * STAGE + mf * 32 * kTilePitch + 64 * c + 32 * h);
@@ -347,7 +345,6 @@ __device__ __forceinline__ void duo_tile(
     read_a(0, 0, 0, af[0]);
     __builtin_amdgcn_sched_barrier(0);
 
-    LQ_DSTAMP(1);
     if (WS == 2) {
         for (int s = 0; s < stages; s += 2) {
             stage(s, wr[0], pr[0], wr[1], pr[1], 0);
@@ -375,7 +372,6 @@ __device__ __forceinline__ void duo_tile(
             }
         }
     }
-    LQ_DSTAMP(2);
     // fragments that the loop did not compute come into being only here (no registers before)
 #pragma unroll
     for (int mf = MFC; mf < MF; ++mf)
@@ -416,7 +412,6 @@ __device__ __forceinline__ void duo_tile(
                 if (t == 0) lds_barrier();
             }
         }
-        LQ_DSTAMP(3);
         if (S > 1) {
             // Grid-level split-K (same protocol as the stream kernels): every block publishes its
             // INT32 partial tile with device-scope write-through stores, takes a ticket, and the
@@ -445,7 +440,6 @@ __device__ __forceinline__ void duo_tile(
                 }
             }
             wait_vmcnt0();
-            LQ_DSTAMP(4);
             __syncthreads();
             if (threadIdx.x == 0) {
                 const unsigned tk = __hip_atomic_fetch_add(&pl.tickets[tile], 1u, __ATOMIC_RELAXED,
@@ -453,7 +447,6 @@ __device__ __forceinline__ void duo_tile(
                 s_last = (tk == (unsigned)(S - 1));
             }
             __syncthreads();
-            LQ_DSTAMP(5);
             if (!s_last) return;
             // The 8 loads of one row fragment (2 column tiles x 4 pieces of 16 bytes per lane)
             // are in flight before the first is waited for: the latency of these device-scope
@@ -483,14 +476,12 @@ __device__ __forceinline__ void duo_tile(
                             for (int e = 0; e < 4; ++e) acc[MF0 + i][t][4 * q + e] += v[t][q][e];
                 }
             }
-            LQ_DSTAMP(6);
             if (threadIdx.x == 0)
                 __hip_atomic_store(&pl.tickets[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (!active) return;
         store_tile<MFK>(*reinterpret_cast<const v16i(*)[MFK][2]>(&acc[MF0]), M, N, m0 + 32 * MF0,
                         64 * ng + 2 * j, lane, sx, sw, Y, ACC);
-        LQ_DSTAMP(7);
     };
     if (KG == 1 || grp == 0)
         finish(std::integral_constant<int, 0>{});
@@ -501,31 +492,33 @@ __device__ __forceinline__ void duo_tile(
 // ALL3 = every row tile of the launch has 65..96 rows (M itself has): the kernel holds that
 // path only.  (Inside the general two-k-group kernel it would be a third copy of the tile code,
 // and the register allocation of the four-fragment copy, which has none to spare, then spills.)
-template <bool G128, int KG, int TM = 128, bool ALL3 = false>
+template <bool G128, int KG, int TM = 128, bool ALL3 = false, int DQ = 0>
 __device__ __forceinline__ void duo_block(
     const Place pl, const int bm, const int bn, int M, int N, int K, const int8_t *__restrict__ X,
     const float *__restrict__ sx, const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp,
     const float *__restrict__ sw, __half *__restrict__ Y, int32_t *__restrict__ ACC,
     int32_t *__restrict__ partials)
 {
-    if (ALL3)
-        duo_tile<G128, KG, 4, 128, 3>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+    if (DQ != 0)  // ablation variant: the four-fragment path only (rows past M are computed and not stored)
+        duo_tile<G128, KG, 4, 128, 4, DQ>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+    else if (ALL3)
+        duo_tile<G128, KG, 4, 128, 3, DQ>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
     else if (TM == 64)
-        duo_tile<G128, KG, 2, 64>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+        duo_tile<G128, KG, 2, 64, 2, DQ>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
     else if (M - 128 * bm <= 64)  // block-uniform
-        duo_tile<G128, KG, 2>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+        duo_tile<G128, KG, 2, 128, 2, DQ>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
     else {
         if constexpr (KG == 1) {
             if (M - 128 * bm <= 96) {
-                duo_tile<G128, KG, 3>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+                duo_tile<G128, KG, 3, 128, 3, DQ>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
                 return;
             }
         }
-        duo_tile<G128, KG, 4>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+        duo_tile<G128, KG, 4, 128, 4, DQ>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
     }
 }
 
-template <bool G128, int KG, int TM = 128, bool ALL3 = false>
+template <bool G128, int KG, int TM = 128, bool ALL3 = false, int DQ = 0>
 __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
     int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
@@ -534,7 +527,7 @@ __global__ __launch_bounds__(256 * KG, KG == 1 ? 2 : 1) void w4a8_duo_kernel(
 {
     int bm, bn;
     block_coords(blocks_m, blocks_n, bm, bn);
-    duo_block<G128, KG, TM, ALL3>(grid_place(tickets), bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
+    duo_block<G128, KG, TM, ALL3, DQ>(grid_place(tickets), bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, partials);
 }
 
 // The same barrier for code that waits for its loads itself: a fence would also wait for

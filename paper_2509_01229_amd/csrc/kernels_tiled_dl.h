@@ -24,7 +24,6 @@ __device__ __forceinline__ void duo_dl_tile(
     const float *__restrict__ sw, __half *__restrict__ Y, int32_t *__restrict__ ACC,
     int32_t *__restrict__ partials)
 {
-    constexpr int KG = 1;  // (for the stamps of the experiments build)
     constexpr int XP = MF;
     constexpr int STAGE = 128 * 128;
     constexpr int PER_STAGE = XP + 6;  // loads of one stage: XP of X, 4 of codes, 2 of parameters
@@ -45,16 +44,6 @@ __device__ __forceinline__ void duo_dl_tile(
     const int stages_total = K >> 7;
     const int chunks_per_tile = K >> 6;
 
-    LQ_DSTAMP(0);
-#ifdef LQ_ABLATE  // experiments only: where the wave runs (XCC id, hardware id register)
-    {
-        const unsigned w_ = (blockIdx.y * gridDim.x + blockIdx.x) * (4 * KG) + (threadIdx.x >> 6);
-        if ((threadIdx.x & 63) == 0 && w_ < 8192) {
-            g_dbg_stamps[8 * w_ + 3] = __builtin_amdgcn_s_getreg(0xF814);
-            g_dbg_stamps[8 * w_ + 4] = __builtin_amdgcn_s_getreg(0xF804);
-        }
-    }
-#endif
     v16i acc[MF][2];
 #pragma unroll
     for (int mf = 0; mf < MF; ++mf)
@@ -91,9 +80,6 @@ __device__ __forceinline__ void duo_dl_tile(
     const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) void *)lds;
     auto issue_x = [&](int s, int buf) {
         s = min(s, stages - 1);
-#if defined(LQ_ABLATE) && (LQ_DUO_ABL & 8)  // experiments only: every stage re-reads stage 0 (cache hits)
-        s = 0;
-#endif
         const uint32_t so = (uint32_t)s * 128;
 #pragma unroll
         for (int i = 0; i < XP; ++i)
@@ -104,9 +90,6 @@ __device__ __forceinline__ void duo_dl_tile(
     };
     auto load_w = [&](int s, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
         s = min(s, stages - 1);
-#if defined(LQ_ABLATE) && (LQ_DUO_ABL & 16)  // experiments only: every stage re-reads stage 0 (cache hits)
-        s = 0;
-#endif
         const uint32_t wo = wl + (uint32_t)s * 2048, po = pl_off + (uint32_t)s * (G128 ? 64 : 128);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
@@ -197,7 +180,6 @@ __device__ __forceinline__ void duo_dl_tile(
     read_a(0, 0, 0, af[0]);
     __builtin_amdgcn_sched_barrier(0);
 
-    LQ_DSTAMP(1);
     // Three stages per trip (one turn of the W registers) without branches inside, so that
     // every load stays where the in-flight count above expects it; the one or two stages
     // that may be left over run after the loop, waiting for everything still in flight.
@@ -212,7 +194,6 @@ __device__ __forceinline__ void duo_dl_tile(
     // the (clamped) prefetches past the last stage write LDS too: they must have landed
     // before the block ends and its LDS goes to another block
     wait_vmcnt0();
-    LQ_DSTAMP(2);
 
     if (S > 1) {
         // grid-level split-K: same protocol and workspace layout as duo_tile with one k group
@@ -274,7 +255,6 @@ __device__ __forceinline__ void duo_dl_tile(
     }
     if (!active) return;
     store_tile<MF>(acc, M, N, m0, 64 * ng + 2 * j, lane, sx, sw, Y, ACC);
-    LQ_DSTAMP(7);
 }
 
 template <bool G128>

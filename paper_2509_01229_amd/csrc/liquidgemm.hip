@@ -34,6 +34,9 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <map>
+#include <mutex>
+#include <utility>
 
 #include "lqq_common.h"
 #include "lqq_device.h"
@@ -109,15 +112,29 @@ struct Args {
 
 typedef int (*LaunchFn)(const Args &);
 
+// Kernels that need more than the default 48 KiB of dynamic LDS must be told so once per
+// device; the grant is remembered, so the launch path of a short kernel pays one map lookup
+// instead of a runtime call.
+static int allow_lds_once(const void *kernel, size_t bytes)
+{
+    static std::mutex mu;
+    static std::map<std::pair<int, const void *>, size_t> granted;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return fail(LQ_ERR_HIP, "hipGetDevice failed");
+    std::lock_guard<std::mutex> lock(mu);
+    size_t &have = granted[{dev, kernel}];
+    if (have >= bytes) return LQ_OK;
+    const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess)
+        return fail(LQ_ERR_HIP, "hipFuncSetAttribute(%zu bytes of LDS): %s", bytes, hipGetErrorString(e));
+    have = bytes;
+    return LQ_OK;
+}
 template <class Kernel>
 static int allow_lds(Kernel kernel, size_t bytes)
 {
     if (bytes <= 48 * 1024) return LQ_OK;
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-    if (e != hipSuccess)
-        return fail(LQ_ERR_HIP, "hipFuncSetAttribute(%zu bytes of LDS): %s", bytes, hipGetErrorString(e));
-    return LQ_OK;
+    return allow_lds_once(reinterpret_cast<const void *>(kernel), bytes);
 }
 
 // Grid-level split of K for the stream kernels: enough blocks for every CU to hold two
@@ -213,7 +230,7 @@ static int launch_stream_auto(const Args &a)
     return xl ? launch_stream_shaped<1, true>(a) : launch_stream_shaped<1, false>(a);
 }
 
-template <int F, int NW, int SPLIT, int ABL = 0, int UU = 1>
+template <int F, int NW, int SPLIT, int UU = 1>
 static int launch_stream16(const Args &a)
 {
     if (a.M > 16) return fail(LQ_ERR_INVALID, "stream16 variants handle M <= 16, got %d", a.M);
@@ -238,12 +255,12 @@ static int launch_stream16(const Args &a)
     unsigned int *tickets = static_cast<unsigned int *>(a.ws);
     int32_t *partials = a.ws ? reinterpret_cast<int32_t *>(static_cast<char *>(a.ws) + kTicketBytes) : nullptr;
     if (a.group == 128) {
-        if (int rc = allow_lds(&w4a8_stream16_kernel<F, NW, UU, true, ABL>, lds_bytes)) return rc;
-        hipLaunchKernelGGL((w4a8_stream16_kernel<F, NW, UU, true, ABL>), grid, block, lds_bytes, a.stream, a.M, a.N,
+        if (int rc = allow_lds(&w4a8_stream16_kernel<F, NW, UU, true>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_stream16_kernel<F, NW, UU, true>), grid, block, lds_bytes, a.stream, a.M, a.N,
                            a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials, tickets);
     } else {
-        if (int rc = allow_lds(&w4a8_stream16_kernel<F, NW, UU, false, ABL>, lds_bytes)) return rc;
-        hipLaunchKernelGGL((w4a8_stream16_kernel<F, NW, UU, false, ABL>), grid, block, lds_bytes, a.stream, a.M, a.N,
+        if (int rc = allow_lds(&w4a8_stream16_kernel<F, NW, UU, false>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_stream16_kernel<F, NW, UU, false>), grid, block, lds_bytes, a.stream, a.M, a.N,
                            a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, partials, tickets);
     }
     return LQ_OK;
@@ -403,6 +420,22 @@ static int launch_excp(const Args &a)
     return LQ_OK;
 }
 
+// The tiled kernel with the overflow-safe widened dequantisation in place of LiquidQuant's
+// (the dequantisation half of the paper's ablation, Sec. 7.3; measured only, never dispatched).
+static int launch_duo_widened(const Args &a)
+{
+    const int blocks_n = (a.N + 255) / 256, blocks_m = (a.M + 127) / 128;
+    const size_t lds_bytes = 2 * (size_t)128 * kTilePitch;
+    const dim3 grid((unsigned)(blocks_n * blocks_m), 1u), block(256);
+    if (a.group == 128)
+        hipLaunchKernelGGL((w4a8_duo_kernel<true, 1, 128, false, 1>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
+                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n, nullptr, nullptr);
+    else
+        hipLaunchKernelGGL((w4a8_duo_kernel<false, 1, 128, false, 1>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
+                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n, nullptr, nullptr);
+    return LQ_OK;
+}
+
 // The same kernel on a grid of 64-row tiles (two row fragments per wave, two k groups per
 // block): twice the tiles for a given M, half the partial-tile volume per slice.
 static int duo64_split(int M, int N, int K)
@@ -485,9 +518,9 @@ static const Variant kVariants[] = {
     {"stream16_f1_w8_s1", &launch_stream16<1, 8, 1>, 16, 1, 1},
     {"stream16_f2_w16_s1", &launch_stream16<2, 16, 1>, 16, 2, 1},
     {"stream16_f1_w16_s1", &launch_stream16<1, 16, 1>, 16, 1, 1},
-    {"stream16_f1_w8_u4", &launch_stream16<1, 8, 0, 0, 4>, 16, 1, 8},
-    {"stream16_f1_w8_u4_s1", &launch_stream16<1, 8, 1, 0, 4>, 16, 1, 8},
-    {"stream16_f1_w8_u4_s2", &launch_stream16<1, 8, 2, 0, 4>, 16, 1, 8},
+    {"stream16_f1_w8_u4", &launch_stream16<1, 8, 0, 4>, 16, 1, 8},
+    {"stream16_f1_w8_u4_s1", &launch_stream16<1, 8, 1, 4>, 16, 1, 8},
+    {"stream16_f1_w8_u4_s2", &launch_stream16<1, 8, 2, 4>, 16, 1, 8},
     {"tile_m32", &launch_tile<1>, 0, 1, 1},
     {"tile_m64", &launch_tile<2>, 0, 1, 1},
     {"tile_m128", &launch_tile<4>, 0, 1, 1},
@@ -500,6 +533,7 @@ static const Variant kVariants[] = {
     {"duo_dl_m128_s2", &launch_duo_dl<2>, 0, 1, 1},
     {"duo_dl_m128_s3", &launch_duo_dl<3>, 0, 1, 1},
     {"excp_m128", &launch_excp, 0, 1, 1},
+    {"widened_dq_m128", &launch_duo_widened, 0, 1, 1},
     {"duo_m64", &launch_duo64<0>, 0, 1, 1, 512},
     {"duo_m64_s1", &launch_duo64<1>, 0, 1, 1, 512},
     {"duo_m64_s2", &launch_duo64<2>, 0, 1, 1, 512},
@@ -511,15 +545,6 @@ static const Variant kVariants[] = {
     {"duo_m128_g2_s3", &launch_duo<3, 2>, 0, 1, 1},
     {"duo_m128_g2_s4", &launch_duo<4, 2>, 0, 1, 1},
     {"duo_m128_g2_s6", &launch_duo<6, 2>, 0, 1, 1},
-#ifdef LQ_ABLATE
-    {"abl_s16_noX", &launch_stream16<2, 4, 1, 1>, 16, 2, 1},
-    {"abl_s16_noP", &launch_stream16<2, 4, 1, 2>, 16, 2, 1},
-    {"abl_s16_noDq", &launch_stream16<2, 4, 1, 4>, 16, 2, 1},
-    {"abl_s16_noRed", &launch_stream16<2, 4, 1, 8>, 16, 2, 1},
-    {"abl_s16_noXP", &launch_stream16<2, 4, 1, 3>, 16, 2, 1},
-    {"abl_s16_noXPDq", &launch_stream16<2, 4, 1, 7>, 16, 2, 1},
-    {"abl_s16_onlyW", &launch_stream16<2, 4, 1, 15>, 16, 2, 1},
-#endif
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -579,7 +604,7 @@ static int select_variant(int M, int N, int K)
     // more 128 x 256 tiles than CUs (blocks of one k group): the deeper memory pipeline of the
     // direct-to-LDS form pays (3 to 6 % measured from 320 tiles up, 1 to 5 % at 264..288); with
     // one tile per CU or fewer, the two k groups per block of the other form do
-    if (((M + 127) / 128) * ((N + 255) / 256) > 256 && (long long)M * K < (1ll << 32))
+    if (((M + 127) / 128) * ((N + 255) / 256) > 256)
         return find_variant("duo_dl_m128");
     // few tiles: a grid of 64-row tiles can fill the chip with half the split-K exchange
     return find_variant(prefer_64_row_tiles(M, N, K) ? "duo_m64" : "duo_m128");
@@ -611,7 +636,20 @@ static int run(int variant, const Args &a)
         return fail(LQ_ERR_INVALID, "variant %s cannot run M=%d N=%d K=%d", kVariants[variant].name, a.M, a.N,
                     a.K);
     (void)hipGetLastError();
-    if (int rc = kVariants[variant].fn(a)) return rc;
+    // The tiled kernels address X with 32-bit byte offsets.  A batch with M * K >= 2^32 is
+    // run as consecutive row chunks (multiples of 128 rows, so every chunk keeps the
+    // alignment and the tile grid of a call of its own) on the same stream; rows are
+    // independent, so the result is that of one launch.
+    const long long rows_max = ((1ll << 32) - 1) / a.K / 128 * 128;
+    for (long long r0 = 0; r0 < a.M; r0 += rows_max) {
+        Args c = a;
+        c.M = (int)std::min<long long>(rows_max, a.M - r0);
+        c.X = a.X + r0 * a.K;
+        if (a.sx) c.sx = a.sx + r0;
+        if (a.Y) c.Y = a.Y + r0 * a.N;
+        if (a.ACC) c.ACC = a.ACC + r0 * a.N;
+        if (int rc = kVariants[variant].fn(c)) return rc;
+    }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return fail(LQ_ERR_HIP, "launch of %s failed: %s", kVariants[variant].name, hipGetErrorString(e));
@@ -807,13 +845,6 @@ int w4a8_gemm_variant(int variant, int M, int N, int K, int group, const int8_t 
     return run(variant, a);
 }
 
-#ifdef LQ_ABLATE
-int w4a8_debug_stamps(long long *host, int n)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg_stamps), sizeof(long long) * n);
-}
-#endif
-
 int w4a8_variant_count(void) { return kNumVariants; }
 
 const char *w4a8_variant_name(int variant)
@@ -863,8 +894,12 @@ int w4a8_grouped_gemm(int E, const int *row_offsets, int N, int K, int group, co
         return fail(LQ_ERR_INVALID, "bad shape N=%d K=%d group=%d (need N%%64==0, K%%256==0, group 64|128, K<=131072)",
                     N, K, group);
     if (!row_offsets || row_offsets[0] != 0) return fail(LQ_ERR_INVALID, "row_offsets must start at 0");
-    for (int e = 0; e < E; ++e)
+    for (int e = 0; e < E; ++e) {
         if (row_offsets[e + 1] < row_offsets[e]) return fail(LQ_ERR_INVALID, "row_offsets must not decrease");
+        // the kernels address an expert's rows of X with 32-bit byte offsets
+        if ((long long)(row_offsets[e + 1] - row_offsets[e]) * K >= (1ll << 32))
+            return fail(LQ_ERR_INVALID, "expert %d has rows * K >= 2^32 bytes of X; split it into two experts", e);
+    }
     if (row_offsets[E] == 0) return LQ_OK;
     if (!Y && !ACC) return fail(LQ_ERR_INVALID, "no output pointer");
     if (!X || !W_packed || !gparams) return fail(LQ_ERR_INVALID, "null input pointer");

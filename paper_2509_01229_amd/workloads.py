@@ -1,16 +1,17 @@
 """Seeded synthetic inputs shaped like the paper's LLM linear layers.
 
 This module is the only code shared by the tests of the CPU oracle and of the HIP
-library.  It holds none of the method's arithmetic (no LiquidQuant, no dequantization,
-no matmul): it draws FP16 weights and activations, and turns activations into the
-INT8-plus-per-token-scale form in which they reach the W4A8 GEMM (Sec. 6 of the paper:
-dynamic per-token quantization happens upstream of the kernel).
+library.  It holds none of the method's arithmetic (no LiquidQuant, no activation
+quantization, no dequantization, no matmul): it draws FP16 weights and FP16 activations
+and nothing else.  The INT8-plus-per-token-scale form in which activations reach the W4A8
+GEMM (Sec. 6 of the paper: dynamic per-token quantization upstream of the kernel) is
+produced by each side for itself: the tests take it from the oracle, the benchmark from
+the library's own activation-quantization kernel.
 
 Recipe: numpy.random.Generator(PCG64(seed)); draw order W, then X, then the outlier
 channel indices.  W ~ N(0, sigma) in FP32 rounded to FP16; X ~ N(0, 1) rounded to FP16;
 `outlier_frac` of the K channels (at least one when the fraction is non-zero) are
-multiplied by 20 before quantization.  Per token m: s_x[m] = max_k |X[m,k]| / 127 in
-FP32 (1 for an all-zero row), X_i8 = clamp(rint(X / s_x), -127, 127).
+multiplied by 20 (and rounded to FP16 again).
 """
 from __future__ import annotations
 
@@ -62,15 +63,6 @@ def by_name(name: str) -> GemmShape:
     return GemmShape(name, int(m.group(1)), int(m.group(2)), int(m.group(3)), group=int(m.group(4) or 64), seed=4)
 
 
-def quantize_activations(X):
-    """Per-token symmetric INT8: returns (X_i8 [M,K] int8, s_x [M] float32)."""
-    X = np.asarray(X, dtype=np.float32)
-    amax = np.max(np.abs(X), axis=1).astype(np.float32)
-    s_x = np.where(amax > 0, amax / np.float32(127), np.float32(1.0)).astype(np.float32)
-    q = np.clip(np.rint(X / s_x[:, None]), -127, 127)
-    return q.astype(np.int8), s_x
-
-
 def make_weights(N, K, sigma=0.02, seed=0, rng=None):
     """FP16-valued weights W [N,K] returned as float32 (exactly representable in FP16)."""
     rng = rng or np.random.Generator(np.random.PCG64(seed))
@@ -96,17 +88,12 @@ def make_smooth(K, seed=0):
     return np.exp(rng.standard_normal(K, dtype=np.float32) * np.float32(0.5)).astype(np.float32)
 
 
-def make_activations(M, K, outlier_frac=0.0, seed=0, rng=None):
-    """INT8 activations and per-token scales: (X_i8 [M,K], s_x [M])."""
-    return quantize_activations(make_activations_f16(M, K, outlier_frac, seed, rng).astype(np.float32))
-
-
-def make_problem(shape: GemmShape):
-    """Returns (W float32 [N,K] with FP16 values, X_i8 [M,K], s_x [M]) for one shape."""
+def make_problem_f16(shape: GemmShape):
+    """Returns (W float32 [N,K] with FP16 values, X float16 [M,K]) for one shape."""
     rng = np.random.Generator(np.random.PCG64(shape.seed))
     W = make_weights(shape.N, shape.K, shape.sigma_w, rng=rng)
-    X_i8, s_x = make_activations(shape.M, shape.K, shape.outlier_frac, rng=rng)
-    return W, X_i8, s_x
+    X = make_activations_f16(shape.M, shape.K, shape.outlier_frac, rng=rng)
+    return W, X
 
 
 def make_q_i8(N, K, seed=0, lo=-119, hi=119, style="uniform"):

@@ -1,15 +1,13 @@
 """GPU parity at the full benchmark sizes, in the launch configuration bench.py times
 (the dispatcher's own kernel choice through w4a8_gemm / w4a8_gemm_i32).
 
-A full element-by-element oracle run is out of reach at these sizes, so every shape is
-checked three ways against the oracle's quantised weights:
-  * sampled outputs: a random set of rows x channels recomputed one by one by the oracle
-    (INT32 bit-exact, FP16 within one ulp);
-  * checksums over every output: row sums  sum_n ACC[m,n] = X[m,:] . colsum(Wd)  and column
-    sums  sum_m ACC[m,n] = Wd[n,:] . colsum(X), both exact in int64/float64, so a single
-    wrong accumulator anywhere fails;
-  * the whole FP16 matrix against fp16(ACC * s_x * s_w) recomputed in double from the
-    kernel's own (already verified) accumulators.
+Every shape is checked two ways against the oracle's quantised weights:
+  * the WHOLE accumulator matrix against the exact product X . Wd^T of the oracle's
+    dequantised weights, computed with the float64 BLAS (every partial sum is an integer
+    below 2^53, so the product is exact), and the WHOLE FP16 matrix against the epilogue
+    definition applied to that product -- no value of the comparison comes from the GPU;
+  * sampled outputs: a random set of rows x channels recomputed one by one by the oracle's
+    own int64 matmul (INT32 bit-exact, FP16 within one ulp).
 """
 import sys
 
@@ -21,6 +19,7 @@ from paper_2509_01229_amd import api
 from paper_2509_01229_amd import workloads as WL
 
 import gpu_helpers as H
+import inputs as I
 
 pytestmark = pytest.mark.gpu
 
@@ -52,21 +51,22 @@ def _say(msg):
     sys.stdout.flush()
 
 
-def _oracle_column_sums(P, xsums, block=2048):
-    """colsum[k] = sum_n Wd[n,k] and, per activation set, Wd @ colsum(X): exact (int64 /
-    float64 on integers below 2^53), computed from the oracle's quantisation in row blocks."""
-    N, K = P.N, P.K
-    colsum = np.zeros(K, dtype=np.int64)
-    rowdot = {M: np.empty(N, dtype=np.float64) for M in xsums}
+def _oracle_exact_products(P, acts, block=2048):
+    """ACC_ref[M] = X . Wd^T for every activation set, as int32: float64 BLAS on integers
+    (exact: |sum| <= K * 127 * 126 < 2^53), from the oracle's quantisation in blocks of channels."""
+    N = P.N
+    ref = {M: np.empty((M, N), dtype=np.int32) for M in acts}
+    X64 = {M: X.astype(np.float64) for M, (X, _) in acts.items()}
     s_w = np.empty(N, dtype=np.float32)
     for r0 in range(0, N, block):
         rows = np.arange(r0, min(N, r0 + block))
         Wd, s_w[rows] = P.oracle_wd(rows)
-        colsum += Wd.astype(np.int64).sum(axis=0)
-        Wf = Wd.astype(np.float64)
-        for M, xs in xsums.items():
-            rowdot[M][rows] = Wf @ xs
-    return colsum, rowdot, s_w
+        WfT = np.ascontiguousarray(Wd.astype(np.float64).T)
+        for M in acts:
+            prod = X64[M] @ WfT
+            assert np.abs(prod).max() < 2.0 ** 31
+            ref[M][:, rows] = prod.astype(np.int32)
+    return ref, s_w
 
 
 @pytest.mark.parametrize("name,shapes", FAMILIES, ids=[f[0] for f in FAMILIES])
@@ -80,10 +80,9 @@ def test_full_size_family(name, shapes):
     P = H.Problem(s0.N, s0.K, s0.group, W=W)
     acts = {}
     for shp in shapes:
-        acts[shp.M] = WL.make_activations(shp.M, shp.K, shp.outlier_frac, seed=shp.seed + 1000 + shp.M)
-    xsums = {M: X.astype(np.float64).sum(axis=0) for M, (X, _) in acts.items()}
-    _say(f"{name}: oracle column sums")
-    colsum, rowdot, s_w_oracle = _oracle_column_sums(P, xsums)
+        acts[shp.M] = I.make_activations(shp.M, shp.K, shp.outlier_frac, seed=shp.seed + 1000 + shp.M)
+    _say(f"{name}: exact float64 product of the oracle's weights for {sorted(acts)} rows")
+    acc_ref, s_w_oracle = _oracle_exact_products(P, acts)
     assert np.array_equal(P.w_scales.view(np.uint32), s_w_oracle.view(np.uint32)), "level-1 scales differ"
 
     pick = np.random.default_rng(17)
@@ -99,18 +98,15 @@ def test_full_size_family(name, shapes):
         torch.cuda.synchronize()
         ACC = ACC.cpu().numpy()
         Y = Y.cpu().numpy()
-        # checksums over every accumulator
-        got_rows = ACC.sum(axis=1, dtype=np.int64)
-        assert np.array_equal(got_rows, X.astype(np.int64) @ colsum), f"{shp.name}: row checksums differ"
-        got_cols = ACC.sum(axis=0, dtype=np.int64).astype(np.float64)
-        assert np.array_equal(got_cols, rowdot[M]), f"{shp.name}: column checksums differ"
+        # every accumulator against the exact product
+        assert np.array_equal(ACC, acc_ref[M]), f"{shp.name}: {np.count_nonzero(ACC != acc_ref[M])} accumulators differ"
         # sampled outputs against the oracle, element by element
         m_idx = np.arange(M) if M <= 48 else np.sort(pick.choice(M, size=48, replace=False))
         ACC_ref, Y_ref64 = P.oracle_sampled(X, s_x, m_idx, n_idx)
         assert np.array_equal(ACC[np.ix_(m_idx, n_idx)], ACC_ref), f"{shp.name}: sampled accumulators differ"
         H.assert_fp16_close(Y[np.ix_(m_idx, n_idx)], Y_ref64, shp.name)
-        # whole FP16 matrix against the epilogue definition applied to the accumulators
-        ref64 = O.scale_epilogue_f64(ACC, s_x, s_w_oracle)
+        # whole FP16 matrix against the epilogue definition applied to the exact product
+        ref64 = O.scale_epilogue_f64(acc_ref[M], s_x, s_w_oracle)
         H.assert_fp16_close(Y, ref64, shp.name + " (all outputs)")
         del ACC, Y, ref64, dX
     del P

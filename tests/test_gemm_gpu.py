@@ -12,6 +12,7 @@ from paper_2509_01229_amd import api
 from paper_2509_01229_amd import workloads as WL
 
 import gpu_helpers as H
+import inputs as I
 
 pytestmark = pytest.mark.gpu
 
@@ -82,7 +83,7 @@ SMALL = [
 @pytest.mark.parametrize("M,N,K,g", SMALL)
 def test_every_variant_bit_exact(M, N, K, g):
     P = H.Problem(N, K, g, seed=M * 7 + N)
-    X, s_x = WL.make_activations(M, K, outlier_frac=0.01, seed=M + K)
+    X, s_x = I.make_activations(M, K, outlier_frac=0.01, seed=M + K)
     ACC_ref, Y_ref = P.oracle_gemm(X, s_x)
     q = P.oracle_full()
     ref64 = O.scale_epilogue_f64(ACC_ref, s_x, q["s_w"])
@@ -137,7 +138,7 @@ def test_extreme_weight_ranges(style):
     _say(f"extreme weights style={style}")
     Q = WL.make_q_i8(N, K, seed=9, style=style)
     P = H.Problem(N, K, g, Q_i8=Q)
-    X, s_x = WL.make_activations(M, K, seed=1)
+    X, s_x = I.make_activations(M, K, seed=1)
     X[0, :] = 127
     ACC_ref, _ = P.oracle_gemm(X, s_x)
     for v in H.variants_for(M, N, K, g):
@@ -149,7 +150,7 @@ def test_fp16_overflow_and_tiny_scales():
     M, N, K, g = 4, 64, 256, 64
     _say("fp16 overflow / underflow")
     P = H.Problem(N, K, g, seed=2)
-    X, _ = WL.make_activations(M, K, seed=2)
+    X, _ = I.make_activations(M, K, seed=2)
     s_x = np.array([1e4, 1e-3, 1e-9, 1.0], dtype=np.float32)
     ACC_ref, _ = P.oracle_gemm(X, s_x)
     ref64 = O.scale_epilogue_f64(ACC_ref, s_x, P.oracle_full()["s_w"])
@@ -169,7 +170,7 @@ def test_empty_batch_and_determinism():
     Y0 = api.w4a8_gemm(X0, s0, P.d_packed, P.d_gparams, P.d_w_scales, N, K, g)
     assert tuple(Y0.shape) == (0, N)
     _say("determinism")
-    X, s_x = WL.make_activations(16, K, seed=8)
+    X, s_x = I.make_activations(16, K, seed=8)
     a1 = P.run(X, s_x)
     a2 = P.run(X, s_x)
     assert np.array_equal(a1[1], a2[1]) and np.array_equal(a1[0].view(np.uint16), a2[0].view(np.uint16))
@@ -202,7 +203,7 @@ def test_workspace_is_optional_for_the_dispatcher():
         _say(f"small workspace M={M} N={N} K={K}")
         assert api.w4a8_gemm_workspace_size(M, N, K, g) > 16
         P = H.Problem(N, K, g, seed=11)
-        X, s_x = WL.make_activations(M, K, seed=12)
+        X, s_x = I.make_activations(M, K, seed=12)
         ACC_ref, _ = P.oracle_gemm(X, s_x)
         dX = torch.from_numpy(X).cuda()
         tiny = torch.empty(16, dtype=torch.uint8, device="cuda")
@@ -250,7 +251,7 @@ def test_random_shapes_through_the_dispatcher():
         picked = api.w4a8_variant_name(api.w4a8_select_variant(M, N, K, g))
         _say(f"random shape {case}: M={M} N={N} K={K} g={g} -> {picked}")
         P = H.Problem(N, K, g, seed=1000 + case)
-        X, s_x = WL.make_activations(M, K, outlier_frac=0.01, seed=2000 + case)
+        X, s_x = I.make_activations(M, K, outlier_frac=0.01, seed=2000 + case)
         ACC_ref, _ = P.oracle_gemm(X, s_x)
         ref64 = O.scale_epilogue_f64(ACC_ref, s_x, P.oracle_full()["s_w"])
         dX, dsx = torch.from_numpy(X).cuda(), torch.from_numpy(s_x).cuda()
@@ -280,7 +281,7 @@ def test_random_large_grids_through_the_dispatcher():
         seen.add(picked)
         _say(f"large grid {case}: M={M} N={N} K={K} g={g} -> {picked}")
         P = H.Problem(N, K, g, seed=500 + case)
-        X, s_x = WL.make_activations(M, K, outlier_frac=0.01, seed=900 + case)
+        X, s_x = I.make_activations(M, K, outlier_frac=0.01, seed=900 + case)
         Wd, s_w = P.oracle_wd()
         ref = X.astype(np.float64) @ Wd.astype(np.float64).T      # exact: |acc| < 2^31 << 2^53
         dX, dsx = torch.from_numpy(X).cuda(), torch.from_numpy(s_x).cuda()
@@ -320,7 +321,7 @@ def test_random_small_batches_through_the_dispatcher():
         seen.add(picked)
         _say(f"small batch {case}: M={M} N={N} K={K} g={g} -> {picked}")
         P = H.Problem(N, K, g, seed=700 + case)
-        X, s_x = WL.make_activations(M, K, outlier_frac=0.01, seed=1100 + case)
+        X, s_x = I.make_activations(M, K, outlier_frac=0.01, seed=1100 + case)
         Wd, s_w = P.oracle_wd()
         ref = X.astype(np.float64) @ Wd.astype(np.float64).T      # exact: |acc| < 2^31 << 2^53
         dX, dsx = torch.from_numpy(X).cuda(), torch.from_numpy(s_x).cuda()
@@ -373,7 +374,7 @@ def test_wide_layer_large_grid():
     P = H.Problem(N, K, g, seed=31)
     Wd, _ = P.oracle_wd()
     for M in (2, 20, 50, 130):
-        X, s_x = WL.make_activations(M, K, seed=M)
+        X, s_x = I.make_activations(M, K, seed=M)
         ACC = api.w4a8_gemm_i32(torch.from_numpy(X).cuda(), P.d_packed, P.d_gparams, N, K, g)
         torch.cuda.synchronize()
         ref = X.astype(np.float64) @ Wd.astype(np.float64).T
@@ -392,8 +393,8 @@ def test_hip_graph_replays_of_split_k_kernels():
         picked = api.w4a8_variant_name(api.w4a8_select_variant(M, N, K, g))
         _say(f"graph replay M={M} N={N} K={K} -> {picked}")
         P = H.Problem(N, K, g, seed=M)
-        X, s_x = WL.make_activations(M, K, seed=M + 1)
-        X2, s_x2 = WL.make_activations(M, K, seed=M + 2)
+        X, s_x = I.make_activations(M, K, seed=M + 1)
+        X2, s_x2 = I.make_activations(M, K, seed=M + 2)
         dX, dsx = torch.from_numpy(X).cuda(), torch.from_numpy(s_x).cuda()
         dX2, dsx2 = torch.from_numpy(X2).cuda(), torch.from_numpy(s_x2).cuda()
         ws = torch.zeros(api.w4a8_gemm_workspace_size(M, N, K, g) + 16, dtype=torch.uint8, device="cuda")
@@ -425,7 +426,7 @@ def test_workspace_init_and_concurrent_streams():
     M, N, K, g = 8, 1024, 8192, 64          # stream16 with grid split-K
     assert api.w4a8_variant_name(api.w4a8_select_variant(M, N, K, g)).startswith("stream16")
     P = H.Problem(N, K, g, seed=77)
-    X, s_x = WL.make_activations(M, K, seed=78)
+    X, s_x = I.make_activations(M, K, seed=78)
     ACC_ref, _ = P.oracle_gemm(X, s_x)
     ref = torch.from_numpy(ACC_ref).cuda()
     dX = torch.from_numpy(X).cuda()
@@ -450,3 +451,41 @@ def test_workspace_init_and_concurrent_streams():
     for o in outs:
         for t in o:
             assert torch.equal(t, ref)
+
+
+def test_batch_beyond_32_bit_offsets_of_x():
+    """M * K just above 2^32 (the kernels address X with 32-bit byte offsets; the entry point
+    runs such a batch as consecutive row chunks): every accumulator and every FP16 output
+    against the exact float64 product of the oracle's weights, for the dispatcher's kernel
+    (w4a8_gemm, w4a8_gemm_i32) and, on the rows around the chunk boundary, for a named tiled
+    variant."""
+    import torch
+
+    N, K, g = 64, 131072, 128
+    M = (1 << 32) // K + 64                       # 32832 rows: M * K = 2^32 + 2^23
+    assert M * K > (1 << 32)
+    _say(f"M*K beyond 2^32: M={M} N={N} K={K}")
+    P = H.Problem(N, K, g, sigma=0.02, seed=5)
+    Wd, s_w = P.oracle_wd()
+    WfT = np.ascontiguousarray(Wd.astype(np.float64).T)
+    rng = np.random.Generator(np.random.PCG64(6))
+    X = rng.integers(-127, 128, size=(M, K), dtype=np.int8)
+    X[-1] = 127                                   # the last row of the last chunk is distinctive
+    s_x = (0.5 + rng.random(M, dtype=np.float32)) * np.float32(1e-4)
+    ref = np.empty((M, N), dtype=np.int32)
+    for r0 in range(0, M, 2048):
+        prod = X[r0:r0 + 2048].astype(np.float64) @ WfT
+        assert np.abs(prod).max() < 2.0 ** 31
+        ref[r0:r0 + 2048] = prod.astype(np.int32)
+    _say("GPU run")
+    dX, dsx = torch.from_numpy(X).cuda(), torch.from_numpy(s_x).cuda()
+    ACC = api.w4a8_gemm_i32(dX, P.d_packed, P.d_gparams, N, K, g)
+    Y = api.w4a8_gemm(dX, dsx, P.d_packed, P.d_gparams, P.d_w_scales, N, K, g)
+    torch.cuda.synchronize()
+    assert np.array_equal(ACC.cpu().numpy(), ref), "accumulators differ"
+    H.assert_fp16_close(Y.cpu().numpy(), O.scale_epilogue_f64(ref, s_x, s_w), "M*K beyond 2^32")
+    names = api.w4a8_variant_names()
+    _, ACC2 = api.w4a8_gemm_variant(names.index("duo_m128_s1"), dX, dsx, P.d_packed, P.d_gparams, P.d_w_scales,
+                                    N, K, g, want_y=False)
+    torch.cuda.synchronize()
+    assert np.array_equal(ACC2.cpu().numpy(), ref), "accumulators of the named variant differ"

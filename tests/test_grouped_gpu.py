@@ -11,6 +11,7 @@ from paper_2509_01229_amd import api
 from paper_2509_01229_amd import workloads as WL
 
 import gpu_helpers as H
+import inputs as I
 
 pytestmark = pytest.mark.gpu
 
@@ -38,7 +39,7 @@ class Experts:
 
         offs = np.concatenate([[0], np.cumsum(rows)]).astype(int)
         M = int(offs[-1])
-        X, s_x = WL.make_activations(M, self.K, outlier_frac=0.01, seed=seed)
+        X, s_x = I.make_activations(M, self.K, outlier_frac=0.01, seed=seed)
         ACC_ref, _ = O.grouped_w4a8_gemm(X, s_x, offs, self.oracle)
         s_w_rows = np.concatenate([np.repeat(self.oracle[e]["s_w"][None, :], rows[e], axis=0)
                                    for e in range(self.E)]) if M else np.zeros((0, self.N), np.float32)
@@ -138,7 +139,7 @@ def test_grouped_full_size_layer_all_families():
     d_gparams = torch.from_numpy(np.concatenate([p[1] for p in packs])).cuda()
     d_sw = torch.from_numpy(np.stack([p[2] for p in packs])).cuda()
     offs = np.concatenate([[0], np.cumsum(rows)]).astype(int)
-    X, s_x = WL.make_activations(int(offs[-1]), K, outlier_frac=0.001, seed=77)
+    X, s_x = I.make_activations(int(offs[-1]), K, outlier_frac=0.001, seed=77)
     Y, ACC = api.w4a8_grouped_gemm(offs, torch.from_numpy(X).cuda(), torch.from_numpy(s_x).cuda(), d_packed,
                                    d_gparams, d_sw, N, K, g, want_y=True, want_acc=True)
     torch.cuda.synchronize()

@@ -14,6 +14,8 @@ from oracle import c_oracle
 from oracle import lqq_oracle as O
 from paper_2509_01229_amd import workloads as WL
 
+import inputs as I
+
 
 # --------------------------------------------------------------------------
 # Worked example of Sec. 4 (values from tests/golden/worked_example_sec4.txt)
@@ -128,6 +130,28 @@ def test_constant_group_takes_scale_one():
     Q_u4, s_u8, mn = O.level2_quantize(Q, 64)
     assert (s_u8 == 1).all() and (Q_u4 == 0).all() and (mn == -7).all()
     assert (O.dequant_plain(Q_u4, s_u8, mn, 64) == -7).all()
+
+
+def test_level2_codes_round_half_up_hand_example():
+    """The tie rule of Eq. 7's rounding to nearest, worked by hand.  A group whose values
+    span 0..30 has s_u8 = round(30 / 15) = 2, so every odd Q_u8 is a tie: 1/2 = 0.5,
+    3/2 = 1.5, 5/2 = 2.5.  Half-up (the reading taken) gives codes 1, 2, 3; half-to-even
+    would give 0, 2, 2 and half-down 0, 1, 2, so this one group tells the three apart.
+    The shifted group (min = -50) must give the same codes."""
+    for shift in (0, -50):
+        Q = np.zeros((1, 64), dtype=np.int8)
+        Q[0, :6] = np.array([0, 1, 3, 5, 29, 30]) + shift
+        Q[0, 6:] = shift
+        Q_u4, s_u8, mn = O.level2_quantize(Q, 64)
+        assert s_u8[0, 0] == 2 and mn[0, 0] == shift
+        assert Q_u4[0, :6].tolist() == [0, 1, 2, 3, 15, 15]
+        # what the codes decode to (Eq. 8): multiples of s above the minimum
+        assert O.dequant_plain(Q_u4, s_u8, mn, 64)[0, :6].tolist() == [shift + v for v in (0, 2, 4, 6, 30, 30)]
+    # a tie at s = 4 (R = 60): Q_u8 = 2, 6, 10 -> 0.5, 1.5, 2.5 -> codes 1, 2, 3
+    Q = np.zeros((1, 64), dtype=np.int8)
+    Q[0, :4] = [2, 6, 10, 60]
+    Q_u4, s_u8, _ = O.level2_quantize(Q, 64)
+    assert s_u8[0, 0] == 4 and Q_u4[0, :4].tolist() == [1, 2, 3, 15]
 
 
 def test_groups_run_along_k():
@@ -245,7 +269,7 @@ def test_epilogue_exact_cases():
 # --------------------------------------------------------------------------
 def test_whole_path_tiny_config_three_ways():
     shp = WL.TINY[0]
-    W, X, s_x = WL.make_problem(shp)
+    W, X, s_x = I.make_problem(shp)
     q = O.quantize_weights(W, shp.group)
     ACC, Y = O.w4a8_gemm(X, s_x, q["packed"], q["s_u8"], q["a"], q["s_w"], shp.group)
     ACC_c, Y_c = c_oracle.w4a8_gemm(X, s_x, q["packed"], q["s_u8"], q["a"], q["s_w"], shp.group)
@@ -274,7 +298,7 @@ def test_whole_path_tiny_config_three_ways():
 @pytest.mark.parametrize("M,N,K,g,seed", [(1, 64, 256, 64, 1), (5, 128, 512, 128, 2), (17, 64, 768, 64, 3)])
 def test_c_oracle_matches_numpy_oracle(M, N, K, g, seed):
     W = WL.make_weights(N, K, seed=seed)
-    X, s_x = WL.make_activations(M, K, outlier_frac=0.01, seed=seed + 100)
+    X, s_x = I.make_activations(M, K, outlier_frac=0.01, seed=seed + 100)
     q = O.quantize_weights(W, g)
     ACC, Y = O.w4a8_gemm(X, s_x, q["packed"], q["s_u8"], q["a"], q["s_w"], g)
     ACC_c, Y_c = c_oracle.w4a8_gemm(X, s_x, q["packed"], q["s_u8"], q["a"], q["s_w"], g)

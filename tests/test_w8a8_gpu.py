@@ -11,6 +11,7 @@ from paper_2509_01229_amd import api
 from paper_2509_01229_amd import workloads as WL
 
 import gpu_helpers as H
+import inputs as I
 
 pytestmark = pytest.mark.gpu
 
@@ -38,7 +39,7 @@ def test_w8a8_matches_oracle(M, N, K):
     rng = np.random.default_rng(M + N + K)
     W = WL.make_weights(N, K, 0.02, rng=rng)
     Q_i8, s_w = O.level1_quantize(W)
-    X, s_x = WL.make_activations(M, K, outlier_frac=0.01, seed=M)
+    X, s_x = I.make_activations(M, K, outlier_frac=0.01, seed=M)
     ACC_ref, _ = O.w8a8_gemm(X, s_x, Q_i8, s_w)
     ref64 = O.scale_epilogue_f64(ACC_ref, s_x, s_w)
     dW = torch.from_numpy(api.w8a8_pack_weights(Q_i8)).cuda()
@@ -63,7 +64,7 @@ def test_w8a8_on_dequantised_weights_equals_w4a8():
     M, N, K, g = 260, 512, 2048, 64
     _say("w8a8 vs w4a8 on the same dequantised weights")
     P = H.Problem(N, K, g, seed=9)
-    X, s_x = WL.make_activations(M, K, outlier_frac=0.002, seed=10)
+    X, s_x = I.make_activations(M, K, outlier_frac=0.002, seed=10)
     Wd = api.w4a8_dequant_dump(P.d_packed, P.d_gparams, N, K, g)
     torch.cuda.synchronize()
     Wd_ref, _ = P.oracle_wd()
