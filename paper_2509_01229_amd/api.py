@@ -216,6 +216,8 @@ def _ws(workspace, M=0, N=0, K=0, group=64, device=None, stream=None):
     import torch
 
     if workspace is None:
+        if device is not None and torch.device(device).type != "cuda":
+            raise TypeError("X must be a torch tensor on the GPU")
         need = w4a8_gemm_workspace_size(M, N, K, group) if M > 0 else 0
         if need == 0:
             return None, 0
