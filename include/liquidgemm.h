@@ -126,6 +126,24 @@ int w4a8_gemm(int M, int N, int K, int group, const int8_t *X, const float *act_
               const void *W_packed, const uint8_t *gparams, const float *w_scales, uint16_t *Y,
               void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* w4a8_gemm for callers that cannot allocate device memory or pass a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments
+ * without the workspace, same kernels, same result bit for bit.  The split-K state lives in
+ * a workspace built into the library, 32 KiB of tickets + 32 MiB of partial tiles of static
+ * device memory per GPU, held until the process ends; the call allocates nothing (no
+ * hipMalloc / hipFree, no allocating library routine) and only enqueues kernels on
+ * `hip_stream`.
+ *   - Shapes whose dispatcher kernel would use more split-K workspace than that are rejected
+ *     with LQ_ERR_WORKSPACE (the message names both sizes); use w4a8_gemm with a workspace
+ *     of the caller for them.
+ *   - Every call on a GPU shares that GPU's built-in workspace: calls that may overlap in time
+ *     on one GPU (different streams, or graphs replayed concurrently) race on it and give
+ *     undefined results; calls ordered on one stream are safe.  The tickets are zero when the
+ *     library is loaded and every call leaves them zero; partial tiles need no clearing. */
+int w4a8_gemm_static(int M, int N, int K, int group, const int8_t *X, const float *act_scales,
+                     const void *W_packed, const uint8_t *gparams, const float *w_scales, uint16_t *Y,
+                     void *hip_stream);
+
 /* Parity hook: the raw INT32 accumulators ACC[M,N] (device, row-major) of the same
  * kernels, without the scaling epilogue. */
 int w4a8_gemm_i32(int M, int N, int K, int group, const int8_t *X, const void *W_packed,

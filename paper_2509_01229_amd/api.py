@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
     L.w4a8_workspace_init.argtypes = [vp, sz, vp]
     L.w4a8_gemm.restype = i
     L.w4a8_gemm.argtypes = [i, i, i, i, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.w4a8_gemm_static.restype = i
+    L.w4a8_gemm_static.argtypes = [i, i, i, i, vp, vp, vp, vp, vp, vp, vp]
     L.w4a8_gemm_i32.restype = i
     L.w4a8_gemm_i32.argtypes = [i, i, i, i, vp, vp, vp, vp, vp, sz, vp]
     L.w4a8_gemm_variant.restype = i
@@ -252,6 +254,22 @@ def w4a8_gemm(X, act_scales, W_packed, gparams, w_scales, N: int, K: int, group:
                            _dev(gparams, torch.uint8, (gb,), "gparams"),
                            _dev(w_scales, torch.float32, (N,), "w_scales"),
                            _dev(out, torch.float16, (M, N), "out"), wsp, wsb, _stream(stream)))
+    return out
+
+
+def w4a8_gemm_static(X, act_scales, W_packed, gparams, w_scales, N: int, K: int, group: int, out, stream=None):
+    """w4a8_gemm on the library's built-in split-K workspace: nothing is allocated, so `out`
+    ([M,N] float16 on the GPU) must be given."""
+    import torch
+
+    M = X.shape[0]
+    cb, gb = liquidquant_packed_size(N, K, group)
+    _check(lib().w4a8_gemm_static(M, N, K, group, _dev(X, torch.int8, (M, K), "X"),
+                                  _dev(act_scales, torch.float32, (M,), "act_scales"),
+                                  _dev(W_packed, torch.uint8, (cb,), "W_packed"),
+                                  _dev(gparams, torch.uint8, (gb,), "gparams"),
+                                  _dev(w_scales, torch.float32, (N,), "w_scales"),
+                                  _dev(out, torch.float16, (M, N), "out"), _stream(stream)))
     return out
 
 

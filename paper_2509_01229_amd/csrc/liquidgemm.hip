@@ -34,9 +34,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
-#include <map>
 #include <mutex>
-#include <utility>
 
 #include "lqq_common.h"
 #include "lqq_device.h"
@@ -108,6 +106,7 @@ struct Args {
     hipStream_t stream;
     void *ws;
     size_t ws_bytes;
+    size_t *query = nullptr;  // set: store the workspace bytes the launch would use and launch nothing
 };
 
 typedef int (*LaunchFn)(const Args &);
@@ -117,17 +116,26 @@ typedef int (*LaunchFn)(const Args &);
 // instead of a runtime call.
 static int allow_lds_once(const void *kernel, size_t bytes)
 {
+    struct Grant {
+        int dev;
+        const void *kernel;
+        size_t bytes;
+    };
     static std::mutex mu;
-    static std::map<std::pair<int, const void *>, size_t> granted;
+    static Grant granted[512];  // (device, kernel) pairs seen so far; no heap
+    static int count = 0;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return fail(LQ_ERR_HIP, "hipGetDevice failed");
     std::lock_guard<std::mutex> lock(mu);
-    size_t &have = granted[{dev, kernel}];
-    if (have >= bytes) return LQ_OK;
+    Grant *g = nullptr;
+    for (int i = 0; i < count && !g; ++i)
+        if (granted[i].dev == dev && granted[i].kernel == kernel) g = &granted[i];
+    if (g && g->bytes >= bytes) return LQ_OK;
     const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
     if (e != hipSuccess)
         return fail(LQ_ERR_HIP, "hipFuncSetAttribute(%zu bytes of LDS): %s", bytes, hipGetErrorString(e));
-    have = bytes;
+    if (!g && count < 512) g = &granted[count++];
+    if (g) *g = Grant{dev, kernel, bytes};  // a full table only means asking again next time
     return LQ_OK;
 }
 template <class Kernel>
@@ -167,6 +175,7 @@ static int launch_stream_as(const Args &a, int S, bool named)
     S = std::max(1, std::min(S, a.K / 128));
     if (S > 1 && groups > kMaxTicketGroups) S = 1;
     size_t need = stream_ws_bytes(a.M, a.N, S, MF);
+    if (a.query) return *a.query = need, LQ_OK;
     if (need > 0 && (!a.ws || a.ws_bytes < need)) {
         if (named)
             return fail(LQ_ERR_WORKSPACE, "split-K needs %zu bytes of workspace, got %zu", need,
@@ -243,6 +252,7 @@ static int launch_stream16(const Args &a)
     S = std::min(S, a.K / (128 * UU));
     if (S > 1 && groups > kMaxTicketGroups) S = 1;
     size_t need = S > 1 ? kTicketBytes + (size_t)S * (a.N / 32) * 8 * 64 * sizeof(int32_t) : 0;
+    if (a.query) return *a.query = need, LQ_OK;
     if (need > 0 && (!a.ws || a.ws_bytes < need)) {
         if (SPLIT)
             return fail(LQ_ERR_WORKSPACE, "split-K needs %zu bytes of workspace, got %zu", need,
@@ -269,6 +279,7 @@ static int launch_stream16(const Args &a)
 template <int MF>
 static int launch_tile(const Args &a)
 {
+    if (a.query) return LQ_OK;  // no workspace
     constexpr int WM = 32 * MF;
     const int blocks_n = (a.N + 255) / 256, blocks_m = (a.M + WM - 1) / WM;
     const size_t lds_bytes = 2 * (size_t)WM * kTilePitch;
@@ -317,6 +328,7 @@ static int launch_duo_as(const Args &a, int S)
     S = std::min(S, a.K / (256 * KG));  // every k group of every slice gets at least one unit
     if (blocks_n * blocks_m > kMaxTicketGroups || S < 1) S = 1;
     size_t need = duo_ws_bytes(a.M, a.N, S, TM);
+    if (a.query) return *a.query = need, LQ_OK;
     if (need > 0 && (!a.ws || a.ws_bytes < need)) {
         if (SPLIT)
             return fail(LQ_ERR_WORKSPACE, "split-K needs %zu bytes of workspace, got %zu", need,
@@ -381,6 +393,7 @@ static int launch_duo_dl(const Args &a)
     int S = std::min(std::max(1, SPLIT), a.K / 256);
     if (blocks_n * blocks_m > kMaxTicketGroups) S = 1;
     const size_t need = duo_ws_bytes(a.M, a.N, S);
+    if (a.query) return *a.query = need, LQ_OK;
     if (need > 0 && (!a.ws || a.ws_bytes < need))
         return fail(LQ_ERR_WORKSPACE, "split-K needs %zu bytes of workspace, got %zu", need, a.ws ? a.ws_bytes : 0);
     const size_t lds_bytes = 4 * (size_t)128 * 128;
@@ -402,6 +415,7 @@ static int launch_duo_dl(const Args &a)
 // the explicit producer / consumer form (measured only, never dispatched)
 static int launch_excp(const Args &a)
 {
+    if (a.query) return LQ_OK;  // no workspace
     const int blocks_n = (a.N + 255) / 256, blocks_m = (a.M + 127) / 128;
     if ((long long)a.M * a.K >= (1ll << 32))
         return fail(LQ_ERR_INVALID, "M * K = %lld is beyond the 2^32 - 1 bytes of X one call addresses; split the batch",
@@ -424,6 +438,7 @@ static int launch_excp(const Args &a)
 // (the dequantisation half of the paper's ablation, Sec. 7.3; measured only, never dispatched).
 static int launch_duo_widened(const Args &a)
 {
+    if (a.query) return LQ_OK;  // no workspace
     const int blocks_n = (a.N + 255) / 256, blocks_m = (a.M + 127) / 128;
     const size_t lds_bytes = 2 * (size_t)128 * kTilePitch;
     const dim3 grid((unsigned)(blocks_n * blocks_m), 1u), block(256);
@@ -641,15 +656,20 @@ static int run(int variant, const Args &a)
     // alignment and the tile grid of a call of its own) on the same stream; rows are
     // independent, so the result is that of one launch.
     const long long rows_max = ((1ll << 32) - 1) / a.K / 128 * 128;
+    size_t need_max = 0;
     for (long long r0 = 0; r0 < a.M; r0 += rows_max) {
         Args c = a;
+        size_t need = 0;
+        if (a.query) c.query = &need;
         c.M = (int)std::min<long long>(rows_max, a.M - r0);
         c.X = a.X + r0 * a.K;
         if (a.sx) c.sx = a.sx + r0;
         if (a.Y) c.Y = a.Y + r0 * a.N;
         if (a.ACC) c.ACC = a.ACC + r0 * a.N;
         if (int rc = kVariants[variant].fn(c)) return rc;
+        need_max = std::max(need_max, need);
     }
+    if (a.query) return *a.query = need_max, LQ_OK;
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return fail(LQ_ERR_HIP, "launch of %s failed: %s", kVariants[variant].name, hipGetErrorString(e));
@@ -780,6 +800,36 @@ static int grouped_run(const GroupedArgs &a)
     return LQ_OK;
 }
 
+// ------------------------------------------------------------------------------------
+// Built-in split-K workspace for callers that cannot allocate (w4a8_gemm_static): tickets
+// followed by partial tiles, laid out exactly like a caller's workspace.  Zero when the code
+// object is loaded; the kernels leave the tickets zero after every call.  The array's name
+// is only a host-side handle: its address on the current device comes from the runtime.
+// ------------------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes = kTicketBytes + ((size_t)32 << 20);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+
+static int static_scratch_ptr(void **out)
+{
+    static std::mutex mu;
+    static void *addr[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(LQ_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(LQ_ERR_INVALID, "device %d out of range", dev);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(LQ_ERR_HIP, "hipGetSymbolAddress(built-in workspace): %s", hipGetErrorString(e));
+        addr[dev] = p;
+    }
+    *out = addr[dev];
+    return LQ_OK;
+}
+
 }  // namespace lqq
 
 using namespace lqq;
@@ -821,6 +871,31 @@ int w4a8_gemm(int M, int N, int K, int group, const int8_t *X, const float *act_
     if (!Y && M != 0) return fail(LQ_ERR_INVALID, "null Y");
     const Args a{M, N, K, group, X, act_scales, static_cast<const u32x4 *>(W_packed), gparams, w_scales,
                  reinterpret_cast<__half *>(Y), nullptr, static_cast<hipStream_t>(hip_stream), workspace, workspace_bytes};
+    return run(-1, a);
+}
+
+int w4a8_gemm_static(int M, int N, int K, int group, const int8_t *X, const float *act_scales,
+                     const void *W_packed, const uint8_t *gparams, const float *w_scales, uint16_t *Y,
+                     void *hip_stream)
+{
+    if (!Y && M != 0) return fail(LQ_ERR_INVALID, "null Y");
+    Args a{M, N, K, group, X, act_scales, static_cast<const u32x4 *>(W_packed), gparams, w_scales,
+           reinterpret_cast<__half *>(Y), nullptr, static_cast<hipStream_t>(hip_stream), nullptr, 0};
+    // what the dispatcher's kernel for this shape would use of a workspace (nothing is launched)
+    size_t need = 0;
+    a.query = &need;
+    if (int rc = run(-1, a)) return rc;
+    a.query = nullptr;
+    if (M == 0) return LQ_OK;
+    if (need > kStaticScratchBytes)
+        return fail(LQ_ERR_WORKSPACE,
+                    "M=%d N=%d K=%d needs %zu bytes of split-K workspace, the built-in one holds %zu: "
+                    "use w4a8_gemm with a workspace of the caller",
+                    M, N, K, need, kStaticScratchBytes);
+    if (need > 0) {
+        if (int rc = static_scratch_ptr(&a.ws)) return rc;
+        a.ws_bytes = kStaticScratchBytes;
+    }
     return run(-1, a);
 }
 
