@@ -103,6 +103,26 @@ __device__ __forceinline__ void duo_dl_tile(
                 p[t].raw = *reinterpret_cast<const uint32_t *>(pb + po);
         }
     };
+    // the same loads one piece / one tile at a time (for the pinned instruction order below)
+    auto issue_x1 = [&](int s, int buf, int i) {
+        s = min(s, stages - 1);
+        asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     : "+v"(wl)
+                     : "v"(xg[i % XP] + (uint32_t)s * 128), "s"(xbase), "s"(lds0 + buf * STAGE + (4 * i + wave) * 1024)
+                     : "memory", "m0");
+    };
+    auto load_w1 = [&](int s, int t, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
+        s = min(s, stages - 1);
+        const uint32_t wo = wl + (uint32_t)s * 2048, po = pl_off + (uint32_t)s * (G128 ? 64 : 128);
+        const char *wb = wbase + t * wg_stride;
+        const char *pb = pbase + t * pg_stride;
+        w[t][0] = *reinterpret_cast<const u32x4 *>(wb + wo);
+        w[t][1] = *reinterpret_cast<const u32x4 *>(wb + wo + 1024);
+        if (G128)
+            p[t].raw = *reinterpret_cast<const uint16_t *>(pb + po);
+        else
+            p[t].raw = *reinterpret_cast<const uint32_t *>(pb + po);
+    };
     auto build_b = [&](const u32x4 (&w)[2][2], const UnitParams<G128> (&p)[2], int c, int h, v4i (&b)[2]) {
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
@@ -161,6 +181,108 @@ __device__ __forceinline__ void duo_dl_tile(
         mma(af[1], bf[1]);
         __builtin_amdgcn_sched_barrier(0);
     };
+    // ---- the four-fragment tile: the same stage with its instruction order pinned ----------
+    // Left to itself the compiler emits the 8 MFMAs of a k-step in pairs and the dequantisation
+    // in runs of 20 to 30 vector instructions (serialised through one temporary, with a wait
+    // state between each packed multiply-add and its XOR), so the two waves of a SIMD often
+    // have no matrix instruction to offer at the same time.  Here every MFMA is followed by one
+    // phase of the dequantisation of one tile's four registers (shift, mask, multiply-add or
+    // XOR: four independent instructions) and, in the first half of the k-step, one fragment
+    // read from LDS; scheduling barriers keep that order.  An 8-pass MFMA leaves room for about
+    // four other vector instructions, so this is the densest order the k-step allows.
+    uint32_t s2v[2], a4v[2];  // broadcast parameters of the chunk whose B operands are being built
+    uint32_t tq[4];           // the four registers in flight through the phases
+    auto SB = [] { __builtin_amdgcn_sched_barrier(0); };
+    auto mm = [&](int i, const v4i (&a)[MF], const v4i (&b)[2]) {
+        acc[(i >> 1) % MF][i & 1] = mfma_i8(a[(i >> 1) % MF], b[i & 1], acc[(i >> 1) % MF][i & 1]);
+    };
+    auto rd = [&](int buf, int c, int h, int mf, v4i (&a)[MF]) {
+        a[mf % MF] = *reinterpret_cast<const v4i *>(xs + 16 * ((4 * c + 2 * h + kb) ^ jr) + buf * STAGE + (mf % MF) * 4096);
+    };
+    auto ph_par = [&](const UnitParams<G128> (&p)[2], int c) {
+        p[0].get(c, s2v[0], a4v[0]);
+        p[1].get(c, s2v[1], a4v[1]);
+    };
+    auto ph_shr = [&](const u32x4 &w) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) tq[d] = w[d] >> 4;
+    };
+    auto ph_and_hi = [&] {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) tq[d] &= 0x0F0F0F0Fu;
+    };
+    auto ph_and_lo = [&](const u32x4 &w) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) tq[d] = w[d] & 0x0F0F0F0Fu;
+    };
+    auto ph_mad = [&](int t) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) tq[d] = pk_mad_u16(tq[d], s2v[t], a4v[t]);
+    };
+    auto ph_xor = [&](v4i &b) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) b[d] = (int)(tq[d] ^ 0x80808080u);
+    };
+    // A fragments are single-buffered and refreshed in place: fragment 3 of the running k-step
+    // is read in its slot 0 (its registers were last used by slot 7 of the k-step before) and
+    // fragments 0..2 of the next k-step in slots 2, 4 and 6, right behind their last use;
+    // every read is six MFMAs ahead of its first use.  (cb, cc, ch) = LDS stage, chunk and half
+    // of the running k-step, (nb, nc, nh) of the next one.
+    v4i (&a1)[MF] = af[0];
+    // k-step that multiplies (a1, bc) and builds bn = B(c, 1) of w
+    auto kstep_hi = [&](const v4i (&bc)[2], v4i (&bn)[2], const u32x4 (&w)[2][2], int c, int cb, int cc, int ch,
+                        int nb, int nc, int nh) {
+        mm(0, a1, bc); rd(cb, cc, ch, 3, a1); ph_shr(w[0][c]); SB();
+        mm(1, a1, bc); ph_and_hi(); SB();
+        mm(2, a1, bc); rd(nb, nc, nh, 0, a1); ph_mad(0); SB();
+        mm(3, a1, bc); ph_xor(bn[0]); SB();
+        mm(4, a1, bc); rd(nb, nc, nh, 1, a1); ph_shr(w[1][c]); SB();
+        mm(5, a1, bc); ph_and_hi(); SB();
+        mm(6, a1, bc); rd(nb, nc, nh, 2, a1); ph_mad(1); SB();
+        mm(7, a1, bc); ph_xor(bn[1]); SB();
+    };
+    // k-step that multiplies (a1, bc) and builds bn = B(c, 0) of (w, p)
+    auto kstep_lo = [&](const v4i (&bc)[2], v4i (&bn)[2], const u32x4 (&w)[2][2], const UnitParams<G128> (&p)[2],
+                        int c, int cb, int cc, int ch, int nb, int nc, int nh) {
+        mm(0, a1, bc); rd(cb, cc, ch, 3, a1); ph_par(p, c); SB();
+        mm(1, a1, bc); ph_and_lo(w[0][c]); SB();
+        mm(2, a1, bc); rd(nb, nc, nh, 0, a1); ph_mad(0); SB();
+        mm(3, a1, bc); ph_xor(bn[0]); SB();
+        mm(4, a1, bc); rd(nb, nc, nh, 1, a1); ph_and_lo(w[1][c]); SB();
+        mm(5, a1, bc); ph_mad(1); SB();
+        mm(6, a1, bc); rd(nb, nc, nh, 2, a1); ph_xor(bn[1]); SB();
+        mm(7, a1, bc); SB();
+    };
+    // One stage, same contract as stage() above (bf[0] holds B(0, 0) of the stage on entry and
+    // of the next stage on exit).  The last k-step builds that next B(0, 0); the stage barrier
+    // sits behind its second MFMA, before the first fragment read of the next stage, and the
+    // prefetches follow the last MFMA.
+    auto stage_pinned = [&](int s, u32x4 (&w_cur)[2][2], UnitParams<G128> (&p_cur)[2], u32x4 (&w_nxt)[2][2],
+                            UnitParams<G128> (&p_nxt)[2], auto tail_tag) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
+        const int buf = s & 3, nbuf = (s + 1) & 3;
+        kstep_hi(bf[0], bf[1], w_cur, 0, buf, 0, 0, buf, 0, 1);
+        kstep_lo(bf[1], bf[0], w_cur, p_cur, 1, buf, 0, 1, buf, 1, 0);
+        kstep_hi(bf[0], bf[1], w_cur, 1, buf, 1, 0, buf, 1, 1);
+        mm(0, a1, bf[1]); rd(buf, 1, 1, 3, a1); ph_par(p_nxt, 0); SB();
+        mm(1, a1, bf[1]); ph_and_lo(w_nxt[0][0]);
+        asm volatile("" : "+v"(tq[0]), "+v"(tq[1]), "+v"(tq[2]), "+v"(tq[3]));  // (that use of W(s+1) stays above the barrier, see stage())
+        if (TAIL)
+            wait_vmcnt0();
+        else
+            wait_vmcnt<PER_STAGE>();
+        // X(s+1) is complete and visible and every wave is done reading X(s-1), whose LDS stage
+        // the prefetches below refill.  No wait for this wave's own fragment reads still in
+        // flight: they are of stage s, which nothing overwrites before the next barrier.
+        asm volatile("s_barrier" ::: "memory");
+        SB();
+        mm(2, a1, bf[1]); rd(nbuf, 0, 0, 0, a1); ph_mad(0); if (!TAIL) issue_x1(s + 3, (s + 3) & 3, 0); SB();
+        mm(3, a1, bf[1]); ph_xor(bf[0][0]); if (!TAIL) issue_x1(s + 3, (s + 3) & 3, 1); SB();
+        mm(4, a1, bf[1]); rd(nbuf, 0, 0, 1, a1); ph_and_lo(w_nxt[1][0]); if (!TAIL) issue_x1(s + 3, (s + 3) & 3, 2); SB();
+        mm(5, a1, bf[1]); ph_mad(1); if (!TAIL) issue_x1(s + 3, (s + 3) & 3, 3); SB();
+        mm(6, a1, bf[1]); rd(nbuf, 0, 0, 2, a1); ph_xor(bf[0][1]); if (!TAIL) load_w1(s + 3, 0, w_cur, p_cur); SB();
+        mm(7, a1, bf[1]); if (!TAIL) load_w1(s + 3, 1, w_cur, p_cur); SB();
+    };
     const std::false_type body{};
     const std::true_type tail{};
 
@@ -174,23 +296,43 @@ __device__ __forceinline__ void duo_dl_tile(
     load_w(2, wr[2], pr[2]);
     __builtin_amdgcn_sched_barrier(0);
     build_b(wr[0], pr[0], 0, 0, bf[0]);
+    ph_par(pr[0], 0);
     asm volatile("" : "+v"(bf[0][0]), "+v"(bf[0][1]));
     wait_vmcnt<2 * PER_STAGE>();
     lds_barrier_raw();
-    read_a(0, 0, 0, af[0]);
+    if constexpr (MF == 4) {
+        rd(0, 0, 0, 0, af[0]), rd(0, 0, 0, 1, af[0]), rd(0, 0, 0, 2, af[0]);  // the first k-step reads fragment 3 itself
+    } else {
+        read_a(0, 0, 0, af[0]);
+    }
     __builtin_amdgcn_sched_barrier(0);
 
     // Three stages per trip (one turn of the W registers) without branches inside, so that
     // every load stays where the in-flight count above expects it; the one or two stages
     // that may be left over run after the loop, waiting for everything still in flight.
     int s = 0;
-    for (; s + 3 <= stages; s += 3) {
-        stage(s, wr[0], pr[0], wr[1], pr[1], body);
-        stage(s + 1, wr[1], pr[1], wr[2], pr[2], body);
-        stage(s + 2, wr[2], pr[2], wr[0], pr[0], body);
+    if constexpr (MF == 4) {
+        for (; s + 3 <= stages; s += 3) {
+            stage_pinned(s, wr[0], pr[0], wr[1], pr[1], body);
+            stage_pinned(s + 1, wr[1], pr[1], wr[2], pr[2], body);
+            stage_pinned(s + 2, wr[2], pr[2], wr[0], pr[0], body);
+        }
+        // the one or two stages that may remain run in the compiler's own order (same contract,
+        // fragment 3 of their first k-step read here)
+        if (s < stages) {
+            rd(s & 3, 0, 0, 3, af[0]);
+            stage(s, wr[0], pr[0], wr[1], pr[1], tail);
+        }
+        if (s + 1 < stages) stage(s + 1, wr[1], pr[1], wr[2], pr[2], tail);
+    } else {
+        for (; s + 3 <= stages; s += 3) {
+            stage(s, wr[0], pr[0], wr[1], pr[1], body);
+            stage(s + 1, wr[1], pr[1], wr[2], pr[2], body);
+            stage(s + 2, wr[2], pr[2], wr[0], pr[0], body);
+        }
+        if (s < stages) stage(s, wr[0], pr[0], wr[1], pr[1], tail);
+        if (s + 1 < stages) stage(s + 1, wr[1], pr[1], wr[2], pr[2], tail);
     }
-    if (s < stages) stage(s, wr[0], pr[0], wr[1], pr[1], tail);
-    if (s + 1 < stages) stage(s + 1, wr[1], pr[1], wr[2], pr[2], tail);
     // the (clamped) prefetches past the last stage write LDS too: they must have landed
     // before the block ends and its LDS goes to another block
     wait_vmcnt0();
