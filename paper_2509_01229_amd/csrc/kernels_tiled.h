@@ -330,6 +330,115 @@ __device__ __forceinline__ void duo_tile(
         __builtin_amdgcn_sched_barrier(0);
     };
 
+    // ---- the four-fragment tile: the same stage with its instruction order pinned ----------
+    // (see duo_dl_tile: one phase of the dequantisation of one tile's four registers behind
+    // every MFMA, fragment reads in the first half of a k-step, the X stores, X loads and W
+    // loads of the stage one piece per MFMA; scheduling barriers keep the order)
+    uint32_t s2v[2], a4v[2];  // broadcast parameters of the chunk whose B operands are being built
+    uint32_t tq[4];           // the four registers in flight through the phases
+    auto SB = [] { __builtin_amdgcn_sched_barrier(0); };
+    auto mm = [&](int i, const v4i (&a)[MFC], const v4i (&b)[2]) {
+        acc[(i >> 1) % MFC][i & 1] = mfma_i8(a[(i >> 1) % MFC], b[i & 1], acc[(i >> 1) % MFC][i & 1]);
+    };
+    auto rd = [&](int buf, int c, int h, int mf, v4i (&a)[MFC]) {
+        a[mf % MFC] = *reinterpret_cast<const v4i *>(xs + buf * STAGE + (mf % MFC) * 32 * kTilePitch + 64 * c + 32 * h);
+    };
+    auto load_x1 = [&](int s, int i) {
+        if (KG > 1 && s >= my_stages) {
+            xr[i % XP] = u32x4{0, 0, 0, 0};
+            return;
+        }
+        s = min(s, my_stages - 1);
+        xr[i % XP] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)s * 128 + xg[i % XP]);
+    };
+    auto store_x1 = [&](int buf, int i) {
+        *reinterpret_cast<u32x4 *>(lds_g + buf * STAGE + xl + (i % XP) * 32 * kTilePitch) = xr[i % XP];
+    };
+    auto load_w1 = [&](int s, int t, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
+        s = min(s, my_stages - 1);
+        const u32x4 *wg = wg0 + t * wg_stride;
+        const uint8_t *pg = pg0 + t * pg_stride;
+        w[t][0] = wg[(size_t)s * 128];
+        w[t][1] = wg[(size_t)s * 128 + 64];
+        if (G128)
+            p[t].raw = *reinterpret_cast<const uint16_t *>(pg + (size_t)s * 64);
+        else
+            p[t].raw = *reinterpret_cast<const uint32_t *>(pg + (size_t)s * 128);
+    };
+    auto ph_par = [&](const UnitParams<G128> (&p)[2], int c) {
+        p[0].get(c, s2v[0], a4v[0]);
+        p[1].get(c, s2v[1], a4v[1]);
+    };
+    auto ph_shr = [&](const u32x4 &w) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) tq[d] = w[d] >> 4;
+    };
+    auto ph_and_hi = [&] {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) tq[d] &= 0x0F0F0F0Fu;
+    };
+    auto ph_and_lo = [&](const u32x4 &w) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) tq[d] = w[d] & 0x0F0F0F0Fu;
+    };
+    auto ph_mad = [&](int t) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) tq[d] = pk_mad_u16(tq[d], s2v[t], a4v[t]);
+    };
+    auto ph_xor = [&](v4i &b) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) b[d] = (int)(tq[d] ^ 0x80808080u);
+    };
+    // A fragments are single-buffered and refreshed in place (fragment 3 of the running k-step
+    // in its slot 0, fragments 0..2 of the next k-step in slots 2, 4 and 6, behind their last
+    // use).  With two LDS stages the stage barrier must find no read of the running stage in
+    // flight (the fence in lds_barrier() waits for them), so in the last k-step it sits behind
+    // the fourth MFMA, three slots after the last such read, and the first fragments of the
+    // next stage are read in slots 4 to 6.
+    auto stage_pinned = [&](int s, u32x4 (&w_cur)[2][2], UnitParams<G128> (&p_cur)[2], u32x4 (&w_nxt)[2][2],
+                            UnitParams<G128> (&p_nxt)[2], int buf) {
+        v4i (&a1)[MFC] = af[0];
+        // k-step (0,0): builds B(0,1), stores X(s+1) into the other LDS stage
+        mm(0, a1, bf[0]); rd(buf, 0, 0, 3, a1); ph_shr(w_cur[0][0]); SB();
+        mm(1, a1, bf[0]); store_x1(buf ^ 1, 0); ph_and_hi(); SB();
+        mm(2, a1, bf[0]); rd(buf, 0, 1, 0, a1); ph_mad(0); SB();
+        mm(3, a1, bf[0]); store_x1(buf ^ 1, 1); ph_xor(bf[1][0]); SB();
+        mm(4, a1, bf[0]); rd(buf, 0, 1, 1, a1); ph_shr(w_cur[1][0]); SB();
+        mm(5, a1, bf[0]); store_x1(buf ^ 1, 2); ph_and_hi(); SB();
+        mm(6, a1, bf[0]); rd(buf, 0, 1, 2, a1); ph_mad(1); SB();
+        mm(7, a1, bf[0]); store_x1(buf ^ 1, 3); ph_xor(bf[1][1]); SB();
+        // k-step (0,1): builds B(1,0), loads X(s+2)
+        mm(0, a1, bf[1]); rd(buf, 0, 1, 3, a1); ph_par(p_cur, 1); SB();
+        mm(1, a1, bf[1]); load_x1(s + 2, 0); ph_and_lo(w_cur[0][1]); SB();
+        mm(2, a1, bf[1]); rd(buf, 1, 0, 0, a1); ph_mad(0); SB();
+        mm(3, a1, bf[1]); load_x1(s + 2, 1); ph_xor(bf[0][0]); SB();
+        mm(4, a1, bf[1]); rd(buf, 1, 0, 1, a1); ph_and_lo(w_cur[1][1]); SB();
+        mm(5, a1, bf[1]); load_x1(s + 2, 2); ph_mad(1); SB();
+        mm(6, a1, bf[1]); rd(buf, 1, 0, 2, a1); ph_xor(bf[0][1]); SB();
+        mm(7, a1, bf[1]); load_x1(s + 2, 3); SB();
+        // k-step (1,0): builds B(1,1)
+        mm(0, a1, bf[0]); rd(buf, 1, 0, 3, a1); ph_shr(w_cur[0][1]); SB();
+        mm(1, a1, bf[0]); ph_and_hi(); SB();
+        mm(2, a1, bf[0]); rd(buf, 1, 1, 0, a1); ph_mad(0); SB();
+        mm(3, a1, bf[0]); ph_xor(bf[1][0]); SB();
+        mm(4, a1, bf[0]); rd(buf, 1, 1, 1, a1); ph_shr(w_cur[1][1]); SB();
+        mm(5, a1, bf[0]); ph_and_hi(); SB();
+        mm(6, a1, bf[0]); rd(buf, 1, 1, 2, a1); ph_mad(1); SB();
+        mm(7, a1, bf[0]); ph_xor(bf[1][1]); SB();
+        // k-step (1,1): builds B(0,0) of the next stage, loads W(s+WS)
+        mm(0, a1, bf[1]); rd(buf, 1, 1, 3, a1); ph_par(p_nxt, 0); SB();
+        mm(1, a1, bf[1]); ph_and_lo(w_nxt[0][0]); SB();
+        mm(2, a1, bf[1]); ph_mad(0); SB();
+        mm(3, a1, bf[1]); ph_xor(bf[0][0]); SB();
+        lds_barrier();  // X(s+1) is complete; every wave is done reading this stage
+        SB();
+        mm(4, a1, bf[1]); rd(buf ^ 1, 0, 0, 0, a1); ph_and_lo(w_nxt[1][0]); SB();
+        mm(5, a1, bf[1]); rd(buf ^ 1, 0, 0, 1, a1); ph_mad(1); load_w1(s + WS, 0, w_cur, p_cur); SB();
+        mm(6, a1, bf[1]); rd(buf ^ 1, 0, 0, 2, a1); ph_xor(bf[0][1]); SB();
+        mm(7, a1, bf[1]); load_w1(s + WS, 1, w_cur, p_cur); SB();
+    };
+    constexpr bool PINNED = MF == 4 && MFC == 4 && DQ == 0;
+
     // prologue (the W loads are issued after X(1) so that, as in the steady state, the
     // only loads younger than an X stage are one stage of W)
     load_x(0);
@@ -341,11 +450,21 @@ __device__ __forceinline__ void duo_tile(
     if (WS == 3) load_w(2, wr[WS - 1], pr[WS - 1]);
     __builtin_amdgcn_sched_barrier(0);
     build_b(wr[0], pr[0], 0, 0, bf[0]);
+    if (PINNED) ph_par(pr[0], 0);
     lds_barrier();
-    read_a(0, 0, 0, af[0]);
+    if constexpr (PINNED) {
+        rd(0, 0, 0, 0, af[0]), rd(0, 0, 0, 1, af[0]), rd(0, 0, 0, 2, af[0]);  // the first k-step reads fragment 3 itself
+    } else {
+        read_a(0, 0, 0, af[0]);
+    }
     __builtin_amdgcn_sched_barrier(0);
 
-    if (WS == 2) {
+    if constexpr (PINNED) {
+        for (int s = 0; s < stages; s += 2) {
+            stage_pinned(s, wr[0], pr[0], wr[1], pr[1], 0);
+            stage_pinned(s + 1, wr[1], pr[1], wr[0], pr[0], 1);
+        }
+    } else if (WS == 2) {
         for (int s = 0; s < stages; s += 2) {
             stage(s, wr[0], pr[0], wr[1], pr[1], 0);
             stage(s + 1, wr[1], pr[1], wr[0], pr[0], 1);
