@@ -39,6 +39,7 @@ def build_library(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     usage = kernel_resource_usage(res.stderr)
     spilling = {k: v for k, v in usage.items() if v.get("ScratchSize [bytes/lane]", 0) > 0}
     if spilling:
+        os.remove(out)  # never leave a library behind that must not be run
         raise RuntimeError("kernels must not use scratch memory, but these do: "
                            + ", ".join(f"{k} ({v['ScratchSize [bytes/lane]']} B/lane)" for k, v in spilling.items()))
     if verbose:

@@ -3,7 +3,8 @@
 // with nothing else in the way.  bench.py reports them beside the nominal peaks.
 //
 //   w4a8_calib_stream_read : every byte of a buffer read once with 16-byte non-temporal
-//                            loads, nothing computed, nothing of size written.
+//                            loads (one contiguous share per block), nothing computed,
+//                            nothing of size written.
 //   w4a8_calib_mfma_i8     : back-to-back v_mfma_i32_32x32x32_i8 on register operands,
 //                            two waves per SIMD, with the register pressure of a real
 //                            kernel (8 independent 32x32 accumulators per wave).
@@ -18,21 +19,26 @@ namespace lqq {
 // dropped by the compiler while practically nothing is stored.
 __device__ unsigned int g_calib_sink[64];
 
-constexpr int kReadBlocksPerCU = 8, kCUs = 256;
+constexpr int kReadBlocksPerCU = 4, kCUs = 256;
 
+// Every block streams its own contiguous share of the buffer, eight 16-byte loads per thread
+// in flight: many concurrent sequential streams, the pattern of the GEMM kernels themselves
+// (a block walks the contiguous code stream of its tiles) and, among the launch shapes tried
+// (grid-stride or block-contiguous, 2 to 8 loads in flight, 256 to 4096 blocks), the fastest.
 __global__ __launch_bounds__(256) void calib_read_kernel(const u32x4 *__restrict__ p, size_t n16)
 {
-    const size_t stride = (size_t)gridDim.x * 256;
-    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
+    const size_t begin = (size_t)blockIdx.x * per, end = begin + per < n16 ? begin + per : n16;
+    size_t i = begin + threadIdx.x;
     u32x4 x = {0, 0, 0, 0};
-    for (; i + 3 * stride < n16; i += 4 * stride) {
-        const u32x4 a = __builtin_nontemporal_load(p + i);
-        const u32x4 b = __builtin_nontemporal_load(p + i + stride);
-        const u32x4 c = __builtin_nontemporal_load(p + i + 2 * stride);
-        const u32x4 d = __builtin_nontemporal_load(p + i + 3 * stride);
-        x ^= a ^ b ^ c ^ d;
+    for (; i + 7 * 256 < end; i += 8 * 256) {
+        u32x4 v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(p + i + j * 256);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x ^= v[j];
     }
-    for (; i < n16; i += stride) x ^= __builtin_nontemporal_load(p + i);
+    for (; i < end; i += 256) x ^= __builtin_nontemporal_load(p + i);
     if ((x[0] ^ x[1] ^ x[2] ^ x[3]) == 0x5eed1234u) g_calib_sink[threadIdx.x & 63] = 1;
 }
 

@@ -172,7 +172,6 @@ __device__ __forceinline__ void duo_tile(
     static_assert(32 * MF <= TM, "a tile cannot hold more row fragments than its height");
     constexpr int STAGE = 128 * kTilePitch;
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
-    __shared__ int s_last;
 
     const int tid = threadIdx.x & 255;  // thread within its k group
     const int grp = KG == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 8));
@@ -531,10 +530,16 @@ __device__ __forceinline__ void duo_tile(
                 if (t == 0) lds_barrier();
             }
         }
+        // the fragments this group finishes, in registers of their own: the rest of acc is dead
+        v16i fin[MFK][2];
+#pragma unroll
+        for (int i = 0; i < MFK; ++i)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) fin[i][t] = acc[MF0 + i][t];
         if (S > 1) {
-            // Grid-level split-K (same protocol as the stream kernels): every block publishes its
-            // INT32 partial tile with device-scope write-through stores, takes a ticket, and the
-            // last one of the S slices adds the others to its registers and runs the epilogue.
+            // Grid-level split-K: every wave publishes its part of the block's INT32 partial tile
+            // with device-scope write-through stores and takes a ticket; the last one of the S
+            // slices adds the others to its registers and runs the epilogue.
             // Layout: [tile][slice][wave of the block][MFK*8 x (64 lanes x 16 B)], fully coalesced.
             constexpr int EPW = (4 / KG) * 8;  // slots of a full 4-fragment tile, whatever MF is
             const size_t tile = pl.gx;
@@ -549,8 +554,8 @@ __device__ __forceinline__ void duo_tile(
                 for (int t = 0; t < 2; ++t) {
                     int32_t *frag = mine + (i * 2 + t) * 4 * 256;
                     auto part = [&](int q) {
-                        return v4i{acc[MF0 + i][t][4 * q], acc[MF0 + i][t][4 * q + 1], acc[MF0 + i][t][4 * q + 2],
-                                   acc[MF0 + i][t][4 * q + 3]};
+                        return v4i{fin[i][t][4 * q], fin[i][t][4 * q + 1], fin[i][t][4 * q + 2],
+                                   fin[i][t][4 * q + 3]};
                     };
                     store_sc1_x4<0>(frag, part(0));
                     store_sc1_x4<1024>(frag, part(1));
@@ -558,48 +563,56 @@ __device__ __forceinline__ void duo_tile(
                     store_sc1_x4<3072>(frag, part(3));
                 }
             }
+            // Every wave owns its 64 channels of the tile in every slice, so the protocol runs per
+            // wave, without block barriers: stores acknowledged, then a ticket of this (tile, wave);
+            // the wave that draws the last of the S tickets adds the other slices and finishes.
             wait_vmcnt0();
-            __syncthreads();
-            if (threadIdx.x == 0) {
-                const unsigned tk = __hip_atomic_fetch_add(&pl.tickets[tile], 1u, __ATOMIC_RELAXED,
-                                                           __HIP_MEMORY_SCOPE_AGENT);
-                s_last = (tk == (unsigned)(S - 1));
-            }
-            __syncthreads();
-            if (!s_last) return;
-            // The 8 loads of one row fragment (2 column tiles x 4 pieces of 16 bytes per lane)
-            // are in flight before the first is waited for: the latency of these device-scope
-            // reads, not their volume, is what this tail costs.
+            unsigned int *ticket = pl.tickets + tile * 8 + bw;
+            unsigned tk = 0;
+            if (lane == 0) tk = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            tk = (unsigned)__builtin_amdgcn_readfirstlane((int)tk);
+            if (tk != (unsigned)(S - 1)) return;
+            // The loads of up to two row fragments (2 x 2 column tiles x 4 pieces of 16 bytes per
+            // lane) are in flight before the first is waited for: the latency of these
+            // device-scope reads, not their volume, is what this tail costs.
+            constexpr int FB = 1;  // (two at a time would not fit the registers of the two-k-group kernel)
             for (int k2 = 0; k2 < S; ++k2) {
                 if (k2 == ks) continue;
                 const int32_t *other = partials + (((tile * S + k2) * (4 * KG) + bw) * EPW) * 256 + lane * 4;
 #pragma unroll
-                for (int i = 0; i < MFK; ++i) {
-                    if (!live(i)) continue;
-                    v4i v[2][4];
+                for (int i0 = 0; i0 < MFK; i0 += FB) {
+                    v4i v[FB][2][4];
 #pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        const int32_t *frag = other + (i * 2 + t) * 4 * 256;
-                        v[t][0] = load_sc1_x4<0>(frag);
-                        v[t][1] = load_sc1_x4<1024>(frag);
-                        v[t][2] = load_sc1_x4<2048>(frag);
-                        v[t][3] = load_sc1_x4<3072>(frag);
+                    for (int f = 0; f < FB; ++f) {
+                        if (!live(i0 + f)) continue;
+#pragma unroll
+                        for (int t = 0; t < 2; ++t) {
+                            const int32_t *frag = other + ((i0 + f) * 2 + t) * 4 * 256;
+                            v[f][t][0] = load_sc1_x4<0>(frag);
+                            v[f][t][1] = load_sc1_x4<1024>(frag);
+                            v[f][t][2] = load_sc1_x4<2048>(frag);
+                            v[f][t][3] = load_sc1_x4<3072>(frag);
+                        }
                     }
-                    wait_vmcnt0(v[0][0], v[0][1], v[0][2], v[0][3]);
-                    wait_vmcnt0(v[1][0], v[1][1], v[1][2], v[1][3]);
 #pragma unroll
-                    for (int t = 0; t < 2; ++t)
+                    for (int f = 0; f < FB; ++f) {
+                        if (!live(i0 + f)) continue;
+                        wait_vmcnt0(v[f][0][0], v[f][0][1], v[f][0][2], v[f][0][3]);
+                        wait_vmcnt0(v[f][1][0], v[f][1][1], v[f][1][2], v[f][1][3]);
 #pragma unroll
-                        for (int q = 0; q < 4; ++q)
+                        for (int t = 0; t < 2; ++t)
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) acc[MF0 + i][t][4 * q + e] += v[t][q][e];
+                            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) fin[i0 + f][t][4 * q + e] += v[f][t][q][e];
+                    }
                 }
             }
-            if (threadIdx.x == 0)
-                __hip_atomic_store(&pl.tickets[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (lane == 0)  // ready for the next call
+                __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (!active) return;
-        store_tile<MFK>(*reinterpret_cast<const v16i(*)[MFK][2]>(&acc[MF0]), M, N, m0 + 32 * MF0,
+        store_tile<MFK>(fin, M, N, m0 + 32 * MF0,
                         64 * ng + 2 * j, lane, sx, sw, Y, ACC);
     };
     if (KG == 1 || grp == 0)

@@ -326,7 +326,7 @@ static int launch_duo_as(const Args &a, int S)
         return fail(LQ_ERR_INVALID, "M * K = %lld is beyond the 2^32 - 1 bytes of X one call addresses; split the batch",
                     (long long)a.M * a.K);
     S = std::min(S, a.K / (256 * KG));  // every k group of every slice gets at least one unit
-    if (blocks_n * blocks_m > kMaxTicketGroups || S < 1) S = 1;
+    if (blocks_n * blocks_m * 8 > kMaxTicketGroups || S < 1) S = 1;  // one ticket per (tile, wave of the block)
     size_t need = duo_ws_bytes(a.M, a.N, S, TM);
     if (a.query) return *a.query = need, LQ_OK;
     if (need > 0 && (!a.ws || a.ws_bytes < need)) {
