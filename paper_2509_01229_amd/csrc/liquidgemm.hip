@@ -88,6 +88,7 @@ __device__ __forceinline__ __half scale_to_half(int acc, float sx, float sw)
 #include "kernels_stream.h"
 #include "kernels_tiled.h"
 #include "kernels_tiled_dl.h"
+#include "kernels_tiled_pt.h"
 #include "kernels_reference.h"
 #include "kernels_grouped.h"
 
@@ -412,6 +413,38 @@ static int launch_duo_dl(const Args &a)
     return LQ_OK;
 }
 
+// The persistent form of the direct-to-LDS kernel: one block per resident slot (two per CU),
+// each walking its share of the tiles as one stream of stages.  Needs K % 512 == 0.
+static bool duo_pt_fits(int M, int N, int K)
+{
+    // (a ragged last row tile of at most 64 rows is better off with the two-fragment path of
+    // the one-tile-per-block kernels)
+    return K % 512 == 0 && (M % 128 == 0 || M % 128 > 64);
+}
+static int launch_duo_pt(const Args &a)
+{
+    if (a.query) return LQ_OK;  // no workspace
+    if (a.K % 512 != 0) return fail(LQ_ERR_INVALID, "the persistent tiled variant needs K %% 512 == 0, got %d", a.K);
+    const int blocks_n = (a.N + 255) / 256, blocks_m = (a.M + 127) / 128;
+    if ((long long)a.M * a.K >= (1ll << 32))
+        return fail(LQ_ERR_INVALID, "M * K = %lld is beyond the 2^32 - 1 bytes of X one call addresses; split the batch",
+                    (long long)a.M * a.K);
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    const int grid = std::min(blocks_m * blocks_n, 2 * std::max(cus, 1));
+    const size_t lds_bytes = 4 * (size_t)128 * 128;
+    if (a.group == 128) {
+        if (int rc = allow_lds(w4a8_duo_pt_kernel<true>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_duo_pt_kernel<true>), dim3((unsigned)grid), dim3(256), lds_bytes, a.stream, a.M, a.N,
+                           a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
+    } else {
+        if (int rc = allow_lds(w4a8_duo_pt_kernel<false>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_duo_pt_kernel<false>), dim3((unsigned)grid), dim3(256), lds_bytes, a.stream, a.M, a.N,
+                           a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
+    }
+    return LQ_OK;
+}
+
 // the explicit producer / consumer form (measured only, never dispatched)
 static int launch_excp(const Args &a)
 {
@@ -545,6 +578,7 @@ static const Variant kVariants[] = {
     {"duo_m128_s4", &launch_duo<4, 1>, 0, 1, 1},
     {"duo_m128_s8", &launch_duo<8, 1>, 0, 1, 1},
     {"duo_dl_m128", &launch_duo_dl<0>, 0, 1, 1},
+    {"duo_pt_m128", &launch_duo_pt, 0, 1, 8, 512},
     {"duo_dl_m128_s2", &launch_duo_dl<2>, 0, 1, 1},
     {"duo_dl_m128_s3", &launch_duo_dl<3>, 0, 1, 1},
     {"excp_m128", &launch_excp, 0, 1, 1},
@@ -619,8 +653,10 @@ static int select_variant(int M, int N, int K)
     // more 128 x 256 tiles than CUs (blocks of one k group): the deeper memory pipeline of the
     // direct-to-LDS form pays (3 to 6 % measured from 320 tiles up, 1 to 5 % at 264..288); with
     // one tile per CU or fewer, the two k groups per block of the other form do
+    // (from two tiles per resident slot on and with whole 512-k units, its persistent form:
+    // one pipeline fill per block instead of per tile, 1 to 2 % measured)
     if (((M + 127) / 128) * ((N + 255) / 256) > 256)
-        return find_variant("duo_dl_m128");
+        return find_variant(duo_pt_fits(M, N, K) ? "duo_pt_m128" : "duo_dl_m128");
     // few tiles: a grid of 64-row tiles can fill the chip with half the split-K exchange
     return find_variant(prefer_64_row_tiles(M, N, K) ? "duo_m64" : "duo_m128");
 }

@@ -20,10 +20,11 @@ def test_dispatcher_families_on_the_workloads():
         elif s.M <= 64 and s.N <= 16384:
             assert name == "stream_m64", (s.name, name)
         else:
-            assert name in ("duo_m64", "duo_m128", "duo_dl_m128"), (s.name, name)
+            assert name in ("duo_m64", "duo_m128", "duo_dl_m128", "duo_pt_m128"), (s.name, name)
             tiles128 = -(-s.M // 128) * -(-s.N // 256)
-            if tiles128 > 256:        # more tiles than CUs: the direct-to-LDS pipeline
-                assert name == "duo_dl_m128", (s.name, name)
+            if tiles128 > 256:        # more tiles than CUs: the direct-to-LDS pipeline, persistent where it fits
+                fits = s.K % 512 == 0 and (s.M % 128 == 0 or s.M % 128 > 64)
+                assert name == ("duo_pt_m128" if fits else "duo_dl_m128"), (s.name, name)
             elif -(-s.M // 64) * -(-s.N // 256) > 256:
                 assert name == "duo_m128", (s.name, name)
         v = api.w4a8_select_variant(s.M, s.N, s.K, s.group)
@@ -57,8 +58,11 @@ def test_dispatcher_boundaries():
     assert _pick(256, 8192, 28672, 128) == "duo_m128"          # long K: more slices of 128-row tiles win
     assert _pick(256, 8192, 8192) == "duo_m64" and _pick(256, 10240, 8192, 128) == "duo_m128"
     assert _pick(128, 4096, 256) == "duo_m128"                 # one k unit: no room for two k groups
-    assert _pick(1152, 8192, 8192) == "duo_dl_m128" and _pick(1024, 8192, 8192) == "duo_m128"   # 288 / 256 tiles
-    assert _pick(4096, 8192, 8192) == "duo_dl_m128" and _pick(1024, 28672, 8192, 128) == "duo_dl_m128"
+    assert _pick(1152, 8192, 8192) == "duo_pt_m128" and _pick(1024, 8192, 8192) == "duo_m128"   # 288 / 256 tiles
+    assert _pick(4096, 8192, 8192) == "duo_pt_m128" and _pick(1024, 28672, 8192, 128) == "duo_pt_m128"
+    assert _pick(4096, 8192, 11008) == "duo_dl_m128"           # K not a multiple of 512: one tile per block
+    assert _pick(4096 + 40, 8192, 8192) == "duo_dl_m128"       # ragged last row tile of at most 64 rows: its two-fragment path
+    assert _pick(4096 + 100, 8192, 8192) == "duo_pt_m128"
     with pytest.raises(api.LiquidGemmError):
         api.w4a8_select_variant(8, 100, 512, 64)                # bad shape
 

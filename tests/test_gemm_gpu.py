@@ -291,7 +291,7 @@ def test_random_large_grids_through_the_dispatcher():
         assert np.array_equal(ACC.cpu().numpy().astype(np.float64), ref), f"case {case}: accumulators differ"
         H.assert_fp16_close(Y.cpu().numpy(), O.scale_epilogue_f64(ref, s_x, s_w), f"case {case}")
         del P, dX, ACC, Y
-    assert "duo_dl_m128" in seen and seen & {"duo_m128", "duo_m64"}
+    assert {"duo_dl_m128", "duo_pt_m128"} <= seen and seen & {"duo_m128", "duo_m64"}
 
 
 def test_random_small_batches_through_the_dispatcher():
@@ -489,3 +489,25 @@ def test_batch_beyond_32_bit_offsets_of_x():
                                     N, K, g, want_y=False)
     torch.cuda.synchronize()
     assert np.array_equal(ACC2.cpu().numpy(), ref), "accumulators of the named variant differ"
+
+
+@pytest.mark.parametrize("M,N,K,g", [(1541, 12352, 512, 64), (2048, 10240, 1024, 128), (700, 2048, 1536, 64)])
+def test_persistent_tile_kernel(M, N, K, g):
+    """The persistent form of the tiled kernel (blocks walk several tiles as one stream of
+    stages): more tiles than resident blocks, so that blocks cross tile boundaries; a ragged
+    last row tile, an N tail, tile counts that are and are not multiples of the XCD count, and a
+    grid smaller than the number of resident slots.  Every accumulator and every FP16 output
+    against the exact float64 product of the oracle's weights."""
+    import torch
+
+    names = api.w4a8_variant_names()
+    v = names.index("duo_pt_m128")
+    assert api.w4a8_variant_supports(v, M, N, K, g)
+    _say(f"persistent tiles M={M} N={N} K={K} g={g}")
+    P = H.Problem(N, K, g, seed=M)
+    Wd, s_w = P.oracle_wd()
+    X, s_x = I.make_activations(M, K, outlier_frac=0.01, seed=M + N)
+    ref = (X.astype(np.float64) @ Wd.astype(np.float64).T).astype(np.int64)
+    Y, ACC = P.run(X, s_x, variant=v)
+    assert np.array_equal(ACC.astype(np.int64), ref), f"{np.count_nonzero(ACC != ref)} accumulators differ"
+    H.assert_fp16_close(Y, O.scale_epilogue_f64(ref, s_x, s_w), "persistent tiles")
