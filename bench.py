@@ -40,14 +40,17 @@ import numpy as np  # noqa: E402
 PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, published
 PEAK_INT8_TOPS = 5033.0   # dense INT8 MFMA: 256 CU x 4 SIMD x 2048 ops/clk x 2.4 GHz
 ROTATE_BYTES = 512 << 20
-# HBM-side bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE counter runs of this file
-# (scaled by what the same counters read for a plain 1 GiB copy, --copy-ref); the commands
-# and raw figures are in profiles/.  Counters cannot be read from inside a timed run, so
-# the figure is carried here per (workload, kernel) and is null for anything not profiled.
-MEASURED_TRAFFIC_BYTES = {
-    ("prefill_M4096_N8192_K8192", "duo_dl_m128"): 478.4e6,
-    ("l70b_up_M16_N28672_K8192", "stream16_f2_w4"): 123.3e6,
-}
+# HBM-side bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this file, scaled by what
+# the same counters read for a plain 1 GiB copy, --copy-ref) cannot be read from inside a timed
+# run: they are carried per (workload, kernel) in profiles/traffic.json, the data file the
+# summaries under profiles/ are written from, and are null for anything not profiled.
+def measured_traffic(workload, kernel):
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
+            table = json.load(f)
+        return table.get(f"{workload}|{kernel}", {}).get("bytes_per_launch")
+    except (OSError, ValueError):
+        return None
 
 
 def algorithmic_bytes(M, N, K, g):
@@ -443,7 +446,7 @@ def main():
                 "unit": "GB/s"}
     roof["frac"] = round(roof["achieved"] / roof["peak"], 4)
     roof["kernel"] = hp["variant"]
-    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((head.name, hp["variant"]))
+    roof["traffic"] = measured_traffic(head.name, hp["variant"])
     roof["algorithmic_bytes"] = byt
     roof["algorithmic_ops"] = ops
 
@@ -512,7 +515,7 @@ def main():
             out["roofline_hbm"] = {
                 "bound": "hbm", "achieved": hb["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(hb["gbs"] / PEAK_HBM_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get((hb["workload"], hb["variant"])),
+                "traffic": measured_traffic(hb["workload"], hb["variant"]),
                 "algorithmic_bytes": algorithmic_bytes(hb["M"], hb["N"], hb["K"], hb["group"]),
                 "kernel": hb["variant"], "workload": hb["workload"]}
             if calib:

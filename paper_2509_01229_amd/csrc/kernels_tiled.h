@@ -1,128 +1,6 @@
-// Tiled kernels (larger M): the plain tile kernel and the duo kernel (two waves per SIMD).
+// Tiled kernel (larger M): the duo kernel (two waves per SIMD), X staged through registers.
 // (part of liquidgemm.hip: included there, inside namespace lqq)
 #pragma once
-
-// ------------------------------------------------------------------------------------
-// tile kernel.  MF = 32-row fragments per wave; block tile = (32*MF) x 256.
-// ------------------------------------------------------------------------------------
-template <int MF, bool G128>
-__global__ __launch_bounds__(256, 2) void w4a8_tile_kernel(
-    int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
-    const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
-    __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n)
-{
-    constexpr int WM = 32 * MF;
-    constexpr int XP = MF;  // 16-byte X pieces per thread per stage of 128 k
-    constexpr int STAGE = WM * kTilePitch;
-    extern __shared__ __attribute__((aligned(16))) int8_t lds[];
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int j = lane & 31, kb = lane >> 5;
-    int bm, bn;
-    block_coords(blocks_m, blocks_n, bm, bn);
-    const int m0 = bm * WM;
-    const int ng = bn * 4 + wave;  // 64-channel group of this wave
-    const bool active = ng < (N >> 6);
-    // A wave past the last group recomputes the last one and stores nothing, so that the
-    // main loop has no divergent path around its barriers.
-    const int t0 = 2 * (active ? ng : (N >> 6) - 1);
-    const int stages = K >> 7;
-    const int chunks_per_tile = K >> 6;
-
-    v16i acc[MF][2];
-#pragma unroll
-    for (int mf = 0; mf < MF; ++mf)
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mf][t][r] = 0;
-
-    u32x4 xr[XP];
-    u32x4 wc[2][2], wn[2][2];
-    UnitParams<G128> pc[2], pn[2];
-
-    // Rows past M read row M-1: an output row depends only on its own X row, and rows
-    // past M are never stored.
-    auto load_x = [&](int s) {
-#pragma unroll
-        for (int i = 0; i < XP; ++i) {
-            const int q = tid + 256 * i;
-            const int row = q >> 3, col = q & 7;
-            const int m = min(m0 + row, M - 1);
-            xr[i] = *reinterpret_cast<const u32x4 *>(X + (size_t)m * K + (size_t)s * 128 + 16 * col);
-        }
-    };
-    auto store_x = [&](int buf) {
-        int8_t *base = lds + buf * STAGE;
-#pragma unroll
-        for (int i = 0; i < XP; ++i) {
-            const int q = tid + 256 * i;
-            const int row = q >> 3, col = q & 7;
-            *reinterpret_cast<u32x4 *>(base + row * kTilePitch + 16 * col) = xr[i];
-        }
-    };
-    auto load_w = [&](int s, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const u32x4 *base = Wp + ((size_t)(t0 + t) * chunks_per_tile + 2 * (size_t)s) * 64 + lane;
-            w[t][0] = base[0];
-            w[t][1] = base[64];
-            p[t].load(gp, (size_t)(t0 + t) * stages + s, j);
-        }
-    };
-    auto compute = [&](int buf) {
-        const int8_t *xs = lds + buf * STAGE + j * kTilePitch + 16 * kb;
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            v4i blo[2], bhi[2];
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                uint32_t s2, a4;
-                pc[t].get(c, s2, a4);
-                dequant_chunk(wc[t][c], s2, a4, blo[t], bhi[t]);
-            }
-#pragma unroll
-            for (int mf = 0; mf < MF; ++mf) {
-                const v4i a0 = *reinterpret_cast<const v4i *>(xs + mf * 32 * kTilePitch + 64 * c);
-                const v4i a1 = *reinterpret_cast<const v4i *>(xs + mf * 32 * kTilePitch + 64 * c + 32);
-#pragma unroll
-                for (int t = 0; t < 2; ++t) acc[mf][t] = mfma_i8(a0, blo[t], acc[mf][t]);
-#pragma unroll
-                for (int t = 0; t < 2; ++t) acc[mf][t] = mfma_i8(a1, bhi[t], acc[mf][t]);
-            }
-        }
-    };
-
-    load_x(0);
-    load_w(0, wc, pc);
-    store_x(0);
-    __syncthreads();
-
-    // Steady state: the global loads of stage s+1 are issued before the MFMAs of stage s
-    // and land in LDS / registers after them.
-    for (int s = 0; s + 1 < stages; ++s) {
-        load_x(s + 1);
-        load_w(s + 1, wn, pn);
-        __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of the MFMAs
-        compute(s & 1);
-        __builtin_amdgcn_sched_barrier(0);
-        store_x((s + 1) & 1);
-        __syncthreads();
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            wc[t][0] = wn[t][0];
-            wc[t][1] = wn[t][1];
-            pc[t] = pn[t];
-        }
-    }
-    compute((stages - 1) & 1);
-
-    if (!active) return;
-    // Epilogue: element r of acc[mf][t] is row m0 + 32*mf + acc_row(r), channel
-    // 64*ng + 2*j + t: the two tiles give 2 adjacent channels per lane.
-    store_tile<MF>(acc, M, N, m0, 64 * ng + 2 * j, lane, sx, sw, Y, ACC);
-}
 
 // Block barrier that orders LDS traffic only: __syncthreads() would also wait for every
 // outstanding global load (vmcnt(0)), which is exactly what the prefetches must not do.

@@ -17,8 +17,10 @@
 //           weights in registers (global -> VGPR, never through LDS: the dequantised
 //           operand is consumed by the MFMA of the same wave, which is the point of the
 //           paper's implicit fine-grained pipeline, Sec. 5.1) and reuses every dequantised
-//           fragment for 4 MFMAs.  `duo` is the kernel that is dispatched (two waves per
-//           SIMD); `tile` is its plain predecessor, kept as a named variant.
+//           fragment for 4 MFMAs.  Three forms: `duo` (X staged through registers, two k
+//           groups per block for grids of at most one block per CU), `duo_dl` (X straight
+//           into LDS, deeper pipeline, grids that fill the chip) and `duo_pt` (duo_dl with
+//           resident blocks walking several tiles as one stream of stages).
 //
 // All compute Y = X W^T with the weights on the B operand of the INT8 MFMA, so that a lane
 // ends up with 2 adjacent output channels of one row (the tile interleave of the layout)
@@ -277,26 +279,6 @@ static int launch_stream16(const Args &a)
     return LQ_OK;
 }
 
-template <int MF>
-static int launch_tile(const Args &a)
-{
-    if (a.query) return LQ_OK;  // no workspace
-    constexpr int WM = 32 * MF;
-    const int blocks_n = (a.N + 255) / 256, blocks_m = (a.M + WM - 1) / WM;
-    const size_t lds_bytes = 2 * (size_t)WM * kTilePitch;
-    const dim3 grid((unsigned)(blocks_n * blocks_m)), block(256);
-    if (a.group == 128) {
-        if (int rc = allow_lds(&w4a8_tile_kernel<MF, true>, lds_bytes)) return rc;
-        hipLaunchKernelGGL((w4a8_tile_kernel<MF, true>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
-                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
-    } else {
-        if (int rc = allow_lds(&w4a8_tile_kernel<MF, false>, lds_bytes)) return rc;
-        hipLaunchKernelGGL((w4a8_tile_kernel<MF, false>), grid, block, lds_bytes, a.stream, a.M, a.N, a.K,
-                           a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
-    }
-    return LQ_OK;
-}
-
 // Grid-level split of K for the duo kernel with two k groups per block (grids of at most
 // one block per CU).  Measured: a slice costs about as much in partial-tile exchange
 // (128 KiB per tile and slice, added up by the last block) as half a 256-k unit costs in
@@ -527,73 +509,39 @@ struct Variant {
     int min_k = 256;
 };
 
-// stream_f<F>_w<NW>[_s<S>]: F tiles per block, NW waves splitting the block's K slice,
-// S grid-level K slices (chosen from the shape when not named).
+// stream*_f<F>_w<NW>[_s<S>]: F tiles per block, NW waves splitting the block's K slice,
+// S grid-level K slices (chosen from the shape when not named); _u4 = four 128-k units per
+// pipeline step; x = X fragments through LDS; g2 = two k groups per block.
 static const Variant kVariants[] = {
-    {"stream_f2_w8", &launch_stream<2, 8, 0>, 32, 2, 1},
-    {"stream_f2_w8_s1", &launch_stream<2, 8, 1>, 32, 2, 1},
-    {"stream_f2_w8_s2", &launch_stream<2, 8, 2>, 32, 2, 1},
-    {"stream_f2_w8_s4", &launch_stream<2, 8, 4>, 32, 2, 1},
-    {"stream_f1_w8_s1", &launch_stream<1, 8, 1>, 32, 1, 1},
-    {"stream_f1_w8_s2", &launch_stream<1, 8, 2>, 32, 1, 1},
-    {"stream_f1_w8_s4", &launch_stream<1, 8, 4>, 32, 1, 1},
-    {"stream_m32", &launch_stream_auto<1>, 32, 2, 1},
-    {"stream_m64", &launch_stream_auto<2>, 64, 2, 1},
-    {"stream_m64_f2_w8", &launch_stream<2, 8, 0, 2>, 64, 2, 1},
-    {"stream_m64_f2_w8_s1", &launch_stream<2, 8, 1, 2>, 64, 2, 1},
-    {"stream_m64_f2_w8_s2", &launch_stream<2, 8, 2, 2>, 64, 2, 1},
-    {"stream_m64_f2_w8_s4", &launch_stream<2, 8, 4, 2>, 64, 2, 1},
-    {"stream_m64_f1_w8_s1", &launch_stream<1, 8, 1, 2>, 64, 1, 1},
-    {"stream_m64_f1_w8_s2", &launch_stream<1, 8, 2, 2>, 64, 1, 1},
-    {"stream_m64x_f1_w8_s1", &launch_stream<1, 8, 1, 2, true>, 64, 1, 1},
-    {"stream_m64x_f1_w8_s2", &launch_stream<1, 8, 2, 2, true>, 64, 1, 1},
-    {"stream_m64x_f2_w8_s1", &launch_stream<2, 8, 1, 2, true>, 64, 2, 1},
-    {"stream_m64x_f2_w8_s2", &launch_stream<2, 8, 2, 2, true>, 64, 2, 1},
-    {"stream_m64x_f1_w8_s4", &launch_stream<1, 8, 4, 2, true>, 64, 1, 1},
-    {"stream_m64x_f2_w8_s4", &launch_stream<2, 8, 4, 2, true>, 64, 2, 1},
-    {"stream_x_f1_w8_s1", &launch_stream<1, 8, 1, 1, true>, 32, 1, 1},
-    {"stream_x_f1_w8_s2", &launch_stream<1, 8, 2, 1, true>, 32, 1, 1},
-    {"stream_x_f1_w8_s4", &launch_stream<1, 8, 4, 1, true>, 32, 1, 1},
-    {"stream_x_f2_w8_s1", &launch_stream<2, 8, 1, 1, true>, 32, 2, 1},
-    {"stream_x_f2_w8_s2", &launch_stream<2, 8, 2, 1, true>, 32, 2, 1},
-    {"stream_x_f2_w8_s4", &launch_stream<2, 8, 4, 1, true>, 32, 2, 1},
-    {"stream16_f2_w8", &launch_stream16<2, 8, 0>, 16, 2, 1},
-    {"stream16_f2_w4", &launch_stream16<2, 4, 0>, 16, 2, 1},
-    {"stream16_f2_w8_s1", &launch_stream16<2, 8, 1>, 16, 2, 1},
-    {"stream16_f2_w8_s2", &launch_stream16<2, 8, 2>, 16, 2, 1},
-    {"stream16_f2_w8_s4", &launch_stream16<2, 8, 4>, 16, 2, 1},
-    {"stream16_f1_w8", &launch_stream16<1, 8, 0>, 16, 1, 1},
-    {"stream16_f1_w8_s1", &launch_stream16<1, 8, 1>, 16, 1, 1},
-    {"stream16_f2_w16_s1", &launch_stream16<2, 16, 1>, 16, 2, 1},
+    // --- dispatched (select_variant) ---
     {"stream16_f1_w16_s1", &launch_stream16<1, 16, 1>, 16, 1, 1},
     {"stream16_f1_w8_u4", &launch_stream16<1, 8, 0, 4>, 16, 1, 8},
-    {"stream16_f1_w8_u4_s1", &launch_stream16<1, 8, 1, 4>, 16, 1, 8},
-    {"stream16_f1_w8_u4_s2", &launch_stream16<1, 8, 2, 4>, 16, 1, 8},
-    {"tile_m32", &launch_tile<1>, 0, 1, 1},
-    {"tile_m64", &launch_tile<2>, 0, 1, 1},
-    {"tile_m128", &launch_tile<4>, 0, 1, 1},
+    {"stream16_f1_w8", &launch_stream16<1, 8, 0>, 16, 1, 1},
+    {"stream16_f2_w8", &launch_stream16<2, 8, 0>, 16, 2, 1},
+    {"stream16_f2_w16_s1", &launch_stream16<2, 16, 1>, 16, 2, 1},
+    {"stream16_f2_w4", &launch_stream16<2, 4, 0>, 16, 2, 1},
+    {"stream_m32", &launch_stream_auto<1>, 32, 2, 1},
+    {"stream_m64", &launch_stream_auto<2>, 64, 2, 1},
+    {"duo_m64", &launch_duo64<0>, 0, 1, 1, 512},
     {"duo_m128", &launch_duo<0, 0>, 0, 1, 1},
-    {"duo_m128_s1", &launch_duo<1, 1>, 0, 1, 1},
-    {"duo_m128_s2", &launch_duo<2, 1>, 0, 1, 1},
-    {"duo_m128_s4", &launch_duo<4, 1>, 0, 1, 1},
-    {"duo_m128_s8", &launch_duo<8, 1>, 0, 1, 1},
     {"duo_dl_m128", &launch_duo_dl<0>, 0, 1, 1},
     {"duo_pt_m128", &launch_duo_pt, 0, 1, 8, 512},
+    // --- the same kernels with a named number of K slices: the split paths at sizes where the
+    //     dispatcher would not split (parity tests) ---
+    {"stream16_f2_w8_s2", &launch_stream16<2, 8, 2>, 16, 2, 1},
+    {"stream16_f1_w8_u4_s2", &launch_stream16<1, 8, 2, 4>, 16, 1, 8},
+    {"stream_f2_w8_s2", &launch_stream<2, 8, 2>, 32, 2, 1},
+    {"stream_x_f1_w8_s2", &launch_stream<1, 8, 2, 1, true>, 32, 1, 1},
+    {"stream_m64x_f1_w8_s2", &launch_stream<1, 8, 2, 2, true>, 64, 1, 1},
+    {"stream_m64x_f2_w8_s4", &launch_stream<2, 8, 4, 2, true>, 64, 2, 1},
+    {"duo_m64_s2", &launch_duo64<2>, 0, 1, 1, 512},
+    {"duo_m128_s1", &launch_duo<1, 1>, 0, 1, 1},
+    {"duo_m128_s2", &launch_duo<2, 1>, 0, 1, 1},
+    {"duo_m128_g2_s2", &launch_duo<2, 2>, 0, 1, 1},
     {"duo_dl_m128_s2", &launch_duo_dl<2>, 0, 1, 1},
-    {"duo_dl_m128_s3", &launch_duo_dl<3>, 0, 1, 1},
+    // --- ablation forms (Sec. 7.3), measured by the benchmark, never dispatched ---
     {"excp_m128", &launch_excp, 0, 1, 1},
     {"widened_dq_m128", &launch_duo_widened, 0, 1, 1},
-    {"duo_m64", &launch_duo64<0>, 0, 1, 1, 512},
-    {"duo_m64_s1", &launch_duo64<1>, 0, 1, 1, 512},
-    {"duo_m64_s2", &launch_duo64<2>, 0, 1, 1, 512},
-    {"duo_m64_s3", &launch_duo64<3>, 0, 1, 1, 512},
-    {"duo_m64_s4", &launch_duo64<4>, 0, 1, 1, 512},
-    {"duo_m128_g2", &launch_duo<0, 2>, 0, 1, 1},
-    {"duo_m128_g2_s1", &launch_duo<1, 2>, 0, 1, 1},
-    {"duo_m128_g2_s2", &launch_duo<2, 2>, 0, 1, 1},
-    {"duo_m128_g2_s3", &launch_duo<3, 2>, 0, 1, 1},
-    {"duo_m128_g2_s4", &launch_duo<4, 2>, 0, 1, 1},
-    {"duo_m128_g2_s6", &launch_duo<6, 2>, 0, 1, 1},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
