@@ -231,16 +231,21 @@ __device__ __forceinline__ void duo_tile(
     auto store_x1 = [&](int buf, int i) {
         *reinterpret_cast<u32x4 *>(lds_g + buf * STAGE + xl + (i % XP) * 32 * kTilePitch) = xr[i % XP];
     };
+    // (wave-uniform bases plus 32-bit lane offsets: no 64-bit address arithmetic per load)
+    const char *wbase_u = reinterpret_cast<const char *>(Wp + ((size_t)t0 * chunks_per_tile + 2 * (size_t)s_begin) * 64);
+    const char *pbase_u = reinterpret_cast<const char *>(gp) + ((size_t)t0 * stages_total + s_begin) * 32 * (G128 ? 2 : 4);
+    const uint32_t wl_off = lane * 16, pl_off = j * (G128 ? 2 : 4);
     auto load_w1 = [&](int s, int t, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
         s = min(s, my_stages - 1);
-        const u32x4 *wg = wg0 + t * wg_stride;
-        const uint8_t *pg = pg0 + t * pg_stride;
-        w[t][0] = wg[(size_t)s * 128];
-        w[t][1] = wg[(size_t)s * 128 + 64];
+        const uint32_t wo = wl_off + (uint32_t)s * 2048, po = pl_off + (uint32_t)s * (G128 ? 64 : 128);
+        const char *wb = wbase_u + t * (wg_stride * 16);
+        const char *pb = pbase_u + t * pg_stride;
+        w[t][0] = *reinterpret_cast<const u32x4 *>(wb + wo);
+        w[t][1] = *reinterpret_cast<const u32x4 *>(wb + wo + 1024);
         if (G128)
-            p[t].raw = *reinterpret_cast<const uint16_t *>(pg + (size_t)s * 64);
+            p[t].raw = *reinterpret_cast<const uint16_t *>(pb + po);
         else
-            p[t].raw = *reinterpret_cast<const uint32_t *>(pg + (size_t)s * 128);
+            p[t].raw = *reinterpret_cast<const uint32_t *>(pb + po);
     };
     auto ph_par = [&](const UnitParams<G128> (&p)[2], int c) {
         p[0].get(c, s2v[0], a4v[0]);
@@ -314,7 +319,39 @@ __device__ __forceinline__ void duo_tile(
         mm(6, a1, bf[1]); rd(buf ^ 1, 0, 0, 2, a1); ph_xor(bf[0][1]); SB();
         mm(7, a1, bf[1]); load_w1(s + WS, 1, w_cur, p_cur); SB();
     };
+    // The two-fragment tile (64-row tiles, ragged last tiles): 4 MFMAs per k-step against 28
+    // to 32 dequantisation instructions, so the vector port sets the pace and the order only has
+    // to keep it full: two phases (eight independent instructions) behind every MFMA, no
+    // dependent instruction next to its producer (a packed multiply-add followed directly by its
+    // XOR costs a wait state), fragments double-buffered.
+    auto stage_pinned2 = [&](int s, u32x4 (&w_cur)[2][2], UnitParams<G128> (&p_cur)[2], u32x4 (&w_nxt)[2][2],
+                             UnitParams<G128> (&p_nxt)[2], int buf) {
+        // k-step (0,0): builds B(0,1), reads A(0,1), stores X(s+1) into the other LDS stage
+        mm(0, af[0], bf[0]); rd(buf, 0, 1, 0, af[1]); ph_shr(w_cur[0][0]); ph_and_hi(); SB();
+        mm(1, af[0], bf[0]); rd(buf, 0, 1, 1, af[1]); ph_mad(0); ph_xor(bf[1][0]); SB();
+        mm(2, af[0], bf[0]); store_x1(buf ^ 1, 0); ph_shr(w_cur[1][0]); ph_and_hi(); SB();
+        mm(3, af[0], bf[0]); store_x1(buf ^ 1, 1); ph_mad(1); ph_xor(bf[1][1]); SB();
+        // k-step (0,1): builds B(1,0), reads A(1,0), loads X(s+2)
+        mm(0, af[1], bf[1]); rd(buf, 1, 0, 0, af[0]); ph_par(p_cur, 1); ph_and_lo(w_cur[0][1]); SB();
+        mm(1, af[1], bf[1]); rd(buf, 1, 0, 1, af[0]); ph_mad(0); ph_xor(bf[0][0]); SB();
+        mm(2, af[1], bf[1]); load_x1(s + 2, 0); ph_and_lo(w_cur[1][1]); ph_mad(1); SB();
+        mm(3, af[1], bf[1]); load_x1(s + 2, 1); ph_xor(bf[0][1]); SB();
+        // k-step (1,0): builds B(1,1), reads A(1,1)
+        mm(0, af[0], bf[0]); rd(buf, 1, 1, 0, af[1]); ph_shr(w_cur[0][1]); ph_and_hi(); SB();
+        mm(1, af[0], bf[0]); rd(buf, 1, 1, 1, af[1]); ph_mad(0); ph_xor(bf[1][0]); SB();
+        mm(2, af[0], bf[0]); ph_shr(w_cur[1][1]); ph_and_hi(); SB();
+        mm(3, af[0], bf[0]); ph_mad(1); ph_xor(bf[1][1]); SB();
+        // k-step (1,1): builds B(0,0) of the next stage; barrier; fragments of the next stage;
+        // loads of W(s+WS)
+        mm(0, af[1], bf[1]); ph_par(p_nxt, 0); ph_and_lo(w_nxt[0][0]); SB();
+        mm(1, af[1], bf[1]); ph_mad(0); ph_xor(bf[0][0]); SB();
+        lds_barrier();  // X(s+1) is complete; every wave is done reading this stage
+        SB();
+        mm(2, af[1], bf[1]); rd(buf ^ 1, 0, 0, 0, af[0]); rd(buf ^ 1, 0, 0, 1, af[0]); ph_and_lo(w_nxt[1][0]); ph_mad(1); SB();
+        mm(3, af[1], bf[1]); ph_xor(bf[0][1]); load_w1(s + WS, 0, w_cur, p_cur); load_w1(s + WS, 1, w_cur, p_cur); SB();
+    };
     constexpr bool PINNED = MF == 4 && MFC == 4 && DQ == 0;
+    constexpr bool PINNED2 = MF == 2 && MFC == 2 && DQ == 0;
 
     // prologue (the W loads are issued after X(1) so that, as in the steady state, the
     // only loads younger than an X stage are one stage of W)
@@ -327,7 +364,7 @@ __device__ __forceinline__ void duo_tile(
     if (WS == 3) load_w(2, wr[WS - 1], pr[WS - 1]);
     __builtin_amdgcn_sched_barrier(0);
     build_b(wr[0], pr[0], 0, 0, bf[0]);
-    if (PINNED) ph_par(pr[0], 0);
+    if (PINNED || PINNED2) ph_par(pr[0], 0);
     lds_barrier();
     if constexpr (PINNED) {
         rd(0, 0, 0, 0, af[0]), rd(0, 0, 0, 1, af[0]), rd(0, 0, 0, 2, af[0]);  // the first k-step reads fragment 3 itself
@@ -350,21 +387,28 @@ __device__ __forceinline__ void duo_tile(
         // three W stages against two X stages: the pattern repeats every six stages.  The
         // loop has one exit (with more the register allocator spills); the two or four
         // stages that may remain (the number of stages is even) follow it.
+        auto ST = [&](int s_, u32x4 (&wc)[2][2], UnitParams<G128> (&pc)[2], u32x4 (&wn)[2][2], UnitParams<G128> (&pn)[2],
+                      int buf) {
+            if constexpr (PINNED2)
+                stage_pinned2(s_, wc, pc, wn, pn, buf);
+            else
+                stage(s_, wc, pc, wn, pn, buf);
+        };
         int s = 0;
         for (; s + 6 <= stages; s += 6) {
-            stage(s, wr[0], pr[0], wr[1], pr[1], 0);
-            stage(s + 1, wr[1], pr[1], wr[WS - 1], pr[WS - 1], 1);
-            stage(s + 2, wr[WS - 1], pr[WS - 1], wr[0], pr[0], 0);
-            stage(s + 3, wr[0], pr[0], wr[1], pr[1], 1);
-            stage(s + 4, wr[1], pr[1], wr[WS - 1], pr[WS - 1], 0);
-            stage(s + 5, wr[WS - 1], pr[WS - 1], wr[0], pr[0], 1);
+            ST(s, wr[0], pr[0], wr[1], pr[1], 0);
+            ST(s + 1, wr[1], pr[1], wr[WS - 1], pr[WS - 1], 1);
+            ST(s + 2, wr[WS - 1], pr[WS - 1], wr[0], pr[0], 0);
+            ST(s + 3, wr[0], pr[0], wr[1], pr[1], 1);
+            ST(s + 4, wr[1], pr[1], wr[WS - 1], pr[WS - 1], 0);
+            ST(s + 5, wr[WS - 1], pr[WS - 1], wr[0], pr[0], 1);
         }
         if (s < stages) {
-            stage(s, wr[0], pr[0], wr[1], pr[1], 0);
-            stage(s + 1, wr[1], pr[1], wr[WS - 1], pr[WS - 1], 1);
+            ST(s, wr[0], pr[0], wr[1], pr[1], 0);
+            ST(s + 1, wr[1], pr[1], wr[WS - 1], pr[WS - 1], 1);
             if (s + 2 < stages) {
-                stage(s + 2, wr[WS - 1], pr[WS - 1], wr[0], pr[0], 0);
-                stage(s + 3, wr[0], pr[0], wr[1], pr[1], 1);
+                ST(s + 2, wr[WS - 1], pr[WS - 1], wr[0], pr[0], 0);
+                ST(s + 3, wr[0], pr[0], wr[1], pr[1], 1);
             }
         }
     }
