@@ -1,0 +1,390 @@
+// solo kernel: persistent tiles of 256 x 256, one wave per SIMD, 256 x 64 per wave.
+// (part of liquidgemm.hip: included there, inside namespace lqq)
+#pragma once
+
+// ------------------------------------------------------------------------------------
+// With two waves per SIMD and 128 x 64 per wave the tiled kernels issue 3.5 dequantisation
+// instructions per MFMA, and measured without them the same kernel needs a sixth fewer cycles:
+// an 8-pass MFMA leaves the SIMD's vector issue free for about four other instructions, and
+// dequantisation plus addressing use all of them (paper Sec. 3.2: T_DQ per MMA shrinks with
+// the rows that reuse a dequantised fragment; Eq. 6).  This kernel doubles that reuse instead
+// of the waves: one wave per SIMD owns 256 rows x 64 channels, its 256 accumulator registers
+// live in the accumulation half of the register file, and every dequantised B operand feeds
+// eight MFMAs (1.75 dequantisation instructions per MFMA).  A single wave has nobody to cover
+// its stalls, so everything is software-pipelined in one pinned instruction stream: per MFMA
+// one half phase of the dequantisation (two instructions) and every second MFMA one fragment
+// read, fragments refreshed in place 14 MFMAs ahead of their use, X and W prefetched three
+// stages ahead, and -- as in duo_pt -- the block is persistent, so that the stream of stages
+// continues across tile boundaries.
+//
+// Block = 4 waves (one per SIMD), tile 256 x 256, one block per CU; LDS = 4 stages of
+// 256 rows x 128 bytes in the layout of duo_dl_tile (1 KiB pieces of 8 rows, 16-byte columns
+// rotated by the row) plus two copies of a tile's 256 activation and 256 channel scales; four register stages
+// of W.  K % 512 == 0.
+// ------------------------------------------------------------------------------------
+template <bool G128>
+__global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
+    int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
+    const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
+    __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n)
+{
+    constexpr int MF = 8;
+    constexpr int STAGE = 256 * 128;
+    constexpr int PER_STAGE = 8 + 6;  // loads of one stage: 8 of X, 4 of codes, 2 of parameters
+    extern __shared__ __attribute__((aligned(16))) int8_t lds[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int j = lane & 31, kb = lane >> 5, jr = j & 7;
+    const int stages = K >> 7;  // per tile, a multiple of four
+    const int chunks_per_tile = K >> 6;
+    const int tiles = blocks_m * blocks_n, G = (int)gridDim.x;
+
+    // logical tile id -> (bm, bn): the ids of one XCD (hardware block id mod 8; b + i G keeps
+    // it) form a contiguous range, walked four row blocks at a time (see block_coords)
+    auto coords = [&](int lid, int &bm, int &bn) {
+        if ((tiles & 7) == 0 && (G & 7) == 0) lid = (lid & 7) * (tiles >> 3) + (lid >> 3);
+        constexpr int GM = 4;
+        const int per_group = GM * blocks_n;
+        const int first = (lid / per_group) * GM;
+        const int gsz = min(blocks_m - first, GM);
+        const int in_group = lid % per_group;
+        bm = first + in_group % gsz;
+        bn = in_group / gsz;
+    };
+
+    // ---- load side: the tile whose stages are being prefetched ------------------------------
+    const int ld_r = (lane >> 3) ^ (wave & 1), ld_c = (lane & 7) ^ ld_r;
+    int ld_row = 8 * wave + ld_r;
+    const size_t wg_stride = (size_t)chunks_per_tile * 1024;
+    const size_t pg_stride = (size_t)stages * 32 * (G128 ? 2 : 4);
+    uint32_t wl = lane * 16;  // (not const: the X loads name it as an operand, see issue_x1)
+    const uint32_t pl_off = j * (G128 ? 2 : 4);
+    const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) void *)lds;
+    int l_lid = (int)blockIdx.x, l_s = 0;  // tile and stage the next prefetch takes
+    uint32_t xg[8];
+    const char *wbase, *pbase;
+    auto load_side_tile = [&](int lid) {
+        int bm, bn;
+        coords(lid, bm, bn);
+        const int ng = bn * 4 + wave;
+        const int t0 = 2 * min(ng, (N >> 6) - 1);
+        // (recomputed from one register per tile: eight row numbers kept across the tile loop
+        // would not fit beside the epilogue)
+        asm volatile("" : "+v"(ld_row));
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            xg[i] = (uint32_t)min(bm * 256 + 32 * i + ld_row, M - 1) * (uint32_t)K + 16 * ld_c;
+        wbase = reinterpret_cast<const char *>(Wp + (size_t)t0 * chunks_per_tile * 64);
+        pbase = reinterpret_cast<const char *>(gp) + (size_t)t0 * stages * 32 * (G128 ? 2 : 4);
+    };
+    // after the last stage of the block's last tile the load side stays on that stage (the
+    // prefetches past the end re-read it; nothing consumes them)
+    auto load_side_advance = [&] {
+        if (++l_s == stages) {
+            asm volatile("" ::: "memory");  // (a real branch: none of this is worth computing speculatively in every stage)
+            if (l_lid + G < tiles) {
+                l_lid += G;
+                l_s = 0;
+                load_side_tile(l_lid);
+            } else {
+                l_s = stages - 1;
+            }
+        }
+    };
+    // piece i of a stage: rows 32 i + 8 wave .. + 7, into 1 KiB piece 4 i + wave of LDS stage buf
+    auto issue_x1 = [&](int buf, int i) {
+        asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     : "+v"(wl)  // untouched; makes the W loads that follow depend on this statement
+                     : "v"(xg[i] + (uint32_t)l_s * 128), "s"(X), "s"(lds0 + buf * STAGE + (4 * i + wave) * 1024)
+                     : "memory", "m0");
+    };
+    // The W loads are written out as well, so that every wait of the stage loop is one that is
+    // written here: the compiler does not see the X loads, and its own wait for a W register
+    // would count only the W loads behind it -- far fewer than are in flight -- and so would
+    // also wait for the X of the stage issued last.  With one wave per SIMD that wait is not
+    // covered by anybody.  The registers must not be touched between load_w1 and arrive_w (the
+    // compiler takes them for complete): no kernel here may spill, and wr and pr are written and
+    // read in place.
+    auto load_w1 = [&](int t, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
+        const uint32_t wo = wl + (uint32_t)l_s * 2048, po = pl_off + (uint32_t)l_s * (G128 ? 64 : 128);
+        const char *wb = wbase + t * wg_stride;
+        const char *pb = pbase + t * pg_stride;
+        if (G128)
+            asm volatile("global_load_dwordx4 %0, %3, %4\n\tglobal_load_dwordx4 %1, %3, %4 offset:1024\n\t"
+                         "global_load_ushort %2, %5, %6"
+                         : "=&v"(w[t][0]), "=&v"(w[t][1]), "=&v"(p[t].raw)
+                         : "v"(wo), "s"(wb), "v"(po), "s"(pb)
+                         : "memory");
+        else
+            asm volatile("global_load_dwordx4 %0, %3, %4\n\tglobal_load_dwordx4 %1, %3, %4 offset:1024\n\t"
+                         "global_load_dword %2, %5, %6"
+                         : "=&v"(w[t][0]), "=&v"(w[t][1]), "=&v"(p[t].raw)
+                         : "v"(wo), "s"(wb), "v"(po), "s"(pb)
+                         : "memory");
+    };
+    // waits until at most PENDING loads of this wave are in flight; every use of (w, p) behind it
+    auto arrive_w = [&](auto pending_tag, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
+        asm volatile("s_waitcnt vmcnt(%6)"
+                     : "+v"(w[0][0]), "+v"(w[0][1]), "+v"(w[1][0]), "+v"(w[1][1]), "+v"(p[0].raw), "+v"(p[1].raw)
+                     : "n"(decltype(pending_tag)::value)
+                     : "memory");
+    };
+    // ---- compute side ------------------------------------------------------------------------
+    v16i acc[MF][2];
+    auto clear_acc = [&] {
+#pragma unroll
+        for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[mf][t][r] = 0;
+    };
+    clear_acc();
+    // one accumulator element, read where it sits (a copy of a whole 16-register fragment into
+    // vector registers needs 16 contiguous free ones, which the allocator does not find here)
+    auto acc_elem = [&](int mf, int t, int r) {
+        int v;
+        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc[mf][t][r]));
+        return v;
+    };
+    u32x4 wr[4][2][2];  // [stage mod 4][tile][chunk]
+    UnitParams<G128> pr[4][2];
+    v4i bf[2][2];
+    v4i a1[MF];
+    uint32_t s2v[2], a4v[2];  // broadcast parameters of the chunk whose B operands are being built
+    uint32_t tq[4];           // the four registers of one tile in flight through the dequantisation
+    // fragment row j of fragment mf sits in 1 KiB piece 4 mf + (j >> 3) at position
+    // 8 (r ^ (piece & 1)) + (c ^ r), r = j & 7: one base per 16-byte column pair (c, h) and
+    // half of the LDS (the offset field of an LDS read has 16 bits), the rest is an immediate
+    const int8_t *xs = lds + (j >> 3) * 1024 + 128 * ((j & 7) ^ ((j >> 3) & 1));
+    const int8_t *xs_ch[2][2][2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) xs_ch[u][c][h] = xs + u * (2 * STAGE) + 16 * ((4 * c + 2 * h + kb) ^ jr);
+
+    auto SB = [] { __builtin_amdgcn_sched_barrier(0); };
+    auto mm = [&](int i, const v4i (&b)[2]) {
+        acc[i >> 1][i & 1] = mfma_i8(a1[i >> 1], b[i & 1], acc[i >> 1][i & 1]);
+    };
+    auto rd = [&](int buf, int c, int h, int mf) {
+        a1[mf] = *reinterpret_cast<const v4i *>(xs_ch[buf >> 1][c][h] + (buf & 1) * STAGE + mf * 4096);
+    };
+    // one half phase (registers 2 half, 2 half + 1 of a tile's four) of the dequantisation:
+    // step 0 shift (high nibbles only), 1 mask, 2 multiply-add, 3 XOR
+    auto dq_half = [&](int step, int half, int t, const u32x4 &w, v4i &b, bool hi) {
+#pragma unroll
+        for (int d = 2 * half; d < 2 * half + 2; ++d) {
+            if (step == 0)
+                tq[d] = w[d] >> 4;
+            else if (step == 1)
+                tq[d] = (hi ? tq[d] : w[d]) & 0x0F0F0F0Fu;
+            else if (step == 2)
+                tq[d] = pk_mad_u16(tq[d], s2v[t], a4v[t]);
+            else
+                b[d] = (int)(tq[d] ^ 0x80808080u);
+        }
+    };
+    // slot i (0..15) of a k-step that builds bn = B(c, 1) of w: 16 half phases
+    auto build_hi = [&](int i, const u32x4 (&w)[2][2], int c, v4i (&bn)[2]) {
+        const int t = i >> 3, k = i & 7;
+        dq_half(k >> 1, k & 1, t, w[t][c], bn[t], true);
+    };
+    // slot i of a k-step that builds bn = B(c, 0) of (w, p): parameters, then 12 half phases
+    auto build_lo = [&](int i, const u32x4 (&w)[2][2], const UnitParams<G128> (&p)[2], int c, v4i (&bn)[2]) {
+        if (i < 2) {
+            p[i].get(c, s2v[i], a4v[i]);
+        } else if (i < 14) {
+            const int t = (i - 2) / 6, k = (i - 2) % 6;
+            dq_half(1 + (k >> 1), k & 1, t, w[t][c], bn[t], false);
+        }
+    };
+    // Fragment mf is used by slots 2 mf and 2 mf + 1; fragment 7 of the running k-step is read
+    // in its slot 0 and fragment mf of the next k-step in slot 2 mf + 2 (14 MFMAs ahead).
+    // (cb, cc, ch) = LDS stage, chunk and half of the running k-step, (nb, nc, nh) of the next.
+    auto kstep_hi = [&](const v4i (&bc)[2], v4i (&bn)[2], const u32x4 (&w)[2][2], int c, int cb, int cc, int ch,
+                        int nb, int nc, int nh) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            mm(i, bc);
+            if (i == 0)
+                rd(cb, cc, ch, 7);
+            else if (!(i & 1))
+                rd(nb, nc, nh, i / 2 - 1);
+            build_hi(i, w, c, bn);
+            SB();
+        }
+    };
+    auto kstep_lo = [&](const v4i (&bc)[2], v4i (&bn)[2], const u32x4 (&w)[2][2], const UnitParams<G128> (&p)[2],
+                        int c, int cb, int cc, int ch, int nb, int nc, int nh) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            mm(i, bc);
+            if (i == 0)
+                rd(cb, cc, ch, 7);
+            else if (!(i & 1))
+                rd(nb, nc, nh, i / 2 - 1);
+            build_lo(i, w, p, c, bn);
+            SB();
+        }
+    };
+    // builds bf[0] = B(0, 0) of stage set q and reads fragments 0..6 of its first k-step
+    auto first_operands = [&](int q) {
+#pragma unroll
+        for (int i = 0; i < 14; ++i) build_lo(i, wr[q], pr[q], 0, bf[0]);
+#pragma unroll
+        for (int mf = 0; mf < 7; ++mf) rd(q, 0, 0, mf);
+    };
+    // One stage q (= stage mod 4: LDS stage and W register set; bf[0] holds its B(0, 0), a1 its
+    // fragments 0..6 on entry).  In its last k-step: the stage barrier behind the second MFMA
+    // (X of the next stage complete and visible; the LDS stage of the stage before released),
+    // then the prefetch of the stage three ahead into that LDS stage and the free register set.
+    // The next stage may belong to the block's next tile: its operands then wait in registers
+    // while the epilogue runs (after the last tile they are those of a re-read stage, unused).
+    auto stage = [&](auto q_tag) {
+        constexpr int q = decltype(q_tag)::value, nq = (q + 1) & 3, fq = (q + 3) & 3;
+        kstep_hi(bf[0], bf[1], wr[q], 0, q, 0, 0, q, 0, 1);
+        kstep_lo(bf[1], bf[0], wr[q], pr[q], 1, q, 0, 1, q, 1, 0);
+        kstep_hi(bf[0], bf[1], wr[q], 1, q, 1, 0, q, 1, 1);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            mm(i, bf[1]);
+            if (i == 0)
+                rd(q, 1, 1, 7);
+            else if (!(i & 1))
+                rd(nq, 0, 0, i / 2 - 1);
+            // (slot 0: X and W of the next stage have landed, the stage behind it may be in
+            // flight; slot 1: every wave's part of that X is visible, and the LDS stage of the
+            // stage before this one is released)
+            if (i == 0) arrive_w(std::integral_constant<int, PER_STAGE>{}, wr[nq], pr[nq]);
+            build_lo(i, wr[nq], pr[nq], 0, bf[0]);
+            if (i == 1) asm volatile("s_barrier" ::: "memory");
+            if (i >= 2 && i < 10) issue_x1(fq, i - 2);
+            if (i == 10) load_w1(0, wr[fq], pr[fq]);
+            if (i == 11) load_w1(1, wr[fq], pr[fq]);
+            SB();
+        }
+        // (the next stage's first B operand is complete here, also where the next stage is the
+        // next trip of a loop: nothing of it may sink into the loop's latch)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int d = 0; d < 4; ++d) asm volatile("" : "+v"(bf[0][t][d]));
+        load_side_advance();
+        SB();
+    };
+    const std::integral_constant<int, 0> q0{};
+    const std::integral_constant<int, 1> q1{};
+    const std::integral_constant<int, 2> q2{};
+    const std::integral_constant<int, 3> q3{};
+
+    // ---- pipeline fill: stages 0, 1, 2 of the first tile ------------------------------------
+    load_side_tile(l_lid);
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) issue_x1(q, i);
+        load_w1(0, wr[q], pr[q]);
+        load_w1(1, wr[q], pr[q]);
+        __builtin_amdgcn_sched_barrier(0);
+        load_side_advance();
+    }
+    arrive_w(std::integral_constant<int, 2 * PER_STAGE>{}, wr[0], pr[0]);  // and X(0) of this wave is in LDS
+    asm volatile("s_barrier" ::: "memory");
+    first_operands(0);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- the block's tiles ---------------------------------------------------------------------
+    uint32_t sx_par = 0;  // which of the two copies of the tile's activation scales is this tile's
+    for (int lid = (int)blockIdx.x; lid < tiles; lid += G) {
+        int bm, bn;
+        coords(lid, bm, bn);
+        const int ng = bn * 4 + wave;
+        // The tile's 256 activation scales go to LDS now (64 per wave, rows past M take the last
+        // row's): the epilogue of a single wave per SIMD would otherwise sit through the latency
+        // of its scale loads once per fragment.  Complete and visible after the waits and
+        // barriers of the first stages; two copies, so that a wave still in its epilogue is not
+        // overtaken by the next tile's load.
+        // (A call for the INT32 accumulators alone passes no scales.)
+        if (Y) {
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                         :
+                         : "v"((uint32_t)min(bm * 256 + 64 * wave + lane, M - 1) * 4u), "s"(sx),
+                           "s"(lds0 + 4 * STAGE + sx_par * 1024 + wave * 256)
+                         : "memory", "m0");
+            // (and the wave's 64 channel scales, for the same reason)
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                         :
+                         : "v"((uint32_t)(64 * min(ng, (N >> 6) - 1) + lane) * 4u), "s"(sw),
+                           "s"(lds0 + 4 * STAGE + 2048 + sx_par * 1024 + wave * 256)
+                         : "memory", "m0");
+        }
+        for (int it = 0; it < stages; it += 4) {
+            stage(q0);
+            stage(q1);
+            stage(q2);
+            stage(q3);
+        }
+        // epilogue of the tile (the prefetches of the next tile's first stages are in flight)
+        const float *sx_tile = reinterpret_cast<const float *>(lds + 4 * STAGE + sx_par * 1024);
+        const float2 swv = *reinterpret_cast<const float2 *>(lds + 4 * STAGE + 2048 + sx_par * 1024 + wave * 256 + 8 * j);
+        sx_par ^= 1;
+        // One fragment at a time, fenced: the accumulators sit in the accumulation registers, and
+        // an epilogue free to read all 256 of them at once does not fit beside the prefetched W.
+        // Element r of a fragment is row 8 (r >> 2) + 4 kb + (r & 3); a row's address is a
+        // wave-uniform base plus one 32-bit lane offset.
+        // (acc_elem reads inside inline assembly, where the compiler does not count the wait
+        // states an MFMA result needs before it is read: the last MFMA is further back than that
+        // anyway, and this says so)
+        asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+        if (ng < (N >> 6)) {
+            const int n = 64 * ng + 2 * j;
+            const uint32_t lane_off = (uint32_t)(4 * kb) * (uint32_t)N + (uint32_t)n;  // in elements
+#pragma unroll
+            for (int mf = 0; mf < MF; ++mf) {
+                const int row0 = bm * 256 + 32 * mf;  // wave-uniform
+                if (Y) {
+                    float sxv[16];
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const float4 v = *reinterpret_cast<const float4 *>(sx_tile + 32 * mf + 8 * q4 + 4 * kb);
+                        sxv[4 * q4 + 0] = v.x;
+                        sxv[4 * q4 + 1] = v.y;
+                        sxv[4 * q4 + 2] = v.z;
+                        sxv[4 * q4 + 3] = v.w;
+                    }
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int ur = row0 + 8 * (r >> 2) + (r & 3);
+                        union {
+                            __half h[2];
+                            uint32_t u;
+                        } o;
+                        o.h[0] = scale_to_half(acc_elem(mf, 0, r), sxv[r], swv.x);
+                        o.h[1] = scale_to_half(acc_elem(mf, 1, r), sxv[r], swv.y);
+                        char *row = reinterpret_cast<char *>(Y) + (size_t)ur * (size_t)N * 2;
+                        if (ur + 4 * kb < M) *reinterpret_cast<uint32_t *>(row + (size_t)lane_off * 2) = o.u;
+                    }
+                }
+                if (ACC) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int ur = row0 + 8 * (r >> 2) + (r & 3);
+                        char *row = reinterpret_cast<char *>(ACC) + (size_t)ur * (size_t)N * 4;
+                        if (ur + 4 * kb < M)
+                            *reinterpret_cast<int2 *>(row + (size_t)lane_off * 4) = int2{acc_elem(mf, 0, r), acc_elem(mf, 1, r)};
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        clear_acc();
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // the prefetches past the last stage write LDS too: they must have landed before the block
+    // ends and its LDS goes to another block
+    wait_vmcnt0();
+}

@@ -91,6 +91,7 @@ __device__ __forceinline__ __half scale_to_half(int acc, float sx, float sw)
 #include "kernels_tiled.h"
 #include "kernels_tiled_dl.h"
 #include "kernels_tiled_pt.h"
+#include "kernels_tiled_solo.h"
 #include "kernels_reference.h"
 #include "kernels_grouped.h"
 
@@ -427,6 +428,31 @@ static int launch_duo_pt(const Args &a)
     return LQ_OK;
 }
 
+// Persistent 256 x 256 tiles, one wave per SIMD (see kernels_tiled_solo.h).  Needs K % 512 == 0.
+static int launch_solo_pt(const Args &a)
+{
+    if (a.query) return LQ_OK;  // no workspace
+    if (a.K % 512 != 0) return fail(LQ_ERR_INVALID, "the 256-row persistent variant needs K %% 512 == 0, got %d", a.K);
+    const int blocks_n = (a.N + 255) / 256, blocks_m = (a.M + 255) / 256;
+    if ((long long)a.M * a.K >= (1ll << 32))
+        return fail(LQ_ERR_INVALID, "M * K = %lld is beyond the 2^32 - 1 bytes of X one call addresses; split the batch",
+                    (long long)a.M * a.K);
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    const int grid = std::min(blocks_m * blocks_n, std::max(cus, 1));
+    const size_t lds_bytes = 4 * (size_t)256 * 128 + 4 * 1024;  // X stages; two copies of both scales
+    if (a.group == 128) {
+        if (int rc = allow_lds(w4a8_solo_pt_kernel<true>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_solo_pt_kernel<true>), dim3((unsigned)grid), dim3(256), lds_bytes, a.stream, a.M, a.N,
+                           a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
+    } else {
+        if (int rc = allow_lds(w4a8_solo_pt_kernel<false>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_solo_pt_kernel<false>), dim3((unsigned)grid), dim3(256), lds_bytes, a.stream, a.M, a.N,
+                           a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
+    }
+    return LQ_OK;
+}
+
 // the explicit producer / consumer form (measured only, never dispatched)
 static int launch_excp(const Args &a)
 {
@@ -526,6 +552,7 @@ static const Variant kVariants[] = {
     {"duo_m128", &launch_duo<0, 0>, 0, 1, 1},
     {"duo_dl_m128", &launch_duo_dl<0>, 0, 1, 1},
     {"duo_pt_m128", &launch_duo_pt, 0, 1, 8, 512},
+    {"solo_pt_m256", &launch_solo_pt, 0, 1, 8, 512},
     // --- the same kernels with a named number of K slices: the split paths at sizes where the
     //     dispatcher would not split (parity tests) ---
     {"stream16_f2_w8_s2", &launch_stream16<2, 8, 2>, 16, 2, 1},
@@ -557,6 +584,24 @@ static int find_variant(const char *name)
     for (int i = 0; i < kNumVariants; ++i)
         if (!strcmp(kVariants[i].name, name)) return i;
     return -1;
+}
+
+// 256 x 256 tiles with one wave per SIMD against 128 x 256 tiles with two, both persistent.
+// Half the dequantisation per MFMA makes a round of 256-row tiles about 7 % shorter than the
+// two rounds of 128-row tiles it replaces (2 % with K below 4096, where the tile's epilogue
+// weighs more); but one block per CU runs whole rounds, while two blocks per CU share it, so
+// that a last round of the 128-row tiles that is half empty also takes about half the time
+// (measured: 3.5 rounds on 2048 x 28672 x 8192 take 397 us against 435).
+constexpr long long kAssumedCUs = 256;  // the shape rules of the dispatcher are written for the MI355X
+static bool solo_pt_pays(int M, int N, int K)
+{
+    if (K % 512 != 0) return false;
+    const long long t256 = (long long)((M + 255) / 256) * ((N + 255) / 256);
+    const long long t128 = (long long)((M + 127) / 128) * ((N + 255) / 256);
+    if (t256 < kAssumedCUs) return false;
+    const double rounds_solo = (double)((t256 + kAssumedCUs - 1) / kAssumedCUs) * (K >= 4096 ? 0.93 : 0.98);
+    const double rounds_duo = (double)t128 / (2.0 * kAssumedCUs);
+    return rounds_solo < rounds_duo;
 }
 
 // Shape -> kernel.  Up to 32 rows the weights are streamed once with X fragments in
@@ -603,8 +648,11 @@ static int select_variant(int M, int N, int K)
     // one tile per CU or fewer, the two k groups per block of the other form do
     // (from two tiles per resident slot on and with whole 512-k units, its persistent form:
     // one pipeline fill per block instead of per tile, 1 to 2 % measured)
-    if (((M + 127) / 128) * ((N + 255) / 256) > 256)
+    // (and with enough whole rounds of them, 256-row tiles)
+    if (((M + 127) / 128) * ((N + 255) / 256) > 256) {
+        if (solo_pt_pays(M, N, K)) return find_variant("solo_pt_m256");
         return find_variant(duo_pt_fits(M, N, K) ? "duo_pt_m128" : "duo_dl_m128");
+    }
     // few tiles: a grid of 64-row tiles can fill the chip with half the split-K exchange
     return find_variant(prefer_64_row_tiles(M, N, K) ? "duo_m64" : "duo_m128");
 }
@@ -636,10 +684,10 @@ static int run(int variant, const Args &a)
                     a.K);
     (void)hipGetLastError();
     // The tiled kernels address X with 32-bit byte offsets.  A batch with M * K >= 2^32 is
-    // run as consecutive row chunks (multiples of 128 rows, so every chunk keeps the
+    // run as consecutive row chunks (multiples of 256 rows, so every chunk keeps the
     // alignment and the tile grid of a call of its own) on the same stream; rows are
     // independent, so the result is that of one launch.
-    const long long rows_max = ((1ll << 32) - 1) / a.K / 128 * 128;
+    const long long rows_max = ((1ll << 32) - 1) / a.K / 256 * 256;
     size_t need_max = 0;
     for (long long r0 = 0; r0 < a.M; r0 += rows_max) {
         Args c = a;

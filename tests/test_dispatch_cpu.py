@@ -20,11 +20,17 @@ def test_dispatcher_families_on_the_workloads():
         elif s.M <= 64 and s.N <= 16384:
             assert name == "stream_m64", (s.name, name)
         else:
-            assert name in ("duo_m64", "duo_m128", "duo_dl_m128", "duo_pt_m128"), (s.name, name)
+            assert name in ("duo_m64", "duo_m128", "duo_dl_m128", "duo_pt_m128", "solo_pt_m256"), (s.name, name)
             tiles128 = -(-s.M // 128) * -(-s.N // 256)
+            tiles256 = -(-s.M // 256) * -(-s.N // 256)
             if tiles128 > 256:        # more tiles than CUs: the direct-to-LDS pipeline, persistent where it fits
                 fits = s.K % 512 == 0 and (s.M % 128 == 0 or s.M % 128 > 64)
-                assert name == ("duo_pt_m128" if fits else "duo_dl_m128"), (s.name, name)
+                # 256-row tiles (one block per CU) when their whole rounds are fewer, 7 % apiece
+                # taken off, than the rounds of 128-row tiles shared two blocks to a CU
+                solo = (s.K % 512 == 0 and tiles256 >= 256
+                        and -(-tiles256 // 256) * (0.93 if s.K >= 4096 else 0.98) < tiles128 / 512)
+                want = "solo_pt_m256" if solo else "duo_pt_m128" if fits else "duo_dl_m128"
+                assert name == want, (s.name, name)
             elif -(-s.M // 64) * -(-s.N // 256) > 256:
                 assert name == "duo_m128", (s.name, name)
         v = api.w4a8_select_variant(s.M, s.N, s.K, s.group)
@@ -59,9 +65,14 @@ def test_dispatcher_boundaries():
     assert _pick(256, 8192, 8192) == "duo_m64" and _pick(256, 10240, 8192, 128) == "duo_m128"
     assert _pick(128, 4096, 256) == "duo_m128"                 # one k unit: no room for two k groups
     assert _pick(1152, 8192, 8192) == "duo_pt_m128" and _pick(1024, 8192, 8192) == "duo_m128"   # 288 / 256 tiles
-    assert _pick(4096, 8192, 8192) == "duo_pt_m128" and _pick(1024, 28672, 8192, 128) == "duo_pt_m128"
+    assert _pick(2560, 8192, 8192) == "duo_pt_m128" and _pick(1024, 28672, 8192, 128) == "duo_pt_m128"
+    # whole rounds of 256 x 256 tiles: one wave per SIMD
+    assert _pick(4096, 8192, 8192) == "solo_pt_m256" and _pick(2048, 8192, 28672, 128) == "solo_pt_m256"
+    assert _pick(8192, 8192, 8192) == "solo_pt_m256" and _pick(4096, 8192, 2048) == "solo_pt_m256"
+    assert _pick(2048, 28672, 8192, 128) == "duo_pt_m128"      # 3.5 rounds: two blocks per CU share the last one
+    assert _pick(1792, 8192, 8192) == "duo_pt_m128"            # fewer 256-row tiles than CUs
     assert _pick(4096, 8192, 11008) == "duo_dl_m128"           # K not a multiple of 512: one tile per block
-    assert _pick(4096 + 40, 8192, 8192) == "duo_dl_m128"       # ragged last row tile of at most 64 rows: its two-fragment path
+    assert _pick(4096 + 40, 8192, 8192) == "duo_dl_m128"       # (rounds of 256-row tiles: 3 against 2.06) ragged last row tile of at most 64 rows: its two-fragment path
     assert _pick(4096 + 100, 8192, 8192) == "duo_pt_m128"
     with pytest.raises(api.LiquidGemmError):
         api.w4a8_select_variant(8, 100, 512, 64)                # bad shape

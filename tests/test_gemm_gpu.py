@@ -491,19 +491,19 @@ def test_batch_beyond_32_bit_offsets_of_x():
     assert np.array_equal(ACC2.cpu().numpy(), ref), "accumulators of the named variant differ"
 
 
+@pytest.mark.parametrize("kernel", ["duo_pt_m128", "solo_pt_m256"])
 @pytest.mark.parametrize("M,N,K,g", [(1541, 12352, 512, 64), (2048, 10240, 1024, 128), (700, 2048, 1536, 64)])
-def test_persistent_tile_kernel(M, N, K, g):
-    """The persistent form of the tiled kernel (blocks walk several tiles as one stream of
-    stages): more tiles than resident blocks, so that blocks cross tile boundaries; a ragged
-    last row tile, an N tail, tile counts that are and are not multiples of the XCD count, and a
-    grid smaller than the number of resident slots.  Every accumulator and every FP16 output
-    against the exact float64 product of the oracle's weights."""
-    import torch
-
+def test_persistent_tile_kernel(M, N, K, g, kernel):
+    """The persistent forms of the tiled kernel (blocks walk several tiles as one stream of
+    stages; 128-row tiles with two waves per SIMD, 256-row tiles with one): more tiles than
+    resident blocks, so that blocks cross tile boundaries; a ragged last row tile, an N tail,
+    tile counts that are and are not multiples of the XCD count, and a grid smaller than the
+    number of resident slots.  Every accumulator and every FP16 output against the exact float64
+    product of the oracle's weights."""
     names = api.w4a8_variant_names()
-    v = names.index("duo_pt_m128")
+    v = names.index(kernel)
     assert api.w4a8_variant_supports(v, M, N, K, g)
-    _say(f"persistent tiles M={M} N={N} K={K} g={g}")
+    _say(f"persistent tiles {kernel} M={M} N={N} K={K} g={g}")
     P = H.Problem(N, K, g, seed=M)
     Wd, s_w = P.oracle_wd()
     X, s_x = I.make_activations(M, K, outlier_frac=0.01, seed=M + N)
@@ -511,3 +511,10 @@ def test_persistent_tile_kernel(M, N, K, g):
     Y, ACC = P.run(X, s_x, variant=v)
     assert np.array_equal(ACC.astype(np.int64), ref), f"{np.count_nonzero(ACC != ref)} accumulators differ"
     H.assert_fp16_close(Y, O.scale_epilogue_f64(ref, s_x, s_w), "persistent tiles")
+    # the accumulators alone: such a call passes no scales (null pointers), which no kernel may read
+    import torch
+
+    _, ACC2 = api.w4a8_gemm_variant(v, torch.from_numpy(X).cuda(), None, P.d_packed, P.d_gparams, None, N, K, g,
+                                    want_y=False)
+    torch.cuda.synchronize()
+    assert np.array_equal(ACC2.cpu().numpy().astype(np.int64), ref), "accumulator-only call differs"
