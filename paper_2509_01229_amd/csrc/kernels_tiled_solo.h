@@ -205,8 +205,9 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
     // Fragment mf is used by slots 2 mf and 2 mf + 1; fragment 7 of the running k-step is read
     // in its slot 0 and fragment mf of the next k-step in slot 2 mf + 2 (14 MFMAs ahead).
     // (cb, cc, ch) = LDS stage, chunk and half of the running k-step, (nb, nc, nh) of the next.
+    // ex(i): what else slot i carries (a piece of the prefetch, the stage's wait and barrier)
     auto kstep_hi = [&](const v4i (&bc)[2], v4i (&bn)[2], const u32x4 (&w)[2][2], int c, int cb, int cc, int ch,
-                        int nb, int nc, int nh) {
+                        int nb, int nc, int nh, auto ex) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             mm(i, bc);
@@ -215,11 +216,12 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
             else if (!(i & 1))
                 rd(nb, nc, nh, i / 2 - 1);
             build_hi(i, w, c, bn);
+            ex(i);
             SB();
         }
     };
     auto kstep_lo = [&](const v4i (&bc)[2], v4i (&bn)[2], const u32x4 (&w)[2][2], const UnitParams<G128> (&p)[2],
-                        int c, int cb, int cc, int ch, int nb, int nc, int nh) {
+                        int c, int cb, int cc, int ch, int nb, int nc, int nh, auto ex) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             mm(i, bc);
@@ -227,7 +229,9 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
                 rd(cb, cc, ch, 7);
             else if (!(i & 1))
                 rd(nb, nc, nh, i / 2 - 1);
+            if (i == 0) ex(-1);  // (before the slot's phase: the wait for the registers it expands)
             build_lo(i, w, p, c, bn);
+            ex(i);
             SB();
         }
     };
@@ -239,41 +243,45 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
         for (int mf = 0; mf < 7; ++mf) rd(q, 0, 0, mf);
     };
     // One stage q (= stage mod 4: LDS stage and W register set; bf[0] holds its B(0, 0), a1 its
-    // fragments 0..6 on entry).  In its last k-step: the stage barrier behind the second MFMA
-    // (X of the next stage complete and visible; the LDS stage of the stage before released),
-    // then the prefetch of the stage three ahead into that LDS stage and the free register set.
+    // fragments 0..6 on entry).  Its last k-step first waits for X and W of the next stage, then
+    // meets the other waves (their parts of that X are visible; the LDS stage of the stage before
+    // this one is released) and starts the prefetch of the stage three ahead into that LDS stage
+    // and the free register set.  The 14 loads of a prefetch are spread over the 62 slots up to
+    // the next stage's barrier -- four in the last k-step, ten in the first three of the next
+    // stage: the four waves of a CU share one path from the L1, and all of a stage's loads
+    // within one k-step ask twice what it delivers, which stalls the issue of every wave.
     // The next stage may belong to the block's next tile: its operands then wait in registers
     // while the epilogue runs (after the last tile they are those of a re-read stage, unused).
     auto stage = [&](auto q_tag) {
-        constexpr int q = decltype(q_tag)::value, nq = (q + 1) & 3, fq = (q + 3) & 3;
-        kstep_hi(bf[0], bf[1], wr[q], 0, q, 0, 0, q, 0, 1);
-        kstep_lo(bf[1], bf[0], wr[q], pr[q], 1, q, 0, 1, q, 1, 0);
-        kstep_hi(bf[0], bf[1], wr[q], 1, q, 1, 0, q, 1, 1);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            mm(i, bf[1]);
-            if (i == 0)
-                rd(q, 1, 1, 7);
-            else if (!(i & 1))
-                rd(nq, 0, 0, i / 2 - 1);
-            // (slot 0: X and W of the next stage have landed, the stage behind it may be in
-            // flight; slot 1: every wave's part of that X is visible, and the LDS stage of the
-            // stage before this one is released)
-            if (i == 0) arrive_w(std::integral_constant<int, PER_STAGE>{}, wr[nq], pr[nq]);
-            build_lo(i, wr[nq], pr[nq], 0, bf[0]);
+        constexpr int q = decltype(q_tag)::value, nq = (q + 1) & 3, gq = (q + 2) & 3, fq = (q + 3) & 3;
+        kstep_hi(bf[0], bf[1], wr[q], 0, q, 0, 0, q, 0, 1, [&](int i) {
+            if (i == 2) issue_x1(gq, 4);
+            if (i == 7) issue_x1(gq, 5);
+            if (i == 12) issue_x1(gq, 6);
+        });
+        kstep_lo(bf[1], bf[0], wr[q], pr[q], 1, q, 0, 1, q, 1, 0, [&](int i) {
+            if (i == 2) issue_x1(gq, 7);
+            if (i == 8) load_w1(0, wr[gq], pr[gq]);
+        });
+        kstep_hi(bf[0], bf[1], wr[q], 1, q, 1, 0, q, 1, 1, [&](int i) {
+            if (i == 4) load_w1(1, wr[gq], pr[gq]);
+        });
+        load_side_advance();
+        SB();
+        kstep_lo(bf[1], bf[0], wr[nq], pr[nq], 0, q, 1, 1, nq, 0, 0, [&](int i) {
+            if (i == -1) arrive_w(std::integral_constant<int, PER_STAGE>{}, wr[nq], pr[nq]);
             if (i == 1) asm volatile("s_barrier" ::: "memory");
-            if (i >= 2 && i < 10) issue_x1(fq, i - 2);
-            if (i == 10) load_w1(0, wr[fq], pr[fq]);
-            if (i == 11) load_w1(1, wr[fq], pr[fq]);
-            SB();
-        }
+            if (i == 3) issue_x1(fq, 0);
+            if (i == 6) issue_x1(fq, 1);
+            if (i == 9) issue_x1(fq, 2);
+            if (i == 12) issue_x1(fq, 3);
+        });
         // (the next stage's first B operand is complete here, also where the next stage is the
         // next trip of a loop: nothing of it may sink into the loop's latch)
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int d = 0; d < 4; ++d) asm volatile("" : "+v"(bf[0][t][d]));
-        load_side_advance();
         SB();
     };
     const std::integral_constant<int, 0> q0{};
@@ -281,10 +289,10 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
     const std::integral_constant<int, 2> q2{};
     const std::integral_constant<int, 3> q3{};
 
-    // ---- pipeline fill: stages 0, 1, 2 of the first tile ------------------------------------
+    // ---- pipeline fill: stages 0 and 1 of the first tile and the first four loads of stage 2 ----
     load_side_tile(l_lid);
 #pragma unroll
-    for (int q = 0; q < 3; ++q) {
+    for (int q = 0; q < 2; ++q) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) issue_x1(q, i);
         load_w1(0, wr[q], pr[q]);
@@ -292,7 +300,9 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
         __builtin_amdgcn_sched_barrier(0);
         load_side_advance();
     }
-    arrive_w(std::integral_constant<int, 2 * PER_STAGE>{}, wr[0], pr[0]);  // and X(0) of this wave is in LDS
+#pragma unroll
+    for (int i = 0; i < 4; ++i) issue_x1(2, i);
+    arrive_w(std::integral_constant<int, PER_STAGE + 4>{}, wr[0], pr[0]);  // and X(0) of this wave is in LDS
     asm volatile("s_barrier" ::: "memory");
     first_operands(0);
     __builtin_amdgcn_sched_barrier(0);
