@@ -19,10 +19,17 @@
 //
 // Block = 4 waves (one per SIMD), tile 256 x 256, one block per CU; LDS = 4 stages of
 // 256 rows x 128 bytes in the layout of duo_dl_tile (1 KiB pieces of 8 rows, 16-byte columns
-// rotated by the row) plus two copies of a tile's 256 activation and 256 channel scales; four register stages
-// of W.  K % 512 == 0.
+// rotated by the row) plus two copies of a tile's 256 activation and 256 channel scales; four
+// register stages of W.  K % 512 == 0.
+//
+// KG = 2 is the form for outputs with fewer 256 x 256 tiles than CUs: tile 256 x 128, the four
+// waves are two k groups of two; both groups walk every stage, group g computing the stage's
+// chunk g (64 of its 128 k) -- so the ring of four LDS stages still runs three stages ahead --
+// and after the tile's last stage the groups exchange half of their accumulators through the
+// (drained) LDS ring and each finishes four of the eight row fragments.  Tiles are separate
+// there: the pipeline drains and refills between them.
 // ------------------------------------------------------------------------------------
-template <bool G128>
+template <bool G128, int KG = 1>
 __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
     int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
@@ -30,12 +37,15 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
 {
     constexpr int MF = 8;
     constexpr int STAGE = 256 * 128;
-    constexpr int PER_STAGE = 8 + 6;  // loads of one stage: 8 of X, 4 of codes, 2 of parameters
+    constexpr int PER_STAGE = 8 + (KG == 1 ? 6 : 4);  // loads of one stage: 8 of X, 4 / KG of codes, 2 of parameters
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int j = lane & 31, kb = lane >> 5, jr = j & 7;
+    const int grp = KG == 2 ? wave >> 1 : 0;          // KG = 2: the chunk of every stage this wave computes
+    const int colw = KG == 2 ? (wave & 1) : wave;     // which 64 channels of the block's 256 / KG
+    constexpr int WPB = 4 / KG;                       // 64-channel groups per block
     const int stages = K >> 7;  // per tile, a multiple of four
     const int chunks_per_tile = K >> 6;
     const int tiles = blocks_m * blocks_n, G = (int)gridDim.x;
@@ -67,7 +77,7 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
     auto load_side_tile = [&](int lid) {
         int bm, bn;
         coords(lid, bm, bn);
-        const int ng = bn * 4 + wave;
+        const int ng = bn * WPB + colw;
         const int t0 = 2 * min(ng, (N >> 6) - 1);
         // (recomputed from one register per tile: eight row numbers kept across the tile loop
         // would not fit beside the epilogue)
@@ -78,12 +88,12 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
         wbase = reinterpret_cast<const char *>(Wp + (size_t)t0 * chunks_per_tile * 64);
         pbase = reinterpret_cast<const char *>(gp) + (size_t)t0 * stages * 32 * (G128 ? 2 : 4);
     };
-    // after the last stage of the block's last tile the load side stays on that stage (the
-    // prefetches past the end re-read it; nothing consumes them)
+    // after the last stage of the block's last tile (KG = 2: of every tile) the load side stays
+    // on that stage (the prefetches past the end re-read it; nothing consumes them)
     auto load_side_advance = [&] {
         if (++l_s == stages) {
             asm volatile("" ::: "memory");  // (a real branch: none of this is worth computing speculatively in every stage)
-            if (l_lid + G < tiles) {
+            if (KG == 1 && l_lid + G < tiles) {
                 l_lid += G;
                 l_s = 0;
                 load_side_tile(l_lid);
@@ -110,7 +120,18 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
         const uint32_t wo = wl + (uint32_t)l_s * 2048, po = pl_off + (uint32_t)l_s * (G128 ? 64 : 128);
         const char *wb = wbase + t * wg_stride;
         const char *pb = pbase + t * pg_stride;
-        if (G128)
+        if (KG == 2) {  // the wave's chunk only
+            if (G128)
+                asm volatile("global_load_dwordx4 %0, %2, %3\n\tglobal_load_ushort %1, %4, %5"
+                             : "=&v"(w[t][0]), "=&v"(p[t].raw)
+                             : "v"(wo + (uint32_t)grp * 1024), "s"(wb), "v"(po), "s"(pb)
+                             : "memory");
+            else
+                asm volatile("global_load_dwordx4 %0, %2, %3\n\tglobal_load_dword %1, %4, %5"
+                             : "=&v"(w[t][0]), "=&v"(p[t].raw)
+                             : "v"(wo + (uint32_t)grp * 1024), "s"(wb), "v"(po), "s"(pb)
+                             : "memory");
+        } else if (G128)
             asm volatile("global_load_dwordx4 %0, %3, %4\n\tglobal_load_dwordx4 %1, %3, %4 offset:1024\n\t"
                          "global_load_ushort %2, %5, %6"
                          : "=&v"(w[t][0]), "=&v"(w[t][1]), "=&v"(p[t].raw)
@@ -125,6 +146,12 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
     };
     // waits until at most PENDING loads of this wave are in flight; every use of (w, p) behind it
     auto arrive_w = [&](auto pending_tag, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
+        if (KG == 2)
+            asm volatile("s_waitcnt vmcnt(%4)"
+                         : "+v"(w[0][0]), "+v"(w[1][0]), "+v"(p[0].raw), "+v"(p[1].raw)
+                         : "n"(decltype(pending_tag)::value)
+                         : "memory");
+        else
         asm volatile("s_waitcnt vmcnt(%6)"
                      : "+v"(w[0][0]), "+v"(w[0][1]), "+v"(w[1][0]), "+v"(w[1][1]), "+v"(p[0].raw), "+v"(p[1].raw)
                      : "n"(decltype(pending_tag)::value)
@@ -164,7 +191,8 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
 #pragma unroll
         for (int c = 0; c < 2; ++c)
 #pragma unroll
-            for (int h = 0; h < 2; ++h) xs_ch[u][c][h] = xs + u * (2 * STAGE) + 16 * ((4 * c + 2 * h + kb) ^ jr);
+            for (int h = 0; h < 2; ++h)  // (KG = 2: entry 0 is the wave's own chunk)
+                xs_ch[u][c][h] = xs + u * (2 * STAGE) + 16 * ((4 * (KG == 2 ? grp : c) + 2 * h + kb) ^ jr);
 
     auto SB = [] { __builtin_amdgcn_sched_barrier(0); };
     auto mm = [&](int i, const v4i (&b)[2]) {
@@ -194,9 +222,10 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
         dq_half(k >> 1, k & 1, t, w[t][c], bn[t], true);
     };
     // slot i of a k-step that builds bn = B(c, 0) of (w, p): parameters, then 12 half phases
-    auto build_lo = [&](int i, const u32x4 (&w)[2][2], const UnitParams<G128> (&p)[2], int c, v4i (&bn)[2]) {
+    // (c = which of the stage's chunk registers, pc = which chunk's parameters: the same but for KG = 2)
+    auto build_lo = [&](int i, const u32x4 (&w)[2][2], const UnitParams<G128> (&p)[2], int c, int pc, v4i (&bn)[2]) {
         if (i < 2) {
-            p[i].get(c, s2v[i], a4v[i]);
+            p[i].get(pc, s2v[i], a4v[i]);
         } else if (i < 14) {
             const int t = (i - 2) / 6, k = (i - 2) % 6;
             dq_half(1 + (k >> 1), k & 1, t, w[t][c], bn[t], false);
@@ -221,7 +250,7 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
         }
     };
     auto kstep_lo = [&](const v4i (&bc)[2], v4i (&bn)[2], const u32x4 (&w)[2][2], const UnitParams<G128> (&p)[2],
-                        int c, int cb, int cc, int ch, int nb, int nc, int nh, auto ex) {
+                        int c, int pc, int cb, int cc, int ch, int nb, int nc, int nh, auto ex) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             mm(i, bc);
@@ -230,15 +259,15 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
             else if (!(i & 1))
                 rd(nb, nc, nh, i / 2 - 1);
             if (i == 0) ex(-1);  // (before the slot's phase: the wait for the registers it expands)
-            build_lo(i, w, p, c, bn);
+            build_lo(i, w, p, c, pc, bn);
             ex(i);
             SB();
         }
     };
-    // builds bf[0] = B(0, 0) of stage set q and reads fragments 0..6 of its first k-step
+    // builds bf[0] = B(first chunk, 0) of stage set q and reads fragments 0..6 of its first k-step
     auto first_operands = [&](int q) {
 #pragma unroll
-        for (int i = 0; i < 14; ++i) build_lo(i, wr[q], pr[q], 0, bf[0]);
+        for (int i = 0; i < 14; ++i) build_lo(i, wr[q], pr[q], 0, grp, bf[0]);
 #pragma unroll
         for (int mf = 0; mf < 7; ++mf) rd(q, 0, 0, mf);
     };
@@ -254,12 +283,33 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
     // while the epilogue runs (after the last tile they are those of a re-read stage, unused).
     auto stage = [&](auto q_tag) {
         constexpr int q = decltype(q_tag)::value, nq = (q + 1) & 3, gq = (q + 2) & 3, fq = (q + 3) & 3;
+        if constexpr (KG == 2) {
+            // two k-steps: the wave's chunk; the ten later loads of the running prefetch in the first
+            kstep_hi(bf[0], bf[1], wr[q], 0, q, 0, 0, q, 0, 1, [&](int i) {
+                if (i == 1) issue_x1(gq, 4);
+                if (i == 4) issue_x1(gq, 5);
+                if (i == 7) issue_x1(gq, 6);
+                if (i == 10) issue_x1(gq, 7);
+                if (i == 12) load_w1(0, wr[gq], pr[gq]);
+                if (i == 14) load_w1(1, wr[gq], pr[gq]);
+            });
+            load_side_advance();
+            SB();
+            kstep_lo(bf[1], bf[0], wr[nq], pr[nq], 0, grp, q, 0, 1, nq, 0, 0, [&](int i) {
+                if (i == -1) arrive_w(std::integral_constant<int, PER_STAGE>{}, wr[nq], pr[nq]);
+                if (i == 1) asm volatile("s_barrier" ::: "memory");
+                if (i == 3) issue_x1(fq, 0);
+                if (i == 6) issue_x1(fq, 1);
+                if (i == 9) issue_x1(fq, 2);
+                if (i == 12) issue_x1(fq, 3);
+            });
+        } else {
         kstep_hi(bf[0], bf[1], wr[q], 0, q, 0, 0, q, 0, 1, [&](int i) {
             if (i == 2) issue_x1(gq, 4);
             if (i == 7) issue_x1(gq, 5);
             if (i == 12) issue_x1(gq, 6);
         });
-        kstep_lo(bf[1], bf[0], wr[q], pr[q], 1, q, 0, 1, q, 1, 0, [&](int i) {
+        kstep_lo(bf[1], bf[0], wr[q], pr[q], 1, 1, q, 0, 1, q, 1, 0, [&](int i) {
             if (i == 2) issue_x1(gq, 7);
             if (i == 8) load_w1(0, wr[gq], pr[gq]);
         });
@@ -268,7 +318,7 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
         });
         load_side_advance();
         SB();
-        kstep_lo(bf[1], bf[0], wr[nq], pr[nq], 0, q, 1, 1, nq, 0, 0, [&](int i) {
+        kstep_lo(bf[1], bf[0], wr[nq], pr[nq], 0, 0, q, 1, 1, nq, 0, 0, [&](int i) {
             if (i == -1) arrive_w(std::integral_constant<int, PER_STAGE>{}, wr[nq], pr[nq]);
             if (i == 1) asm volatile("s_barrier" ::: "memory");
             if (i == 3) issue_x1(fq, 0);
@@ -276,6 +326,7 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
             if (i == 9) issue_x1(fq, 2);
             if (i == 12) issue_x1(fq, 3);
         });
+        }
         // (the next stage's first B operand is complete here, also where the next stage is the
         // next trip of a loop: nothing of it may sink into the loop's latch)
 #pragma unroll
@@ -289,30 +340,120 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
     const std::integral_constant<int, 2> q2{};
     const std::integral_constant<int, 3> q3{};
 
-    // ---- pipeline fill: stages 0 and 1 of the first tile and the first four loads of stage 2 ----
-    load_side_tile(l_lid);
+    // ---- epilogue of one tile (Sec. 4, first-level dequantisation: acc * s_x[row] * s_w[channel]) ----
+    auto store_y = [&](uint32_t byte_off, uint32_t two_halves, const char *row) {
+        asm volatile("global_store_dword %0, %1, %2" : : "v"(byte_off), "v"(two_halves), "s"(row) : "memory");
+    };
+    auto store_acc = [&](uint32_t byte_off, int a, int b, const char *row) {
+        const uint64_t two = (uint32_t)a | ((uint64_t)(uint32_t)b << 32);
+        asm volatile("global_store_dwordx2 %0, %1, %2" : : "v"(byte_off), "v"(two), "s"(row) : "memory");
+    };
+    // KG = 1: all eight fragments.  KG = 2: the four from MF0 on, each element the sum of this
+    // wave's and of the other k group's, which lies in LDS at `other` ([fragment][channel tile]
+    // [4 registers] x 64 lanes x 16 bytes).
+    auto epilogue = [&](auto full_tag, auto mf0_tag, int bm, int ng, const float *sx_tile, const float2 swv,
+                        const int8_t *other) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        constexpr int MF0 = decltype(mf0_tag)::value;
+        const uint32_t lane_off = (uint32_t)(4 * kb) * (uint32_t)N + (uint32_t)(64 * ng + 2 * j);  // in elements
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
+        for (int mf = MF0; mf < MF0 + MF / KG; ++mf) {
+            const int row0 = bm * 256 + 32 * mf;  // wave-uniform
+            v4i add[2][4];
+            if constexpr (KG == 2) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) issue_x1(q, i);
-        load_w1(0, wr[q], pr[q]);
-        load_w1(1, wr[q], pr[q]);
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4)
+                        add[t][q4] = *reinterpret_cast<const v4i *>(other + (((mf - MF0) * 2 + t) * 4 + q4) * 1024 + lane * 16);
+            }
+            auto element = [&](int t, int r) {
+                if constexpr (KG == 2)
+                    return acc_elem(mf, t, r) + add[t][r >> 2][r & 3];
+                else
+                    return acc_elem(mf, t, r);
+            };
+            if (Y) {
+                float sxv[16];
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const float4 v = *reinterpret_cast<const float4 *>(sx_tile + 32 * mf + 8 * q4 + 4 * kb);
+                    sxv[4 * q4 + 0] = v.x;
+                    sxv[4 * q4 + 1] = v.y;
+                    sxv[4 * q4 + 2] = v.z;
+                    sxv[4 * q4 + 3] = v.w;
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int ur = row0 + 8 * (r >> 2) + (r & 3);
+                    union {
+                        __half h[2];
+                        uint32_t u;
+                    } o;
+                    o.h[0] = scale_to_half(element(0, r), sxv[r], swv.x);
+                    o.h[1] = scale_to_half(element(1, r), sxv[r], swv.y);
+                    const char *row = reinterpret_cast<const char *>(Y) + (size_t)ur * (size_t)N * 2;
+                    if (FULL || ur + 4 * kb < M) store_y(lane_off * 2, o.u, row);
+                }
+            }
+            if (ACC) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int ur = row0 + 8 * (r >> 2) + (r & 3);
+                    const char *row = reinterpret_cast<const char *>(ACC) + (size_t)ur * (size_t)N * 4;
+                    if (FULL || ur + 4 * kb < M) store_acc(lane_off * 4, element(0, r), element(1, r), row);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    // KG = 2: the four fragments from MF0 on go to this wave's 32 KiB of the LDS ring
+    auto send_fragments = [&](auto mf0_tag) {
+        constexpr int MF0 = decltype(mf0_tag)::value;
+        int8_t *mine = lds + wave * STAGE + lane * 16;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+                    *reinterpret_cast<v4i *>(mine + ((i * 2 + t) * 4 + q4) * 1024) =
+                        v4i{acc_elem(MF0 + i, t, 4 * q4), acc_elem(MF0 + i, t, 4 * q4 + 1),
+                            acc_elem(MF0 + i, t, 4 * q4 + 2), acc_elem(MF0 + i, t, 4 * q4 + 3)};
+    };
+
+    // ---- pipeline fill: stages 0 and 1 of a tile and the first four loads of stage 2 ----------
+    auto fill = [&] {
+        load_side_tile(l_lid);
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) issue_x1(q, i);
+            load_w1(0, wr[q], pr[q]);
+            load_w1(1, wr[q], pr[q]);
+            __builtin_amdgcn_sched_barrier(0);
+            load_side_advance();
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) issue_x1(2, i);
+        arrive_w(std::integral_constant<int, PER_STAGE + 4>{}, wr[0], pr[0]);  // and X(0) of this wave is in LDS
+        asm volatile("s_barrier" ::: "memory");
+        first_operands(0);
         __builtin_amdgcn_sched_barrier(0);
-        load_side_advance();
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) issue_x1(2, i);
-    arrive_w(std::integral_constant<int, PER_STAGE + 4>{}, wr[0], pr[0]);  // and X(0) of this wave is in LDS
-    asm volatile("s_barrier" ::: "memory");
-    first_operands(0);
-    __builtin_amdgcn_sched_barrier(0);
+    };
+    if (KG == 1) fill();
 
     // ---- the block's tiles ---------------------------------------------------------------------
     uint32_t sx_par = 0;  // which of the two copies of the tile's activation scales is this tile's
     for (int lid = (int)blockIdx.x; lid < tiles; lid += G) {
         int bm, bn;
         coords(lid, bm, bn);
-        const int ng = bn * 4 + wave;
+        const int ng = bn * WPB + colw;
+        if (KG == 2) {
+            l_lid = lid;
+            l_s = 0;
+            fill();
+        }
         // The tile's 256 activation scales go to LDS now (64 per wave, rows past M take the last
         // row's): the epilogue of a single wave per SIMD would otherwise sit through the latency
         // of its scale loads once per fragment.  Complete and visible after the waits and
@@ -345,51 +486,50 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
         // One fragment at a time, fenced: the accumulators sit in the accumulation registers, and
         // an epilogue free to read all 256 of them at once does not fit beside the prefetched W.
         // Element r of a fragment is row 8 (r >> 2) + 4 kb + (r & 3); a row's address is a
-        // wave-uniform base plus one 32-bit lane offset.
+        // wave-uniform base (scalar registers) plus one 32-bit lane offset, which is the form
+        // written out in store_y / store_acc.  A tile with all of its 256 rows inside M stores
+        // without a test per row.
         // (acc_elem reads inside inline assembly, where the compiler does not count the wait
         // states an MFMA result needs before it is read: the last MFMA is further back than that
         // anyway, and this says so)
         asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
-        if (ng < (N >> 6)) {
-            const int n = 64 * ng + 2 * j;
-            const uint32_t lane_off = (uint32_t)(4 * kb) * (uint32_t)N + (uint32_t)n;  // in elements
-#pragma unroll
-            for (int mf = 0; mf < MF; ++mf) {
-                const int row0 = bm * 256 + 32 * mf;  // wave-uniform
-                if (Y) {
-                    float sxv[16];
-#pragma unroll
-                    for (int q4 = 0; q4 < 4; ++q4) {
-                        const float4 v = *reinterpret_cast<const float4 *>(sx_tile + 32 * mf + 8 * q4 + 4 * kb);
-                        sxv[4 * q4 + 0] = v.x;
-                        sxv[4 * q4 + 1] = v.y;
-                        sxv[4 * q4 + 2] = v.z;
-                        sxv[4 * q4 + 3] = v.w;
-                    }
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int ur = row0 + 8 * (r >> 2) + (r & 3);
-                        union {
-                            __half h[2];
-                            uint32_t u;
-                        } o;
-                        o.h[0] = scale_to_half(acc_elem(mf, 0, r), sxv[r], swv.x);
-                        o.h[1] = scale_to_half(acc_elem(mf, 1, r), sxv[r], swv.y);
-                        char *row = reinterpret_cast<char *>(Y) + (size_t)ur * (size_t)N * 2;
-                        if (ur + 4 * kb < M) *reinterpret_cast<uint32_t *>(row + (size_t)lane_off * 2) = o.u;
-                    }
-                }
-                if (ACC) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int ur = row0 + 8 * (r >> 2) + (r & 3);
-                        char *row = reinterpret_cast<char *>(ACC) + (size_t)ur * (size_t)N * 4;
-                        if (ur + 4 * kb < M)
-                            *reinterpret_cast<int2 *>(row + (size_t)lane_off * 4) = int2{acc_elem(mf, 0, r), acc_elem(mf, 1, r)};
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
+        const bool full = bm * 256 + 256 <= M;
+        if constexpr (KG == 1) {
+            const std::integral_constant<int, 0> f0{};
+            if (ng < (N >> 6)) {
+                if (full)
+                    epilogue(std::true_type{}, f0, bm, ng, sx_tile, swv, nullptr);
+                else
+                    epilogue(std::false_type{}, f0, bm, ng, sx_tile, swv, nullptr);
             }
+        } else {
+            // every load of this tile has landed (those past its end too) and every wave is past
+            // its last read of the ring: the ring is free for the exchange.  Group 0 finishes
+            // fragments 0..3 and sends 4..7, group 1 the other way round.
+            const std::integral_constant<int, 0> f0{};
+            const std::integral_constant<int, 4> f4{};
+            wait_vmcnt0();
+            __syncthreads();
+            if (grp == 0)
+                send_fragments(f4);
+            else
+                send_fragments(f0);
+            __syncthreads();
+            const int8_t *other = lds + (wave ^ 2) * STAGE;
+            if (ng < (N >> 6)) {
+                if (grp == 0) {
+                    if (full)
+                        epilogue(std::true_type{}, f0, bm, ng, sx_tile, swv, other);
+                    else
+                        epilogue(std::false_type{}, f0, bm, ng, sx_tile, swv, other);
+                } else {
+                    if (full)
+                        epilogue(std::true_type{}, f4, bm, ng, sx_tile, swv, other);
+                    else
+                        epilogue(std::false_type{}, f4, bm, ng, sx_tile, swv, other);
+                }
+            }
+            __syncthreads();  // the ring is read; the next tile's fill may overwrite it
         }
         clear_acc();
         __builtin_amdgcn_sched_barrier(0);

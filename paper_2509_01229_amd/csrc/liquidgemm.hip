@@ -428,27 +428,32 @@ static int launch_duo_pt(const Args &a)
     return LQ_OK;
 }
 
-// Persistent 256 x 256 tiles, one wave per SIMD (see kernels_tiled_solo.h).  Needs K % 512 == 0.
+// Persistent 256 x 256 tiles, one wave per SIMD (see kernels_tiled_solo.h); KG = 2: 256 x 128
+// tiles with the four waves as two k groups.  Needs K % 512 == 0.
+template <int KG>
 static int launch_solo_pt(const Args &a)
 {
     if (a.query) return LQ_OK;  // no workspace
-    if (a.K % 512 != 0) return fail(LQ_ERR_INVALID, "the 256-row persistent variant needs K %% 512 == 0, got %d", a.K);
-    const int blocks_n = (a.N + 255) / 256, blocks_m = (a.M + 255) / 256;
+    if (a.K % 512 != 0) return fail(LQ_ERR_INVALID, "the 256-row tile variants need K %% 512 == 0, got %d", a.K);
+    constexpr int TN = 256 / KG;
+    const int blocks_n = (a.N + TN - 1) / TN, blocks_m = (a.M + 255) / 256;
     if ((long long)a.M * a.K >= (1ll << 32))
         return fail(LQ_ERR_INVALID, "M * K = %lld is beyond the 2^32 - 1 bytes of X one call addresses; split the batch",
                     (long long)a.M * a.K);
+    if (a.N > (1 << 26))  // (a row's lane offsets are 32-bit byte offsets)
+        return fail(LQ_ERR_INVALID, "the 256-row tile variants take N up to 2^26, got %d", a.N);
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     const int grid = std::min(blocks_m * blocks_n, std::max(cus, 1));
     const size_t lds_bytes = 4 * (size_t)256 * 128 + 4 * 1024;  // X stages; two copies of both scales
     if (a.group == 128) {
-        if (int rc = allow_lds(w4a8_solo_pt_kernel<true>, lds_bytes)) return rc;
-        hipLaunchKernelGGL((w4a8_solo_pt_kernel<true>), dim3((unsigned)grid), dim3(256), lds_bytes, a.stream, a.M, a.N,
-                           a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
+        if (int rc = allow_lds(w4a8_solo_pt_kernel<true, KG>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_solo_pt_kernel<true, KG>), dim3((unsigned)grid), dim3(256), lds_bytes, a.stream, a.M,
+                           a.N, a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
     } else {
-        if (int rc = allow_lds(w4a8_solo_pt_kernel<false>, lds_bytes)) return rc;
-        hipLaunchKernelGGL((w4a8_solo_pt_kernel<false>), dim3((unsigned)grid), dim3(256), lds_bytes, a.stream, a.M, a.N,
-                           a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
+        if (int rc = allow_lds(w4a8_solo_pt_kernel<false, KG>, lds_bytes)) return rc;
+        hipLaunchKernelGGL((w4a8_solo_pt_kernel<false, KG>), dim3((unsigned)grid), dim3(256), lds_bytes, a.stream, a.M,
+                           a.N, a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
     }
     return LQ_OK;
 }
@@ -552,7 +557,8 @@ static const Variant kVariants[] = {
     {"duo_m128", &launch_duo<0, 0>, 0, 1, 1},
     {"duo_dl_m128", &launch_duo_dl<0>, 0, 1, 1},
     {"duo_pt_m128", &launch_duo_pt, 0, 1, 8, 512},
-    {"solo_pt_m256", &launch_solo_pt, 0, 1, 8, 512},
+    {"solo_pt_m256", &launch_solo_pt<1>, 0, 1, 8, 512},
+    {"solo_g2_m256", &launch_solo_pt<2>, 0, 1, 8, 512},
     // --- the same kernels with a named number of K slices: the split paths at sizes where the
     //     dispatcher would not split (parity tests) ---
     {"stream16_f2_w8_s2", &launch_stream16<2, 8, 2>, 16, 2, 1},
@@ -586,22 +592,34 @@ static int find_variant(const char *name)
     return -1;
 }
 
-// 256 x 256 tiles with one wave per SIMD against 128 x 256 tiles with two, both persistent.
-// Half the dequantisation per MFMA makes a round of 256-row tiles about 7 % shorter than the
-// two rounds of 128-row tiles it replaces (2 % with K below 4096, where the tile's epilogue
-// weighs more); but one block per CU runs whole rounds, while two blocks per CU share it, so
-// that a last round of the 128-row tiles that is half empty also takes about half the time
-// (measured: 3.5 rounds on 2048 x 28672 x 8192 take 397 us against 435).
+// The 256-row tiles with one wave per SIMD (solo_pt_m256: 256 x 256; solo_g2_m256: 256 x 128
+// with two k groups per block) against the 128 x 256 tiles with two waves per SIMD.  Half the
+// dequantisation per MFMA makes their stage loop shorter -- per 128 x 256 of output and 1024 k,
+// 6.0 us (256 x 256) and 7.0 us (256 x 128) against 7.1 to 7.4 us measured on N = K = 8192 --
+// but they run one block per CU, in whole rounds, and rows past M in a 256-row tile are lost.
+// Costs in units of one 128 x 256 tile's time on a CU; returns 1 for 256 x 256, 2 for 256 x 128,
+// 0 for neither.
 constexpr long long kAssumedCUs = 256;  // the shape rules of the dispatcher are written for the MI355X
-static bool solo_pt_pays(int M, int N, int K)
+static int solo_form_that_pays(int M, int N, int K)
 {
-    if (K % 512 != 0) return false;
-    const long long t256 = (long long)((M + 255) / 256) * ((N + 255) / 256);
+    if (K % 512 != 0) return 0;
+    const long long bm256 = (M + 255) / 256;
+    const long long t256 = bm256 * ((N + 255) / 256), t2 = bm256 * ((N + 127) / 128);
     const long long t128 = (long long)((M + 127) / 128) * ((N + 255) / 256);
-    if (t256 < kAssumedCUs) return false;
-    const double rounds_solo = (double)((t256 + kAssumedCUs - 1) / kAssumedCUs) * (K >= 4096 ? 0.93 : 0.98);
-    const double rounds_duo = (double)t128 / (2.0 * kAssumedCUs);
-    return rounds_solo < rounds_duo;
+    // two resident blocks per CU (block b and b + 256 land on one CU) walk tiles b, b + 512, ...
+    const long long rem = t128 % (2 * kAssumedCUs);
+    // (up to one tile per CU they split K across blocks to fill the chip, at about a tenth more)
+    const double duo = t128 <= kAssumedCUs ? std::max(0.25, (double)t128 / kAssumedCUs * (8 * t128 > 7 * kAssumedCUs ? 1.0 : 1.1))
+                                           : 2.0 * (t128 / (2 * kAssumedCUs)) + (rem > 0) + (rem > kAssumedCUs);
+    const double short_k = K >= 4096 ? 1.0 : 1.06;  // (their longer epilogue weighs more)
+    // (a round of 256 x 256 tiles that leaves CUs idle still runs at this cost: 160 tiles took 82.6 us
+    // against 97 to 101 us of the 128-row forms on 1024 x 10240 x 8192; the 256 x 128 form pays only
+    // as one round that nearly fills the chip -- its tiles are separate, a second round costs a tenth more)
+    const double solo = 2.0 * ((t256 + kAssumedCUs - 1) / kAssumedCUs) * 0.86 * short_k;
+    const double g2 = 4 * t2 >= 3 * kAssumedCUs && t2 <= kAssumedCUs ? 0.96 * short_k : 1e30;
+    if (solo < duo && solo <= g2) return 1;
+    if (g2 < duo) return 2;
+    return 0;
 }
 
 // Shape -> kernel.  Up to 32 rows the weights are streamed once with X fragments in
@@ -643,16 +661,15 @@ static int select_variant(int M, int N, int K)
     // and the tiles' split-K grid is 8-16 % ahead, 32.8 against 38.1 us at 64 rows on 6144 x 28672)
     if (M <= 64 && N / 32 <= 512 && !(M >= 48 && N / 32 > 128 && N / 32 <= 256 && K >= 24576))
         return find_variant("stream_m64");
+    // 256-row tiles with one wave per SIMD where their whole rounds come out ahead
+    if (const int form = solo_form_that_pays(M, N, K)) return find_variant(form == 1 ? "solo_pt_m256" : "solo_g2_m256");
     // more 128 x 256 tiles than CUs (blocks of one k group): the deeper memory pipeline of the
     // direct-to-LDS form pays (3 to 6 % measured from 320 tiles up, 1 to 5 % at 264..288); with
     // one tile per CU or fewer, the two k groups per block of the other form do
     // (from two tiles per resident slot on and with whole 512-k units, its persistent form:
     // one pipeline fill per block instead of per tile, 1 to 2 % measured)
-    // (and with enough whole rounds of them, 256-row tiles)
-    if (((M + 127) / 128) * ((N + 255) / 256) > 256) {
-        if (solo_pt_pays(M, N, K)) return find_variant("solo_pt_m256");
+    if (((M + 127) / 128) * ((N + 255) / 256) > 256)
         return find_variant(duo_pt_fits(M, N, K) ? "duo_pt_m128" : "duo_dl_m128");
-    }
     // few tiles: a grid of 64-row tiles can fill the chip with half the split-K exchange
     return find_variant(prefer_64_row_tiles(M, N, K) ? "duo_m64" : "duo_m128");
 }

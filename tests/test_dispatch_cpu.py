@@ -10,6 +10,26 @@ def _pick(M, N, K, g=64):
     return api.w4a8_variant_name(api.w4a8_select_variant(M, N, K, g))
 
 
+def _solo_form(M, N, K):
+    """The dispatcher's cost rule for the 256-row tiles, restated: costs in 128 x 256 tile times per
+    CU; 1 = 256 x 256 tiles, 2 = 256 x 128 tiles with two k groups, 0 = neither."""
+    if K % 512:
+        return 0
+    bm = -(-M // 256)
+    t256, t2, t128 = bm * -(-N // 256), bm * -(-N // 128), -(-M // 128) * -(-N // 256)
+    rem = t128 % 512
+    if t128 <= 256:
+        duo = max(0.25, t128 / 256 * (1.0 if 8 * t128 > 7 * 256 else 1.1))
+    else:
+        duo = 2.0 * (t128 // 512) + (rem > 0) + (rem > 256)
+    short_k = 1.0 if K >= 4096 else 1.06
+    solo = 2.0 * -(-t256 // 256) * 0.86 * short_k
+    g2 = 0.96 * short_k if 192 <= t2 <= 256 else 1e30
+    if solo < duo and solo <= g2:
+        return 1
+    return 2 if g2 < duo else 0
+
+
 def test_dispatcher_families_on_the_workloads():
     for s in WL.ALL_SHAPES:
         name = _pick(s.M, s.N, s.K, s.group)
@@ -20,17 +40,14 @@ def test_dispatcher_families_on_the_workloads():
         elif s.M <= 64 and s.N <= 16384:
             assert name == "stream_m64", (s.name, name)
         else:
-            assert name in ("duo_m64", "duo_m128", "duo_dl_m128", "duo_pt_m128", "solo_pt_m256"), (s.name, name)
+            assert name in ("duo_m64", "duo_m128", "duo_dl_m128", "duo_pt_m128", "solo_pt_m256", "solo_g2_m256"), (s.name, name)
             tiles128 = -(-s.M // 128) * -(-s.N // 256)
-            tiles256 = -(-s.M // 256) * -(-s.N // 256)
-            if tiles128 > 256:        # more tiles than CUs: the direct-to-LDS pipeline, persistent where it fits
+            form = _solo_form(s.M, s.N, s.K)
+            if form:                  # 256-row tiles, one wave per SIMD, where their whole rounds come out ahead
+                assert name == ("solo_pt_m256" if form == 1 else "solo_g2_m256"), (s.name, name)
+            elif tiles128 > 256:      # more tiles than CUs: the direct-to-LDS pipeline, persistent where it fits
                 fits = s.K % 512 == 0 and (s.M % 128 == 0 or s.M % 128 > 64)
-                # 256-row tiles (one block per CU) when their whole rounds are fewer, 7 % apiece
-                # taken off, than the rounds of 128-row tiles shared two blocks to a CU
-                solo = (s.K % 512 == 0 and tiles256 >= 256
-                        and -(-tiles256 // 256) * (0.93 if s.K >= 4096 else 0.98) < tiles128 / 512)
-                want = "solo_pt_m256" if solo else "duo_pt_m128" if fits else "duo_dl_m128"
-                assert name == want, (s.name, name)
+                assert name == ("duo_pt_m128" if fits else "duo_dl_m128"), (s.name, name)
             elif -(-s.M // 64) * -(-s.N // 256) > 256:
                 assert name == "duo_m128", (s.name, name)
         v = api.w4a8_select_variant(s.M, s.N, s.K, s.group)
@@ -59,18 +76,25 @@ def test_dispatcher_boundaries():
     assert _pick(64, 8192, 28672, 128) in ("duo_m64", "duo_m128") and _pick(48, 6144, 28672, 128) in ("duo_m64", "duo_m128")
     assert _pick(64, 4096, 28672, 128) == "stream_m64" and _pick(64, 8192, 16384, 128) == "stream_m64"
     assert _pick(64, 28672, 8192) == "duo_m64" and _pick(65, 4096, 4096) == "duo_m64"
-    assert _pick(256, 28672, 8192) == "duo_m128"
+    assert _pick(256, 28672, 8192) == "solo_g2_m256"           # 224 tiles of 256 x 128: one round, 62 against 66 us
+    assert _pick(192, 28672, 8192) == "solo_g2_m256" and _pick(128, 28672, 8192) == "duo_m128"
     assert _pick(512, 4096, 4096) == "duo_m64" and _pick(1025, 4096, 4096) == "duo_m128"
     assert _pick(256, 8192, 28672, 128) == "duo_m128"          # long K: more slices of 128-row tiles win
     assert _pick(256, 8192, 8192) == "duo_m64" and _pick(256, 10240, 8192, 128) == "duo_m128"
     assert _pick(128, 4096, 256) == "duo_m128"                 # one k unit: no room for two k groups
-    assert _pick(1152, 8192, 8192) == "duo_pt_m128" and _pick(1024, 8192, 8192) == "duo_m128"   # 288 / 256 tiles
-    assert _pick(2560, 8192, 8192) == "duo_pt_m128" and _pick(1024, 28672, 8192, 128) == "duo_pt_m128"
-    # whole rounds of 256 x 256 tiles: one wave per SIMD
+    assert _pick(768, 8192, 8192) == "duo_m128"                # 192 tiles: K slices across blocks fill the chip
+    # 256-row tiles, one wave per SIMD: 256 x 128 as one round that nearly fills the chip ...
+    assert _pick(1024, 8192, 8192) == "solo_g2_m256" and _pick(960, 8192, 8192) == "solo_g2_m256"
+    assert _pick(2048, 4096, 11264) == "solo_g2_m256"
+    # ... 256 x 256 where their whole rounds cost less than the rounds of 128-row tiles, two blocks to a CU
+    assert _pick(1152, 8192, 8192) == "solo_pt_m256" and _pick(1280, 8192, 8192) == "solo_pt_m256"   # 160 tiles, one round
     assert _pick(4096, 8192, 8192) == "solo_pt_m256" and _pick(2048, 8192, 28672, 128) == "solo_pt_m256"
     assert _pick(8192, 8192, 8192) == "solo_pt_m256" and _pick(4096, 8192, 2048) == "solo_pt_m256"
-    assert _pick(2048, 28672, 8192, 128) == "duo_pt_m128"      # 3.5 rounds: two blocks per CU share the last one
-    assert _pick(1792, 8192, 8192) == "duo_pt_m128"            # fewer 256-row tiles than CUs
+    assert _pick(1024, 28672, 8192, 128) == "solo_pt_m256" and _pick(2048, 28672, 8192, 128) == "solo_pt_m256"
+    assert _pick(1024, 10240, 8192, 128) == "solo_pt_m256" and _pick(1024, 11008, 4096) == "solo_pt_m256"
+    # ... and the 128-row tiles where a last round of 256-row tiles would be mostly empty
+    assert _pick(2560, 8192, 8192) == "duo_pt_m128" and _pick(3072, 8192, 8192) == "duo_pt_m128"
+    assert _pick(2048, 10240, 8192, 128) == "duo_pt_m128" and _pick(2048, 11008, 4096) == "duo_pt_m128"
     assert _pick(4096, 8192, 11008) == "duo_dl_m128"           # K not a multiple of 512: one tile per block
     assert _pick(4096 + 40, 8192, 8192) == "duo_dl_m128"       # (rounds of 256-row tiles: 3 against 2.06) ragged last row tile of at most 64 rows: its two-fragment path
     assert _pick(4096 + 100, 8192, 8192) == "duo_pt_m128"
