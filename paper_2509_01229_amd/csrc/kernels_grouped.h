@@ -106,3 +106,38 @@ __global__ __launch_bounds__(256, 2) void w4a8_duo_dl_grouped_kernel(const Group
     else
         duo_dl_tile<G128, 4>(pl, bm, bn, M, N, K, X, sx, Wp, gp, sw, Y, ACC, nullptr);
 }
+
+// The 256 x 256 tiles (one wave per SIMD, see kernels_tiled_solo.h) of all experts of a launch as
+// one persistent stream: resident blocks walk the tiles of every expert, prefetching across the
+// boundaries between them.  block_end counts 256 x 256 tiles here.
+struct SoloGrouped {
+    const GroupTable &g;
+    const GroupedPtrs &p;
+    int N, K, blocks_n;
+    __device__ __forceinline__ int tiles() const { return g.block_end[g.count - 1]; }
+    __device__ __forceinline__ SoloTile tile(int lid, int G) const
+    {
+        lid = solo_xcd_order(lid, tiles(), G);
+        int i = 0;
+        while (i < g.count - 1 && lid >= g.block_end[i]) ++i;
+        const int local = lid - (i ? g.block_end[i - 1] : 0);
+        const int M = g.rows[i], e = g.expert[i], r0 = g.row_off[i];
+        int bm, bn;
+        solo_coords(local, (M + 255) / 256, blocks_n, bm, bn);
+        return SoloTile{M,
+                        bm,
+                        bn,
+                        p.X + (size_t)r0 * K,
+                        p.sx + r0,
+                        p.Wp + e * p.w_stride,
+                        p.gp + e * p.gp_stride,
+                        p.sw + (size_t)e * N,
+                        p.Y ? p.Y + (size_t)r0 * N : nullptr,
+                        p.ACC ? p.ACC + (size_t)r0 * N : nullptr};
+    }
+};
+template <bool G128>
+__global__ __launch_bounds__(256, 1) void w4a8_solo_grouped_kernel(const GroupTable g, const GroupedPtrs p, int N, int K)
+{
+    solo_body<G128, 1>(SoloGrouped{g, p, N, K, (N + 255) / 256}, N, K);
+}

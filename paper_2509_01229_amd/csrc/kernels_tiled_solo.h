@@ -29,11 +29,56 @@
 // (drained) LDS ring and each finishes four of the eight row fragments.  Tiles are separate
 // there: the pipeline drains and refills between them.
 // ------------------------------------------------------------------------------------
-template <bool G128, int KG = 1>
-__global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
-    int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
-    const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
-    __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n)
+// One tile of a launch: rows bm * 256 .. of a matrix of M rows, channels bn * (256 / KG) ..
+struct SoloTile {
+    int M, bm, bn;
+    const int8_t *X;
+    const float *sx;
+    const u32x4 *Wp;
+    const uint8_t *gp;
+    const float *sw;
+    __half *Y;
+    int32_t *ACC;
+};
+// Logical tile id of a persistent launch of G blocks -> position in a grid of blocks_m x blocks_n:
+// the ids of one XCD (hardware block id mod 8; b + i G keeps it) form a contiguous range,
+// walked four row blocks at a time (see block_coords).
+__device__ __forceinline__ int solo_xcd_order(int lid, int tiles, int G)
+{
+    return (tiles & 7) == 0 && (G & 7) == 0 ? (lid & 7) * (tiles >> 3) + (lid >> 3) : lid;
+}
+__device__ __forceinline__ void solo_coords(int lid, int blocks_m, int blocks_n, int &bm, int &bn)
+{
+    constexpr int GM = 4;
+    const int per_group = GM * blocks_n;
+    const int first = (lid / per_group) * GM;
+    const int gsz = min(blocks_m - first, GM);
+    const int in_group = lid % per_group;
+    bm = first + in_group % gsz;
+    bn = in_group / gsz;
+}
+// The tiles of one GEMM.
+struct SoloDense {
+    int M;
+    const int8_t *X;
+    const float *sx;
+    const u32x4 *Wp;
+    const uint8_t *gp;
+    const float *sw;
+    __half *Y;
+    int32_t *ACC;
+    int blocks_m, blocks_n;
+    __device__ __forceinline__ int tiles() const { return blocks_m * blocks_n; }
+    __device__ __forceinline__ SoloTile tile(int lid, int G) const
+    {
+        int bm, bn;
+        solo_coords(solo_xcd_order(lid, tiles(), G), blocks_m, blocks_n, bm, bn);
+        return SoloTile{M, bm, bn, X, sx, Wp, gp, sw, Y, ACC};
+    }
+};
+
+template <bool G128, int KG, class Src>
+__device__ __forceinline__ void solo_body(const Src &src, const int N, const int K)
 {
     constexpr int MF = 8;
     constexpr int STAGE = 256 * 128;
@@ -48,20 +93,7 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
     constexpr int WPB = 4 / KG;                       // 64-channel groups per block
     const int stages = K >> 7;  // per tile, a multiple of four
     const int chunks_per_tile = K >> 6;
-    const int tiles = blocks_m * blocks_n, G = (int)gridDim.x;
-
-    // logical tile id -> (bm, bn): the ids of one XCD (hardware block id mod 8; b + i G keeps
-    // it) form a contiguous range, walked four row blocks at a time (see block_coords)
-    auto coords = [&](int lid, int &bm, int &bn) {
-        if ((tiles & 7) == 0 && (G & 7) == 0) lid = (lid & 7) * (tiles >> 3) + (lid >> 3);
-        constexpr int GM = 4;
-        const int per_group = GM * blocks_n;
-        const int first = (lid / per_group) * GM;
-        const int gsz = min(blocks_m - first, GM);
-        const int in_group = lid % per_group;
-        bm = first + in_group % gsz;
-        bn = in_group / gsz;
-    };
+    const int tiles = src.tiles(), G = (int)gridDim.x;
 
     // ---- load side: the tile whose stages are being prefetched ------------------------------
     const int ld_r = (lane >> 3) ^ (wave & 1), ld_c = (lane & 7) ^ ld_r;
@@ -74,10 +106,11 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
     int l_lid = (int)blockIdx.x, l_s = 0;  // tile and stage the next prefetch takes
     uint32_t xg[8];
     const char *wbase, *pbase;
+    const int8_t *ld_X;
     auto load_side_tile = [&](int lid) {
-        int bm, bn;
-        coords(lid, bm, bn);
-        const int ng = bn * WPB + colw;
+        const SoloTile t = src.tile(lid, G);
+        const int bm = t.bm, M = t.M;
+        const int ng = t.bn * WPB + colw;
         const int t0 = 2 * min(ng, (N >> 6) - 1);
         // (recomputed from one register per tile: eight row numbers kept across the tile loop
         // would not fit beside the epilogue)
@@ -85,8 +118,9 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
 #pragma unroll
         for (int i = 0; i < 8; ++i)
             xg[i] = (uint32_t)min(bm * 256 + 32 * i + ld_row, M - 1) * (uint32_t)K + 16 * ld_c;
-        wbase = reinterpret_cast<const char *>(Wp + (size_t)t0 * chunks_per_tile * 64);
-        pbase = reinterpret_cast<const char *>(gp) + (size_t)t0 * stages * 32 * (G128 ? 2 : 4);
+        ld_X = t.X;
+        wbase = reinterpret_cast<const char *>(t.Wp + (size_t)t0 * chunks_per_tile * 64);
+        pbase = reinterpret_cast<const char *>(t.gp) + (size_t)t0 * stages * 32 * (G128 ? 2 : 4);
     };
     // after the last stage of the block's last tile (KG = 2: of every tile) the load side stays
     // on that stage (the prefetches past the end re-read it; nothing consumes them)
@@ -106,7 +140,7 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
     auto issue_x1 = [&](int buf, int i) {
         asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                      : "+v"(wl)  // untouched; makes the W loads that follow depend on this statement
-                     : "v"(xg[i] + (uint32_t)l_s * 128), "s"(X), "s"(lds0 + buf * STAGE + (4 * i + wave) * 1024)
+                     : "v"(xg[i] + (uint32_t)l_s * 128), "s"(ld_X), "s"(lds0 + buf * STAGE + (4 * i + wave) * 1024)
                      : "memory", "m0");
     };
     // The W loads are written out as well, so that every wait of the stage loop is one that is
@@ -351,6 +385,9 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
     // KG = 1: all eight fragments.  KG = 2: the four from MF0 on, each element the sum of this
     // wave's and of the other k group's, which lies in LDS at `other` ([fragment][channel tile]
     // [4 registers] x 64 lanes x 16 bytes).
+    int M = 0;  // of the tile in its epilogue
+    __half *Y = nullptr;
+    int32_t *ACC = nullptr;
     auto epilogue = [&](auto full_tag, auto mf0_tag, int bm, int ng, const float *sx_tile, const float2 swv,
                         const int8_t *other) {
         constexpr bool FULL = decltype(full_tag)::value;
@@ -446,9 +483,9 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
     // ---- the block's tiles ---------------------------------------------------------------------
     uint32_t sx_par = 0;  // which of the two copies of the tile's activation scales is this tile's
     for (int lid = (int)blockIdx.x; lid < tiles; lid += G) {
-        int bm, bn;
-        coords(lid, bm, bn);
-        const int ng = bn * WPB + colw;
+        const SoloTile cur = src.tile(lid, G);
+        const int bm = cur.bm, ng = cur.bn * WPB + colw;
+        M = cur.M, Y = cur.Y, ACC = cur.ACC;
         if (KG == 2) {
             l_lid = lid;
             l_s = 0;
@@ -463,13 +500,13 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
         if (Y) {
             asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
                          :
-                         : "v"((uint32_t)min(bm * 256 + 64 * wave + lane, M - 1) * 4u), "s"(sx),
+                         : "v"((uint32_t)min(bm * 256 + 64 * wave + lane, M - 1) * 4u), "s"(cur.sx),
                            "s"(lds0 + 4 * STAGE + sx_par * 1024 + wave * 256)
                          : "memory", "m0");
             // (and the wave's 64 channel scales, for the same reason)
             asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
                          :
-                         : "v"((uint32_t)(64 * min(ng, (N >> 6) - 1) + lane) * 4u), "s"(sw),
+                         : "v"((uint32_t)(64 * min(ng, (N >> 6) - 1) + lane) * 4u), "s"(cur.sw),
                            "s"(lds0 + 4 * STAGE + 2048 + sx_par * 1024 + wave * 256)
                          : "memory", "m0");
         }
@@ -537,4 +574,13 @@ __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
     // the prefetches past the last stage write LDS too: they must have landed before the block
     // ends and its LDS goes to another block
     wait_vmcnt0();
+}
+
+template <bool G128, int KG = 1>
+__global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
+    int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
+    const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
+    __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n)
+{
+    solo_body<G128, KG>(SoloDense{M, X, sx, Wp, gp, sw, Y, ACC, blocks_m, blocks_n}, N, K);
 }

@@ -597,18 +597,15 @@ static int find_variant(const char *name)
 // dequantisation per MFMA makes their stage loop shorter -- per 128 x 256 of output and 1024 k,
 // 6.0 us (256 x 256) and 7.0 us (256 x 128) against 7.1 to 7.4 us measured on N = K = 8192 --
 // but they run one block per CU, in whole rounds, and rows past M in a 256-row tile are lost.
-// Costs in units of one 128 x 256 tile's time on a CU; returns 1 for 256 x 256, 2 for 256 x 128,
-// 0 for neither.
+// Costs in units of one 128 x 256 tile's time on a CU, from the numbers of tiles of each form;
+// returns 1 for 256 x 256, 2 for 256 x 128, 0 for neither.
 constexpr long long kAssumedCUs = 256;  // the shape rules of the dispatcher are written for the MI355X
-static int solo_form_that_pays(int M, int N, int K)
+static int solo_form_for(long long t128, long long t256, long long t2, int K)
 {
     if (K % 512 != 0) return 0;
-    const long long bm256 = (M + 255) / 256;
-    const long long t256 = bm256 * ((N + 255) / 256), t2 = bm256 * ((N + 127) / 128);
-    const long long t128 = (long long)((M + 127) / 128) * ((N + 255) / 256);
     // two resident blocks per CU (block b and b + 256 land on one CU) walk tiles b, b + 512, ...
-    const long long rem = t128 % (2 * kAssumedCUs);
     // (up to one tile per CU they split K across blocks to fill the chip, at about a tenth more)
+    const long long rem = t128 % (2 * kAssumedCUs);
     const double duo = t128 <= kAssumedCUs ? std::max(0.25, (double)t128 / kAssumedCUs * (8 * t128 > 7 * kAssumedCUs ? 1.0 : 1.1))
                                            : 2.0 * (t128 / (2 * kAssumedCUs)) + (rem > 0) + (rem > kAssumedCUs);
     const double short_k = K >= 4096 ? 1.0 : 1.06;  // (their longer epilogue weighs more)
@@ -620,6 +617,12 @@ static int solo_form_that_pays(int M, int N, int K)
     if (solo < duo && solo <= g2) return 1;
     if (g2 < duo) return 2;
     return 0;
+}
+static int solo_form_that_pays(int M, int N, int K)
+{
+    const long long bm256 = (M + 255) / 256;
+    return solo_form_for((long long)((M + 127) / 128) * ((N + 255) / 256), bm256 * ((N + 255) / 256),
+                         bm256 * ((N + 127) / 128), K);
 }
 
 // Shape -> kernel.  Up to 32 rows the weights are streamed once with X fragments in
@@ -749,23 +752,74 @@ static int launch_checked(const char *what, Kernel kernel, dim3 grid, dim3 block
     return LQ_OK;
 }
 
+// The experts of more than 32 rows (or row ranges of them) as 128- or 64-row tiles: one launch.
+static int grouped_tiles_run(const GroupedArgs &a, GroupTable &big)
+{
+    const bool g128 = a.group == 128;
+    const int blocks_n = (a.N + 255) / 256;
+    long long big_blocks = 0, big_blocks64 = 0;
+    for (int i = 0; i < big.count; ++i) {
+        big_blocks += (long long)((big.rows[i] + 127) / 128) * blocks_n;
+        big_blocks64 += (long long)((big.rows[i] + 63) / 64) * blocks_n;
+        if (big_blocks > 0x7fffffff) return fail(LQ_ERR_INVALID, "grouped GEMM too large for one launch");
+        big.block_end[i] = (int)big_blocks;
+    }
+    if (big_blocks64 <= 256 && big_blocks64 > big_blocks && a.K >= 512) {
+        // few blocks and experts of more than 64 rows: a grid of 64-row tiles has up to twice the
+        // blocks, still at most one per CU (8 experts of 72 rows on 4096 x 14336: 128 -> 256 blocks)
+        long long end = 0;
+        for (int i = 0; i < big.count; ++i) {
+            end += (long long)((big.rows[i] + 63) / 64) * blocks_n;
+            big.block_end[i] = (int)end;
+        }
+        const dim3 grid((unsigned)big_blocks64);
+        const size_t lds2 = std::max<size_t>(4 * (size_t)128 * kTilePitch, 64 * 1024);
+        return g128 ? launch_checked("grouped duo", w4a8_duo_grouped_kernel<true, 2, 64>, grid, dim3(512), lds2, a.stream,
+                                     big, a.p, a.N, a.K)
+                    : launch_checked("grouped duo", w4a8_duo_grouped_kernel<false, 2, 64>, grid, dim3(512), lds2, a.stream,
+                                     big, a.p, a.N, a.K);
+    }
+    const dim3 grid((unsigned)big_blocks);
+    // as for single GEMMs: two k groups per block while the grid gives at most one block per CU
+    const bool kg2 = big_blocks <= 256 && a.K >= 512;
+    const size_t lds1 = 2 * (size_t)128 * kTilePitch;
+    const size_t lds2 = std::max<size_t>(2 * lds1, 64 * 1024);
+    // more blocks than CUs: the direct-to-LDS form, as for single GEMMs (its X offsets have 32
+    // bits) -- unless the experts are so small that most tiles have two row fragments, which
+    // the other form runs with a deeper W pipeline (8 experts of 58..71 rows: 63 against 67 us;
+    // of 128 rows: 91 against 79; of about 1000: 531 against 513)
+    bool dl = !kg2 && a.K >= 512;
+    long long big_rows = 0;
+    for (int i = 0; i < big.count; ++i) {
+        dl = dl && (long long)big.rows[i] * a.K < (1ll << 32);
+        big_rows += big.rows[i];
+    }
+    dl = dl && big_rows > 96ll * big.count;
+    if (dl)
+        return g128 ? launch_checked("grouped duo", w4a8_duo_dl_grouped_kernel<true>, grid, dim3(256),
+                                     4 * (size_t)128 * 128, a.stream, big, a.p, a.N, a.K)
+                    : launch_checked("grouped duo", w4a8_duo_dl_grouped_kernel<false>, grid, dim3(256),
+                                     4 * (size_t)128 * 128, a.stream, big, a.p, a.N, a.K);
+    if (kg2)
+        return g128 ? launch_checked("grouped duo", w4a8_duo_grouped_kernel<true, 2>, grid, dim3(512), lds2, a.stream, big,
+                                     a.p, a.N, a.K)
+                    : launch_checked("grouped duo", w4a8_duo_grouped_kernel<false, 2>, grid, dim3(512), lds2, a.stream, big,
+                                     a.p, a.N, a.K);
+    return g128 ? launch_checked("grouped duo", w4a8_duo_grouped_kernel<true, 1>, grid, dim3(256), lds1, a.stream, big,
+                                 a.p, a.N, a.K)
+                : launch_checked("grouped duo", w4a8_duo_grouped_kernel<false, 1>, grid, dim3(256), lds1, a.stream, big,
+                                 a.p, a.N, a.K);
+}
+
 static int grouped_run(const GroupedArgs &a)
 {
     GroupTable small{}, mid{}, big{};
-    long long big_blocks = 0, big_blocks64 = 0;
-    const int blocks_n = (a.N + 255) / 256;
     for (int e = 0; e < a.E; ++e) {
         const int r0 = a.row_offsets[e], rows = a.row_offsets[e + 1] - r0;
         if (rows == 0) continue;
         GroupTable &t = rows <= 16 ? small : (rows <= 32 ? mid : big);
         const int i = t.count++;
         t.expert[i] = e, t.row_off[i] = r0, t.rows[i] = rows;
-        if (&t == &big) {
-            big_blocks += (long long)((rows + 127) / 128) * blocks_n;
-            big_blocks64 += (long long)((rows + 63) / 64) * blocks_n;
-            if (big_blocks > 0x7fffffff) return fail(LQ_ERR_INVALID, "grouped GEMM too large for one launch");
-            t.block_end[i] = (int)big_blocks;
-        }
     }
     const bool g128 = a.group == 128;
     const int groups = a.N / 64;  // stream kernels: two tiles of 32 channels per block
@@ -796,57 +850,45 @@ static int grouped_run(const GroupedArgs &a)
                                              lds, a.stream, mid, a.p, a.N, a.K, groups);
         if (rc) return rc;
     }
-    if (big.count && big_blocks64 <= 256 && big_blocks64 > big_blocks && a.K >= 512) {
-        // few blocks and experts of more than 64 rows: a grid of 64-row tiles has up to twice the
-        // blocks, still at most one per CU (8 experts of 72 rows on 4096 x 14336: 128 -> 256 blocks)
-        long long end = 0;
-        for (int i = 0; i < big.count; ++i) {
-            end += (long long)((big.rows[i] + 63) / 64) * blocks_n;
-            big.block_end[i] = (int)end;
+    if (!big.count) return LQ_OK;
+    // The larger experts: whole 256-row blocks of them (and a last block of more than 128 rows) as
+    // 256 x 256 tiles of the one-wave-per-SIMD kernel, one persistent launch over all experts, where
+    // those tiles pay; what is left of each expert (at most 128 rows) and everything else as 128- or
+    // 64-row tiles in a launch of their own.
+    const int blocks_n = (a.N + 255) / 256;
+    GroupTable main{}, rest{};
+    long long main_t128 = 0, main_t256 = 0;
+    bool fits = a.N <= (1 << 26);
+    for (int i = 0; i < big.count; ++i) {
+        const int rows = big.rows[i], tail = rows % 256;
+        const int rows_rest = tail > 0 && tail <= 128 ? tail : 0, rows_main = rows - rows_rest;
+        fits = fits && (long long)rows * a.K < (1ll << 32);
+        if (rows_main) {
+            const int k = main.count++;
+            main.expert[k] = big.expert[i], main.row_off[k] = big.row_off[i], main.rows[k] = rows_main;
+            main_t128 += (long long)((rows_main + 127) / 128) * blocks_n;
+            main_t256 += (long long)((rows_main + 255) / 256) * blocks_n;
+            if (main_t256 > 0x7fffffff) return fail(LQ_ERR_INVALID, "grouped GEMM too large for one launch");
+            main.block_end[k] = (int)main_t256;
         }
-        const dim3 grid((unsigned)big_blocks64);
-        const size_t lds2 = std::max<size_t>(4 * (size_t)128 * kTilePitch, 64 * 1024);
-        const int rc = g128 ? launch_checked("grouped duo", w4a8_duo_grouped_kernel<true, 2, 64>, grid, dim3(512), lds2,
-                                             a.stream, big, a.p, a.N, a.K)
-                            : launch_checked("grouped duo", w4a8_duo_grouped_kernel<false, 2, 64>, grid, dim3(512), lds2,
-                                             a.stream, big, a.p, a.N, a.K);
-        if (rc) return rc;
-    } else if (big.count) {
-        const dim3 grid((unsigned)big_blocks);
-        // as for single GEMMs: two k groups per block while the grid gives at most one block per CU
-        const bool kg2 = big_blocks <= 256 && a.K >= 512;
-        const size_t lds1 = 2 * (size_t)128 * kTilePitch;
-        const size_t lds2 = std::max<size_t>(2 * lds1, 64 * 1024);
-        int rc;
-        // more blocks than CUs: the direct-to-LDS form, as for single GEMMs (its X offsets have 32
-        // bits) -- unless the experts are so small that most tiles have two row fragments, which
-        // the other form runs with a deeper W pipeline (8 experts of 58..71 rows: 63 against 67 us;
-        // of 128 rows: 91 against 79; of about 1000: 531 against 513)
-        bool dl = !kg2 && a.K >= 512;
-        long long big_rows = 0;
-        for (int i = 0; i < big.count; ++i) {
-            dl = dl && (long long)big.rows[i] * a.K < (1ll << 32);
-            big_rows += big.rows[i];
+        if (rows_rest) {
+            const int k = rest.count++;
+            rest.expert[k] = big.expert[i], rest.row_off[k] = big.row_off[i] + rows_main, rest.rows[k] = rows_rest;
         }
-        dl = dl && big_rows > 96ll * big.count;
-        if (dl)
-            rc = g128 ? launch_checked("grouped duo", w4a8_duo_dl_grouped_kernel<true>, grid, dim3(256),
-                                       4 * (size_t)128 * 128, a.stream, big, a.p, a.N, a.K)
-                      : launch_checked("grouped duo", w4a8_duo_dl_grouped_kernel<false>, grid, dim3(256),
-                                       4 * (size_t)128 * 128, a.stream, big, a.p, a.N, a.K);
-        else if (kg2)
-            rc = g128 ? launch_checked("grouped duo", w4a8_duo_grouped_kernel<true, 2>, grid, dim3(512), lds2, a.stream,
-                                       big, a.p, a.N, a.K)
-                      : launch_checked("grouped duo", w4a8_duo_grouped_kernel<false, 2>, grid, dim3(512), lds2, a.stream,
-                                       big, a.p, a.N, a.K);
-        else
-            rc = g128 ? launch_checked("grouped duo", w4a8_duo_grouped_kernel<true, 1>, grid, dim3(256), lds1, a.stream,
-                                       big, a.p, a.N, a.K)
-                      : launch_checked("grouped duo", w4a8_duo_grouped_kernel<false, 1>, grid, dim3(256), lds1, a.stream,
-                                       big, a.p, a.N, a.K);
-        if (rc) return rc;
     }
-    return LQ_OK;
+    if (main.count && fits && solo_form_for(main_t128, main_t256, 0, a.K) == 1) {
+        int dev = 0, cus = 256;
+        if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        const dim3 grid((unsigned)std::min<long long>(main_t256, std::max(cus, 1)));
+        const size_t lds = 4 * (size_t)256 * 128 + 4 * 1024;
+        const int rc = g128 ? launch_checked("grouped solo", w4a8_solo_grouped_kernel<true>, grid, dim3(256), lds,
+                                             a.stream, main, a.p, a.N, a.K)
+                            : launch_checked("grouped solo", w4a8_solo_grouped_kernel<false>, grid, dim3(256), lds,
+                                             a.stream, main, a.p, a.N, a.K);
+        if (rc) return rc;
+        return rest.count ? grouped_tiles_run(a, rest) : LQ_OK;
+    }
+    return grouped_tiles_run(a, big);
 }
 
 // ------------------------------------------------------------------------------------

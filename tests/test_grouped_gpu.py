@@ -155,3 +155,38 @@ def test_grouped_full_size_layer_all_families():
         assert np.array_equal(ACC[r0:r1].astype(np.float64), ref), f"expert {e}: accumulators differ"
         H.assert_fp16_close(Y[r0:r1], ref * s_x[r0:r1, None].astype(np.float64) * q["s_w"][None, :].astype(np.float64),
                             f"expert {e}")
+
+
+def test_grouped_large_experts_take_256_row_tiles():
+    """Experts of several hundred rows on a layer wide enough that whole rounds of 256 x 256 tiles
+    pay: the big experts run as one persistent launch of the one-wave-per-SIMD kernel over all of
+    them (ragged last row tiles of 8, 132 and 188 rows, an expert of exactly 256 rows, tile
+    boundaries between experts inside a block's stream), the small ones in their own families.
+    Checked in full against the exact float64 product of the oracle's dequantised weights."""
+    import torch
+
+    E, N, K, g = 7, 4096, 1024, 128
+    rows = [700, 5, 520, 900, 40, 256, 1000]
+    _say(f"grouped 256-row tiles E={E} N={N} K={K} rows={rows}")
+    Ws = [WL.make_weights(N, K, 0.02, seed=300 + e) for e in range(E)]
+    packs = [api.liquidquant_pack_weights(W, g) for W in Ws]
+    d_packed = torch.from_numpy(np.concatenate([p[0] for p in packs])).cuda()
+    d_gparams = torch.from_numpy(np.concatenate([p[1] for p in packs])).cuda()
+    d_sw = torch.from_numpy(np.stack([p[2] for p in packs])).cuda()
+    offs = np.concatenate([[0], np.cumsum(rows)]).astype(int)
+    X, s_x = I.make_activations(int(offs[-1]), K, outlier_frac=0.001, seed=78)
+    dX, dsx = torch.from_numpy(X).cuda(), torch.from_numpy(s_x).cuda()
+    Y, ACC = api.w4a8_grouped_gemm(offs, dX, dsx, d_packed, d_gparams, d_sw, N, K, g, want_y=True, want_acc=True)
+    # the accumulators alone: no scales are passed, none may be read
+    _, ACC2 = api.w4a8_grouped_gemm(offs, dX, None, d_packed, d_gparams, None, N, K, g, want_y=False, want_acc=True)
+    torch.cuda.synchronize()
+    ACC, Y, ACC2 = ACC.cpu().numpy(), Y.cpu().numpy(), ACC2.cpu().numpy()
+    assert np.array_equal(ACC, ACC2), "accumulator-only call differs"
+    for e in range(E):
+        r0, r1 = offs[e], offs[e + 1]
+        q = O.quantize_weights(Ws[e], g)
+        Wd = O.dequant_plain(q["Q_u4"], q["s_u8"], q["mn"], g)
+        ref = X[r0:r1].astype(np.float64) @ Wd.astype(np.float64).T
+        assert np.array_equal(ACC[r0:r1].astype(np.float64), ref), f"expert {e}: accumulators differ"
+        H.assert_fp16_close(Y[r0:r1], ref * s_x[r0:r1, None].astype(np.float64) * q["s_w"][None, :].astype(np.float64),
+                            f"expert {e}")
