@@ -167,7 +167,8 @@ def point(shape, M, ms, api, calib=None, ms_same=None):
         "tops": round(ops / t / 1e12, 3), "gbs": round(byt / t / 1e9, 1),
         "bound": "hbm" if t_mem >= t_mma else "mfma",
         "frac_of_roofline": round(max(t_mem, t_mma) / t, 4),
-        "variant": api.w4a8_variant_name(api.w4a8_select_variant(M, shape.N, shape.K, shape.group)),
+        "variant": "+".join(api.w4a8_variant_name(v) + (f"[{rows} rows]" if rows != M else "")
+                            for rows, v in api.w4a8_select_plan(M, shape.N, shape.K, shape.group)),
     }
     if ms_same is not None:
         p["us_same_buffer"] = round(ms_same * 1e3, 3)

@@ -74,6 +74,8 @@ def lib() -> ctypes.CDLL:
     L.w4a8_variant_supports.argtypes = [i, i, i, i, i]
     L.w4a8_select_variant.restype = i
     L.w4a8_select_variant.argtypes = [i, i, i, i]
+    L.w4a8_select_plan.restype = i
+    L.w4a8_select_plan.argtypes = [i, i, i, i, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
     L.w4a8_dequant_dump.restype = i
     L.w4a8_dequant_dump.argtypes = [vp, vp, i, i, i, vp, vp]
     L.w4a8_grouped_gemm.restype = i
@@ -335,6 +337,19 @@ def w4a8_select_variant(M: int, N: int, K: int, group: int) -> int:
     if v < 0:
         _check(v)
     return v
+
+
+def w4a8_select_plan(M: int, N: int, K: int, group: int):
+    """What w4a8_gemm launches for the shape: [(rows, variant index), ...], one or two launches
+    over consecutive rows."""
+    rows_first, rest = ctypes.c_int(0), ctypes.c_int(-1)
+    v = int(lib().w4a8_select_plan(M, N, K, group, ctypes.byref(rows_first), ctypes.byref(rest)))
+    if v < 0:
+        _check(v)
+    plan = [(int(rows_first.value), v)]
+    if rest.value >= 0:
+        plan.append((M - int(rows_first.value), int(rest.value)))
+    return plan
 
 
 def w4a8_dequant_dump(W_packed, gparams, N: int, K: int, group: int, out=None, stream=None):

@@ -600,9 +600,13 @@ static int find_variant(const char *name)
 // Costs in units of one 128 x 256 tile's time on a CU, from the numbers of tiles of each form;
 // returns 1 for 256 x 256, 2 for 256 x 128, 0 for neither.
 constexpr long long kAssumedCUs = 256;  // the shape rules of the dispatcher are written for the MI355X
-static int solo_form_for(long long t128, long long t256, long long t2, int K)
+struct TiledCosts {
+    double duo, solo, g2;
+    double best() const { return std::min(duo, std::min(solo, g2)); }
+};
+static TiledCosts tiled_costs(long long t128, long long t256, long long t2, int K)
 {
-    if (K % 512 != 0) return 0;
+    if (K % 512 != 0) return TiledCosts{1.0, 1e30, 1e30};
     // two resident blocks per CU (block b and b + 256 land on one CU) walk tiles b, b + 512, ...
     // (up to one tile per CU they split K across blocks to fill the chip, at about a tenth more)
     const long long rem = t128 % (2 * kAssumedCUs);
@@ -614,8 +618,19 @@ static int solo_form_for(long long t128, long long t256, long long t2, int K)
     // as one round that nearly fills the chip -- its tiles are separate, a second round costs a tenth more)
     const double solo = 2.0 * ((t256 + kAssumedCUs - 1) / kAssumedCUs) * 0.86 * short_k;
     const double g2 = 4 * t2 >= 3 * kAssumedCUs && t2 <= kAssumedCUs ? 0.96 * short_k : 1e30;
-    if (solo < duo && solo <= g2) return 1;
-    if (g2 < duo) return 2;
+    return TiledCosts{duo, solo, g2};
+}
+static TiledCosts tiled_costs(int M, int N, int K)
+{
+    const long long bm256 = (M + 255) / 256;
+    return tiled_costs((long long)((M + 127) / 128) * ((N + 255) / 256), bm256 * ((N + 255) / 256),
+                       bm256 * ((N + 127) / 128), K);
+}
+static int solo_form_for(long long t128, long long t256, long long t2, int K)
+{
+    const TiledCosts c = tiled_costs(t128, t256, t2, K);
+    if (c.solo < c.duo && c.solo <= c.g2) return 1;
+    if (c.g2 < c.duo) return 2;
     return 0;
 }
 static int solo_form_that_pays(int M, int N, int K)
@@ -677,6 +692,33 @@ static int select_variant(int M, int N, int K)
     return find_variant(prefer_64_row_tiles(M, N, K) ? "duo_m64" : "duo_m128");
 }
 
+// A batch whose 256 x 256 tiles are whole rounds plus a few rows (4096 + 40 rows on 8192 x 8192)
+// is better run as two launches over consecutive rows: the row blocks that fill whole rounds with
+// the 256 x 256 tiles, and the rest with whatever the dispatcher picks for it -- 226 us against
+// 259 us of the best single kernel there.  Only for a rest of at most 256 rows: with larger ones
+// (1536 + 512 rows on the 70B qkv projection, 2048 + 1024 on 8192 x 8192, 4096 + 1904 on 4096 x
+// 4096) the two launches were measured equal to the single one or 5 % behind -- the second kernel
+// starts when the first has drained, and the kernels for a few hundred rows are the least
+// efficient ones.  Same cost units as solo_form_for; a second launch is charged 12 us.  Returns
+// the rows of the first piece (M if the batch stays whole).
+static int rows_of_first_launch(int M, int N, int K)
+{
+    if (K % 512 != 0 || M <= 256) return M;
+    const int bm = (M + 255) / 256, bn = (N + 255) / 256;
+    double best = tiled_costs(M, N, K).best() * 0.97;  // (a split has to win by 3 %)
+    const double second_launch = 12.0 / (7.2 * K / 1024.0);
+    const double short_k = K >= 4096 ? 1.0 : 1.06;
+    int rows = M;
+    for (int rounds = 1; rounds <= 8; ++rounds) {
+        const int rb = (int)(kAssumedCUs * rounds / bn);  // row blocks whose tiles fill `rounds` rounds
+        if (rb >= bm) break;
+        if (rb < 1 || M - 256 * rb > 256) continue;
+        const double c = rounds * 2.0 * 0.86 * short_k + tiled_costs(M - 256 * rb, N, K).best() + second_launch;
+        if (c < best) best = c, rows = 256 * rb;
+    }
+    return rows;
+}
+
 static int check_device_args(const Args &a)
 {
     if (a.M < 0 || !shape_ok(a.N, a.K, a.group))
@@ -693,10 +735,8 @@ static int check_device_args(const Args &a)
     return LQ_OK;
 }
 
-static int run(int variant, const Args &a)
+static int run_rows(int variant, const Args &a)
 {
-    if (int rc = check_device_args(a)) return rc;
-    if (a.M == 0) return LQ_OK;
     if (variant < 0) variant = select_variant(a.M, a.N, a.K);
     if (variant < 0 || variant >= kNumVariants) return fail(LQ_ERR_INVALID, "unknown variant %d", variant);
     if (!variant_supports(variant, a.M, a.N, a.K))
@@ -725,6 +765,28 @@ static int run(int variant, const Args &a)
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return fail(LQ_ERR_HIP, "launch of %s failed: %s", kVariants[variant].name, hipGetErrorString(e));
+    return LQ_OK;
+}
+
+static int run(int variant, const Args &a)
+{
+    if (int rc = check_device_args(a)) return rc;
+    if (a.M == 0) return LQ_OK;
+    const int first = variant < 0 ? rows_of_first_launch(a.M, a.N, a.K) : a.M;
+    if (first == a.M) return run_rows(variant, a);
+    // two launches on the same stream (rows are independent); a workspace serves both in turn
+    Args head = a, rest = a;
+    size_t need_head = 0, need_rest = 0;
+    if (a.query) head.query = &need_head, rest.query = &need_rest;
+    head.M = first;
+    rest.M = a.M - first;
+    rest.X = a.X + (size_t)first * a.K;
+    if (a.sx) rest.sx = a.sx + first;
+    if (a.Y) rest.Y = a.Y + (size_t)first * a.N;
+    if (a.ACC) rest.ACC = a.ACC + (size_t)first * a.N;
+    if (int rc = run_rows(find_variant("solo_pt_m256"), head)) return rc;
+    if (int rc = run_rows(-1, rest)) return rc;
+    if (a.query) *a.query = std::max(need_head, need_rest);
     return LQ_OK;
 }
 
@@ -1028,6 +1090,15 @@ int w4a8_select_variant(int M, int N, int K, int group)
 {
     if (M < 0 || !shape_ok(N, K, group)) return fail(LQ_ERR_INVALID, "bad shape");
     return select_variant(M, N, K);
+}
+
+int w4a8_select_plan(int M, int N, int K, int group, int *rows_first, int *variant_rest)
+{
+    if (M < 0 || !shape_ok(N, K, group) || !rows_first || !variant_rest) return fail(LQ_ERR_INVALID, "bad shape");
+    const int first = M > 0 ? rows_of_first_launch(M, N, K) : M;
+    *rows_first = first;
+    *variant_rest = first == M ? -1 : select_variant(M - first, N, K);
+    return first == M ? select_variant(M, N, K) : find_variant("solo_pt_m256");
 }
 
 int w4a8_dequant_dump(const void *W_packed, const uint8_t *gparams, int N, int K, int group,

@@ -102,6 +102,30 @@ def test_dispatcher_boundaries():
         api.w4a8_select_variant(8, 100, 512, 64)                # bad shape
 
 
+def _plan(M, N, K, g=64):
+    return [(rows, api.w4a8_variant_name(v)) for rows, v in api.w4a8_select_plan(M, N, K, g)]
+
+
+def test_two_launch_plans():
+    """Batches whose 256 x 256 tiles make whole rounds of the chip plus a rest of at most 256 rows
+    run as two launches over consecutive rows; everything else as one, which is then the
+    dispatcher's choice."""
+    assert _plan(4096 + 40, 8192, 8192) == [(4096, "solo_pt_m256"), (40, "stream_m64")]      # a ragged tail of the batch
+    assert _plan(2048 + 100, 8192, 4096) == [(2048, "solo_pt_m256"), (100, "duo_m64")]
+    assert _plan(1024 + 30, 16384, 4096, 128) == [(1024, "solo_pt_m256"), (30, "stream_m32")]
+    # larger rests stay in one launch (measured equal or behind as two)
+    assert _plan(2048, 10240, 8192, 128) == [(2048, "duo_pt_m128")] and _plan(3072, 8192, 8192) == [(3072, "duo_pt_m128")]
+    assert _plan(6000, 4096, 4096) == [(6000, "duo_pt_m128")]
+    for M, N, K, g in [(4096, 8192, 8192, 64), (2048, 28672, 8192, 128), (1536, 8192, 8192, 64), (16, 8192, 8192, 64),
+                       (256, 8192, 8192, 64), (2048, 11008, 4096, 64), (3072, 8192, 8448, 64), (0, 4096, 4096, 64)]:
+        assert _plan(M, N, K, g) == [(M, _pick(M, N, K, g))], (M, N, K)
+    for s in WL.ALL_SHAPES:
+        plan = api.w4a8_select_plan(s.M, s.N, s.K, s.group)
+        assert sum(rows for rows, _ in plan) == s.M and all(rows > 0 for rows, _ in plan)
+        assert all(api.w4a8_variant_supports(v, rows, s.N, s.K, s.group) for rows, v in plan)
+        assert len(plan) == 1 or plan[0][0] % 256 == 0
+
+
 def test_variant_table_is_consistent():
     names = api.w4a8_variant_names()
     assert len(names) == len(set(names)) == api.w4a8_variant_count()

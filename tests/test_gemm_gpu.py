@@ -520,3 +520,25 @@ def test_persistent_tile_kernel(M, N, K, g, kernel):
                                     want_y=False)
     torch.cuda.synchronize()
     assert np.array_equal(ACC2.cpu().numpy().astype(np.int64), ref), "accumulator-only call differs"
+
+
+@pytest.mark.parametrize("M,N,K,g", [(2048 + 100, 8192, 4096, 64), (4096 + 40, 8192, 2048, 128), (1024 + 30, 16384, 4096, 128)])
+def test_two_launch_plans(M, N, K, g):
+    """Batches that the dispatcher runs as two launches over consecutive rows (whole rounds of
+    256 x 256 tiles, then the rest with its own kernel): every accumulator and every FP16 output
+    against the exact float64 product, through both public entry points."""
+    import torch
+
+    plan = api.w4a8_select_plan(M, N, K, g)
+    assert len(plan) == 2, plan
+    _say(f"two launches M={M} N={N} K={K} g={g}: {[(r, api.w4a8_variant_name(v)) for r, v in plan]}")
+    P = H.Problem(N, K, g, seed=M + 3)
+    Wd, s_w = P.oracle_wd()
+    X, s_x = I.make_activations(M, K, outlier_frac=0.01, seed=M + N)
+    ref = X.astype(np.float64) @ Wd.astype(np.float64).T
+    dX, dsx = torch.from_numpy(X).cuda(), torch.from_numpy(s_x).cuda()
+    Y = api.w4a8_gemm(dX, dsx, P.d_packed, P.d_gparams, P.d_w_scales, N, K, g)
+    ACC = api.w4a8_gemm_i32(dX, P.d_packed, P.d_gparams, N, K, g)
+    torch.cuda.synchronize()
+    assert np.array_equal(ACC.cpu().numpy().astype(np.float64), ref), "accumulators differ"
+    H.assert_fp16_close(Y.cpu().numpy(), O.scale_epilogue_f64(ref, s_x, s_w), "two launches")
