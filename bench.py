@@ -183,7 +183,8 @@ def point(shape, M, ms, api, calib=None, ms_same=None):
 
         rates = CM.Rates(calib["stream_read_gbs"] * 1e9, calib["mfma_i8_random_tops"] * 1e12,
                          CM.NOMINAL_VALU_LANE_OPS_PER_S)
-        m_tile = 16 if M <= 16 else (32 if M <= 32 else 128)
+        first = p["variant"].split("+")[0]
+        m_tile = 16 if M <= 16 else 32 if M <= 32 else 256 if first.startswith("solo") else 64 if "m64" in first else 128
         pr = CM.predict(M, shape.N, shape.K, shape.group, rates, m_tile)
         p["model_us"] = {"eq6_serial": round(pr["serial"] * 1e6, 2), "overlapped": round(pr["overlapped"] * 1e6, 2)}
     return p

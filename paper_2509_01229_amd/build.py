@@ -27,7 +27,27 @@ FLAGS = [
 ]
 
 
+# The kernels that load straight into LDS and the one-wave-per-SIMD kernels count their loads in
+# flight by hand (s_waitcnt vmcnt(N) in assembly) and rely on the order in which this compiler
+# emits the statements between scheduling barriers; the GPU parity tests are what validates a
+# compiler.  Another compiler must be validated the same way before its library is used.
+VALIDATED_COMPILERS = ("roc-7.2.0",)
+
+
+def check_compiler() -> None:
+    res = subprocess.run([HIPCC, "--version"], capture_output=True, text=True)
+    text = res.stdout + res.stderr
+    if any(tag in text for tag in VALIDATED_COMPILERS) or os.environ.get("LIQUIDGEMM_UNVALIDATED_COMPILER") == "1":
+        return
+    raise RuntimeError(
+        "hipcc is not a compiler this library's hand-counted waits were validated with "
+        f"({', '.join(VALIDATED_COMPILERS)}):\n{text}\nRun the GPU parity tests "
+        "(pytest tests -m gpu) on a build made with LIQUIDGEMM_UNVALIDATED_COMPILER=1, then add its tag to "
+        "VALIDATED_COMPILERS in paper_2509_01229_amd/build.py.")
+
+
 def build_library(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
+    check_compiler()
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
     cmd = [HIPCC, *FLAGS, *extra_flags, "-o", out, *srcs]
     if verbose:

@@ -14,10 +14,13 @@ constexpr size_t kTicketBytes = kMaxTicketGroups * sizeof(unsigned int);
 // the plain global load and store, which is what a relaxed agent-scope atomic compiles to.
 // OFF = constant byte offset (0 .. 4095) folded into the instruction, so that the four
 // accesses of one accumulator fragment share one address register pair.
+// (A store of more than 8 bytes reads its data registers for two more cycles; the compiler counts
+// those wait states for its own instructions but does not look into assembly statements, and the
+// next statement may be one that overwrites the registers -- hence the s_nop.)
 template <int OFF = 0>
 __device__ __forceinline__ void store_sc1_x4(int32_t *p, const v4i v)
 {
-    asm volatile("global_store_dwordx4 %0, %1, off offset:%2 sc1" ::"v"(p), "v"(v), "n"(OFF) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off offset:%2 sc1\n\ts_nop 1" ::"v"(p), "v"(v), "n"(OFF) : "memory");
 }
 template <int OFF = 0>
 __device__ __forceinline__ v4i load_sc1_x4(const int32_t *p)

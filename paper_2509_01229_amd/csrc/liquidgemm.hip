@@ -396,6 +396,22 @@ static int launch_duo_dl(const Args &a)
     return LQ_OK;
 }
 
+// Compute units of the current device (the grid of the persistent kernels), asked once per device.
+static int cu_count()
+{
+    static std::mutex mu;
+    static int cached[64];  // 0 = not asked yet
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    std::lock_guard<std::mutex> lock(mu);
+    if (cached[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+        cached[dev] = cus;
+    }
+    return cached[dev];
+}
+
 // The persistent form of the direct-to-LDS kernel: one block per resident slot (two per CU),
 // each walking its share of the tiles as one stream of stages.  Needs K % 512 == 0.
 static bool duo_pt_fits(int M, int N, int K)
@@ -412,8 +428,7 @@ static int launch_duo_pt(const Args &a)
     if ((long long)a.M * a.K >= (1ll << 32))
         return fail(LQ_ERR_INVALID, "M * K = %lld is beyond the 2^32 - 1 bytes of X one call addresses; split the batch",
                     (long long)a.M * a.K);
-    int dev = 0, cus = 256;
-    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    const int cus = cu_count();
     const int grid = std::min(blocks_m * blocks_n, 2 * std::max(cus, 1));
     const size_t lds_bytes = 4 * (size_t)128 * 128;
     if (a.group == 128) {
@@ -442,9 +457,7 @@ static int launch_solo_pt(const Args &a)
                     (long long)a.M * a.K);
     if (a.N > (1 << 26))  // (a row's lane offsets are 32-bit byte offsets)
         return fail(LQ_ERR_INVALID, "the 256-row tile variants take N up to 2^26, got %d", a.N);
-    int dev = 0, cus = 256;
-    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    const int grid = std::min(blocks_m * blocks_n, std::max(cus, 1));
+    const int grid = std::min(blocks_m * blocks_n, std::max(cu_count(), 1));
     const size_t lds_bytes = 4 * (size_t)256 * 128 + 4 * 1024;  // X stages; two copies of both scales
     if (a.group == 128) {
         if (int rc = allow_lds(w4a8_solo_pt_kernel<true, KG>, lds_bytes)) return rc;
@@ -939,8 +952,7 @@ static int grouped_run(const GroupedArgs &a)
         }
     }
     if (main.count && fits && solo_form_for(main_t128, main_t256, 0, a.K) == 1) {
-        int dev = 0, cus = 256;
-        if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        const int cus = cu_count();
         const dim3 grid((unsigned)std::min<long long>(main_t256, std::max(cus, 1)));
         const size_t lds = 4 * (size_t)256 * 128 + 4 * 1024;
         const int rc = g128 ? launch_checked("grouped solo", w4a8_solo_grouped_kernel<true>, grid, dim3(256), lds,
