@@ -150,33 +150,26 @@ __device__ __forceinline__ void solo_body(const Src &src, const int N, const int
     // covered by anybody.  The registers must not be touched between load_w1 and arrive_w (the
     // compiler takes them for complete): no kernel here may spill, and wr and pr are written and
     // read in place.
-    auto load_w1 = [&](int t, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
-        const uint32_t wo = wl + (uint32_t)l_s * 2048, po = pl_off + (uint32_t)l_s * (G128 ? 64 : 128);
+    // piece 0, 1 = the codes of the stage's chunk 0, 1 of channel tile t (KG = 2: piece 0 = the
+    // wave's own chunk, there is no piece 1), piece 2 = the tile's group parameters
+    auto load_w_piece = [&](int t, int piece, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
         const char *wb = wbase + t * wg_stride;
         const char *pb = pbase + t * pg_stride;
-        if (KG == 2) {  // the wave's chunk only
+        if (piece < 2) {
+            const uint32_t wo = wl + (uint32_t)l_s * 2048 + (KG == 2 ? (uint32_t)grp * 1024 : (uint32_t)piece * 1024);
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "=&v"(w[t][piece]) : "v"(wo), "s"(wb) : "memory");
+        } else {
+            const uint32_t po = pl_off + (uint32_t)l_s * (G128 ? 64 : 128);
             if (G128)
-                asm volatile("global_load_dwordx4 %0, %2, %3\n\tglobal_load_ushort %1, %4, %5"
-                             : "=&v"(w[t][0]), "=&v"(p[t].raw)
-                             : "v"(wo + (uint32_t)grp * 1024), "s"(wb), "v"(po), "s"(pb)
-                             : "memory");
+                asm volatile("global_load_ushort %0, %1, %2" : "=&v"(p[t].raw) : "v"(po), "s"(pb) : "memory");
             else
-                asm volatile("global_load_dwordx4 %0, %2, %3\n\tglobal_load_dword %1, %4, %5"
-                             : "=&v"(w[t][0]), "=&v"(p[t].raw)
-                             : "v"(wo + (uint32_t)grp * 1024), "s"(wb), "v"(po), "s"(pb)
-                             : "memory");
-        } else if (G128)
-            asm volatile("global_load_dwordx4 %0, %3, %4\n\tglobal_load_dwordx4 %1, %3, %4 offset:1024\n\t"
-                         "global_load_ushort %2, %5, %6"
-                         : "=&v"(w[t][0]), "=&v"(w[t][1]), "=&v"(p[t].raw)
-                         : "v"(wo), "s"(wb), "v"(po), "s"(pb)
-                         : "memory");
-        else
-            asm volatile("global_load_dwordx4 %0, %3, %4\n\tglobal_load_dwordx4 %1, %3, %4 offset:1024\n\t"
-                         "global_load_dword %2, %5, %6"
-                         : "=&v"(w[t][0]), "=&v"(w[t][1]), "=&v"(p[t].raw)
-                         : "v"(wo), "s"(wb), "v"(po), "s"(pb)
-                         : "memory");
+                asm volatile("global_load_dword %0, %1, %2" : "=&v"(p[t].raw) : "v"(po), "s"(pb) : "memory");
+        }
+    };
+    auto load_w1 = [&](int t, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
+        load_w_piece(t, 0, w, p);
+        if (KG == 1) load_w_piece(t, 1, w, p);
+        load_w_piece(t, 2, w, p);
     };
     // waits until at most PENDING loads of this wave are in flight; every use of (w, p) behind it
     auto arrive_w = [&](auto pending_tag, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
@@ -312,7 +305,8 @@ __device__ __forceinline__ void solo_body(const Src &src, const int N, const int
     // and the free register set.  The 14 loads of a prefetch are spread over the 62 slots up to
     // the next stage's barrier -- four in the last k-step, ten in the first three of the next
     // stage: the four waves of a CU share one path from the L1, and all of a stage's loads
-    // within one k-step ask twice what it delivers, which stalls the issue of every wave.
+    // within one k-step ask twice what it delivers, which stalls the issue of every wave.  They
+    // sit in odd slots, one load each: the even slots carry the fragment reads from LDS.
     // The next stage may belong to the block's next tile: its operands then wait in registers
     // while the epilogue runs (after the last tile they are those of a re-read stage, unused).
     auto stage = [&](auto q_tag) {
@@ -321,11 +315,13 @@ __device__ __forceinline__ void solo_body(const Src &src, const int N, const int
             // two k-steps: the wave's chunk; the ten later loads of the running prefetch in the first
             kstep_hi(bf[0], bf[1], wr[q], 0, q, 0, 0, q, 0, 1, [&](int i) {
                 if (i == 1) issue_x1(gq, 4);
-                if (i == 4) issue_x1(gq, 5);
-                if (i == 7) issue_x1(gq, 6);
-                if (i == 10) issue_x1(gq, 7);
-                if (i == 12) load_w1(0, wr[gq], pr[gq]);
-                if (i == 14) load_w1(1, wr[gq], pr[gq]);
+                if (i == 3) issue_x1(gq, 5);
+                if (i == 5) issue_x1(gq, 6);
+                if (i == 7) issue_x1(gq, 7);
+                if (i == 9) load_w_piece(0, 0, wr[gq], pr[gq]);
+                if (i == 11) load_w_piece(0, 2, wr[gq], pr[gq]);
+                if (i == 13) load_w_piece(1, 0, wr[gq], pr[gq]);
+                if (i == 15) load_w_piece(1, 2, wr[gq], pr[gq]);
             });
             load_side_advance();
             SB();
@@ -333,22 +329,26 @@ __device__ __forceinline__ void solo_body(const Src &src, const int N, const int
                 if (i == -1) arrive_w(std::integral_constant<int, PER_STAGE>{}, wr[nq], pr[nq]);
                 if (i == 1) asm volatile("s_barrier" ::: "memory");
                 if (i == 3) issue_x1(fq, 0);
-                if (i == 6) issue_x1(fq, 1);
-                if (i == 9) issue_x1(fq, 2);
-                if (i == 12) issue_x1(fq, 3);
+                if (i == 7) issue_x1(fq, 1);
+                if (i == 11) issue_x1(fq, 2);
+                if (i == 15) issue_x1(fq, 3);
             });
         } else {
         kstep_hi(bf[0], bf[1], wr[q], 0, q, 0, 0, q, 0, 1, [&](int i) {
-            if (i == 2) issue_x1(gq, 4);
-            if (i == 7) issue_x1(gq, 5);
-            if (i == 12) issue_x1(gq, 6);
+            if (i == 3) issue_x1(gq, 4);
+            if (i == 9) issue_x1(gq, 5);
+            if (i == 15) issue_x1(gq, 6);
         });
         kstep_lo(bf[1], bf[0], wr[q], pr[q], 1, 1, q, 0, 1, q, 1, 0, [&](int i) {
-            if (i == 2) issue_x1(gq, 7);
-            if (i == 8) load_w1(0, wr[gq], pr[gq]);
+            if (i == 5) issue_x1(gq, 7);
+            if (i == 9) load_w_piece(0, 0, wr[gq], pr[gq]);
+            if (i == 13) load_w_piece(0, 1, wr[gq], pr[gq]);
         });
         kstep_hi(bf[0], bf[1], wr[q], 1, q, 1, 0, q, 1, 1, [&](int i) {
-            if (i == 4) load_w1(1, wr[gq], pr[gq]);
+            if (i == 1) load_w_piece(0, 2, wr[gq], pr[gq]);
+            if (i == 5) load_w_piece(1, 0, wr[gq], pr[gq]);
+            if (i == 9) load_w_piece(1, 1, wr[gq], pr[gq]);
+            if (i == 13) load_w_piece(1, 2, wr[gq], pr[gq]);
         });
         load_side_advance();
         SB();
@@ -356,9 +356,9 @@ __device__ __forceinline__ void solo_body(const Src &src, const int N, const int
             if (i == -1) arrive_w(std::integral_constant<int, PER_STAGE>{}, wr[nq], pr[nq]);
             if (i == 1) asm volatile("s_barrier" ::: "memory");
             if (i == 3) issue_x1(fq, 0);
-            if (i == 6) issue_x1(fq, 1);
-            if (i == 9) issue_x1(fq, 2);
-            if (i == 12) issue_x1(fq, 3);
+            if (i == 7) issue_x1(fq, 1);
+            if (i == 11) issue_x1(fq, 2);
+            if (i == 15) issue_x1(fq, 3);
         });
         }
         // (the next stage's first B operand is complete here, also where the next stage is the
