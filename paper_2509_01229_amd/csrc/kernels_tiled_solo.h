@@ -140,7 +140,7 @@ __device__ __forceinline__ void solo_body(const Src &src, const int N, const int
     auto issue_x1 = [&](int buf, int i) {
         asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                      : "+v"(wl)  // untouched; makes the W loads that follow depend on this statement
-                     : "v"(xg[i] + (uint32_t)l_s * 128), "s"(ld_X), "s"(lds0 + buf * STAGE + (4 * i + wave) * 1024)
+                     : "v"(xg[i]), "s"(ld_X + (size_t)l_s * 128), "s"(lds0 + buf * STAGE + (4 * i + wave) * 1024)
                      : "memory", "m0");
     };
     // The W loads are written out as well, so that every wait of the stage loop is one that is
@@ -153,17 +153,16 @@ __device__ __forceinline__ void solo_body(const Src &src, const int N, const int
     // piece 0, 1 = the codes of the stage's chunk 0, 1 of channel tile t (KG = 2: piece 0 = the
     // wave's own chunk, there is no piece 1), piece 2 = the tile's group parameters
     auto load_w_piece = [&](int t, int piece, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
-        const char *wb = wbase + t * wg_stride;
-        const char *pb = pbase + t * pg_stride;
+        // (the stage's offset goes into the scalar base: the lane offsets stay what they are)
         if (piece < 2) {
-            const uint32_t wo = wl + (uint32_t)l_s * 2048 + (KG == 2 ? (uint32_t)grp * 1024 : (uint32_t)piece * 1024);
-            asm volatile("global_load_dwordx4 %0, %1, %2" : "=&v"(w[t][piece]) : "v"(wo), "s"(wb) : "memory");
+            const char *wb = wbase + t * wg_stride + (size_t)l_s * 2048 + (KG == 2 ? grp * 1024 : piece * 1024);
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "=&v"(w[t][piece]) : "v"(wl), "s"(wb) : "memory");
         } else {
-            const uint32_t po = pl_off + (uint32_t)l_s * (G128 ? 64 : 128);
+            const char *pb = pbase + t * pg_stride + (size_t)l_s * (G128 ? 64 : 128);
             if (G128)
-                asm volatile("global_load_ushort %0, %1, %2" : "=&v"(p[t].raw) : "v"(po), "s"(pb) : "memory");
+                asm volatile("global_load_ushort %0, %1, %2" : "=&v"(p[t].raw) : "v"(pl_off), "s"(pb) : "memory");
             else
-                asm volatile("global_load_dword %0, %1, %2" : "=&v"(p[t].raw) : "v"(po), "s"(pb) : "memory");
+                asm volatile("global_load_dword %0, %1, %2" : "=&v"(p[t].raw) : "v"(pl_off), "s"(pb) : "memory");
         }
     };
     auto load_w1 = [&](int t, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
