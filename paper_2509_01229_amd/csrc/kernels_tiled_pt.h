@@ -92,19 +92,39 @@ __global__ __launch_bounds__(256, 2) void w4a8_duo_pt_kernel(
     auto issue_x1 = [&](int buf, int i) {
         asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                      : "+v"(wl)  // untouched; makes the W loads that follow depend on this statement
-                     : "v"(xg[i] + (uint32_t)l_s * 128), "s"(X), "s"(lds0 + buf * STAGE + (4 * i + wave) * 1024)
+                     : "v"(xg[i]), "s"(X + (size_t)l_s * 128), "s"(lds0 + buf * STAGE + (4 * i + wave) * 1024)
                      : "memory", "m0");
     };
+    // The W loads are written out like the X loads, so that the one wait of the stage loop is the
+    // one written here (see w4a8_solo_pt_kernel: the compiler does not see the X loads, and its
+    // own wait for a W register would also drain the X loads of the youngest stage, which keeps
+    // a stage's loads from being spread over the stage).  The registers must not be touched
+    // between a load and arrive_w: no kernel here may spill, and wr and pr are used in place.
+    // piece 0, 1 = the codes of the stage's chunk 0, 1 of channel tile t, piece 2 = its group
+    // parameters; the stage's offset goes into the scalar base.
+    auto load_w_piece = [&](int t, int piece, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
+        if (piece < 2) {
+            const char *wb = wbase + t * wg_stride + (size_t)l_s * 2048 + piece * 1024;
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "=&v"(w[t][piece]) : "v"(wl), "s"(wb) : "memory");
+        } else {
+            const char *pb = pbase + t * pg_stride + (size_t)l_s * (G128 ? 64 : 128);
+            if (G128)
+                asm volatile("global_load_ushort %0, %1, %2" : "=&v"(p[t].raw) : "v"(pl_off), "s"(pb) : "memory");
+            else
+                asm volatile("global_load_dword %0, %1, %2" : "=&v"(p[t].raw) : "v"(pl_off), "s"(pb) : "memory");
+        }
+    };
     auto load_w1 = [&](int t, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
-        const uint32_t wo = wl + (uint32_t)l_s * 2048, po = pl_off + (uint32_t)l_s * (G128 ? 64 : 128);
-        const char *wb = wbase + t * wg_stride;
-        const char *pb = pbase + t * pg_stride;
-        w[t][0] = *reinterpret_cast<const u32x4 *>(wb + wo);
-        w[t][1] = *reinterpret_cast<const u32x4 *>(wb + wo + 1024);
-        if (G128)
-            p[t].raw = *reinterpret_cast<const uint16_t *>(pb + po);
-        else
-            p[t].raw = *reinterpret_cast<const uint32_t *>(pb + po);
+        load_w_piece(t, 0, w, p);
+        load_w_piece(t, 1, w, p);
+        load_w_piece(t, 2, w, p);
+    };
+    // waits until at most PENDING loads of this wave are in flight; every use of (w, p) behind it
+    auto arrive_w = [&](auto pending_tag, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
+        asm volatile("s_waitcnt vmcnt(%6)"
+                     : "+v"(w[0][0]), "+v"(w[0][1]), "+v"(w[1][0]), "+v"(w[1][1]), "+v"(p[0].raw), "+v"(p[1].raw)
+                     : "n"(decltype(pending_tag)::value)
+                     : "memory");
     };
 
     // ---- compute side ------------------------------------------------------------------------
@@ -166,27 +186,28 @@ __global__ __launch_bounds__(256, 2) void w4a8_duo_pt_kernel(
     };
     // k-step that multiplies (a1, bc) and builds bn = B(c, 1) of w; (cb, cc, ch) = LDS stage,
     // chunk and half of the running k-step, (nb, nc, nh) of the next one (see duo_dl_tile)
+    // ex(i): what else slot i carries (a piece of the prefetch: odd slots, the even ones read LDS)
     auto kstep_hi = [&](const v4i (&bc)[2], v4i (&bn)[2], const u32x4 (&w)[2][2], int c, int cb, int cc, int ch,
-                        int nb, int nc, int nh) {
+                        int nb, int nc, int nh, auto ex) {
         mm(0, bc); rd(cb, cc, ch, 3); ph_shr(w[0][c]); SB();
-        mm(1, bc); ph_and_hi(); SB();
+        mm(1, bc); ph_and_hi(); ex(1); SB();
         mm(2, bc); rd(nb, nc, nh, 0); ph_mad(0); SB();
-        mm(3, bc); ph_xor(bn[0]); SB();
+        mm(3, bc); ph_xor(bn[0]); ex(3); SB();
         mm(4, bc); rd(nb, nc, nh, 1); ph_shr(w[1][c]); SB();
-        mm(5, bc); ph_and_hi(); SB();
+        mm(5, bc); ph_and_hi(); ex(5); SB();
         mm(6, bc); rd(nb, nc, nh, 2); ph_mad(1); SB();
-        mm(7, bc); ph_xor(bn[1]); SB();
+        mm(7, bc); ph_xor(bn[1]); ex(7); SB();
     };
     auto kstep_lo = [&](const v4i (&bc)[2], v4i (&bn)[2], const u32x4 (&w)[2][2], const UnitParams<G128> (&p)[2],
-                        int c, int cb, int cc, int ch, int nb, int nc, int nh) {
+                        int c, int cb, int cc, int ch, int nb, int nc, int nh, auto ex) {
         mm(0, bc); rd(cb, cc, ch, 3); ph_par(p, c); SB();
-        mm(1, bc); ph_and_lo(w[0][c]); SB();
+        mm(1, bc); ph_and_lo(w[0][c]); ex(1); SB();
         mm(2, bc); rd(nb, nc, nh, 0); ph_mad(0); SB();
-        mm(3, bc); ph_xor(bn[0]); SB();
+        mm(3, bc); ph_xor(bn[0]); ex(3); SB();
         mm(4, bc); rd(nb, nc, nh, 1); ph_and_lo(w[1][c]); SB();
-        mm(5, bc); ph_mad(1); SB();
+        mm(5, bc); ph_mad(1); ex(5); SB();
         mm(6, bc); rd(nb, nc, nh, 2); ph_xor(bn[1]); SB();
-        mm(7, bc); SB();
+        mm(7, bc); ex(7); SB();
     };
     // builds bf[0] = B(0, 0) of stage set q and reads fragments 0..2 of its first k-step
     auto first_operands = [&](int q) {
@@ -201,27 +222,41 @@ __global__ __launch_bounds__(256, 2) void w4a8_duo_pt_kernel(
     // then the prefetch of the stage three ahead into that LDS stage and the free register set.
     // LAST = last stage of a tile: the first operands of the next stage are left to the caller.
     auto stage = [&](auto q_tag, auto last_tag) {
-        constexpr int q = decltype(q_tag)::value, nq = (q + 1) & 3, fq = (q + 3) & 3;
+        constexpr int q = decltype(q_tag)::value, nq = (q + 1) & 3, gq = (q + 2) & 3, fq = (q + 3) & 3;
         constexpr bool LAST = decltype(last_tag)::value;
-        kstep_hi(bf[0], bf[1], wr[q], 0, q, 0, 0, q, 0, 1);
-        kstep_lo(bf[1], bf[0], wr[q], pr[q], 1, q, 0, 1, q, 1, 0);
-        kstep_hi(bf[0], bf[1], wr[q], 1, q, 1, 0, q, 1, 1);
-        mm(0, bf[1]); rd(q, 1, 1, 3); if (!LAST) ph_par(pr[nq], 0); SB();
-        mm(1, bf[1]); if (!LAST) ph_and_lo(wr[nq][0][0]);
-        // (the use of W of the next stage stays above the barrier: the compiler's own wait for
-        // those registers then also covers the older X loads of that stage, see duo_dl_tile)
-        if (!LAST) asm volatile("" : "+v"(tq[0]), "+v"(tq[1]), "+v"(tq[2]), "+v"(tq[3]));
-        wait_vmcnt<PER_STAGE>();
-        asm volatile("s_barrier" ::: "memory");
-        SB();
-        mm(2, bf[1]); if (!LAST) { rd(nq, 0, 0, 0); ph_mad(0); } issue_x1(fq, 0); SB();
-        mm(3, bf[1]); if (!LAST) ph_xor(bf[0][0]); issue_x1(fq, 1); SB();
-        mm(4, bf[1]); if (!LAST) { rd(nq, 0, 0, 1); ph_and_lo(wr[nq][1][0]); } issue_x1(fq, 2); SB();
-        mm(5, bf[1]); if (!LAST) ph_mad(1); issue_x1(fq, 3); SB();
-        mm(6, bf[1]); if (!LAST) { rd(nq, 0, 0, 2); ph_xor(bf[0][1]); } load_w1(0, wr[fq], pr[fq]); SB();
-        mm(7, bf[1]); load_w1(1, wr[fq], pr[fq]); SB();
+        // the seven later loads of the prefetch that the stage before began (into set gq)
+        kstep_hi(bf[0], bf[1], wr[q], 0, q, 0, 0, q, 0, 1, [&](int i) {
+            if (i == 1) issue_x1(gq, 3);
+            if (i == 5) load_w_piece(0, 0, wr[gq], pr[gq]);
+        });
+        kstep_lo(bf[1], bf[0], wr[q], pr[q], 1, q, 0, 1, q, 1, 0, [&](int i) {
+            if (i == 1) load_w_piece(0, 1, wr[gq], pr[gq]);
+            if (i == 5) load_w_piece(0, 2, wr[gq], pr[gq]);
+        });
+        kstep_hi(bf[0], bf[1], wr[q], 1, q, 1, 0, q, 1, 1, [&](int i) {
+            if (i == 1) load_w_piece(1, 0, wr[gq], pr[gq]);
+            if (i == 3) load_w_piece(1, 1, wr[gq], pr[gq]);
+            if (i == 5) load_w_piece(1, 2, wr[gq], pr[gq]);
+        });
         load_side_advance();
         SB();
+        // last k-step: X and W of the next stage have landed (the stage behind it may be in
+        // flight), then the barrier (every wave's part of that X is visible, the LDS stage of the
+        // stage before this one is released), then the first three loads of the prefetch of the
+        // stage three ahead
+        mm(0, bf[1]); rd(q, 1, 1, 3);
+        arrive_w(std::integral_constant<int, PER_STAGE>{}, wr[nq], pr[nq]);
+        if (!LAST) ph_par(pr[nq], 0);
+        SB();
+        mm(1, bf[1]); if (!LAST) ph_and_lo(wr[nq][0][0]);
+        asm volatile("s_barrier" ::: "memory");
+        SB();
+        mm(2, bf[1]); if (!LAST) { rd(nq, 0, 0, 0); ph_mad(0); } SB();
+        mm(3, bf[1]); if (!LAST) ph_xor(bf[0][0]); issue_x1(fq, 0); SB();
+        mm(4, bf[1]); if (!LAST) { rd(nq, 0, 0, 1); ph_and_lo(wr[nq][1][0]); } SB();
+        mm(5, bf[1]); if (!LAST) ph_mad(1); issue_x1(fq, 1); SB();
+        mm(6, bf[1]); if (!LAST) { rd(nq, 0, 0, 2); ph_xor(bf[0][1]); } SB();
+        mm(7, bf[1]); issue_x1(fq, 2); SB();
     };
     const std::integral_constant<int, 0> q0{};
     const std::integral_constant<int, 1> q1{};
@@ -230,10 +265,10 @@ __global__ __launch_bounds__(256, 2) void w4a8_duo_pt_kernel(
     const std::false_type inner{};
     const std::true_type last{};
 
-    // ---- pipeline fill: stages 0, 1, 2 of the first tile ------------------------------------
+    // ---- pipeline fill: stages 0 and 1 of the first tile and the first three loads of stage 2 ----
     load_side_tile(l_lid);
 #pragma unroll
-    for (int q = 0; q < 3; ++q) {
+    for (int q = 0; q < 2; ++q) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) issue_x1(q, i);
         load_w1(0, wr[q], pr[q]);
@@ -241,10 +276,9 @@ __global__ __launch_bounds__(256, 2) void w4a8_duo_pt_kernel(
         __builtin_amdgcn_sched_barrier(0);
         load_side_advance();
     }
-    ph_par(pr[0], 0);
-    ph_and_lo(wr[0][0][0]);
-    asm volatile("" : "+v"(tq[0]), "+v"(tq[1]), "+v"(tq[2]), "+v"(tq[3]));
-    wait_vmcnt<2 * PER_STAGE>();  // X(0) of this wave is in LDS
+#pragma unroll
+    for (int i = 0; i < 3; ++i) issue_x1(2, i);  // (the rest of stage 2 in the first three k-steps of stage 0)
+    arrive_w(std::integral_constant<int, PER_STAGE + 3>{}, wr[0], pr[0]);  // and X(0) of this wave is in LDS
     asm volatile("s_barrier" ::: "memory");
     first_operands(0);
     __builtin_amdgcn_sched_barrier(0);
