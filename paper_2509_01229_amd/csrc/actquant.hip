@@ -314,9 +314,10 @@ static void launch_quantize(int M, int K, const __half *X, const float *smooth, 
 {
     const dim3 block(kQuantThreads);
     const int pieces = (K / 8 + kQuantThreads - 1) / kQuantThreads;  // 16-byte pieces per thread
-    // tokens per block: as many as leave two blocks per CU (with smooth scales only: without
-    // them there is nothing to share between tokens)
-    const int R = !SMOOTH ? 1 : std::max(1, (M + 511) / 512);
+    // tokens per block: as many as leave four blocks per CU (with smooth scales only: without
+    // them there is nothing to share between tokens; three blocks of this kernel fit a CU, and
+    // 1024 blocks measured 3 to 12 % faster than 512 on 4096 tokens of 8192 and 4096 elements)
+    const int R = !SMOOTH ? 1 : std::max(1, (M + 1023) / 1024);
     const dim3 grid((unsigned)((M + R - 1) / R));
 #define LQ_LAUNCH_Q(ITERS) \
     hipLaunchKernelGGL((quantize_act_rows_kernel<SMOOTH, ITERS, kQuantThreads>), grid, block, 0, st, M, K, R, X, \
