@@ -419,25 +419,30 @@ __device__ __forceinline__ void solo_body(const Src &src, const int N, const int
                     sxv[4 * q4 + 2] = v.z;
                     sxv[4 * q4 + 3] = v.w;
                 }
+                // (the two halves of a store go straight into one register -- low half, then high half
+                // -- and the row base moves by additions: a lone wave pays for every instruction here)
+                const size_t pitch = (size_t)N * 2;
+                const char *row = reinterpret_cast<const char *>(Y) + (size_t)row0 * pitch;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int ur = row0 + 8 * (r >> 2) + (r & 3);
-                    union {
-                        __half h[2];
-                        uint32_t u;
-                    } o;
-                    o.h[0] = scale_to_half(element(0, r), sxv[r], swv.x);
-                    o.h[1] = scale_to_half(element(1, r), sxv[r], swv.y);
-                    const char *row = reinterpret_cast<const char *>(Y) + (size_t)ur * (size_t)N * 2;
-                    if (FULL || ur + 4 * kb < M) store_y(lane_off * 2, o.u, row);
+                    const float x0 = (float)element(0, r) * sxv[r], x1 = (float)element(1, r) * sxv[r];
+                    uint32_t two;  // fp16(x0 * s_w[n]) | fp16(x1 * s_w[n + 1]) << 16, each product rounded to FP32 first
+                    asm("v_fma_mixlo_f16 %0, %1, %2, 0\n\tv_fma_mixhi_f16 %0, %3, %4, 0"
+                        : "=&v"(two)
+                        : "v"(x0), "v"(swv.x), "v"(x1), "v"(swv.y));
+                    if (FULL || ur + 4 * kb < M) store_y(lane_off * 2, two, row);
+                    row += (r & 3) == 3 ? 5 * pitch : pitch;
                 }
             }
             if (ACC) {
+                const size_t pitch = (size_t)N * 4;
+                const char *row = reinterpret_cast<const char *>(ACC) + (size_t)row0 * pitch;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int ur = row0 + 8 * (r >> 2) + (r & 3);
-                    const char *row = reinterpret_cast<const char *>(ACC) + (size_t)ur * (size_t)N * 4;
                     if (FULL || ur + 4 * kb < M) store_acc(lane_off * 4, element(0, r), element(1, r), row);
+                    row += (r & 3) == 3 ? 5 * pitch : pitch;
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
