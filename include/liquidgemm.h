@@ -22,7 +22,8 @@
  *     enqueue work on `hip_stream` (a hipStream_t passed as void*; NULL = default
  *     stream) and return without synchronising.
  *   - Shapes: N % 64 == 0, K % 256 == 0, group in {64, 128}, 0 <= M, K <= 131072
- *     (so that |ACC| <= K * 127 * 127 stays below 2^31).  M = 0 is a successful no-op.
+ *     (so that |ACC| <= K * 127 * 127 stays below 2^31), N <= 2^26 (a row of the output is
+ *     addressed with 32-bit byte offsets).  M = 0 is a successful no-op.
  *     M itself is only bounded by int: the kernels address X with 32-bit byte offsets, and
  *     w4a8_gemm / w4a8_gemm_i32 / w4a8_gemm_variant run a batch with M * K >= 2^32 as
  *     consecutive launches over chunks of rows on the same stream (same result).  The

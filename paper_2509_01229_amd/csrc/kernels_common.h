@@ -63,38 +63,61 @@ __device__ __forceinline__ Place grid_place(unsigned int *tickets)
 // rows at a time (rows past M read s_x[M-1]; only the stores are predicated), so no
 // load sits behind a branch.
 // ------------------------------------------------------------------------------------
+// A row's address is a wave-uniform base (scalar registers, moved from row to row by additions)
+// plus one 32-bit lane offset, the stores are written in that form; the two halves of an FP16
+// store go straight into one register (low half, then high half).  m0 must be wave-uniform.
+__device__ __forceinline__ void store_row_u32(uint32_t byte_off, uint32_t v, const char *row)
+{
+    asm volatile("global_store_dword %0, %1, %2" : : "v"(byte_off), "v"(v), "s"(row) : "memory");
+}
+__device__ __forceinline__ void store_row_i32x2(uint32_t byte_off, int a, int b, const char *row)
+{
+    const uint64_t two = (uint32_t)a | ((uint64_t)(uint32_t)b << 32);
+    asm volatile("global_store_dwordx2 %0, %1, %2" : : "v"(byte_off), "v"(two), "s"(row) : "memory");
+}
+// fp16(x0 * s0) | fp16(x1 * s1) << 16, each product rounded to FP32 first (as scale_to_half does)
+__device__ __forceinline__ uint32_t scale_pair_to_half2(float x0, float s0, float x1, float s1)
+{
+    uint32_t two;
+    asm("v_fma_mixlo_f16 %0, %1, %2, 0\n\tv_fma_mixhi_f16 %0, %3, %4, 0" : "=&v"(two) : "v"(x0), "v"(s0), "v"(x1), "v"(s1));
+    return two;
+}
 template <int MF>
 __device__ __forceinline__ void store_tile(const v16i (&acc)[MF][2], int M, int N, int m0, int n, int lane,
                                            const float *__restrict__ sx, const float *__restrict__ sw,
                                            __half *__restrict__ Y, int32_t *__restrict__ ACC)
 {
     const int kb = lane >> 5;
+    const uint32_t lane_off = (uint32_t)(4 * kb) * (uint32_t)N + (uint32_t)n;  // in elements (N <= 2^26)
+    m0 = __builtin_amdgcn_readfirstlane(m0);
     if (ACC) {
+        const size_t pitch = (size_t)N * 4;
 #pragma unroll
-        for (int mf = 0; mf < MF; ++mf)
+        for (int mf = 0; mf < MF; ++mf) {
+            const char *row = reinterpret_cast<const char *>(ACC) + (size_t)(m0 + 32 * mf) * pitch;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int m = m0 + 32 * mf + 8 * (r >> 2) + 4 * kb + (r & 3);
-                if (m < M) *reinterpret_cast<int2 *>(ACC + (size_t)m * N + n) = int2{acc[mf][0][r], acc[mf][1][r]};
+                if (m < M) store_row_i32x2(lane_off * 4, acc[mf][0][r], acc[mf][1][r], row);
+                row += (r & 3) == 3 ? 5 * pitch : pitch;
             }
+        }
     }
     if (Y) {
         const float2 swv = *reinterpret_cast<const float2 *>(sw + n);
+        const size_t pitch = (size_t)N * 2;
 #pragma unroll
         for (int mf = 0; mf < MF; ++mf) {
             float sxv[16];
 #pragma unroll
             for (int r = 0; r < 16; ++r) sxv[r] = sx[min(m0 + 32 * mf + 8 * (r >> 2) + 4 * kb + (r & 3), M - 1)];
+            const char *row = reinterpret_cast<const char *>(Y) + (size_t)(m0 + 32 * mf) * pitch;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int m = m0 + 32 * mf + 8 * (r >> 2) + 4 * kb + (r & 3);
-                union {
-                    __half h[2];
-                    uint32_t u;
-                } o;
-                o.h[0] = scale_to_half(acc[mf][0][r], sxv[r], swv.x);
-                o.h[1] = scale_to_half(acc[mf][1][r], sxv[r], swv.y);
-                if (m < M) *reinterpret_cast<uint32_t *>(Y + (size_t)m * N + n) = o.u;
+                const uint32_t two = scale_pair_to_half2((float)acc[mf][0][r] * sxv[r], swv.x, (float)acc[mf][1][r] * sxv[r], swv.y);
+                if (m < M) store_row_u32(lane_off * 2, two, row);
+                row += (r & 3) == 3 ? 5 * pitch : pitch;
             }
         }
     }

@@ -15,7 +15,7 @@ int fail(int code, const char *fmt, ...);
 inline bool shape_ok(int N, int K, int group)
 {
     return N > 0 && K > 0 && N % 64 == 0 && K % 256 == 0 && (group == 64 || group == 128) &&
-           K <= 131072;
+           K <= 131072 && N <= (1 << 26);
 }
 
 }  // namespace lqq
