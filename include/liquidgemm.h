@@ -101,7 +101,8 @@ int liquidquant_unpack_weights(const void *W_packed, const uint8_t *gparams, int
 
 /* Bytes of device workspace w4a8_gemm* can use for this shape (0 when no kernel that can run
  * the shape splits K across blocks): 32 KiB of arrival tickets followed by room for the INT32
- * partial tiles of the grid-level split-K.
+ * partial tiles of the grid-level split-K (the 256-row tile kernels with K slices keep a whole
+ * [M,N] INT32 matrix per slice there, at most four).
  *   - The first 32 KiB (or the whole buffer if smaller) must be zero before the first call
  *     that uses the buffer: zero it yourself or enqueue w4a8_workspace_init() once.  The
  *     kernels leave the tickets zero again, so one initialisation serves any number of calls,
@@ -109,8 +110,9 @@ int liquidquant_unpack_weights(const void *W_packed, const uint8_t *gparams, int
  *   - One workspace serves one call at a time: calls that may overlap in time on one GPU
  *     (different streams) need different workspaces; calls on one stream can share one.
  *   - With a smaller (or NULL) workspace the dispatcher runs the same kernels without the
- *     split, which is slower for small N but gives the same result; a variant that names its
- *     split (w4a8_gemm_variant) fails with LQ_ERR_WORKSPACE instead. */
+ *     split (or with as many slices as the workspace holds), which is slower for small N but
+ *     gives the same result; a variant that names its split (w4a8_gemm_variant) fails with
+ *     LQ_ERR_WORKSPACE instead. */
 size_t w4a8_gemm_workspace_size(int M, int N, int K, int group);
 
 /* Enqueue the zeroing of a workspace's ticket area on `hip_stream` (a small fill kernel; safe

@@ -114,6 +114,7 @@ struct SoloGrouped {
     const GroupTable &g;
     const GroupedPtrs &p;
     int N, K, blocks_n;
+    __device__ __forceinline__ int slices() const { return 1; }
     __device__ __forceinline__ int tiles() const { return g.block_end[g.count - 1]; }
     __device__ __forceinline__ SoloTile tile(int lid, int G) const
     {
@@ -127,6 +128,7 @@ struct SoloGrouped {
         return SoloTile{M,
                         bm,
                         bn,
+                        0,
                         p.X + (size_t)r0 * K,
                         p.sx + r0,
                         p.Wp + e * p.w_stride,

@@ -29,9 +29,10 @@
 // (drained) LDS ring and each finishes four of the eight row fragments.  Tiles are separate
 // there: the pipeline drains and refills between them.
 // ------------------------------------------------------------------------------------
-// One tile of a launch: rows bm * 256 .. of a matrix of M rows, channels bn * (256 / KG) ..
+// One tile of a launch: rows bm * 256 .. of a matrix of M rows, channels bn * (256 / KG) ..,
+// and of K slice ks (0 where K is not split across blocks)
 struct SoloTile {
-    int M, bm, bn;
+    int M, bm, bn, ks;
     const int8_t *X;
     const float *sx;
     const u32x4 *Wp;
@@ -57,9 +58,12 @@ __device__ __forceinline__ void solo_coords(int lid, int blocks_m, int blocks_n,
     bm = first + in_group % gsz;
     bn = in_group / gsz;
 }
-// The tiles of one GEMM.
+// The tiles of one GEMM.  With S > 1 every tile is computed in S equal K slices by S blocks,
+// slice ks writing its INT32 partial sums to matrix ks of ACC ([S][M][N]; Y is null then) for
+// splitk_finish_kernel to add up: the form for outputs with too few tiles for the chip
+// (Sec. 3.2: the batch sizes between the memory-bound and the compute-bound regime).
 struct SoloDense {
-    int M;
+    int M, N;
     const int8_t *X;
     const float *sx;
     const u32x4 *Wp;
@@ -67,13 +71,17 @@ struct SoloDense {
     const float *sw;
     __half *Y;
     int32_t *ACC;
-    int blocks_m, blocks_n;
-    __device__ __forceinline__ int tiles() const { return blocks_m * blocks_n; }
+    int blocks_m, blocks_n, S;
+    __device__ __forceinline__ int slices() const { return S; }
+    __device__ __forceinline__ int tiles() const { return blocks_m * blocks_n * S; }
     __device__ __forceinline__ SoloTile tile(int lid, int G) const
     {
         int bm, bn;
-        solo_coords(solo_xcd_order(lid, tiles(), G), blocks_m, blocks_n, bm, bn);
-        return SoloTile{M, bm, bn, X, sx, Wp, gp, sw, Y, ACC};
+        const int per_slice = blocks_m * blocks_n;
+        const int item = solo_xcd_order(lid, tiles(), G);  // an XCD's items: one slice (or part of one) of all tiles
+        const int ks = item / per_slice;
+        solo_coords(item - ks * per_slice, blocks_m, blocks_n, bm, bn);
+        return SoloTile{M, bm, bn, ks, X, sx, Wp, gp, sw, Y, ACC + (size_t)ks * M * N};
     }
 };
 
@@ -91,7 +99,7 @@ __device__ __forceinline__ void solo_body(const Src &src, const int N, const int
     const int grp = KG == 2 ? wave >> 1 : 0;          // KG = 2: the chunk of every stage this wave computes
     const int colw = KG == 2 ? (wave & 1) : wave;     // which 64 channels of the block's 256 / KG
     constexpr int WPB = 4 / KG;                       // 64-channel groups per block
-    const int stages = K >> 7;  // per tile, a multiple of four
+    const int stages = (K >> 7) / src.slices();  // of a tile's K slice, a multiple of four
     const int chunks_per_tile = K >> 6;
     const int tiles = src.tiles(), G = (int)gridDim.x;
 
@@ -99,7 +107,7 @@ __device__ __forceinline__ void solo_body(const Src &src, const int N, const int
     const int ld_r = (lane >> 3) ^ (wave & 1), ld_c = (lane & 7) ^ ld_r;
     int ld_row = 8 * wave + ld_r;
     const size_t wg_stride = (size_t)chunks_per_tile * 1024;
-    const size_t pg_stride = (size_t)stages * 32 * (G128 ? 2 : 4);
+    const size_t pg_stride = (size_t)(K >> 7) * 32 * (G128 ? 2 : 4);
     uint32_t wl = lane * 16;  // (not const: the X loads name it as an operand, see issue_x1)
     const uint32_t pl_off = j * (G128 ? 2 : 4);
     const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) void *)lds;
@@ -118,9 +126,10 @@ __device__ __forceinline__ void solo_body(const Src &src, const int N, const int
 #pragma unroll
         for (int i = 0; i < 8; ++i)
             xg[i] = (uint32_t)min(bm * 256 + 32 * i + ld_row, M - 1) * (uint32_t)K + 16 * ld_c;
-        ld_X = t.X;
-        wbase = reinterpret_cast<const char *>(t.Wp + (size_t)t0 * chunks_per_tile * 64);
-        pbase = reinterpret_cast<const char *>(t.gp) + (size_t)t0 * stages * 32 * (G128 ? 2 : 4);
+        const size_t s0 = (size_t)t.ks * stages;  // first stage of the K slice
+        ld_X = t.X + s0 * 128;
+        wbase = reinterpret_cast<const char *>(t.Wp + (size_t)t0 * chunks_per_tile * 64) + s0 * 2048;
+        pbase = reinterpret_cast<const char *>(t.gp) + (size_t)t0 * pg_stride + s0 * (G128 ? 64 : 128);
     };
     // after the last stage of the block's last tile (KG = 2: of every tile) the load side stays
     // on that stage (the prefetches past the end re-read it; nothing consumes them)
@@ -584,7 +593,34 @@ template <bool G128, int KG = 1>
 __global__ __launch_bounds__(256, 1) void w4a8_solo_pt_kernel(
     int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
-    __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n)
+    __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n, int S)
 {
-    solo_body<G128, KG>(SoloDense{M, X, sx, Wp, gp, sw, Y, ACC, blocks_m, blocks_n}, N, K);
+    solo_body<G128, KG>(SoloDense{M, N, X, sx, Wp, gp, sw, Y, ACC, blocks_m, blocks_n, S}, N, K);
+}
+
+// Adds up the S partial matrices of a launch with K slices and finishes the outputs like the
+// tile epilogue does (Sec. 4: acc * s_x[row] * s_w[channel]).  Four channels per thread.
+__global__ __launch_bounds__(256) void splitk_finish_kernel(
+    const int32_t *__restrict__ part, int S, int M, int N, const float *__restrict__ sx,
+    const float *__restrict__ sw, __half *__restrict__ Y, int32_t *__restrict__ ACC)
+{
+    const size_t quads = (size_t)M * N / 4, MN = (size_t)M * N;
+    const size_t q = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (q >= quads) return;
+    v4i sum = *reinterpret_cast<const v4i *>(part + 4 * q);
+#pragma unroll 4
+    for (int s = 1; s < S; ++s) {
+        const v4i v = *reinterpret_cast<const v4i *>(part + (size_t)s * MN + 4 * q);
+        sum[0] += v[0], sum[1] += v[1], sum[2] += v[2], sum[3] += v[3];
+    }
+    if (ACC) *reinterpret_cast<v4i *>(ACC + 4 * q) = sum;
+    if (Y) {
+        const int m = (int)(4 * q / N), n = (int)(4 * q - (size_t)m * N);
+        const float a = sx[m];
+        const float4 w = *reinterpret_cast<const float4 *>(sw + n);
+        uint2 out;
+        out.x = scale_pair_to_half2((float)sum[0] * a, w.x, (float)sum[1] * a, w.y);
+        out.y = scale_pair_to_half2((float)sum[2] * a, w.z, (float)sum[3] * a, w.w);
+        *reinterpret_cast<uint2 *>(Y + 4 * q) = out;
+    }
 }

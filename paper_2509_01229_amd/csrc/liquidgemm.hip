@@ -396,6 +396,7 @@ static int launch_duo_dl(const Args &a)
     return LQ_OK;
 }
 
+constexpr long long kAssumedCUs = 256;  // the shape rules of the dispatcher are written for the MI355X
 // Compute units of the current device (the grid of the persistent kernels), asked once per device.
 static int cu_count()
 {
@@ -445,10 +446,27 @@ static int launch_duo_pt(const Args &a)
 
 // Persistent 256 x 256 tiles, one wave per SIMD (see kernels_tiled_solo.h); KG = 2: 256 x 128
 // tiles with the four waves as two k groups.  Needs K % 512 == 0.
-template <int KG>
+// K slices across blocks for outputs with fewer tiles than CUs: every slice a multiple of 512 k,
+// tiles * slices at most the CUs (one round), the partial sums of a slice as an INT32 matrix of
+// its own in the workspace and a second, streaming kernel that adds them up.  Unlike the ticket
+// scheme of the 128-row kernels nothing here is serial -- but the partial matrices are 4 S M N
+// bytes written and read once, which is why this pays for long K only.  Returns 1 for no split.
+static int solo_split(int tiles, int K, int cus)
+{
+    const int units = K / 512;
+    int best = 1;
+    for (int s = 2; s <= 4 && s <= units && tiles * s <= cus; ++s)  // (more than four: measured behind the 128-row tiles)
+        if (units % s == 0) best = s;
+    return best;
+}
+static size_t solo_ws_bytes(int M, int N, int S)
+{
+    return S <= 1 ? 0 : kTicketBytes + (size_t)S * M * N * sizeof(int32_t);
+}
+// SPLIT: 0 = no K slices, -1 = as many as solo_split gives and the workspace holds, n = exactly n
+template <int KG, int SPLIT = 0>
 static int launch_solo_pt(const Args &a)
 {
-    if (a.query) return LQ_OK;  // no workspace
     if (a.K % 512 != 0) return fail(LQ_ERR_INVALID, "the 256-row tile variants need K %% 512 == 0, got %d", a.K);
     constexpr int TN = 256 / KG;
     const int blocks_n = (a.N + TN - 1) / TN, blocks_m = (a.M + 255) / 256;
@@ -457,16 +475,46 @@ static int launch_solo_pt(const Args &a)
                     (long long)a.M * a.K);
     if (a.N > (1 << 26))  // (a row's lane offsets are 32-bit byte offsets)
         return fail(LQ_ERR_INVALID, "the 256-row tile variants take N up to 2^26, got %d", a.N);
-    const int grid = std::min(blocks_m * blocks_n, std::max(cu_count(), 1));
+    const int cus = std::max(cu_count(), 1);
+    int S = 1;
+    if (SPLIT > 0) {
+        S = SPLIT;
+        if ((a.K / 512) % S != 0)
+            return fail(LQ_ERR_INVALID, "%d K slices need K %% %d == 0, got %d", S, 512 * S, a.K);
+    } else if (SPLIT < 0) {
+        S = solo_split(blocks_m * blocks_n, a.K, a.query ? (int)kAssumedCUs : cus);
+        // (a workspace too small for them: the largest number of slices it holds)
+        // (a query names its limit, if it has one, in ws_bytes)
+        auto too_large = [&](int s) {
+            const size_t need = solo_ws_bytes(a.M, a.N, s);
+            return a.query ? a.ws_bytes > 0 && a.ws_bytes < need : !a.ws || a.ws_bytes < need;
+        };
+        while (S > 1 && too_large(S)) {
+            do --S; while (S > 1 && (a.K / 512) % S != 0);
+        }
+    }
+    const size_t need = solo_ws_bytes(a.M, a.N, S);
+    if (a.query) return *a.query = need, LQ_OK;
+    if (need > 0 && (!a.ws || a.ws_bytes < need))
+        return fail(LQ_ERR_WORKSPACE, "%d K slices need %zu bytes of workspace, got %zu", S, need, a.ws ? a.ws_bytes : 0);
+    int32_t *partials = S > 1 ? reinterpret_cast<int32_t *>(static_cast<char *>(a.ws) + kTicketBytes) : nullptr;
+    const int grid = std::min(blocks_m * blocks_n * S, cus);
     const size_t lds_bytes = 4 * (size_t)256 * 128 + 4 * 1024;  // X stages; two copies of both scales
+    __half *Y = S > 1 ? nullptr : a.Y;
+    int32_t *ACC = S > 1 ? partials : a.ACC;
     if (a.group == 128) {
         if (int rc = allow_lds(w4a8_solo_pt_kernel<true, KG>, lds_bytes)) return rc;
         hipLaunchKernelGGL((w4a8_solo_pt_kernel<true, KG>), dim3((unsigned)grid), dim3(256), lds_bytes, a.stream, a.M,
-                           a.N, a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
+                           a.N, a.K, a.X, a.sx, a.Wp, a.gp, a.sw, Y, ACC, blocks_m, blocks_n, S);
     } else {
         if (int rc = allow_lds(w4a8_solo_pt_kernel<false, KG>, lds_bytes)) return rc;
         hipLaunchKernelGGL((w4a8_solo_pt_kernel<false, KG>), dim3((unsigned)grid), dim3(256), lds_bytes, a.stream, a.M,
-                           a.N, a.K, a.X, a.sx, a.Wp, a.gp, a.sw, a.Y, a.ACC, blocks_m, blocks_n);
+                           a.N, a.K, a.X, a.sx, a.Wp, a.gp, a.sw, Y, ACC, blocks_m, blocks_n, S);
+    }
+    if (S > 1) {
+        const size_t quads = (size_t)a.M * a.N / 4;
+        hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, a.stream, partials,
+                           S, a.M, a.N, a.sx, a.sw, a.Y, a.ACC);
     }
     return LQ_OK;
 }
@@ -572,6 +620,8 @@ static const Variant kVariants[] = {
     {"duo_pt_m128", &launch_duo_pt, 0, 1, 8, 512},
     {"solo_pt_m256", &launch_solo_pt<1>, 0, 1, 8, 512},
     {"solo_g2_m256", &launch_solo_pt<2>, 0, 1, 8, 512},
+    {"solo_sk_m256", &launch_solo_pt<1, -1>, 0, 1, 8, 512},
+    {"solo_g2_sk_m256", &launch_solo_pt<2, -1>, 0, 1, 8, 512},
     // --- the same kernels with a named number of K slices: the split paths at sizes where the
     //     dispatcher would not split (parity tests) ---
     {"stream16_f2_w8_s2", &launch_stream16<2, 8, 2>, 16, 2, 1},
@@ -585,6 +635,8 @@ static const Variant kVariants[] = {
     {"duo_m128_s2", &launch_duo<2, 1>, 0, 1, 1},
     {"duo_m128_g2_s2", &launch_duo<2, 2>, 0, 1, 1},
     {"duo_dl_m128_s2", &launch_duo_dl<2>, 0, 1, 1},
+    {"solo_pt_m256_s2", &launch_solo_pt<1, 2>, 256, 1, 16, 1024},
+    {"solo_g2_m256_s4", &launch_solo_pt<2, 4>, 256, 1, 32, 2048},
     // --- ablation forms (Sec. 7.3), measured by the benchmark, never dispatched ---
     {"excp_m128", &launch_excp, 0, 1, 1},
     {"widened_dq_m128", &launch_duo_widened, 0, 1, 1},
@@ -612,7 +664,6 @@ static int find_variant(const char *name)
 // but they run one block per CU, in whole rounds, and rows past M in a 256-row tile are lost.
 // Costs in units of one 128 x 256 tile's time on a CU, from the numbers of tiles of each form;
 // returns 1 for 256 x 256, 2 for 256 x 128, 0 for neither.
-constexpr long long kAssumedCUs = 256;  // the shape rules of the dispatcher are written for the MI355X
 struct TiledCosts {
     double duo, solo, g2;
     double best() const { return std::min(duo, std::min(solo, g2)); }
@@ -621,16 +672,23 @@ static TiledCosts tiled_costs(long long t128, long long t256, long long t2, int 
 {
     if (K % 512 != 0) return TiledCosts{1.0, 1e30, 1e30};
     // two resident blocks per CU (block b and b + 256 land on one CU) walk tiles b, b + 512, ...
-    // (up to one tile per CU they split K across blocks to fill the chip, at about a tenth more)
+    // Up to one tile per CU the cost is not proportional to the tiles: a partly filled chip clocks
+    // higher, and up to 128 tiles K slices across blocks fill it -- measured on N = K = 8192, in
+    // units of a full round: 0.44 at 64 tiles, 0.67 at 128, then 0.79 / 0.81 / 0.87 at 144 / 160 / 192.
     const long long rem = t128 % (2 * kAssumedCUs);
-    const double duo = t128 <= kAssumedCUs ? std::max(0.25, (double)t128 / kAssumedCUs * (8 * t128 > 7 * kAssumedCUs ? 1.0 : 1.1))
+    const double fill = (double)t128 / kAssumedCUs;
+    const double duo = t128 <= kAssumedCUs ? (2 * t128 <= kAssumedCUs ? 0.26 + 0.74 * fill : 0.55 + 0.45 * fill)
                                            : 2.0 * (t128 / (2 * kAssumedCUs)) + (rem > 0) + (rem > kAssumedCUs);
     const double short_k = K >= 4096 ? 1.0 : 1.06;  // (their longer epilogue weighs more)
     // (a round of 256 x 256 tiles that leaves CUs idle still runs at this cost: 160 tiles took 82.6 us
     // against 97 to 101 us of the 128-row forms on 1024 x 10240 x 8192; the 256 x 128 form pays only
-    // as one round that nearly fills the chip -- its tiles are separate, a second round costs a tenth more)
+    // as one round -- its tiles are separate, a second round costs a tenth more -- of more than half
+    // the CUs: 45 / 48 / 54 / 62 us at 128 / 160 / 192 / 256 tiles on K = 8192, against 45 / 55 / 58 /
+    // 67 us of the 128-row tiles)
     const double solo = 2.0 * ((t256 + kAssumedCUs - 1) / kAssumedCUs) * 0.86 * short_k;
-    const double g2 = 4 * t2 >= 3 * kAssumedCUs && t2 <= kAssumedCUs ? 0.96 * short_k : 1e30;
+    const double g2 = 16 * t2 > 8.5 * kAssumedCUs && t2 <= kAssumedCUs
+                          ? 0.96 * (0.36 + 0.64 * t2 / kAssumedCUs) * short_k
+                          : 1e30;
     return TiledCosts{duo, solo, g2};
 }
 static TiledCosts tiled_costs(int M, int N, int K)
@@ -694,6 +752,17 @@ static int select_variant(int M, int N, int K)
         return find_variant("stream_m64");
     // 256-row tiles with one wave per SIMD where their whole rounds come out ahead
     if (const int form = solo_form_that_pays(M, N, K)) return find_variant(form == 1 ? "solo_pt_m256" : "solo_g2_m256");
+    // ... and, with very long K and row tiles that are nearly full, their 256 x 128 form with K
+    // slices across blocks where tiles x slices come to one round of at least three quarters of the
+    // CUs (256 x 8192 x 28672: 65 against 70 us; 512 rows: 114 against 121; 256 x 6144 x 16384: 37
+    // against 40; shorter K or emptier rounds: equal or behind -- the partial sums are a matrix per slice)
+    if (K >= 16384 && K % 512 == 0 && (M % 256 == 0 || M % 256 > 192)) {
+        const long long t2 = (long long)((M + 255) / 256) * ((N + 127) / 128);
+        if (t2 <= kAssumedCUs / 2) {
+            const int slices = solo_split((int)t2, K, (int)kAssumedCUs);
+            if (slices > 1 && 4 * t2 * slices >= 3 * kAssumedCUs) return find_variant("solo_g2_sk_m256");
+        }
+    }
     // more 128 x 256 tiles than CUs (blocks of one k group): the deeper memory pipeline of the
     // direct-to-LDS form pays (3 to 6 % measured from 320 tiles up, 1 to 5 % at 264..288); with
     // one tile per CU or fewer, the two k groups per block of the other form do
@@ -1012,6 +1081,13 @@ size_t w4a8_gemm_workspace_size(int M, int N, int K, int group)
     if (M <= 32) need = std::max(need, stream_ws_bytes(M, N, 16));
     if (M <= 64) need = std::max(need, stream_ws_bytes(M, N, 16, 2));
     if (M <= 16) need = std::max(need, kTicketBytes + (size_t)16 * (N / 32) * 8 * 64 * sizeof(int32_t));
+    if (K % 512 == 0) {
+        // the 256-row tiles with K slices: a whole INT32 matrix per slice, at most one round of blocks
+        // (up to 256 rows also the variants with a named number of slices)
+        const long long t256 = (long long)((M + 255) / 256) * ((N + 255) / 256);
+        const int s = M <= 256 ? 4 : (int)std::min<long long>(4, kAssumedCUs / t256);
+        need = std::max(need, solo_ws_bytes(M, N, s));
+    }
     return need;
 }
 
@@ -1046,11 +1122,14 @@ int w4a8_gemm_static(int M, int N, int K, int group, const int8_t *X, const floa
     if (!Y && M != 0) return fail(LQ_ERR_INVALID, "null Y");
     Args a{M, N, K, group, X, act_scales, static_cast<const u32x4 *>(W_packed), gparams, w_scales,
            reinterpret_cast<__half *>(Y), nullptr, static_cast<hipStream_t>(hip_stream), nullptr, 0};
-    // what the dispatcher's kernel for this shape would use of a workspace (nothing is launched)
+    // what the dispatcher's kernel for this shape would use of a workspace (nothing is launched;
+    // a launcher that can make do with fewer K slices is told how much there is)
     size_t need = 0;
     a.query = &need;
+    a.ws_bytes = kStaticScratchBytes;
     if (int rc = run(-1, a)) return rc;
     a.query = nullptr;
+    a.ws_bytes = 0;
     if (M == 0) return LQ_OK;
     if (need > kStaticScratchBytes)
         return fail(LQ_ERR_WORKSPACE,

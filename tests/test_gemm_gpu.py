@@ -522,6 +522,63 @@ def test_persistent_tile_kernel(M, N, K, g, kernel):
     assert np.array_equal(ACC2.cpu().numpy().astype(np.int64), ref), "accumulator-only call differs"
 
 
+@pytest.mark.parametrize("kernel", ["solo_sk_m256", "solo_g2_sk_m256", "solo_pt_m256_s2", "solo_g2_m256_s4"])
+@pytest.mark.parametrize("M,N,K,g", [(300, 640, 2048, 64), (256, 1024, 4608, 128), (520, 320, 1024, 64),
+                                     (200, 448, 4096, 128)])
+def test_solo_k_slices(M, N, K, g, kernel):
+    """The 256-row tile kernels with K slices across blocks (every slice writes an INT32 matrix of
+    partial sums, a second kernel adds them up and scales): slice counts of 2, 3 and 4, ragged row
+    tiles, an N tail, blocks that walk several (tile, slice) items.  Every accumulator and every
+    FP16 output against the exact float64 product of the oracle's weights; then the accumulators
+    alone (no scales passed)."""
+    import torch
+
+    names = api.w4a8_variant_names()
+    v = names.index(kernel)
+    if not api.w4a8_variant_supports(v, M, N, K, g):
+        pytest.skip(f"{kernel} does not take M={M} K={K}")
+    _say(f"K slices {kernel} M={M} N={N} K={K} g={g}")
+    P = H.Problem(N, K, g, seed=M + 11)
+    Wd, s_w = P.oracle_wd()
+    X, s_x = I.make_activations(M, K, outlier_frac=0.01, seed=M + N)
+    ref = (X.astype(np.float64) @ Wd.astype(np.float64).T).astype(np.int64)
+    for rep in range(2):    # the second call finds the first one's partial sums in the workspace
+        Y, ACC = P.run(X, s_x, variant=v)
+        assert np.array_equal(ACC.astype(np.int64), ref), f"call {rep}: {np.count_nonzero(ACC != ref)} accumulators differ"
+        H.assert_fp16_close(Y, O.scale_epilogue_f64(ref, s_x, s_w), "K slices")
+    _, ACC2 = api.w4a8_gemm_variant(v, torch.from_numpy(X).cuda(), None, P.d_packed, P.d_gparams, None, N, K, g,
+                                    want_y=False)
+    torch.cuda.synchronize()
+    assert np.array_equal(ACC2.cpu().numpy().astype(np.int64), ref), "accumulator-only call differs"
+
+
+def test_k_slices_through_the_dispatcher():
+    """A shape the dispatcher runs with K slices across blocks (very long K, one row tile):
+    the public entry points with the workspace the library asks for, then with one that holds
+    fewer slices and with none at all -- the launcher takes what fits."""
+    import torch
+
+    M, N, K, g = 250, 6144, 16384, 128
+    assert api.w4a8_variant_name(api.w4a8_select_variant(M, N, K, g)) == "solo_g2_sk_m256"
+    need = api.w4a8_gemm_workspace_size(M, N, K, g)
+    assert need >= 4 * M * N * 4
+    _say(f"K slices through the dispatcher M={M} N={N} K={K} g={g}, workspace {need} bytes")
+    P = H.Problem(N, K, g, seed=21)
+    Wd, s_w = P.oracle_wd()
+    X, s_x = I.make_activations(M, K, outlier_frac=0.01, seed=22)
+    ref = X.astype(np.float64) @ Wd.astype(np.float64).T
+    ref_y = O.scale_epilogue_f64(ref, s_x, s_w)
+    dX, dsx = torch.from_numpy(X).cuda(), torch.from_numpy(s_x).cuda()
+    for ws_bytes in (need, 32768 + 2 * M * N * 4 + 4096, 32768, 0):
+        _say(f"  workspace of {ws_bytes} bytes")
+        ws = torch.zeros(ws_bytes, dtype=torch.uint8, device="cuda")
+        Y = api.w4a8_gemm(dX, dsx, P.d_packed, P.d_gparams, P.d_w_scales, N, K, g, workspace=ws)
+        ACC = api.w4a8_gemm_i32(dX, P.d_packed, P.d_gparams, N, K, g, workspace=ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(ACC.cpu().numpy().astype(np.float64), ref), "accumulators differ"
+        H.assert_fp16_close(Y.cpu().numpy(), ref_y, "K slices through the dispatcher")
+
+
 @pytest.mark.parametrize("M,N,K,g", [(2048 + 100, 8192, 4096, 64), (4096 + 40, 8192, 2048, 128), (1024 + 30, 16384, 4096, 128)])
 def test_two_launch_plans(M, N, K, g):
     """Batches that the dispatcher runs as two launches over consecutive rows (whole rounds of

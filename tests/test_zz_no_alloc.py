@@ -25,9 +25,11 @@ def test_static_workspace_entry_point_matches_w4a8_gemm():
 
     if not torch.cuda.is_available():
         pytest.skip("needs a GPU")
-    # tiled kernel with K slices, then the 64-row and 16-row stream kernels with K slices
-    # (smaller each time), then a shape that uses no workspace at all
-    cases = [(200, 1024, 4096, 128), (48, 4096, 2048, 64), (8, 1024, 8192, 64), (4096 + 40, 512, 512, 64)]
+    # 256-row tiles with K slices (a matrix of partial sums per slice: nearly all of the built-in
+    # workspace), the 128-row tiled kernel with K slices, then the 64-row and 16-row stream kernels
+    # with K slices (smaller each time), then a shape that uses no workspace at all
+    cases = [(256, 6144, 16384, 128), (200, 1024, 4096, 128), (48, 4096, 2048, 64), (8, 1024, 8192, 64),
+             (4096 + 40, 512, 512, 64)]
     for M, N, K, g in cases:
         picked = api.w4a8_variant_name(api.w4a8_select_variant(M, N, K, g))
         need = api.w4a8_gemm_workspace_size(M, N, K, g)
