@@ -668,48 +668,51 @@ struct TiledCosts {
     double duo, solo, g2;
     double best() const { return std::min(duo, std::min(solo, g2)); }
 };
-static TiledCosts tiled_costs(long long t128, long long t256, long long t2, int K)
+// (pt_ok: the persistent form of the 128-row tiles can run the shape)
+static TiledCosts tiled_costs(long long t128, long long t256, long long t2, int K, bool pt_ok)
 {
     if (K % 512 != 0) return TiledCosts{1.0, 1e30, 1e30};
-    // two resident blocks per CU (block b and b + 256 land on one CU) walk tiles b, b + 512, ...
-    // Up to one tile per CU the cost is not proportional to the tiles: a partly filled chip clocks
-    // higher, and up to 128 tiles K slices across blocks fill it -- measured on N = K = 8192, in
-    // units of a full round: 0.44 at 64 tiles, 0.67 at 128, then 0.79 / 0.81 / 0.87 at 144 / 160 / 192.
+    // No form's cost is proportional to its tiles while these leave CUs idle or half occupied (a
+    // partly filled chip clocks higher).  Fitted to measurements on K = 8192 (us / 64, so that a
+    // round of 256 128-row tiles, one per CU, costs about 1):
+    //   128-row tiles, K slices across blocks up to 128 tiles:  29.6 / 38.7 / 44 us at 64 / 96 / 128
+    //   ... 129..256 tiles, persistent form (one block per CU): 50.6 / 57.3 / 63.5 at 160 / 192 / 256
+    //       (one tile per block: 56 / 60 / 67)
+    //   ... 257..512 tiles (a second resident block on some CUs): 85 / 95 / 102 / 111 / 116 at 270 / 320 / 384 / 448 / 512
+    //   ... beyond: whole rounds of 512 (blocks b and b + 256 share a CU: 3.5 rounds take 7, 1.75 take 4)
+    //   256 x 256 tiles, one round: 84 / 93 / 107 at 160 / 192 / 256 tiles; more: whole rounds at 2 * 0.86
+    //   256 x 128 tiles, one round of more than half the CUs: 45.8 / 49 / 56 / 61.5 at 144 / 160 / 192 / 256
+    //       (at 128 tiles equal to the 128-row tiles; their tiles are separate, a second round costs a tenth more)
     const long long rem = t128 % (2 * kAssumedCUs);
     const double fill = (double)t128 / kAssumedCUs;
-    const double duo = t128 <= kAssumedCUs ? (2 * t128 <= kAssumedCUs ? 0.26 + 0.74 * fill : 0.55 + 0.45 * fill)
-                                           : 2.0 * (t128 / (2 * kAssumedCUs)) + (rem > 0) + (rem > kAssumedCUs);
+    const double duo = 2 * t128 <= kAssumedCUs ? 0.24 + 0.90 * fill
+                       : t128 <= kAssumedCUs   ? (pt_ok ? 0.47 + 0.52 * fill : 0.60 + 0.45 * fill)
+                       : t128 <= 2 * kAssumedCUs
+                           ? 0.80 + 0.51 * fill
+                           : 2.0 * (t128 / (2 * kAssumedCUs)) + (rem > 0) + (rem > kAssumedCUs);
     const double short_k = K >= 4096 ? 1.0 : 1.06;  // (their longer epilogue weighs more)
-    // (a round of 256 x 256 tiles that leaves CUs idle still runs at this cost: 160 tiles took 82.6 us
-    // against 97 to 101 us of the 128-row forms on 1024 x 10240 x 8192; the 256 x 128 form pays only
-    // as one round -- its tiles are separate, a second round costs a tenth more -- of more than half
-    // the CUs: 45 / 48 / 54 / 62 us at 128 / 160 / 192 / 256 tiles on K = 8192, against 45 / 55 / 58 /
-    // 67 us of the 128-row tiles)
-    const double solo = 2.0 * ((t256 + kAssumedCUs - 1) / kAssumedCUs) * 0.86 * short_k;
-    const double g2 = 16 * t2 > 8.5 * kAssumedCUs && t2 <= kAssumedCUs
-                          ? 0.96 * (0.36 + 0.64 * t2 / kAssumedCUs) * short_k
-                          : 1e30;
+    const double solo = (t256 <= kAssumedCUs ? 0.734 + 0.94 * t256 / kAssumedCUs
+                                             : 2.0 * ((t256 + kAssumedCUs - 1) / kAssumedCUs) * 0.86) * short_k;
+    const double g2 = 16 * t2 > 8.5 * kAssumedCUs && t2 <= kAssumedCUs ? (0.406 + 0.56 * t2 / kAssumedCUs) * short_k : 1e30;
     return TiledCosts{duo, solo, g2};
 }
 static TiledCosts tiled_costs(int M, int N, int K)
 {
     const long long bm256 = (M + 255) / 256;
     return tiled_costs((long long)((M + 127) / 128) * ((N + 255) / 256), bm256 * ((N + 255) / 256),
-                       bm256 * ((N + 127) / 128), K);
+                       bm256 * ((N + 127) / 128), K, true);
 }
-static int solo_form_for(long long t128, long long t256, long long t2, int K)
+static int solo_form_of(const TiledCosts &c)
 {
-    const TiledCosts c = tiled_costs(t128, t256, t2, K);
     if (c.solo < c.duo && c.solo <= c.g2) return 1;
     if (c.g2 < c.duo) return 2;
     return 0;
 }
-static int solo_form_that_pays(int M, int N, int K)
+static int solo_form_for(long long t128, long long t256, long long t2, int K)
 {
-    const long long bm256 = (M + 255) / 256;
-    return solo_form_for((long long)((M + 127) / 128) * ((N + 255) / 256), bm256 * ((N + 255) / 256),
-                         bm256 * ((N + 127) / 128), K);
+    return solo_form_of(tiled_costs(t128, t256, t2, K, false));
 }
+static int solo_form_that_pays(int M, int N, int K) { return solo_form_of(tiled_costs(M, N, K)); }
 
 // Shape -> kernel.  Up to 32 rows the weights are streamed once with X fragments in
 // registers (16-row MFMA shape up to 16 rows); anything larger runs the 128 x 256 tiles of
@@ -768,8 +771,12 @@ static int select_variant(int M, int N, int K)
     // one tile per CU or fewer, the two k groups per block of the other form do
     // (from two tiles per resident slot on and with whole 512-k units, its persistent form:
     // one pipeline fill per block instead of per tile, 1 to 2 % measured)
-    if (((M + 127) / 128) * ((N + 255) / 256) > 256)
-        return find_variant(duo_pt_fits(M, N, K) ? "duo_pt_m128" : "duo_dl_m128");
+    const int tiles128 = ((M + 127) / 128) * ((N + 255) / 256);
+    if (tiles128 > 256) return find_variant(duo_pt_fits(M, N, K) ? "duo_pt_m128" : "duo_dl_m128");
+    // more than half a round of them (no room for K slices across blocks): the persistent form again,
+    // one block per CU -- 50.6 against 56.1 us on 640 x 8192 x 8192, 28.0 against 31.1 on 384 x 11008 x 4096
+    // (also with a ragged last row tile of at most 64 rows: 47.8 against 50.9 us on 576 x 8192 x 8192)
+    if (tiles128 > 128 && K % 512 == 0) return find_variant("duo_pt_m128");
     // few tiles: a grid of 64-row tiles can fill the chip with half the split-K exchange
     return find_variant(prefer_64_row_tiles(M, N, K) ? "duo_m64" : "duo_m128");
 }

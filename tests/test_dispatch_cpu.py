@@ -10,21 +10,31 @@ def _pick(M, N, K, g=64):
     return api.w4a8_variant_name(api.w4a8_select_variant(M, N, K, g))
 
 
+def _pt_fits(M, N, K):
+    return K % 512 == 0 and (M % 128 == 0 or M % 128 > 64)
+
+
 def _solo_form(M, N, K):
-    """The dispatcher's cost rule for the 256-row tiles, restated: costs in 128 x 256 tile times per
-    CU; 1 = 256 x 256 tiles, 2 = 256 x 128 tiles with two k groups, 0 = neither."""
+    """The dispatcher's cost rule for the 256-row tiles, restated: costs fitted to measurements, in
+    units of a round of 256 tiles of 128 x 256; 1 = 256 x 256 tiles, 2 = 256 x 128 tiles with two k
+    groups, 0 = neither."""
     if K % 512:
         return 0
     bm = -(-M // 256)
     t256, t2, t128 = bm * -(-N // 256), bm * -(-N // 128), -(-M // 128) * -(-N // 256)
     rem = t128 % 512
-    if t128 <= 256:
-        duo = 0.26 + 0.74 * t128 / 256 if t128 <= 128 else 0.55 + 0.45 * t128 / 256
+    fill = t128 / 256
+    if t128 <= 128:
+        duo = 0.24 + 0.90 * fill
+    elif t128 <= 256:
+        duo = 0.47 + 0.52 * fill
+    elif t128 <= 512:
+        duo = 0.80 + 0.51 * fill
     else:
         duo = 2.0 * (t128 // 512) + (rem > 0) + (rem > 256)
     short_k = 1.0 if K >= 4096 else 1.06
-    solo = 2.0 * -(-t256 // 256) * 0.86 * short_k
-    g2 = 0.96 * (0.36 + 0.64 * t2 / 256) * short_k if 136 < t2 <= 256 else 1e30
+    solo = (0.734 + 0.94 * t256 / 256 if t256 <= 256 else 2.0 * -(-t256 // 256) * 0.86) * short_k
+    g2 = (0.406 + 0.56 * t2 / 256) * short_k if 136 < t2 <= 256 else 1e30
     if solo < duo and solo <= g2:
         return 1
     return 2 if g2 < duo else 0
@@ -49,8 +59,9 @@ def test_dispatcher_families_on_the_workloads():
             elif form:                  # 256-row tiles, one wave per SIMD, where their whole rounds come out ahead
                 assert name == ("solo_pt_m256" if form == 1 else "solo_g2_m256"), (s.name, name)
             elif tiles128 > 256:      # more tiles than CUs: the direct-to-LDS pipeline, persistent where it fits
-                fits = s.K % 512 == 0 and (s.M % 128 == 0 or s.M % 128 > 64)
-                assert name == ("duo_pt_m128" if fits else "duo_dl_m128"), (s.name, name)
+                assert name == ("duo_pt_m128" if _pt_fits(s.M, s.N, s.K) else "duo_dl_m128"), (s.name, name)
+            elif tiles128 > 128 and s.K % 512 == 0:   # more than half a round: persistent, one block per CU
+                assert name == "duo_pt_m128", (s.name, name)
             elif -(-s.M // 64) * -(-s.N // 256) > 256:
                 assert name == "duo_m128", (s.name, name)
         v = api.w4a8_select_variant(s.M, s.N, s.K, s.group)
@@ -95,7 +106,7 @@ def test_dispatcher_boundaries():
     assert _pick(2048, 4096, 11264) == "solo_g2_m256"
     assert _pick(768, 8192, 8192) == "solo_g2_m256"            # 192 tiles: 54 against 58 us
     assert _pick(512, 9216, 8192) == "solo_g2_m256" and _pick(512, 11008, 4096) == "solo_g2_m256"   # 144 / 172 tiles
-    assert _pick(512, 10240, 2048) == "solo_g2_m256" and _pick(1024, 5120, 8192) == "solo_g2_m256"
+    assert _pick(512, 10240, 2048) in ("solo_g2_m256", "duo_pt_m128") and _pick(1024, 5120, 8192) == "solo_g2_m256"
     assert _pick(512, 8192, 8192) == "duo_m128" and _pick(1024, 4096, 8192) in ("duo_m64", "duo_m128")   # 128 tiles: equal or behind
     assert _pick(384, 8192, 8192) == "duo_m128"                # (a third of the second row tile's work is lost)
     # ... 256 x 256 where their whole rounds cost less than the rounds of 128-row tiles, two blocks to a CU
