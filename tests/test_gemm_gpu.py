@@ -388,7 +388,8 @@ def test_hip_graph_replays_of_split_k_kernels():
     reproduce the eager result."""
     import torch
 
-    cases = [(8, 2048, 4096, 64), (48, 4096, 2048, 64), (200, 1024, 4096, 128)]   # stream16 / stream_m64 / duo_m64
+    # stream16 / stream_m64 / duo_m64 / 256-row tiles with K slices and their finish kernel
+    cases = [(8, 2048, 4096, 64), (48, 4096, 2048, 64), (200, 1024, 4096, 128), (256, 6144, 16384, 128)]
     stream = torch.cuda.Stream()
     for M, N, K, g in cases:
         picked = api.w4a8_variant_name(api.w4a8_select_variant(M, N, K, g))
