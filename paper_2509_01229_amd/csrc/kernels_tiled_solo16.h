@@ -1,0 +1,406 @@
+// solo16 kernel: the persistent 256 x 256 tiles of the solo kernel on the 16x16x64 MFMA.
+// (part of liquidgemm.hip: included there, inside namespace lqq, after kernels_tiled_solo.h)
+#pragma once
+
+// ------------------------------------------------------------------------------------
+// Under operands that change from one MFMA to the next this chip is bound by its power, not by
+// its matrix pipes, and the two INT8 MFMA shapes differ there: a loop of v_mfma_i32_16x16x64_i8
+// on random bytes sustains 4.2 POP/s where v_mfma_i32_32x32x32_i8 sustains 3.5 (the small shape
+// moves half the accumulator registers per operation).  This is the solo kernel (one wave per
+// SIMD, wave tile 256 x 64, 256 accumulator registers, every dequantised operand reused by all
+// 256 rows; paper Sec. 3.2, Eq. 6: T_DQ per MMA shrinks with that reuse) with the small shape:
+//   * a k-step is one chunk of 64 k: 64 MFMAs, token fragment i / 4 (16 rows) times channel
+//     fragment i % 4 (16 channels);
+//   * the channel operands of a chunk come from the same two 16-byte lane loads as before: the
+//     low and the high nibbles are dequantised as for the 32x32x32 order (Sec. 5.3, 7
+//     instructions per 8 codes) and one v_permlane16_swap per register regroups them into the
+//     operands of two 16-channel fragments (regroup_16x16), k blocks in the order 0, 2, 1, 3,
+//     which the token fragments are read in as well (kstep16_offset);
+//   * the weights are the MFMA's first operand, so that a lane receives four consecutive slots
+//     of a tile for one token: with the even and the odd channels of the two tiles of a
+//     64-channel group, 8 consecutive channels, stored as one 16-byte piece of FP16.
+// Load side, LDS ring, scale staging and tile walk are those of solo_body (KG = 1).
+// ------------------------------------------------------------------------------------
+// f(integral_constant<int, B>), ..., f(integral_constant<int, E - 1>): the 64 slots of a k-step are
+// written out this way -- a loop of that size is past what the compiler unrolls on request, and
+// accumulators indexed by a loop counter would live in memory
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        static_for<B + 1, E>(f);
+    }
+}
+
+template <bool G128, class Src>
+__device__ __forceinline__ void solo16_body(const Src &src, const int N, const int K)
+{
+    constexpr int TF = 16;  // token fragments of 16 rows per wave
+    constexpr int STAGE = 256 * 128;
+    constexpr int PER_STAGE = 14;  // loads of one stage: 8 of X, 4 of codes, 2 of parameters
+    extern __shared__ __attribute__((aligned(16))) int8_t lds[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int j = lane & 31;
+    const int j16 = lane & 15, kq = lane >> 4;
+    const int stages = (K >> 7) / src.slices();  // of a tile's K slice, a multiple of four
+    const int chunks_per_tile = K >> 6;
+    const int tiles = src.tiles(), G = (int)gridDim.x;
+
+    // ---- load side (as in solo_body): the tile whose stages are being prefetched ------------
+    const int ld_r = (lane >> 3) ^ (wave & 1), ld_c = (lane & 7) ^ ld_r;
+    int ld_row = 8 * wave + ld_r;
+    const size_t wg_stride = (size_t)chunks_per_tile * 1024;
+    const size_t pg_stride = (size_t)(K >> 7) * 32 * (G128 ? 2 : 4);
+    uint32_t wl = lane * 16;  // (not const: the X loads name it as an operand, see issue_x1)
+    const uint32_t pl_off = j * (G128 ? 2 : 4);
+    const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) void *)lds;
+    int l_lid = (int)blockIdx.x, l_s = 0;  // tile and stage the next prefetch takes
+    uint32_t xg[8];
+    const char *wbase, *pbase;
+    const int8_t *ld_X;
+    auto load_side_tile = [&](int lid) {
+        const SoloTile t = src.tile(lid, G);
+        const int bm = t.bm, M = t.M;
+        const int ng = t.bn * 4 + wave;
+        const int t0 = 2 * min(ng, (N >> 6) - 1);
+        asm volatile("" : "+v"(ld_row));
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            xg[i] = (uint32_t)min(bm * 256 + 32 * i + ld_row, M - 1) * (uint32_t)K + 16 * ld_c;
+        const size_t s0 = (size_t)t.ks * stages;  // first stage of the K slice
+        ld_X = t.X + s0 * 128;
+        wbase = reinterpret_cast<const char *>(t.Wp + (size_t)t0 * chunks_per_tile * 64) + s0 * 2048;
+        pbase = reinterpret_cast<const char *>(t.gp) + (size_t)t0 * pg_stride + s0 * (G128 ? 64 : 128);
+    };
+    auto load_side_advance = [&] {
+        if (++l_s == stages) {
+            asm volatile("" ::: "memory");
+            if (l_lid + G < tiles) {
+                l_lid += G;
+                l_s = 0;
+                load_side_tile(l_lid);
+            } else {
+                l_s = stages - 1;
+            }
+        }
+    };
+    auto issue_x1 = [&](int buf, int i) {
+        asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     : "+v"(wl)
+                     : "v"(xg[i]), "s"(ld_X + (size_t)l_s * 128), "s"(lds0 + buf * STAGE + (4 * i + wave) * 1024)
+                     : "memory", "m0");
+    };
+    // piece 0, 1 = the codes of the stage's chunk 0, 1 of channel tile t, piece 2 = its group parameters
+    auto load_w_piece = [&](int t, int piece, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
+        if (piece < 2) {
+            const char *wb = wbase + t * wg_stride + (size_t)l_s * 2048 + piece * 1024;
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "=&v"(w[t][piece]) : "v"(wl), "s"(wb) : "memory");
+        } else {
+            const char *pb = pbase + t * pg_stride + (size_t)l_s * (G128 ? 64 : 128);
+            if (G128)
+                asm volatile("global_load_ushort %0, %1, %2" : "=&v"(p[t].raw) : "v"(pl_off), "s"(pb) : "memory");
+            else
+                asm volatile("global_load_dword %0, %1, %2" : "=&v"(p[t].raw) : "v"(pl_off), "s"(pb) : "memory");
+        }
+    };
+    auto arrive_w = [&](auto pending_tag, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
+        asm volatile("s_waitcnt vmcnt(%6)"
+                     : "+v"(w[0][0]), "+v"(w[0][1]), "+v"(w[1][0]), "+v"(w[1][1]), "+v"(p[0].raw), "+v"(p[1].raw)
+                     : "n"(decltype(pending_tag)::value)
+                     : "memory");
+    };
+
+    // ---- compute side ------------------------------------------------------------------------
+    // acc[tf][2 t + h]: tokens 16 tf .. + 15 x slots 16 h .. + 15 of channel tile t; element v of
+    // lane l = slot 16 h + 4 (l / 16) + v, token 16 tf + l % 16
+    v4i acc[TF][4];
+    auto clear_acc = [&] {
+        static_for<0, 4 * TF>([&](auto i_tag) {
+            constexpr int i = decltype(i_tag)::value;
+            acc[i >> 2][i & 3] = v4i{0, 0, 0, 0};
+            // (each in its own registers from the start: one zero shared by all of them would need
+            // registers beyond the 256 the accumulators fill)
+            asm volatile("" : "+a"(acc[i >> 2][i & 3]));
+        });
+    };
+    clear_acc();
+    asm volatile("s_nop 3" ::: "memory");  // (accumulation registers written by moves: wait states before an MFMA reads them)
+    auto acc_elem = [&](int tf, int f, int v) {
+        int x;
+        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(acc[tf][f][v]));
+        return x;
+    };
+    u32x4 wr[4][2][2];  // [stage mod 4][tile][chunk]
+    UnitParams<G128> pr[4][2];
+    v4i bw[2][4];  // channel operands of the running and of the next k-step
+    v4i ax[8];     // token fragments: fragment tf in ax[tf % 8]
+    uint32_t s2v, a4v;
+    uint32_t lo[4], hi[4];  // one tile's registers on their way through the dequantisation
+    // token row 16 tf + j16 of a stage: 1 KiB piece 2 tf + (j16 >> 3), row slot (j16 & 7) ^ (piece & 1),
+    // 16-byte column (4 c + k block of this lane group) ^ (j16 & 7)
+    const int8_t *xs = lds + (j16 >> 3) * 1024 + 128 * ((j16 & 7) ^ (j16 >> 3));
+    const int8_t *xs_c[2][2];  // [LDS half][chunk]
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+            xs_c[u][c] = xs + u * (2 * STAGE) + 16 * ((4 * c + (kstep16_offset(kq) >> 4)) ^ (j16 & 7));
+
+    auto SB = [] { __builtin_amdgcn_sched_barrier(0); };
+    // (written out: the compiler's own choice for this shape is the form whose result may lie in
+    // other registers than its addend, and with all 256 accumulation registers taken it then
+    // moves accumulators through vector registers and memory.  Nothing here reads an accumulator
+    // sooner than 63 MFMAs after it was written; the epilogue waits by itself.)
+    auto mm = [&](int i, const v4i (&b)[4]) {
+        asm volatile("v_mfma_i32_16x16x64_i8 %0, %1, %2, %0" : "+a"(acc[i >> 2][i & 3]) : "v"(b[i & 3]), "v"(ax[(i >> 2) & 7]));
+    };
+    auto rd = [&](int buf, int c, int tf) {
+        ax[tf & 7] = *reinterpret_cast<const v4i *>(xs_c[buf >> 1][c] + (buf & 1) * STAGE + tf * 2048);
+    };
+    // slot i (0..63) of a k-step that builds bn = the operands of chunk c of (w, p): per tile 32
+    // slots -- parameters, 4 x and, 4 x shift, 4 x and, 8 x multiply-add, 8 x XOR, 4 x regroup
+    auto build = [&](int i, const u32x4 (&w)[2][2], const UnitParams<G128> (&p)[2], int c, v4i (&bn)[4]) {
+        const int t = i >> 5, k = i & 31;
+        const u32x4 &wc = w[t][c];
+        auto regroup = [&](int d) {
+            const auto r = __builtin_amdgcn_permlane16_swap(lo[d], hi[d], false, false);
+            bn[2 * t][d] = (int)r[0];
+            bn[2 * t + 1][d] = (int)r[1];
+        };
+        if (k == 0)
+            p[t].get(c, s2v, a4v);
+        else if (k <= 4)
+            lo[k - 1] = wc[k - 1] & 0x0F0F0F0Fu;
+        else if (k <= 8)
+            hi[k - 5] = wc[k - 5] >> 4;
+        else if (k <= 12)
+            hi[k - 9] &= 0x0F0F0F0Fu;
+        else if (k <= 16)
+            lo[k - 13] = pk_mad_u16(lo[k - 13], s2v, a4v);
+        else if (k <= 20)
+            hi[k - 17] = pk_mad_u16(hi[k - 17], s2v, a4v);
+        else if (k <= 24)
+            lo[k - 21] ^= 0x80808080u;
+        else if (k <= 28)
+            hi[k - 25] ^= 0x80808080u;
+        else if (k == 29)
+            regroup(0);
+        else if (k == 30)
+            regroup(1);
+        else {
+            regroup(2);
+            regroup(3);
+        }
+    };
+    // Token fragment tf is used by slots 4 tf .. 4 tf + 3 and its register set is refilled in the
+    // slot after with the fragment eight further on (28 MFMAs ahead of its use): slot 0 reads
+    // fragment 7 of the running k-step, slots 4 .. 32 its fragments 8 .. 15, slots 36 .. 60
+    // fragments 0 .. 6 of the next k-step.
+    // (cb, cc) = LDS stage and chunk of the running k-step, (nb, nc) of the next.
+    // ex(i): what else slot i carries (a piece of the prefetch, the stage's wait and barrier)
+    auto kstep = [&](const v4i (&bc)[4], v4i (&bn)[4], const u32x4 (&w)[2][2], const UnitParams<G128> (&p)[2], int c,
+                     int cb, int cc, int nb, int nc, auto ex) {
+        static_for<0, 64>([&](auto i_tag) {
+            constexpr int i = decltype(i_tag)::value;
+            mm(i, bc);
+            if (i == 0)
+                rd(cb, cc, 7);
+            else if (!(i & 3) && i <= 32)
+                rd(cb, cc, i / 4 + 7);
+            else if (!(i & 3))
+                rd(nb, nc, i / 4 - 9);
+            if (i == 0) ex(-1);  // (before the slot's phase: the wait for the registers it expands)
+            build(i, w, p, c, bn);
+            ex(i);
+            SB();
+        });
+    };
+    auto first_operands = [&](int q) {
+        static_for<0, 64>([&](auto i_tag) { build(decltype(i_tag)::value, wr[q], pr[q], 0, bw[0]); });
+        static_for<0, 7>([&](auto t_tag) { rd(q, 0, decltype(t_tag)::value); });
+    };
+    // One stage q (= stage mod 4: LDS stage and W register set; bw[0] holds the operands of its
+    // chunk 0, ax its fragments 0..6 on entry): two k-steps.  The second first waits for X and W
+    // of the next stage, then meets the other waves and starts the prefetch of the stage three
+    // ahead; the 14 loads of a prefetch are spread over the 128 slots up to the next stage's barrier.
+    auto stage = [&](auto q_tag) {
+        constexpr int q = decltype(q_tag)::value, nq = (q + 1) & 3, gq = (q + 2) & 3, fq = (q + 3) & 3;
+        kstep(bw[0], bw[1], wr[q], pr[q], 1, q, 0, q, 1, [&](int i) {
+            if (i == 3) issue_x1(gq, 4);
+            if (i == 9) issue_x1(gq, 5);
+            if (i == 15) issue_x1(gq, 6);
+            if (i == 21) issue_x1(gq, 7);
+            if (i == 27) load_w_piece(0, 0, wr[gq], pr[gq]);
+            if (i == 33) load_w_piece(0, 1, wr[gq], pr[gq]);
+            if (i == 39) load_w_piece(0, 2, wr[gq], pr[gq]);
+            if (i == 45) load_w_piece(1, 0, wr[gq], pr[gq]);
+            if (i == 51) load_w_piece(1, 1, wr[gq], pr[gq]);
+            if (i == 57) load_w_piece(1, 2, wr[gq], pr[gq]);
+        });
+        load_side_advance();
+        SB();
+        kstep(bw[1], bw[0], wr[nq], pr[nq], 0, q, 1, nq, 0, [&](int i) {
+            if (i == -1) arrive_w(std::integral_constant<int, PER_STAGE>{}, wr[nq], pr[nq]);
+            if (i == 1) asm volatile("s_barrier" ::: "memory");
+            if (i == 7) issue_x1(fq, 0);
+            if (i == 21) issue_x1(fq, 1);
+            if (i == 35) issue_x1(fq, 2);
+            if (i == 49) issue_x1(fq, 3);
+        });
+        // (the next stage's first operands are complete here, also where the next stage is the
+        // next trip of a loop: nothing of them may sink into the loop's latch)
+#pragma unroll
+        for (int f = 0; f < 4; ++f)
+#pragma unroll
+            for (int d = 0; d < 4; ++d) asm volatile("" : "+v"(bw[0][f][d]));
+        SB();
+    };
+    const std::integral_constant<int, 0> q0{};
+    const std::integral_constant<int, 1> q1{};
+    const std::integral_constant<int, 2> q2{};
+    const std::integral_constant<int, 3> q3{};
+
+    // ---- epilogue of one tile (Sec. 4, first-level dequantisation: acc * s_x[row] * s_w[channel]) ----
+    // Of token 16 tf + j16 a lane holds, for h = 0, 1, the 8 consecutive channels
+    // 64 ng + 32 h + 8 kq .. + 7: slot 16 h + 4 kq + v of the even (t = 0) and of the odd tile.
+    int M = 0;
+    __half *Y = nullptr;
+    int32_t *ACC = nullptr;
+    auto epilogue = [&](auto full_tag, int bm, int ng, const float *sx_tile, const float *sw_wave) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        const uint32_t lane_off = (uint32_t)j16 * (uint32_t)N + (uint32_t)(64 * ng + 8 * kq);  // in elements
+        float swv[2][8];
+        if (Y) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int e4 = 0; e4 < 2; ++e4) {
+                    const float4 v = *reinterpret_cast<const float4 *>(sw_wave + 32 * h + 8 * kq + 4 * e4);
+                    swv[h][4 * e4 + 0] = v.x, swv[h][4 * e4 + 1] = v.y, swv[h][4 * e4 + 2] = v.z, swv[h][4 * e4 + 3] = v.w;
+                }
+        }
+        static_for<0, TF>([&](auto tf_tag) {
+            constexpr int tf = decltype(tf_tag)::value;
+            const int row0 = bm * 256 + 16 * tf;  // wave-uniform
+            const bool live = FULL || row0 + j16 < M;
+            if (Y) {
+                const float sxv = sx_tile[16 * tf + j16];
+                const char *row = reinterpret_cast<const char *>(Y) + (size_t)row0 * ((size_t)N * 2);
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    v4i out;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float x0 = (float)acc_elem(tf, h, v) * sxv, x1 = (float)acc_elem(tf, 2 + h, v) * sxv;
+                        out[v] = (int)scale_pair_to_half2(x0, swv[h][2 * v], x1, swv[h][2 * v + 1]);
+                    }
+                    if (live) {
+                        if (h == 0)
+                            asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" : : "v"(lane_off * 2), "v"(out), "s"(row) : "memory");
+                        else
+                            asm volatile("global_store_dwordx4 %0, %1, %2 offset:64\n\ts_nop 1" : : "v"(lane_off * 2), "v"(out), "s"(row) : "memory");
+                    }
+                }
+            }
+            if (ACC) {
+                const char *row = reinterpret_cast<const char *>(ACC) + (size_t)row0 * ((size_t)N * 4);
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int e4 = 0; e4 < 2; ++e4) {
+                        const v4i out{acc_elem(tf, h, 2 * e4), acc_elem(tf, 2 + h, 2 * e4), acc_elem(tf, h, 2 * e4 + 1),
+                                      acc_elem(tf, 2 + h, 2 * e4 + 1)};
+                        if (live) {
+                            if (h == 0 && e4 == 0)
+                                asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" : : "v"(lane_off * 4), "v"(out), "s"(row) : "memory");
+                            else if (h == 0)
+                                asm volatile("global_store_dwordx4 %0, %1, %2 offset:16\n\ts_nop 1" : : "v"(lane_off * 4), "v"(out), "s"(row) : "memory");
+                            else if (e4 == 0)
+                                asm volatile("global_store_dwordx4 %0, %1, %2 offset:128\n\ts_nop 1" : : "v"(lane_off * 4), "v"(out), "s"(row) : "memory");
+                            else
+                                asm volatile("global_store_dwordx4 %0, %1, %2 offset:144\n\ts_nop 1" : : "v"(lane_off * 4), "v"(out), "s"(row) : "memory");
+                        }
+                    }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+
+    // ---- pipeline fill: stages 0 and 1 of the first tile and the first four loads of stage 2 ----
+    load_side_tile(l_lid);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) issue_x1(q, i);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            load_w_piece(t, 0, wr[q], pr[q]);
+            load_w_piece(t, 1, wr[q], pr[q]);
+            load_w_piece(t, 2, wr[q], pr[q]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        load_side_advance();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) issue_x1(2, i);
+    arrive_w(std::integral_constant<int, PER_STAGE + 4>{}, wr[0], pr[0]);  // and X(0) of this wave is in LDS
+    asm volatile("s_barrier" ::: "memory");
+    first_operands(0);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- the block's tiles ---------------------------------------------------------------------
+    uint32_t sx_par = 0;  // which of the two copies of the tile's scales is this tile's
+    for (int lid = (int)blockIdx.x; lid < tiles; lid += G) {
+        const SoloTile cur = src.tile(lid, G);
+        const int bm = cur.bm, ng = cur.bn * 4 + wave;
+        M = cur.M, Y = cur.Y, ACC = cur.ACC;
+        // the tile's 256 activation scales and the wave's 64 channel scales go to LDS now (see solo_body)
+        if (Y) {
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                         :
+                         : "v"((uint32_t)min(bm * 256 + 64 * wave + lane, M - 1) * 4u), "s"(cur.sx),
+                           "s"(lds0 + 4 * STAGE + sx_par * 1024 + wave * 256)
+                         : "memory", "m0");
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                         :
+                         : "v"((uint32_t)(64 * min(ng, (N >> 6) - 1) + lane) * 4u), "s"(cur.sw),
+                           "s"(lds0 + 4 * STAGE + 2048 + sx_par * 1024 + wave * 256)
+                         : "memory", "m0");
+        }
+        for (int it = 0; it < stages; it += 4) {
+            stage(q0);
+            stage(q1);
+            stage(q2);
+            stage(q3);
+        }
+        const float *sx_tile = reinterpret_cast<const float *>(lds + 4 * STAGE + sx_par * 1024);
+        const float *sw_wave = reinterpret_cast<const float *>(lds + 4 * STAGE + 2048 + sx_par * 1024 + wave * 256);
+        sx_par ^= 1;
+        // (the accumulators are read inside inline assembly, where the compiler does not count the
+        // wait states an MFMA result needs before it is read)
+        asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+        if (ng < (N >> 6)) {
+            if (bm * 256 + 256 <= M)
+                epilogue(std::true_type{}, bm, ng, sx_tile, sw_wave);
+            else
+                epilogue(std::false_type{}, bm, ng, sx_tile, sw_wave);
+        }
+        clear_acc();
+        asm volatile("s_nop 3" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // the prefetches past the last stage write LDS too: they must have landed before the block ends
+    wait_vmcnt0();
+}
+
+template <bool G128>
+__global__ __launch_bounds__(256, 1) void w4a8_solo16_pt_kernel(
+    int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
+    const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
+    __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n, int S)
+{
+    solo16_body<G128>(SoloDense{M, N, X, sx, Wp, gp, sw, Y, ACC, blocks_m, blocks_n, S}, N, K);
+}

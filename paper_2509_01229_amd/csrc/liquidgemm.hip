@@ -92,6 +92,7 @@ __device__ __forceinline__ __half scale_to_half(int acc, float sx, float sw)
 #include "kernels_tiled_dl.h"
 #include "kernels_tiled_pt.h"
 #include "kernels_tiled_solo.h"
+#include "kernels_tiled_solo16.h"
 #include "kernels_reference.h"
 #include "kernels_grouped.h"
 
@@ -464,9 +465,10 @@ static size_t solo_ws_bytes(int M, int N, int S)
     return S <= 1 ? 0 : kTicketBytes + (size_t)S * M * N * sizeof(int32_t);
 }
 // SPLIT: 0 = no K slices, -1 = as many as solo_split gives and the workspace holds, n = exactly n
-template <int KG, int SPLIT = 0>
+template <int KG, int SPLIT = 0, bool SHAPE16 = false>
 static int launch_solo_pt(const Args &a)
 {
+    static_assert(!SHAPE16 || KG == 1, "the 16x16x64 form has one k group");
     if (a.K % 512 != 0) return fail(LQ_ERR_INVALID, "the 256-row tile variants need K %% 512 == 0, got %d", a.K);
     constexpr int TN = 256 / KG;
     const int blocks_n = (a.N + TN - 1) / TN, blocks_m = (a.M + 255) / 256;
@@ -502,7 +504,17 @@ static int launch_solo_pt(const Args &a)
     const size_t lds_bytes = 4 * (size_t)256 * 128 + 4 * 1024;  // X stages; two copies of both scales
     __half *Y = S > 1 ? nullptr : a.Y;
     int32_t *ACC = S > 1 ? partials : a.ACC;
-    if (a.group == 128) {
+    if constexpr (SHAPE16) {
+        if (a.group == 128) {
+            if (int rc = allow_lds(w4a8_solo16_pt_kernel<true>, lds_bytes)) return rc;
+            hipLaunchKernelGGL((w4a8_solo16_pt_kernel<true>), dim3((unsigned)grid), dim3(256), lds_bytes, a.stream, a.M,
+                               a.N, a.K, a.X, a.sx, a.Wp, a.gp, a.sw, Y, ACC, blocks_m, blocks_n, S);
+        } else {
+            if (int rc = allow_lds(w4a8_solo16_pt_kernel<false>, lds_bytes)) return rc;
+            hipLaunchKernelGGL((w4a8_solo16_pt_kernel<false>), dim3((unsigned)grid), dim3(256), lds_bytes, a.stream, a.M,
+                               a.N, a.K, a.X, a.sx, a.Wp, a.gp, a.sw, Y, ACC, blocks_m, blocks_n, S);
+        }
+    } else if (a.group == 128) {
         if (int rc = allow_lds(w4a8_solo_pt_kernel<true, KG>, lds_bytes)) return rc;
         hipLaunchKernelGGL((w4a8_solo_pt_kernel<true, KG>), dim3((unsigned)grid), dim3(256), lds_bytes, a.stream, a.M,
                            a.N, a.K, a.X, a.sx, a.Wp, a.gp, a.sw, Y, ACC, blocks_m, blocks_n, S);
@@ -620,6 +632,7 @@ static const Variant kVariants[] = {
     {"duo_pt_m128", &launch_duo_pt, 0, 1, 8, 512},
     {"solo_pt_m256", &launch_solo_pt<1>, 0, 1, 8, 512},
     {"solo_g2_m256", &launch_solo_pt<2>, 0, 1, 8, 512},
+    {"solo16_pt_m256", &launch_solo_pt<1, 0, true>, 0, 1, 8, 512},
     {"solo_sk_m256", &launch_solo_pt<1, -1>, 0, 1, 8, 512},
     {"solo_g2_sk_m256", &launch_solo_pt<2, -1>, 0, 1, 8, 512},
     // --- the same kernels with a named number of K slices: the split paths at sizes where the

@@ -493,7 +493,7 @@ def test_batch_beyond_32_bit_offsets_of_x():
     assert np.array_equal(ACC2.cpu().numpy(), ref), "accumulators of the named variant differ"
 
 
-@pytest.mark.parametrize("kernel", ["duo_pt_m128", "solo_pt_m256", "solo_g2_m256"])
+@pytest.mark.parametrize("kernel", ["duo_pt_m128", "solo_pt_m256", "solo_g2_m256", "solo16_pt_m256"])
 @pytest.mark.parametrize("M,N,K,g", [(1541, 12352, 512, 64), (2048, 10240, 1024, 128), (700, 2048, 1536, 64)])
 def test_persistent_tile_kernel(M, N, K, g, kernel):
     """The persistent forms of the tiled kernel (blocks walk several tiles as one stream of
