@@ -692,20 +692,24 @@ static TiledCosts tiled_costs(long long t128, long long t256, long long t2, int 
     //   ... 129..256 tiles, persistent form (one block per CU): 50.6 / 57.3 / 63.5 at 160 / 192 / 256
     //       (one tile per block: 56 / 60 / 67)
     //   ... 257..512 tiles (a second resident block on some CUs): 85 / 95 / 102 / 111 / 116 at 270 / 320 / 384 / 448 / 512
-    //   ... beyond: whole rounds of 512 (blocks b and b + 256 share a CU: 3.5 rounds take 7, 1.75 take 4)
+    //   ... beyond: whole rounds of 512 at 2 each, the rest as above
     //   256 x 256 tiles, one round: 84 / 93 / 107 at 160 / 192 / 256 tiles; more: whole rounds at 2 * 0.86
     //   256 x 128 tiles, one round of more than half the CUs: 45.8 / 49 / 56 / 61.5 at 144 / 160 / 192 / 256
     //       (at 128 tiles equal to the 128-row tiles; their tiles are separate, a second round costs a tenth more)
-    const long long rem = t128 % (2 * kAssumedCUs);
+    // one round of up to 512 tiles (or the rest after whole rounds of 512: 4096 + 40 rows on 8192 x 8192,
+    // 1056 tiles, took 259 us against 235 us of 4096 rows)
+    auto part = [](long long t) {
+        const double fill = (double)t / kAssumedCUs;
+        return t == 0 ? 0.0 : 2 * t <= kAssumedCUs ? 0.24 + 0.90 * fill : t <= kAssumedCUs ? 0.47 + 0.52 * fill : 0.80 + 0.51 * fill;
+    };
     const double fill = (double)t128 / kAssumedCUs;
-    const double duo = 2 * t128 <= kAssumedCUs ? 0.24 + 0.90 * fill
-                       : t128 <= kAssumedCUs   ? (pt_ok ? 0.47 + 0.52 * fill : 0.60 + 0.45 * fill)
-                       : t128 <= 2 * kAssumedCUs
-                           ? 0.80 + 0.51 * fill
-                           : 2.0 * (t128 / (2 * kAssumedCUs)) + (rem > 0) + (rem > kAssumedCUs);
+    const double duo = t128 <= kAssumedCUs && 2 * t128 > kAssumedCUs && !pt_ok
+                           ? 0.60 + 0.45 * fill
+                           : 2.0 * (t128 / (2 * kAssumedCUs)) + part(t128 % (2 * kAssumedCUs));
     const double short_k = K >= 4096 ? 1.0 : 1.06;  // (their longer epilogue weighs more)
+    // (those were measured with the 32x32x32 MFMA; on the 16x16x64 one the 256 x 256 tiles take 8 % less)
     const double solo = (t256 <= kAssumedCUs ? 0.734 + 0.94 * t256 / kAssumedCUs
-                                             : 2.0 * ((t256 + kAssumedCUs - 1) / kAssumedCUs) * 0.86) * short_k;
+                                             : 2.0 * ((t256 + kAssumedCUs - 1) / kAssumedCUs) * 0.86) * short_k * 0.92;
     const double g2 = 16 * t2 > 8.5 * kAssumedCUs && t2 <= kAssumedCUs ? (0.406 + 0.56 * t2 / kAssumedCUs) * short_k : 1e30;
     return TiledCosts{duo, solo, g2};
 }
@@ -767,7 +771,7 @@ static int select_variant(int M, int N, int K)
     if (M <= 64 && N / 32 <= 512 && !(M >= 48 && N / 32 > 128 && N / 32 <= 256 && K >= 24576))
         return find_variant("stream_m64");
     // 256-row tiles with one wave per SIMD where their whole rounds come out ahead
-    if (const int form = solo_form_that_pays(M, N, K)) return find_variant(form == 1 ? "solo_pt_m256" : "solo_g2_m256");
+    if (const int form = solo_form_that_pays(M, N, K)) return find_variant(form == 1 ? "solo16_pt_m256" : "solo_g2_m256");
     // ... and, with very long K and row tiles that are nearly full, their 256 x 128 form with K
     // slices across blocks where tiles x slices come to one round of at least three quarters of the
     // CUs (256 x 8192 x 28672: 65 against 70 us; 512 rows: 114 against 121; 256 x 6144 x 16384: 37
@@ -801,21 +805,23 @@ static int select_variant(int M, int N, int K)
 // (1536 + 512 rows on the 70B qkv projection, 2048 + 1024 on 8192 x 8192, 4096 + 1904 on 4096 x
 // 4096) the two launches were measured equal to the single one or 5 % behind -- the second kernel
 // starts when the first has drained, and the kernels for a few hundred rows are the least
-// efficient ones.  Same cost units as solo_form_for; a second launch is charged 12 us.  Returns
+// efficient ones.  Same cost units as solo_form_for; a second launch is charged 5 us
+// (2048 + 100 rows on 8192 x 4096: 55.7 + 16.2 us against 78.4 us of the best single kernel; 1024 + 30 rows on
+// 16384 x 4096: 56 + 11.3 against 79.7).  Returns
 // the rows of the first piece (M if the batch stays whole).
 static int rows_of_first_launch(int M, int N, int K)
 {
     if (K % 512 != 0 || M <= 256) return M;
     const int bm = (M + 255) / 256, bn = (N + 255) / 256;
     double best = tiled_costs(M, N, K).best() * 0.97;  // (a split has to win by 3 %)
-    const double second_launch = 12.0 / (7.2 * K / 1024.0);
+    const double second_launch = 5.0 / (8.0 * K / 1024.0);  // (a unit is 64 us at K = 8192)
     const double short_k = K >= 4096 ? 1.0 : 1.06;
     int rows = M;
     for (int rounds = 1; rounds <= 8; ++rounds) {
         const int rb = (int)(kAssumedCUs * rounds / bn);  // row blocks whose tiles fill `rounds` rounds
         if (rb >= bm) break;
         if (rb < 1 || M - 256 * rb > 256) continue;
-        const double c = rounds * 2.0 * 0.86 * short_k + tiled_costs(M - 256 * rb, N, K).best() + second_launch;
+        const double c = rounds * 2.0 * 0.86 * 0.92 * short_k + tiled_costs(M - 256 * rb, N, K).best() + second_launch;
         if (c < best) best = c, rows = 256 * rb;
     }
     return rows;
@@ -886,7 +892,7 @@ static int run(int variant, const Args &a)
     if (a.sx) rest.sx = a.sx + first;
     if (a.Y) rest.Y = a.Y + (size_t)first * a.N;
     if (a.ACC) rest.ACC = a.ACC + (size_t)first * a.N;
-    if (int rc = run_rows(find_variant("solo_pt_m256"), head)) return rc;
+    if (int rc = run_rows(find_variant("solo16_pt_m256"), head)) return rc;
     if (int rc = run_rows(-1, rest)) return rc;
     if (a.query) *a.query = std::max(need_head, need_rest);
     return LQ_OK;
@@ -1209,7 +1215,7 @@ int w4a8_select_plan(int M, int N, int K, int group, int *rows_first, int *varia
     const int first = M > 0 ? rows_of_first_launch(M, N, K) : M;
     *rows_first = first;
     *variant_rest = first == M ? -1 : select_variant(M - first, N, K);
-    return first == M ? select_variant(M, N, K) : find_variant("solo_pt_m256");
+    return first == M ? select_variant(M, N, K) : find_variant("solo16_pt_m256");
 }
 
 int w4a8_dequant_dump(const void *W_packed, const uint8_t *gparams, int N, int K, int group,

@@ -22,18 +22,12 @@ def _solo_form(M, N, K):
         return 0
     bm = -(-M // 256)
     t256, t2, t128 = bm * -(-N // 256), bm * -(-N // 128), -(-M // 128) * -(-N // 256)
-    rem = t128 % 512
-    fill = t128 / 256
-    if t128 <= 128:
-        duo = 0.24 + 0.90 * fill
-    elif t128 <= 256:
-        duo = 0.47 + 0.52 * fill
-    elif t128 <= 512:
-        duo = 0.80 + 0.51 * fill
-    else:
-        duo = 2.0 * (t128 // 512) + (rem > 0) + (rem > 256)
+    def part(t):
+        fill = t / 256
+        return 0.0 if t == 0 else 0.24 + 0.90 * fill if t <= 128 else 0.47 + 0.52 * fill if t <= 256 else 0.80 + 0.51 * fill
+    duo = 2.0 * (t128 // 512) + part(t128 % 512)
     short_k = 1.0 if K >= 4096 else 1.06
-    solo = (0.734 + 0.94 * t256 / 256 if t256 <= 256 else 2.0 * -(-t256 // 256) * 0.86) * short_k
+    solo = (0.734 + 0.94 * t256 / 256 if t256 <= 256 else 2.0 * -(-t256 // 256) * 0.86) * short_k * 0.92
     g2 = (0.406 + 0.56 * t2 / 256) * short_k if 136 < t2 <= 256 else 1e30
     if solo < duo and solo <= g2:
         return 1
@@ -50,14 +44,14 @@ def test_dispatcher_families_on_the_workloads():
         elif s.M <= 64 and s.N <= 16384:
             assert name == "stream_m64", (s.name, name)
         else:
-            assert name in ("duo_m64", "duo_m128", "duo_dl_m128", "duo_pt_m128", "solo_pt_m256", "solo_g2_m256",
+            assert name in ("duo_m64", "duo_m128", "duo_dl_m128", "duo_pt_m128", "solo16_pt_m256", "solo_g2_m256",
                             "solo_g2_sk_m256"), (s.name, name)
             tiles128 = -(-s.M // 128) * -(-s.N // 256)
             form = _solo_form(s.M, s.N, s.K)
             if name == "solo_g2_sk_m256":   # K slices across blocks: very long K, one round of 256 x 128 tiles x slices
                 assert not form and s.K >= 16384 and -(-s.M // 256) * -(-s.N // 128) <= 128, (s.name, name)
             elif form:                  # 256-row tiles, one wave per SIMD, where their whole rounds come out ahead
-                assert name == ("solo_pt_m256" if form == 1 else "solo_g2_m256"), (s.name, name)
+                assert name == ("solo16_pt_m256" if form == 1 else "solo_g2_m256"), (s.name, name)
             elif tiles128 > 256:      # more tiles than CUs: the direct-to-LDS pipeline, persistent where it fits
                 assert name == ("duo_pt_m128" if _pt_fits(s.M, s.N, s.K) else "duo_dl_m128"), (s.name, name)
             elif tiles128 > 128 and s.K % 512 == 0:   # more than half a round: persistent, one block per CU
@@ -110,11 +104,11 @@ def test_dispatcher_boundaries():
     assert _pick(512, 8192, 8192) == "duo_m128" and _pick(1024, 4096, 8192) in ("duo_m64", "duo_m128")   # 128 tiles: equal or behind
     assert _pick(384, 8192, 8192) == "duo_m128"                # (a third of the second row tile's work is lost)
     # ... 256 x 256 where their whole rounds cost less than the rounds of 128-row tiles, two blocks to a CU
-    assert _pick(1152, 8192, 8192) == "solo_pt_m256" and _pick(1280, 8192, 8192) == "solo_pt_m256"   # 160 tiles, one round
-    assert _pick(4096, 8192, 8192) == "solo_pt_m256" and _pick(2048, 8192, 28672, 128) == "solo_pt_m256"
-    assert _pick(8192, 8192, 8192) == "solo_pt_m256" and _pick(4096, 8192, 2048) == "solo_pt_m256"
-    assert _pick(1024, 28672, 8192, 128) == "solo_pt_m256" and _pick(2048, 28672, 8192, 128) == "solo_pt_m256"
-    assert _pick(1024, 10240, 8192, 128) == "solo_pt_m256" and _pick(1024, 11008, 4096) == "solo_pt_m256"
+    assert _pick(1152, 8192, 8192) == "solo16_pt_m256" and _pick(1280, 8192, 8192) == "solo16_pt_m256"   # 160 tiles, one round
+    assert _pick(4096, 8192, 8192) == "solo16_pt_m256" and _pick(2048, 8192, 28672, 128) == "solo16_pt_m256"
+    assert _pick(8192, 8192, 8192) == "solo16_pt_m256" and _pick(4096, 8192, 2048) == "solo16_pt_m256"
+    assert _pick(1024, 28672, 8192, 128) == "solo16_pt_m256" and _pick(2048, 28672, 8192, 128) == "solo16_pt_m256"
+    assert _pick(1024, 10240, 8192, 128) == "solo16_pt_m256" and _pick(1024, 11008, 4096) == "solo16_pt_m256"
     # ... and the 128-row tiles where a last round of 256-row tiles would be mostly empty
     assert _pick(2560, 8192, 8192) == "duo_pt_m128" and _pick(3072, 8192, 8192) == "duo_pt_m128"
     assert _pick(2048, 10240, 8192, 128) == "duo_pt_m128" and _pick(2048, 11008, 4096) == "duo_pt_m128"
@@ -133,9 +127,9 @@ def test_two_launch_plans():
     """Batches whose 256 x 256 tiles make whole rounds of the chip plus a rest of at most 256 rows
     run as two launches over consecutive rows; everything else as one, which is then the
     dispatcher's choice."""
-    assert _plan(4096 + 40, 8192, 8192) == [(4096, "solo_pt_m256"), (40, "stream_m64")]      # a ragged tail of the batch
-    assert _plan(2048 + 100, 8192, 4096) == [(2048, "solo_pt_m256"), (100, "duo_m64")]
-    assert _plan(1024 + 30, 16384, 4096, 128) == [(1024, "solo_pt_m256"), (30, "stream_m32")]
+    assert _plan(4096 + 40, 8192, 8192) == [(4096, "solo16_pt_m256"), (40, "stream_m64")]      # a ragged tail of the batch
+    assert _plan(2048 + 100, 8192, 4096) == [(2048, "solo16_pt_m256"), (100, "duo_m64")]
+    assert _plan(1024 + 30, 16384, 4096, 128) == [(1024, "solo16_pt_m256"), (30, "stream_m32")]
     # larger rests stay in one launch (measured equal or behind as two)
     assert _plan(2048, 10240, 8192, 128) == [(2048, "duo_pt_m128")] and _plan(3072, 8192, 8192) == [(3072, "duo_pt_m128")]
     assert _plan(6000, 4096, 4096) == [(6000, "duo_pt_m128")]

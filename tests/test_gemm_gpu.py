@@ -292,7 +292,7 @@ def test_random_large_grids_through_the_dispatcher():
         assert np.array_equal(ACC.cpu().numpy().astype(np.float64), ref), f"case {case}: accumulators differ"
         H.assert_fp16_close(Y.cpu().numpy(), O.scale_epilogue_f64(ref, s_x, s_w), f"case {case}")
         del P, dX, ACC, Y
-    assert {"duo_dl_m128", "duo_pt_m128", "solo_pt_m256"} <= seen and seen & {"duo_m128", "duo_m64"}
+    assert {"duo_dl_m128", "duo_pt_m128", "solo16_pt_m256"} <= seen and seen & {"duo_m128", "duo_m64"}
 
 
 def test_random_small_batches_through_the_dispatcher():
