@@ -56,6 +56,10 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
     const size_t pg_stride = (size_t)(K >> 7) * 32 * (G128 ? 2 : 4);
     uint32_t wl = lane * 16;  // (not const: the X loads name it as an operand, see issue_x1)
     const uint32_t pl_off = j * (G128 ? 2 : 4);
+    // lane offsets of the two channel tiles of a wave's 64 channels (a tile's codes and parameters
+    // span less than 4 GiB: K < 2^22 here)
+    uint32_t wl_t[2] = {wl, wl + (uint32_t)wg_stride}, pl_t[2] = {pl_off, pl_off + (uint32_t)pg_stride};
+    asm volatile("" : "+v"(wl_t[0]), "+v"(wl_t[1]), "+v"(pl_t[0]), "+v"(pl_t[1]));
     const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) void *)lds;
     int l_lid = (int)blockIdx.x, l_s = 0;  // tile and stage the next prefetch takes
     uint32_t xg[8];
@@ -75,6 +79,10 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
         wbase = reinterpret_cast<const char *>(t.Wp + (size_t)t0 * chunks_per_tile * 64) + s0 * 2048;
         pbase = reinterpret_cast<const char *>(t.gp) + (size_t)t0 * pg_stride + s0 * (G128 ? 64 : 128);
     };
+    // The load side runs three stages ahead of the compute side and a tile's stages are a
+    // multiple of four, so it reaches the end of a tile only behind a stage with q = 1: the other
+    // stages advance without a test.  After the block's last tile it falls back four stages and
+    // re-reads stages of that tile into LDS stages and registers nobody reads any more.
     auto load_side_advance = [&] {
         if (++l_s == stages) {
             asm volatile("" ::: "memory");
@@ -83,7 +91,7 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
                 l_s = 0;
                 load_side_tile(l_lid);
             } else {
-                l_s = stages - 1;
+                l_s = stages - 4;
             }
         }
     };
@@ -95,15 +103,20 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
     };
     // piece 0, 1 = the codes of the stage's chunk 0, 1 of channel tile t, piece 2 = its group parameters
     auto load_w_piece = [&](int t, int piece, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
+        // (one scalar base per stage for the codes and one for the parameters: the tile is in
+        // the lane offset, the chunk in the instruction's immediate)
         if (piece < 2) {
-            const char *wb = wbase + t * wg_stride + (size_t)l_s * 2048 + piece * 1024;
-            asm volatile("global_load_dwordx4 %0, %1, %2" : "=&v"(w[t][piece]) : "v"(wl), "s"(wb) : "memory");
-        } else {
-            const char *pb = pbase + t * pg_stride + (size_t)l_s * (G128 ? 64 : 128);
-            if (G128)
-                asm volatile("global_load_ushort %0, %1, %2" : "=&v"(p[t].raw) : "v"(pl_off), "s"(pb) : "memory");
+            const char *wb = wbase + (size_t)l_s * 2048;
+            if (piece == 0)
+                asm volatile("global_load_dwordx4 %0, %1, %2" : "=&v"(w[t][piece]) : "v"(wl_t[t]), "s"(wb) : "memory");
             else
-                asm volatile("global_load_dword %0, %1, %2" : "=&v"(p[t].raw) : "v"(pl_off), "s"(pb) : "memory");
+                asm volatile("global_load_dwordx4 %0, %1, %2 offset:1024" : "=&v"(w[t][piece]) : "v"(wl_t[t]), "s"(wb) : "memory");
+        } else {
+            const char *pb = pbase + (size_t)l_s * (G128 ? 64 : 128);
+            if (G128)
+                asm volatile("global_load_ushort %0, %1, %2" : "=&v"(p[t].raw) : "v"(pl_t[t]), "s"(pb) : "memory");
+            else
+                asm volatile("global_load_dword %0, %1, %2" : "=&v"(p[t].raw) : "v"(pl_t[t]), "s"(pb) : "memory");
         }
     };
     auto arrive_w = [&](auto pending_tag, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
@@ -157,6 +170,15 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
     auto mm = [&](int i, const v4i (&b)[4]) {
         asm volatile("v_mfma_i32_16x16x64_i8 %0, %1, %2, %0" : "+a"(acc[i >> 2][i & 3]) : "v"(b[i & 3]), "v"(ax[(i >> 2) & 7]));
     };
+    // The same with piece xi of LDS stage buf of the X prefetch behind it: the MFMA is the wait
+    // state the load needs after the write of m0.
+    auto mm_x = [&](int i, const v4i (&b)[4], int buf, int xi) {
+        asm volatile("s_mov_b32 m0, %4\n\tv_mfma_i32_16x16x64_i8 %0, %5, %6, %0\n\tglobal_load_lds_dwordx4 %2, %3"
+                     : "+a"(acc[i >> 2][i & 3]), "+v"(wl)
+                     : "v"(xg[xi]), "s"(ld_X + (size_t)l_s * 128), "s"(lds0 + buf * STAGE + (4 * xi + wave) * 1024),
+                       "v"(b[i & 3]), "v"(ax[(i >> 2) & 7])
+                     : "memory", "m0");
+    };
     auto rd = [&](int buf, int c, int tf) {
         ax[tf & 7] = *reinterpret_cast<const v4i *>(xs_c[buf >> 1][c] + (buf & 1) * STAGE + tf * 2048);
     };
@@ -200,12 +222,16 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
     // fragment 7 of the running k-step, slots 4 .. 32 its fragments 8 .. 15, slots 36 .. 60
     // fragments 0 .. 6 of the next k-step.
     // (cb, cc) = LDS stage and chunk of the running k-step, (nb, nc) of the next.
-    // ex(i): what else slot i carries (a piece of the prefetch, the stage's wait and barrier)
+    // ex(i): what else slot i carries (a piece of the W prefetch, the stage's wait and barrier);
+    // xsl(i): 8 * LDS stage + piece of the X prefetch that slot i issues with its MFMA, or -1
     auto kstep = [&](const v4i (&bc)[4], v4i (&bn)[4], const u32x4 (&w)[2][2], const UnitParams<G128> (&p)[2], int c,
-                     int cb, int cc, int nb, int nc, auto ex) {
+                     int cb, int cc, int nb, int nc, auto ex, auto xsl) {
         static_for<0, 64>([&](auto i_tag) {
             constexpr int i = decltype(i_tag)::value;
-            mm(i, bc);
+            if (xsl(i) >= 0)
+                mm_x(i, bc, xsl(i) >> 3, xsl(i) & 7);
+            else
+                mm(i, bc);
             if (i == 0)
                 rd(cb, cc, 7);
             else if (!(i & 3) && i <= 32)
@@ -229,27 +255,22 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
     auto stage = [&](auto q_tag) {
         constexpr int q = decltype(q_tag)::value, nq = (q + 1) & 3, gq = (q + 2) & 3, fq = (q + 3) & 3;
         kstep(bw[0], bw[1], wr[q], pr[q], 1, q, 0, q, 1, [&](int i) {
-            if (i == 3) issue_x1(gq, 4);
-            if (i == 9) issue_x1(gq, 5);
-            if (i == 15) issue_x1(gq, 6);
-            if (i == 21) issue_x1(gq, 7);
             if (i == 27) load_w_piece(0, 0, wr[gq], pr[gq]);
             if (i == 33) load_w_piece(0, 1, wr[gq], pr[gq]);
             if (i == 39) load_w_piece(0, 2, wr[gq], pr[gq]);
             if (i == 45) load_w_piece(1, 0, wr[gq], pr[gq]);
             if (i == 51) load_w_piece(1, 1, wr[gq], pr[gq]);
             if (i == 57) load_w_piece(1, 2, wr[gq], pr[gq]);
-        });
-        load_side_advance();
+        }, [&](int i) { return i == 3 ? gq * 8 + 4 : i == 9 ? gq * 8 + 5 : i == 15 ? gq * 8 + 6 : i == 21 ? gq * 8 + 7 : -1; });
+        if (q == 1)
+            load_side_advance();
+        else
+            ++l_s;
         SB();
         kstep(bw[1], bw[0], wr[nq], pr[nq], 0, q, 1, nq, 0, [&](int i) {
             if (i == -1) arrive_w(std::integral_constant<int, PER_STAGE>{}, wr[nq], pr[nq]);
             if (i == 1) asm volatile("s_barrier" ::: "memory");
-            if (i == 7) issue_x1(fq, 0);
-            if (i == 21) issue_x1(fq, 1);
-            if (i == 35) issue_x1(fq, 2);
-            if (i == 49) issue_x1(fq, 3);
-        });
+        }, [&](int i) { return i == 7 ? fq * 8 + 0 : i == 21 ? fq * 8 + 1 : i == 35 ? fq * 8 + 2 : i == 49 ? fq * 8 + 3 : -1; });
         // (the next stage's first operands are complete here, also where the next stage is the
         // next trip of a loop: nothing of them may sink into the loop's latch)
 #pragma unroll
