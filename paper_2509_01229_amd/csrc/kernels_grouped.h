@@ -141,5 +141,5 @@ struct SoloGrouped {
 template <bool G128>
 __global__ __launch_bounds__(256, 1) void w4a8_solo_grouped_kernel(const GroupTable g, const GroupedPtrs p, int N, int K)
 {
-    solo16_body<G128>(SoloGrouped{g, p, N, K, (N + 255) / 256}, N, K);
+    solo16_body<G128, 1>(SoloGrouped{g, p, N, K, (N + 255) / 256}, N, K);
 }

@@ -19,7 +19,14 @@
 //   * the weights are the MFMA's first operand, so that a lane receives four consecutive slots
 //     of a tile for one token: with the even and the odd channels of the two tiles of a
 //     64-channel group, 8 consecutive channels, stored as one 16-byte piece of FP16.
-// Load side, LDS ring, scale staging and tile walk are those of solo_body (KG = 1).
+// Load side, LDS ring, scale staging and tile walk are those of solo_body.
+//
+// KG = 2 (tile 256 x 128 for outputs with fewer 256 x 256 tiles than CUs, as in solo_body): the
+// four waves are two k groups of two, group g computes chunk g of every stage, so a stage is one
+// k-step per wave: its slot 0 waits for the next stage's loads, slot 1 meets the other waves,
+// and the 12 loads of the stage three ahead follow in the same k-step.  After the tile's last
+// stage the groups exchange half of their accumulators through the drained LDS ring and each
+// finishes eight of the sixteen token fragments.  Tiles are separate there (fill per tile).
 // ------------------------------------------------------------------------------------
 // f(integral_constant<int, B>), ..., f(integral_constant<int, E - 1>): the 64 slots of a k-step are
 // written out this way -- a loop of that size is past what the compiler unrolls on request, and
@@ -33,18 +40,21 @@ __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
-template <bool G128, class Src>
+template <bool G128, int KG, class Src>
 __device__ __forceinline__ void solo16_body(const Src &src, const int N, const int K)
 {
     constexpr int TF = 16;  // token fragments of 16 rows per wave
     constexpr int STAGE = 256 * 128;
-    constexpr int PER_STAGE = 14;  // loads of one stage: 8 of X, 4 of codes, 2 of parameters
+    constexpr int PER_STAGE = 8 + (KG == 1 ? 6 : 4);  // loads of one stage: 8 of X, 4 / KG of codes, 2 of parameters
+    constexpr int WPB = 4 / KG;                       // 64-channel groups per block
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int j = lane & 31;
     const int j16 = lane & 15, kq = lane >> 4;
+    const int grp = KG == 2 ? wave >> 1 : 0;       // KG = 2: the chunk of every stage this wave computes
+    const int colw = KG == 2 ? (wave & 1) : wave;  // which 64 channels of the block's 256 / KG
     const int stages = (K >> 7) / src.slices();  // of a tile's K slice, a multiple of four
     const int chunks_per_tile = K >> 6;
     const int tiles = src.tiles(), G = (int)gridDim.x;
@@ -68,7 +78,7 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
     auto load_side_tile = [&](int lid) {
         const SoloTile t = src.tile(lid, G);
         const int bm = t.bm, M = t.M;
-        const int ng = t.bn * 4 + wave;
+        const int ng = t.bn * WPB + colw;
         const int t0 = 2 * min(ng, (N >> 6) - 1);
         asm volatile("" : "+v"(ld_row));
 #pragma unroll
@@ -80,13 +90,14 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
         pbase = reinterpret_cast<const char *>(t.gp) + (size_t)t0 * pg_stride + s0 * (G128 ? 64 : 128);
     };
     // The load side runs three stages ahead of the compute side and a tile's stages are a
-    // multiple of four, so it reaches the end of a tile only behind a stage with q = 1: the other
-    // stages advance without a test.  After the block's last tile it falls back four stages and
-    // re-reads stages of that tile into LDS stages and registers nobody reads any more.
+    // multiple of four, so it reaches the end of a tile only behind a stage with q = 1 (KG = 2:
+    // q = 0): the other stages advance without a test.  After the block's last tile (KG = 2: of
+    // every tile) it falls back four stages and re-reads stages of that tile into LDS stages and
+    // registers nobody reads any more.
     auto load_side_advance = [&] {
         if (++l_s == stages) {
             asm volatile("" ::: "memory");
-            if (l_lid + G < tiles) {
+            if (KG == 1 && l_lid + G < tiles) {
                 l_lid += G;
                 l_s = 0;
                 load_side_tile(l_lid);
@@ -101,12 +112,13 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
                      : "v"(xg[i]), "s"(ld_X + (size_t)l_s * 128), "s"(lds0 + buf * STAGE + (4 * i + wave) * 1024)
                      : "memory", "m0");
     };
-    // piece 0, 1 = the codes of the stage's chunk 0, 1 of channel tile t, piece 2 = its group parameters
+    // piece 0, 1 = the codes of the stage's chunk 0, 1 of channel tile t (KG = 2: piece 0 = the
+    // wave's own chunk, there is no piece 1), piece 2 = its group parameters
     auto load_w_piece = [&](int t, int piece, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
         // (one scalar base per stage for the codes and one for the parameters: the tile is in
         // the lane offset, the chunk in the instruction's immediate)
         if (piece < 2) {
-            const char *wb = wbase + (size_t)l_s * 2048;
+            const char *wb = wbase + (size_t)l_s * 2048 + (KG == 2 ? grp * 1024 : 0);
             if (piece == 0)
                 asm volatile("global_load_dwordx4 %0, %1, %2" : "=&v"(w[t][piece]) : "v"(wl_t[t]), "s"(wb) : "memory");
             else
@@ -120,6 +132,12 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
         }
     };
     auto arrive_w = [&](auto pending_tag, u32x4 (&w)[2][2], UnitParams<G128> (&p)[2]) {
+        if (KG == 2)
+            asm volatile("s_waitcnt vmcnt(%4)"
+                         : "+v"(w[0][0]), "+v"(w[1][0]), "+v"(p[0].raw), "+v"(p[1].raw)
+                         : "n"(decltype(pending_tag)::value)
+                         : "memory");
+        else
         asm volatile("s_waitcnt vmcnt(%6)"
                      : "+v"(w[0][0]), "+v"(w[0][1]), "+v"(w[1][0]), "+v"(w[1][1]), "+v"(p[0].raw), "+v"(p[1].raw)
                      : "n"(decltype(pending_tag)::value)
@@ -155,12 +173,12 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
     // token row 16 tf + j16 of a stage: 1 KiB piece 2 tf + (j16 >> 3), row slot (j16 & 7) ^ (piece & 1),
     // 16-byte column (4 c + k block of this lane group) ^ (j16 & 7)
     const int8_t *xs = lds + (j16 >> 3) * 1024 + 128 * ((j16 & 7) ^ (j16 >> 3));
-    const int8_t *xs_c[2][2];  // [LDS half][chunk]
+    const int8_t *xs_c[2][2];  // [LDS half][chunk] (KG = 2: entry 0 is the wave's own chunk)
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
         for (int c = 0; c < 2; ++c)
-            xs_c[u][c] = xs + u * (2 * STAGE) + 16 * ((4 * c + (kstep16_offset(kq) >> 4)) ^ (j16 & 7));
+            xs_c[u][c] = xs + u * (2 * STAGE) + 16 * ((4 * (KG == 2 ? grp : c) + (kstep16_offset(kq) >> 4)) ^ (j16 & 7));
 
     auto SB = [] { __builtin_amdgcn_sched_barrier(0); };
     // (written out: the compiler's own choice for this shape is the form whose result may lie in
@@ -184,9 +202,10 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
     };
     // slot i (0..63) of a k-step that builds bn = the operands of chunk c of (w, p): per tile 32
     // slots -- parameters, 4 x and, 4 x shift, 4 x and, 8 x multiply-add, 8 x XOR, 4 x regroup
+    // (KG = 2: the wave's chunk is the only one in its registers, entry 0)
     auto build = [&](int i, const u32x4 (&w)[2][2], const UnitParams<G128> (&p)[2], int c, v4i (&bn)[4]) {
         const int t = i >> 5, k = i & 31;
-        const u32x4 &wc = w[t][c];
+        const u32x4 &wc = w[t][KG == 2 ? 0 : c];
         auto regroup = [&](int d) {
             const auto r = __builtin_amdgcn_permlane16_swap(lo[d], hi[d], false, false);
             bn[2 * t][d] = (int)r[0];
@@ -245,7 +264,7 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
         });
     };
     auto first_operands = [&](int q) {
-        static_for<0, 64>([&](auto i_tag) { build(decltype(i_tag)::value, wr[q], pr[q], 0, bw[0]); });
+        static_for<0, 64>([&](auto i_tag) { build(decltype(i_tag)::value, wr[q], pr[q], grp, bw[0]); });
         static_for<0, 7>([&](auto t_tag) { rd(q, 0, decltype(t_tag)::value); });
     };
     // One stage q (= stage mod 4: LDS stage and W register set; bw[0] holds the operands of its
@@ -254,6 +273,27 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
     // ahead; the 14 loads of a prefetch are spread over the 128 slots up to the next stage's barrier.
     auto stage = [&](auto q_tag) {
         constexpr int q = decltype(q_tag)::value, nq = (q + 1) & 3, gq = (q + 2) & 3, fq = (q + 3) & 3;
+        if constexpr (KG == 2) {
+            // one k-step: the wave's chunk of stage q, the operands of its chunk of the next stage
+            // built beside it, and all 12 loads of the stage three ahead
+            kstep(bw[q & 1], bw[~q & 1], wr[nq], pr[nq], grp, q, 0, nq, 0, [&](int i) {
+                if (i == -1) arrive_w(std::integral_constant<int, PER_STAGE>{}, wr[nq], pr[nq]);
+                if (i == 1) asm volatile("s_barrier" ::: "memory");
+                if (i == 50) load_w_piece(0, 0, wr[fq], pr[fq]);
+                if (i == 53) load_w_piece(0, 2, wr[fq], pr[fq]);
+                if (i == 57) load_w_piece(1, 0, wr[fq], pr[fq]);
+                if (i == 61) load_w_piece(1, 2, wr[fq], pr[fq]);
+            }, [&](int i) { return i >= 5 && i <= 47 && (i - 5) % 6 == 0 ? fq * 8 + (i - 5) / 6 : -1; });
+            if (q == 0)
+                load_side_advance();
+            else
+                ++l_s;
+#pragma unroll
+            for (int f = 0; f < 4; ++f)
+#pragma unroll
+                for (int d = 0; d < 4; ++d) asm volatile("" : "+v"(bw[~q & 1][f][d]));
+            SB();
+        } else {
         kstep(bw[0], bw[1], wr[q], pr[q], 1, q, 0, q, 1, [&](int i) {
             if (i == 27) load_w_piece(0, 0, wr[gq], pr[gq]);
             if (i == 33) load_w_piece(0, 1, wr[gq], pr[gq]);
@@ -278,6 +318,7 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
 #pragma unroll
             for (int d = 0; d < 4; ++d) asm volatile("" : "+v"(bw[0][f][d]));
         SB();
+        }
     };
     const std::integral_constant<int, 0> q0{};
     const std::integral_constant<int, 1> q1{};
@@ -290,8 +331,13 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
     int M = 0;
     __half *Y = nullptr;
     int32_t *ACC = nullptr;
-    auto epilogue = [&](auto full_tag, int bm, int ng, const float *sx_tile, const float *sw_wave) {
+    // KG = 1: all sixteen token fragments.  KG = 2: the eight from TF0 on, each element the sum of
+    // this wave's and of the other k group's, which lies in LDS at `other` ([fragment][4 channel
+    // fragments] x 64 lanes x 16 bytes).
+    auto epilogue = [&](auto full_tag, auto tf0_tag, int bm, int ng, const float *sx_tile, const float *sw_wave,
+                        const int8_t *other) {
         constexpr bool FULL = decltype(full_tag)::value;
+        constexpr int TF0 = decltype(tf0_tag)::value;
         const uint32_t lane_off = (uint32_t)j16 * (uint32_t)N + (uint32_t)(64 * ng + 8 * kq);  // in elements
         float swv[2][8];
         if (Y) {
@@ -303,10 +349,22 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
                     swv[h][4 * e4 + 0] = v.x, swv[h][4 * e4 + 1] = v.y, swv[h][4 * e4 + 2] = v.z, swv[h][4 * e4 + 3] = v.w;
                 }
         }
-        static_for<0, TF>([&](auto tf_tag) {
+        static_for<TF0, TF0 + TF / KG>([&](auto tf_tag) {
             constexpr int tf = decltype(tf_tag)::value;
             const int row0 = bm * 256 + 16 * tf;  // wave-uniform
             const bool live = FULL || row0 + j16 < M;
+            v4i add[4];
+            if constexpr (KG == 2) {
+#pragma unroll
+                for (int f = 0; f < 4; ++f)
+                    add[f] = *reinterpret_cast<const v4i *>(other + ((tf - TF0) * 4 + f) * 1024 + lane * 16);
+            }
+            auto element = [&](int f, int v) {
+                if constexpr (KG == 2)
+                    return acc_elem(tf, f, v) + add[f][v];
+                else
+                    return acc_elem(tf, f, v);
+            };
             if (Y) {
                 const float sxv = sx_tile[16 * tf + j16];
                 const char *row = reinterpret_cast<const char *>(Y) + (size_t)row0 * ((size_t)N * 2);
@@ -315,7 +373,7 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
                     v4i out;
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const float x0 = (float)acc_elem(tf, h, v) * sxv, x1 = (float)acc_elem(tf, 2 + h, v) * sxv;
+                        const float x0 = (float)element(h, v) * sxv, x1 = (float)element(2 + h, v) * sxv;
                         out[v] = (int)scale_pair_to_half2(x0, swv[h][2 * v], x1, swv[h][2 * v + 1]);
                     }
                     if (live) {
@@ -332,8 +390,8 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
                 for (int h = 0; h < 2; ++h)
 #pragma unroll
                     for (int e4 = 0; e4 < 2; ++e4) {
-                        const v4i out{acc_elem(tf, h, 2 * e4), acc_elem(tf, 2 + h, 2 * e4), acc_elem(tf, h, 2 * e4 + 1),
-                                      acc_elem(tf, 2 + h, 2 * e4 + 1)};
+                        const v4i out{element(h, 2 * e4), element(2 + h, 2 * e4), element(h, 2 * e4 + 1),
+                                      element(2 + h, 2 * e4 + 1)};
                         if (live) {
                             if (h == 0 && e4 == 0)
                                 asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" : : "v"(lane_off * 4), "v"(out), "s"(row) : "memory");
@@ -350,34 +408,60 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
         });
     };
 
-    // ---- pipeline fill: stages 0 and 1 of the first tile and the first four loads of stage 2 ----
-    load_side_tile(l_lid);
+    // KG = 2: the eight fragments from TF0 on go to this wave's 32 KiB of the LDS ring
+    auto send_fragments = [&](auto tf0_tag) {
+        constexpr int TF0 = decltype(tf0_tag)::value;
+        int8_t *mine = lds + wave * STAGE + lane * 16;
+        static_for<0, 32>([&](auto i_tag) {
+            constexpr int i = decltype(i_tag)::value;
+            *reinterpret_cast<v4i *>(mine + i * 1024) = v4i{acc_elem(TF0 + i / 4, i % 4, 0), acc_elem(TF0 + i / 4, i % 4, 1),
+                                                            acc_elem(TF0 + i / 4, i % 4, 2), acc_elem(TF0 + i / 4, i % 4, 3)};
+        });
+    };
+
+    // ---- pipeline fill: stages 0 and 1 of a tile and the first four loads of stage 2 (KG = 2:
+    // stages 0, 1 and 2) ---------------------------------------------------------------------------
+    auto fill = [&] {
+        load_side_tile(l_lid);
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
+        for (int q = 0; q < (KG == 2 ? 3 : 2); ++q) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) issue_x1(q, i);
+            for (int i = 0; i < 8; ++i) issue_x1(q, i);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            load_w_piece(t, 0, wr[q], pr[q]);
-            load_w_piece(t, 1, wr[q], pr[q]);
-            load_w_piece(t, 2, wr[q], pr[q]);
+            for (int t = 0; t < 2; ++t) {
+                load_w_piece(t, 0, wr[q], pr[q]);
+                if (KG == 1) load_w_piece(t, 1, wr[q], pr[q]);
+                load_w_piece(t, 2, wr[q], pr[q]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (KG == 2)
+                ++l_s;
+            else
+                load_side_advance();
         }
-        __builtin_amdgcn_sched_barrier(0);
-        load_side_advance();
-    }
+        if (KG == 1) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) issue_x1(2, i);
-    arrive_w(std::integral_constant<int, PER_STAGE + 4>{}, wr[0], pr[0]);  // and X(0) of this wave is in LDS
-    asm volatile("s_barrier" ::: "memory");
-    first_operands(0);
-    __builtin_amdgcn_sched_barrier(0);
+            for (int i = 0; i < 4; ++i) issue_x1(2, i);
+        }
+        // X(0) of this wave is in LDS, W(0) in its registers
+        arrive_w(std::integral_constant<int, KG == 2 ? 2 * PER_STAGE : PER_STAGE + 4>{}, wr[0], pr[0]);
+        asm volatile("s_barrier" ::: "memory");
+        first_operands(0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    if (KG == 1) fill();
 
     // ---- the block's tiles ---------------------------------------------------------------------
     uint32_t sx_par = 0;  // which of the two copies of the tile's scales is this tile's
     for (int lid = (int)blockIdx.x; lid < tiles; lid += G) {
         const SoloTile cur = src.tile(lid, G);
-        const int bm = cur.bm, ng = cur.bn * 4 + wave;
+        const int bm = cur.bm, ng = cur.bn * WPB + colw;
         M = cur.M, Y = cur.Y, ACC = cur.ACC;
+        if (KG == 2) {
+            l_lid = lid;
+            l_s = 0;
+            fill();
+        }
         // the tile's 256 activation scales and the wave's 64 channel scales go to LDS now (see solo_body)
         if (Y) {
             asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
@@ -403,11 +487,42 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
         // (the accumulators are read inside inline assembly, where the compiler does not count the
         // wait states an MFMA result needs before it is read)
         asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
-        if (ng < (N >> 6)) {
-            if (bm * 256 + 256 <= M)
-                epilogue(std::true_type{}, bm, ng, sx_tile, sw_wave);
+        const bool full = bm * 256 + 256 <= M;
+        const std::integral_constant<int, 0> f0{};
+        if constexpr (KG == 1) {
+            if (ng < (N >> 6)) {
+                if (full)
+                    epilogue(std::true_type{}, f0, bm, ng, sx_tile, sw_wave, nullptr);
+                else
+                    epilogue(std::false_type{}, f0, bm, ng, sx_tile, sw_wave, nullptr);
+            }
+        } else {
+            // every load of this tile has landed (those past its end too) and every wave is past
+            // its last read of the ring: the ring is free for the exchange.  Group 0 finishes
+            // fragments 0..7 and sends 8..15, group 1 the other way round.
+            const std::integral_constant<int, 8> f8{};
+            wait_vmcnt0();
+            __syncthreads();
+            if (grp == 0)
+                send_fragments(f8);
             else
-                epilogue(std::false_type{}, bm, ng, sx_tile, sw_wave);
+                send_fragments(f0);
+            __syncthreads();
+            const int8_t *other = lds + (wave ^ 2) * STAGE;
+            if (ng < (N >> 6)) {
+                if (grp == 0) {
+                    if (full)
+                        epilogue(std::true_type{}, f0, bm, ng, sx_tile, sw_wave, other);
+                    else
+                        epilogue(std::false_type{}, f0, bm, ng, sx_tile, sw_wave, other);
+                } else {
+                    if (full)
+                        epilogue(std::true_type{}, f8, bm, ng, sx_tile, sw_wave, other);
+                    else
+                        epilogue(std::false_type{}, f8, bm, ng, sx_tile, sw_wave, other);
+                }
+            }
+            __syncthreads();  // the ring is read; the next tile's fill may overwrite it
         }
         clear_acc();
         asm volatile("s_nop 3" ::: "memory");
@@ -417,11 +532,11 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
     wait_vmcnt0();
 }
 
-template <bool G128>
+template <bool G128, int KG = 1>
 __global__ __launch_bounds__(256, 1) void w4a8_solo16_pt_kernel(
     int M, int N, int K, const int8_t *__restrict__ X, const float *__restrict__ sx,
     const u32x4 *__restrict__ Wp, const uint8_t *__restrict__ gp, const float *__restrict__ sw,
     __half *__restrict__ Y, int32_t *__restrict__ ACC, int blocks_m, int blocks_n, int S)
 {
-    solo16_body<G128>(SoloDense{M, N, X, sx, Wp, gp, sw, Y, ACC, blocks_m, blocks_n, S}, N, K);
+    solo16_body<G128, KG>(SoloDense{M, N, X, sx, Wp, gp, sw, Y, ACC, blocks_m, blocks_n, S}, N, K);
 }

@@ -468,7 +468,6 @@ static size_t solo_ws_bytes(int M, int N, int S)
 template <int KG, int SPLIT = 0, bool SHAPE16 = false>
 static int launch_solo_pt(const Args &a)
 {
-    static_assert(!SHAPE16 || KG == 1, "the 16x16x64 form has one k group");
     if (a.K % 512 != 0) return fail(LQ_ERR_INVALID, "the 256-row tile variants need K %% 512 == 0, got %d", a.K);
     constexpr int TN = 256 / KG;
     const int blocks_n = (a.N + TN - 1) / TN, blocks_m = (a.M + 255) / 256;
@@ -506,12 +505,12 @@ static int launch_solo_pt(const Args &a)
     int32_t *ACC = S > 1 ? partials : a.ACC;
     if constexpr (SHAPE16) {
         if (a.group == 128) {
-            if (int rc = allow_lds(w4a8_solo16_pt_kernel<true>, lds_bytes)) return rc;
-            hipLaunchKernelGGL((w4a8_solo16_pt_kernel<true>), dim3((unsigned)grid), dim3(256), lds_bytes, a.stream, a.M,
+            if (int rc = allow_lds(w4a8_solo16_pt_kernel<true, KG>, lds_bytes)) return rc;
+            hipLaunchKernelGGL((w4a8_solo16_pt_kernel<true, KG>), dim3((unsigned)grid), dim3(256), lds_bytes, a.stream, a.M,
                                a.N, a.K, a.X, a.sx, a.Wp, a.gp, a.sw, Y, ACC, blocks_m, blocks_n, S);
         } else {
-            if (int rc = allow_lds(w4a8_solo16_pt_kernel<false>, lds_bytes)) return rc;
-            hipLaunchKernelGGL((w4a8_solo16_pt_kernel<false>), dim3((unsigned)grid), dim3(256), lds_bytes, a.stream, a.M,
+            if (int rc = allow_lds(w4a8_solo16_pt_kernel<false, KG>, lds_bytes)) return rc;
+            hipLaunchKernelGGL((w4a8_solo16_pt_kernel<false, KG>), dim3((unsigned)grid), dim3(256), lds_bytes, a.stream, a.M,
                                a.N, a.K, a.X, a.sx, a.Wp, a.gp, a.sw, Y, ACC, blocks_m, blocks_n, S);
         }
     } else if (a.group == 128) {
@@ -633,6 +632,8 @@ static const Variant kVariants[] = {
     {"solo_pt_m256", &launch_solo_pt<1>, 0, 1, 8, 512},
     {"solo_g2_m256", &launch_solo_pt<2>, 0, 1, 8, 512},
     {"solo16_pt_m256", &launch_solo_pt<1, 0, true>, 0, 1, 8, 512},
+    {"solo16_g2_m256", &launch_solo_pt<2, 0, true>, 0, 1, 8, 512},
+    {"solo16_g2_sk_m256", &launch_solo_pt<2, -1, true>, 0, 1, 8, 512},
     {"solo_sk_m256", &launch_solo_pt<1, -1>, 0, 1, 8, 512},
     {"solo_g2_sk_m256", &launch_solo_pt<2, -1>, 0, 1, 8, 512},
     // --- the same kernels with a named number of K slices: the split paths at sizes where the
@@ -650,6 +651,7 @@ static const Variant kVariants[] = {
     {"duo_dl_m128_s2", &launch_duo_dl<2>, 0, 1, 1},
     {"solo_pt_m256_s2", &launch_solo_pt<1, 2>, 256, 1, 16, 1024},
     {"solo_g2_m256_s4", &launch_solo_pt<2, 4>, 256, 1, 32, 2048},
+    {"solo16_g2_m256_s2", &launch_solo_pt<2, 2, true>, 256, 1, 16, 1024},
     // --- ablation forms (Sec. 7.3), measured by the benchmark, never dispatched ---
     {"excp_m128", &launch_excp, 0, 1, 1},
     {"widened_dq_m128", &launch_duo_widened, 0, 1, 1},
@@ -710,7 +712,11 @@ static TiledCosts tiled_costs(long long t128, long long t256, long long t2, int 
     // (those were measured with the 32x32x32 MFMA; on the 16x16x64 one the 256 x 256 tiles take 8 % less)
     const double solo = (t256 <= kAssumedCUs ? 0.734 + 0.94 * t256 / kAssumedCUs
                                              : 2.0 * ((t256 + kAssumedCUs - 1) / kAssumedCUs) * 0.86) * short_k * 0.92;
-    const double g2 = 16 * t2 > 8.5 * kAssumedCUs && t2 <= kAssumedCUs ? (0.406 + 0.56 * t2 / kAssumedCUs) * short_k : 1e30;
+    // (... and the 256 x 128 tiles 1 to 5 % less, most on a full round: 57.4 against 60.4 us at 256 tiles,
+    // 48.8 against 50.5 at 192, 28.3 against 28.5 at 172 tiles with K = 4096)
+    const double g2 = 16 * t2 > 8.5 * kAssumedCUs && t2 <= kAssumedCUs
+                          ? (0.406 + 0.56 * t2 / kAssumedCUs) * short_k * (1.0 - 0.05 * t2 / kAssumedCUs)
+                          : 1e30;
     return TiledCosts{duo, solo, g2};
 }
 static TiledCosts tiled_costs(int M, int N, int K)
@@ -771,7 +777,7 @@ static int select_variant(int M, int N, int K)
     if (M <= 64 && N / 32 <= 512 && !(M >= 48 && N / 32 > 128 && N / 32 <= 256 && K >= 24576))
         return find_variant("stream_m64");
     // 256-row tiles with one wave per SIMD where their whole rounds come out ahead
-    if (const int form = solo_form_that_pays(M, N, K)) return find_variant(form == 1 ? "solo16_pt_m256" : "solo_g2_m256");
+    if (const int form = solo_form_that_pays(M, N, K)) return find_variant(form == 1 ? "solo16_pt_m256" : "solo16_g2_m256");
     // ... and, with very long K and row tiles that are nearly full, their 256 x 128 form with K
     // slices across blocks where tiles x slices come to one round of at least three quarters of the
     // CUs (256 x 8192 x 28672: 65 against 70 us; 512 rows: 114 against 121; 256 x 6144 x 16384: 37
@@ -780,7 +786,7 @@ static int select_variant(int M, int N, int K)
         const long long t2 = (long long)((M + 255) / 256) * ((N + 127) / 128);
         if (t2 <= kAssumedCUs / 2) {
             const int slices = solo_split((int)t2, K, (int)kAssumedCUs);
-            if (slices > 1 && 4 * t2 * slices >= 3 * kAssumedCUs) return find_variant("solo_g2_sk_m256");
+            if (slices > 1 && 4 * t2 * slices >= 3 * kAssumedCUs) return find_variant("solo16_g2_sk_m256");
         }
     }
     // more 128 x 256 tiles than CUs (blocks of one k group): the deeper memory pipeline of the

@@ -44,14 +44,14 @@ def test_dispatcher_families_on_the_workloads():
         elif s.M <= 64 and s.N <= 16384:
             assert name == "stream_m64", (s.name, name)
         else:
-            assert name in ("duo_m64", "duo_m128", "duo_dl_m128", "duo_pt_m128", "solo16_pt_m256", "solo_g2_m256",
-                            "solo_g2_sk_m256"), (s.name, name)
+            assert name in ("duo_m64", "duo_m128", "duo_dl_m128", "duo_pt_m128", "solo16_pt_m256", "solo16_g2_m256",
+                            "solo16_g2_sk_m256"), (s.name, name)
             tiles128 = -(-s.M // 128) * -(-s.N // 256)
             form = _solo_form(s.M, s.N, s.K)
-            if name == "solo_g2_sk_m256":   # K slices across blocks: very long K, one round of 256 x 128 tiles x slices
+            if name == "solo16_g2_sk_m256":   # K slices across blocks: very long K, one round of 256 x 128 tiles x slices
                 assert not form and s.K >= 16384 and -(-s.M // 256) * -(-s.N // 128) <= 128, (s.name, name)
             elif form:                  # 256-row tiles, one wave per SIMD, where their whole rounds come out ahead
-                assert name == ("solo16_pt_m256" if form == 1 else "solo_g2_m256"), (s.name, name)
+                assert name == ("solo16_pt_m256" if form == 1 else "solo16_g2_m256"), (s.name, name)
             elif tiles128 > 256:      # more tiles than CUs: the direct-to-LDS pipeline, persistent where it fits
                 assert name == ("duo_pt_m128" if _pt_fits(s.M, s.N, s.K) else "duo_dl_m128"), (s.name, name)
             elif tiles128 > 128 and s.K % 512 == 0:   # more than half a round: persistent, one block per CU
@@ -84,23 +84,23 @@ def test_dispatcher_boundaries():
     assert _pick(64, 8192, 28672, 128) in ("duo_m64", "duo_m128") and _pick(48, 6144, 28672, 128) in ("duo_m64", "duo_m128")
     assert _pick(64, 4096, 28672, 128) == "stream_m64" and _pick(64, 8192, 16384, 128) == "stream_m64"
     assert _pick(64, 28672, 8192) == "duo_m64" and _pick(65, 4096, 4096) == "duo_m64"
-    assert _pick(256, 28672, 8192) == "solo_g2_m256"           # 224 tiles of 256 x 128: one round, 62 against 66 us
-    assert _pick(192, 28672, 8192) == "solo_g2_m256" and _pick(128, 28672, 8192) == "duo_m128"
-    assert _pick(512, 4096, 4096) == "duo_m64" and _pick(1025, 4096, 4096) == "solo_g2_m256"
+    assert _pick(256, 28672, 8192) == "solo16_g2_m256"           # 224 tiles of 256 x 128: one round, 62 against 66 us
+    assert _pick(192, 28672, 8192) == "solo16_g2_m256" and _pick(128, 28672, 8192) == "duo_m128"
+    assert _pick(512, 4096, 4096) == "duo_m64" and _pick(1025, 4096, 4096) == "solo16_g2_m256"
     # very long K, nearly full 256-row tiles: the 256 x 128 tiles with K slices across blocks
-    assert _pick(256, 8192, 28672, 128) == "solo_g2_sk_m256" and _pick(512, 8192, 28672, 128) == "solo_g2_sk_m256"
-    assert _pick(256, 6144, 16384, 128) == "solo_g2_sk_m256" and _pick(250, 8192, 16384) == "solo_g2_sk_m256"
+    assert _pick(256, 8192, 28672, 128) == "solo16_g2_sk_m256" and _pick(512, 8192, 28672, 128) == "solo16_g2_sk_m256"
+    assert _pick(256, 6144, 16384, 128) == "solo16_g2_sk_m256" and _pick(250, 8192, 16384) == "solo16_g2_sk_m256"
     assert _pick(256, 4096, 16384, 128) == "duo_m64"           # (four slices of 32 tiles: half a round)
     assert _pick(128, 8192, 28672, 128) in ("duo_m64", "duo_m128") and _pick(384, 8192, 28672, 128) == "duo_m128"
     assert _pick(256, 8192, 14336, 128) in ("duo_m64", "duo_m128")
     assert _pick(256, 8192, 8192) == "duo_m64" and _pick(256, 10240, 8192, 128) == "duo_m128"
     assert _pick(128, 4096, 256) == "duo_m128"                 # one k unit: no room for two k groups
     # 256-row tiles, one wave per SIMD: 256 x 128 as one round on more than half of the CUs ...
-    assert _pick(1024, 8192, 8192) == "solo_g2_m256" and _pick(960, 8192, 8192) == "solo_g2_m256"
-    assert _pick(2048, 4096, 11264) == "solo_g2_m256"
-    assert _pick(768, 8192, 8192) == "solo_g2_m256"            # 192 tiles: 54 against 58 us
-    assert _pick(512, 9216, 8192) == "solo_g2_m256" and _pick(512, 11008, 4096) == "solo_g2_m256"   # 144 / 172 tiles
-    assert _pick(512, 10240, 2048) in ("solo_g2_m256", "duo_pt_m128") and _pick(1024, 5120, 8192) == "solo_g2_m256"
+    assert _pick(1024, 8192, 8192) == "solo16_g2_m256" and _pick(960, 8192, 8192) == "solo16_g2_m256"
+    assert _pick(2048, 4096, 11264) == "solo16_g2_m256"
+    assert _pick(768, 8192, 8192) == "solo16_g2_m256"            # 192 tiles: 54 against 58 us
+    assert _pick(512, 9216, 8192) == "solo16_g2_m256" and _pick(512, 11008, 4096) == "solo16_g2_m256"   # 144 / 172 tiles
+    assert _pick(512, 10240, 2048) in ("solo16_g2_m256", "duo_pt_m128") and _pick(1024, 5120, 8192) == "solo16_g2_m256"
     assert _pick(512, 8192, 8192) == "duo_m128" and _pick(1024, 4096, 8192) in ("duo_m64", "duo_m128")   # 128 tiles: equal or behind
     assert _pick(384, 8192, 8192) == "duo_m128"                # (a third of the second row tile's work is lost)
     # ... 256 x 256 where their whole rounds cost less than the rounds of 128-row tiles, two blocks to a CU
@@ -150,7 +150,7 @@ def test_variant_table_is_consistent():
         # row limits are part of the names' families
         limit = (16 if name.startswith("stream16") else 64 if name.startswith("stream_m64")
                  else 32 if name.startswith(("stream_f", "stream_x_", "stream_m32"))
-                 else 256 if name in ("solo_pt_m256_s2", "solo_g2_m256_s4") else None)
+                 else 256 if name in ("solo_pt_m256_s2", "solo_g2_m256_s4", "solo16_g2_m256_s2") else None)
         if limit:
             assert api.w4a8_variant_supports(v, limit, 256, 2048, 64)
             assert not api.w4a8_variant_supports(v, limit + 1, 256, 2048, 64)

@@ -493,7 +493,7 @@ def test_batch_beyond_32_bit_offsets_of_x():
     assert np.array_equal(ACC2.cpu().numpy(), ref), "accumulators of the named variant differ"
 
 
-@pytest.mark.parametrize("kernel", ["duo_pt_m128", "solo_pt_m256", "solo_g2_m256", "solo16_pt_m256"])
+@pytest.mark.parametrize("kernel", ["duo_pt_m128", "solo_pt_m256", "solo_g2_m256", "solo16_pt_m256", "solo16_g2_m256"])
 @pytest.mark.parametrize("M,N,K,g", [(1541, 12352, 512, 64), (2048, 10240, 1024, 128), (700, 2048, 1536, 64)])
 def test_persistent_tile_kernel(M, N, K, g, kernel):
     """The persistent forms of the tiled kernel (blocks walk several tiles as one stream of
@@ -523,7 +523,8 @@ def test_persistent_tile_kernel(M, N, K, g, kernel):
     assert np.array_equal(ACC2.cpu().numpy().astype(np.int64), ref), "accumulator-only call differs"
 
 
-@pytest.mark.parametrize("kernel", ["solo_sk_m256", "solo_g2_sk_m256", "solo_pt_m256_s2", "solo_g2_m256_s4"])
+@pytest.mark.parametrize("kernel", ["solo_sk_m256", "solo_g2_sk_m256", "solo16_g2_sk_m256", "solo_pt_m256_s2", "solo_g2_m256_s4",
+                                    "solo16_g2_m256_s2"])
 @pytest.mark.parametrize("M,N,K,g", [(300, 640, 2048, 64), (256, 1024, 4608, 128), (520, 320, 1024, 64),
                                      (200, 448, 4096, 128)])
 def test_solo_k_slices(M, N, K, g, kernel):
@@ -560,7 +561,7 @@ def test_k_slices_through_the_dispatcher():
     import torch
 
     M, N, K, g = 250, 6144, 16384, 128
-    assert api.w4a8_variant_name(api.w4a8_select_variant(M, N, K, g)) == "solo_g2_sk_m256"
+    assert api.w4a8_variant_name(api.w4a8_select_variant(M, N, K, g)) == "solo16_g2_sk_m256"
     need = api.w4a8_gemm_workspace_size(M, N, K, g)
     assert need >= 4 * M * N * 4
     _say(f"K slices through the dispatcher M={M} N={N} K={K} g={g}, workspace {need} bytes")
