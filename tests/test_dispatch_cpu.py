@@ -124,15 +124,19 @@ def _plan(M, N, K, g=64):
 
 
 def test_two_launch_plans():
-    """Batches whose 256 x 256 tiles make whole rounds of the chip plus a rest of at most 256 rows
-    run as two launches over consecutive rows; everything else as one, which is then the
-    dispatcher's choice."""
+    """Batches whose 256 x 256 tiles make whole rounds of the chip plus a rest of at most 256 rows,
+    or a larger rest that is one round of 256 x 128 tiles, run as two launches over consecutive
+    rows; everything else as one, which is then the dispatcher's choice."""
     assert _plan(4096 + 40, 8192, 8192) == [(4096, "solo16_pt_m256"), (40, "stream_m64")]      # a ragged tail of the batch
     assert _plan(2048 + 100, 8192, 4096) == [(2048, "solo16_pt_m256"), (100, "duo_m64")]
     assert _plan(1024 + 30, 16384, 4096, 128) == [(1024, "solo16_pt_m256"), (30, "stream_m32")]
-    # larger rests stay in one launch (measured equal or behind as two)
-    assert _plan(2048, 10240, 8192, 128) == [(2048, "duo_pt_m128")] and _plan(3072, 8192, 8192) == [(3072, "duo_pt_m128")]
-    assert _plan(6000, 4096, 4096) == [(6000, "duo_pt_m128")]
+    # larger rests that fill most of a round of 256 x 128 tiles (143 against 150 us, 157 against 162, 240 against 255)
+    assert _plan(2048, 10240, 8192, 128) == [(1536, "solo16_pt_m256"), (512, "solo16_g2_m256")]
+    assert _plan(3072, 8192, 8192) == [(2048, "solo16_pt_m256"), (1024, "solo16_g2_m256")]
+    assert _plan(1280, 28672, 8192, 128) == [(1024, "solo16_pt_m256"), (256, "solo16_g2_m256")]
+    assert _plan(2748, 8192, 4096) == [(2048, "solo16_pt_m256"), (700, "solo16_g2_m256")]
+    # ... others stay in one launch
+    assert _plan(2560, 8192, 8192) == [(2560, "duo_pt_m128")] and _plan(2748, 8192, 512) == [(2748, _pick(2748, 8192, 512))]
     for M, N, K, g in [(4096, 8192, 8192, 64), (2048, 28672, 8192, 128), (1536, 8192, 8192, 64), (16, 8192, 8192, 64),
                        (256, 8192, 8192, 64), (2048, 11008, 4096, 64), (3072, 8192, 8448, 64), (0, 4096, 4096, 64)]:
         assert _plan(M, N, K, g) == [(M, _pick(M, N, K, g))], (M, N, K)
