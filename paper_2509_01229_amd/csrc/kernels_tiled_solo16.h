@@ -334,13 +334,32 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
     // KG = 1: all sixteen token fragments.  KG = 2: the eight from TF0 on, each element the sum of
     // this wave's and of the other k group's, which lies in LDS at `other` ([fragment][4 channel
     // fragments] x 64 lanes x 16 bytes).
+    // The FP16 outputs and the INT32 sums are two passes over the accumulators (a call usually asks
+    // for one of them): no test per fragment, the activation scales of all fragments read from LDS
+    // up front, the row base moved by additions, the other group's sums fetched one fragment ahead.
     auto epilogue = [&](auto full_tag, auto tf0_tag, int bm, int ng, const float *sx_tile, const float *sw_wave,
                         const int8_t *other) {
         constexpr bool FULL = decltype(full_tag)::value;
         constexpr int TF0 = decltype(tf0_tag)::value;
+        constexpr int NF = TF / KG;
         const uint32_t lane_off = (uint32_t)j16 * (uint32_t)N + (uint32_t)(64 * ng + 8 * kq);  // in elements
-        float swv[2][8];
+        const int row_first = bm * 256 + 16 * TF0;  // wave-uniform
+        v4i add[2][4];
+        auto fetch_other = [&](int i) {
+            if constexpr (KG == 2) {
+#pragma unroll
+                for (int f = 0; f < 4; ++f)
+                    add[i & 1][f] = *reinterpret_cast<const v4i *>(other + (i * 4 + f) * 1024 + lane * 16);
+            }
+        };
+        auto element = [&](int i, int f, int v) {
+            if constexpr (KG == 2)
+                return acc_elem(TF0 + i, f, v) + add[i & 1][f][v];
+            else
+                return acc_elem(TF0 + i, f, v);
+        };
         if (Y) {
+            float swv[2][8], sxv[NF];
 #pragma unroll
             for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -348,32 +367,21 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
                     const float4 v = *reinterpret_cast<const float4 *>(sw_wave + 32 * h + 8 * kq + 4 * e4);
                     swv[h][4 * e4 + 0] = v.x, swv[h][4 * e4 + 1] = v.y, swv[h][4 * e4 + 2] = v.z, swv[h][4 * e4 + 3] = v.w;
                 }
-        }
-        static_for<TF0, TF0 + TF / KG>([&](auto tf_tag) {
-            constexpr int tf = decltype(tf_tag)::value;
-            const int row0 = bm * 256 + 16 * tf;  // wave-uniform
-            const bool live = FULL || row0 + j16 < M;
-            v4i add[4];
-            if constexpr (KG == 2) {
 #pragma unroll
-                for (int f = 0; f < 4; ++f)
-                    add[f] = *reinterpret_cast<const v4i *>(other + ((tf - TF0) * 4 + f) * 1024 + lane * 16);
-            }
-            auto element = [&](int f, int v) {
-                if constexpr (KG == 2)
-                    return acc_elem(tf, f, v) + add[f][v];
-                else
-                    return acc_elem(tf, f, v);
-            };
-            if (Y) {
-                const float sxv = sx_tile[16 * tf + j16];
-                const char *row = reinterpret_cast<const char *>(Y) + (size_t)row0 * ((size_t)N * 2);
+            for (int i = 0; i < NF; ++i) sxv[i] = sx_tile[16 * (TF0 + i) + j16];
+            const size_t step = (size_t)N * 32;  // bytes from one token fragment to the next
+            const char *row = reinterpret_cast<const char *>(Y) + (size_t)row_first * ((size_t)N * 2);
+            fetch_other(0);
+            static_for<0, NF>([&](auto i_tag) {
+                constexpr int i = decltype(i_tag)::value;
+                if (i + 1 < NF) fetch_other(i + 1);
+                const bool live = FULL || row_first + 16 * i + j16 < M;
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     v4i out;
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const float x0 = (float)element(h, v) * sxv, x1 = (float)element(2 + h, v) * sxv;
+                        const float x0 = (float)element(i, h, v) * sxv[i], x1 = (float)element(i, 2 + h, v) * sxv[i];
                         out[v] = (int)scale_pair_to_half2(x0, swv[h][2 * v], x1, swv[h][2 * v + 1]);
                     }
                     if (live) {
@@ -383,15 +391,25 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
                             asm volatile("global_store_dwordx4 %0, %1, %2 offset:64\n\ts_nop 1" : : "v"(lane_off * 2), "v"(out), "s"(row) : "memory");
                     }
                 }
-            }
-            if (ACC) {
-                const char *row = reinterpret_cast<const char *>(ACC) + (size_t)row0 * ((size_t)N * 4);
+                row += step;
+                asm volatile("" : "+s"(row));
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        }
+        if (ACC) {
+            const size_t step = (size_t)N * 64;
+            const char *row = reinterpret_cast<const char *>(ACC) + (size_t)row_first * ((size_t)N * 4);
+            fetch_other(0);
+            static_for<0, NF>([&](auto i_tag) {
+                constexpr int i = decltype(i_tag)::value;
+                if (i + 1 < NF) fetch_other(i + 1);
+                const bool live = FULL || row_first + 16 * i + j16 < M;
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
 #pragma unroll
                     for (int e4 = 0; e4 < 2; ++e4) {
-                        const v4i out{element(h, 2 * e4), element(2 + h, 2 * e4), element(h, 2 * e4 + 1),
-                                      element(2 + h, 2 * e4 + 1)};
+                        const v4i out{element(i, h, 2 * e4), element(i, 2 + h, 2 * e4), element(i, h, 2 * e4 + 1),
+                                      element(i, 2 + h, 2 * e4 + 1)};
                         if (live) {
                             if (h == 0 && e4 == 0)
                                 asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" : : "v"(lane_off * 4), "v"(out), "s"(row) : "memory");
@@ -403,9 +421,11 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
                                 asm volatile("global_store_dwordx4 %0, %1, %2 offset:144\n\ts_nop 1" : : "v"(lane_off * 4), "v"(out), "s"(row) : "memory");
                         }
                     }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        });
+                row += step;
+                asm volatile("" : "+s"(row));
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        }
     };
 
     // KG = 2: the eight fragments from TF0 on go to this wave's 32 KiB of the LDS ring
