@@ -154,7 +154,7 @@ def test_variant_table_is_consistent():
         # row limits are part of the names' families
         limit = (16 if name.startswith("stream16") else 64 if name.startswith("stream_m64")
                  else 32 if name.startswith(("stream_f", "stream_x_", "stream_m32"))
-                 else 256 if name in ("solo_pt_m256_s2", "solo_g2_m256_s4", "solo16_g2_m256_s2") else None)
+                 else 256 if name in ("solo16_pt_m256_s2", "solo16_g2_m256_s4") else None)
         if limit:
             assert api.w4a8_variant_supports(v, limit, 256, 2048, 64)
             assert not api.w4a8_variant_supports(v, limit + 1, 256, 2048, 64)

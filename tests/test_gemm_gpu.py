@@ -523,8 +523,7 @@ def test_persistent_tile_kernel(M, N, K, g, kernel):
     assert np.array_equal(ACC2.cpu().numpy().astype(np.int64), ref), "accumulator-only call differs"
 
 
-@pytest.mark.parametrize("kernel", ["solo_sk_m256", "solo_g2_sk_m256", "solo16_g2_sk_m256", "solo_pt_m256_s2", "solo_g2_m256_s4",
-                                    "solo16_g2_m256_s2"])
+@pytest.mark.parametrize("kernel", ["solo16_g2_sk_m256", "solo16_pt_m256_s2", "solo16_g2_m256_s4"])
 @pytest.mark.parametrize("M,N,K,g", [(300, 640, 2048, 64), (256, 1024, 4608, 128), (520, 320, 1024, 64),
                                      (200, 448, 4096, 128)])
 def test_solo_k_slices(M, N, K, g, kernel):
