@@ -18,6 +18,8 @@ range (prefill, M=4096, N=K=8192, group 64).  The same JSON line carries
   * configs: every workload row (decode, 7B MLP, 70B layers, prefill sweep), median of five
     batches, with rotating weights and with one weight buffer (cache-warm) side by side;
   * activation_quant: the per-token FP16 -> INT8 quantisation kernel upstream of the GEMM;
+  * ablation_pipeline, ablation_dequant, mfma_shape: the headline shape on the explicit
+    producer / consumer form, with the widened dequantisation, and on the other MFMA shape;
   * grouped_moe: mixture-of-experts layers in one grouped call vs one call per expert;
   * cpu_baseline: the CPU oracle timed on a bounded sample.
 """
@@ -547,6 +549,15 @@ def main():
             out["ablation_dequant"] = {"workload": head.name, "kernel": "duo_m128_s1",
                                        "liquidquant_us": round(t_lq * 1e3, 2), "widened_us": round(t_wd * 1e3, 2),
                                        "widened_over_liquidquant": round(t_wd / t_lq, 3)}
+        # the MFMA shape under a power-bound load: the same 256 x 256 tile kernel (one wave per
+        # SIMD, persistent) on v_mfma_i32_32x32x32_i8 and on v_mfma_i32_16x16x64_i8
+        if "solo_pt_m256" in names and "solo16_pt_m256" in names:
+            t_32 = statistics.median(time_steps(prob, head.M, 30, 5, torch, api, stream, names.index("solo_pt_m256"))
+                                     for _ in range(3))
+            t_16 = statistics.median(time_steps(prob, head.M, 30, 5, torch, api, stream, names.index("solo16_pt_m256"))
+                                     for _ in range(3))
+            out["mfma_shape"] = {"workload": head.name, "mfma_32x32x32_us": round(t_32 * 1e3, 2),
+                                 "mfma_16x16x64_us": round(t_16 * 1e3, 2), "ratio": round(t_32 / t_16, 3)}
         del prob.d_packed[1:], prob.d_gparams[1:]
         torch.cuda.empty_cache()
         out["reference_w8a8_vendor"] = vendor_w8a8_reference(torch, stream)
