@@ -805,12 +805,13 @@ static int select_variant(int M, int N, int K)
 // A batch whose 256 x 256 tiles are whole rounds plus a few rows (4096 + 40 rows on 8192 x 8192)
 // is better run as two launches over consecutive rows: the row blocks that fill whole rounds with
 // the 256 x 256 tiles, and the rest with whatever the dispatcher picks for it -- 226 us against
-// 259 us of the best single kernel there.  For a rest of at most 256 rows, or a larger one that
-// the cost rule gives to one round of 256 x 128 tiles (1536 + 512 rows on the 70B qkv projection:
-// 143 against 150 us; 2048 + 1024 on 8192 x 8192: 157 against 162; 1024 + 256 on 28672 x 8192: 240
-// against 255; 4096 + 1904 on 4096 x 4096 and 4096 + 1024 on 8192 x 8192: equal); with other large
-// rests the kernels for a few hundred rows, the least efficient ones, follow a first launch that
-// has to drain before they start.  Same cost units as solo_form_for; a second launch is charged 5 us
+// 259 us of the best single kernel there.  Also with a larger rest, unless the rest would run on
+// 256 x 256 tiles itself (then the one persistent launch over all tiles is 1 to 5 % ahead of two):
+// 1536 + 512 rows on the 70B qkv projection 143 against 150 us, 2048 + 1024 on 8192 x 8192 157
+// against 162, 1024 + 256 on 28672 x 8192 240 against 255, 2048 + 512 on 8192 x 8192 143 against
+// 156 and on 8192 x 28672 423 against 513, 3072 + 512 on 5120 x 13824 201 against 245, 4096 + 1024
+// on 4096 x 4096 78 against 84 (4096 + 1904 on 4096 x 4096 and 4096 + 1024 on 8192 x 8192: equal).
+// Same cost units as solo_form_for; a second launch is charged 5 us
 // (2048 + 100 rows on 8192 x 4096: 55.7 + 16.2 us against 78.4 us of the best single kernel; 1024 + 30 rows on
 // 16384 x 4096: 56 + 11.3 against 79.7).  Returns
 // the rows of the first piece (M if the batch stays whole).
@@ -827,8 +828,9 @@ static int rows_of_first_launch(int M, int N, int K)
         if (rb >= bm) break;
         if (rb < 1) continue;
         const TiledCosts rest = tiled_costs(M - 256 * rb, N, K);
-        // (a larger rest only where it is a round of 256 x 128 tiles)
-        if (M - 256 * rb > 256 && solo_form_of(rest) != 2) continue;
+        // (a larger rest not where it would be 256 x 256 tiles again: the one persistent launch
+        // over all of them is 1 to 5 % ahead of two)
+        if (M - 256 * rb > 256 && solo_form_of(rest) == 1) continue;
         const double c = rounds * 2.0 * 0.86 * 0.92 * short_k + rest.best() + second_launch;
         if (c < best) best = c, rows = 256 * rb;
     }

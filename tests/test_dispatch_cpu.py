@@ -125,8 +125,8 @@ def _plan(M, N, K, g=64):
 
 def test_two_launch_plans():
     """Batches whose 256 x 256 tiles make whole rounds of the chip plus a rest of at most 256 rows,
-    or a larger rest that is one round of 256 x 128 tiles, run as two launches over consecutive
-    rows; everything else as one, which is then the dispatcher's choice."""
+    or a larger rest that does not take 256 x 256 tiles itself, run as two launches over consecutive
+    rows where the cost rule says so; everything else as one, which is then the dispatcher's choice."""
     assert _plan(4096 + 40, 8192, 8192) == [(4096, "solo16_pt_m256"), (40, "stream_m64")]      # a ragged tail of the batch
     assert _plan(2048 + 100, 8192, 4096) == [(2048, "solo16_pt_m256"), (100, "duo_m64")]
     assert _plan(1024 + 30, 16384, 4096, 128) == [(1024, "solo16_pt_m256"), (30, "stream_m32")]
@@ -135,8 +135,12 @@ def test_two_launch_plans():
     assert _plan(3072, 8192, 8192) == [(2048, "solo16_pt_m256"), (1024, "solo16_g2_m256")]
     assert _plan(1280, 28672, 8192, 128) == [(1024, "solo16_pt_m256"), (256, "solo16_g2_m256")]
     assert _plan(2748, 8192, 4096) == [(2048, "solo16_pt_m256"), (700, "solo16_g2_m256")]
-    # ... others stay in one launch
-    assert _plan(2560, 8192, 8192) == [(2560, "duo_pt_m128")] and _plan(2748, 8192, 512) == [(2748, _pick(2748, 8192, 512))]
+    # ... also a rest on 128-row tiles (143 against 156 us, 423 against 513)
+    assert _plan(2560, 8192, 8192) == [(2048, "solo16_pt_m256"), (512, "duo_m128")]
+    assert _plan(2560, 8192, 28672, 128) == [(2048, "solo16_pt_m256"), (512, "solo16_g2_sk_m256")]
+    # ... but not a rest that would be 256 x 256 tiles again, nor with short K
+    assert _plan(3584, 8192, 8192) == [(3584, "solo16_pt_m256")] and _plan(2304, 11008, 4096) == [(2304, "solo16_pt_m256")]
+    assert _plan(2748, 8192, 512) == [(2748, _pick(2748, 8192, 512))]
     for M, N, K, g in [(4096, 8192, 8192, 64), (2048, 28672, 8192, 128), (1536, 8192, 8192, 64), (16, 8192, 8192, 64),
                        (256, 8192, 8192, 64), (2048, 11008, 4096, 64), (3072, 8192, 8448, 64), (0, 4096, 4096, 64)]:
         assert _plan(M, N, K, g) == [(M, _pick(M, N, K, g))], (M, N, K)

@@ -581,11 +581,11 @@ def test_k_slices_through_the_dispatcher():
 
 
 @pytest.mark.parametrize("M,N,K,g", [(2048 + 100, 8192, 4096, 64), (4096 + 40, 8192, 2048, 128), (1024 + 30, 16384, 4096, 128),
-                                     (2048 + 700, 8192, 4096, 64)])
+                                     (2048 + 700, 8192, 4096, 64), (2048 + 512, 8192, 4096, 128)])
 def test_two_launch_plans(M, N, K, g):
     """Batches that the dispatcher runs as two launches over consecutive rows (whole rounds of
-    256 x 256 tiles, then the rest with its own kernel; the last case a rest of several row tiles
-    with a ragged one): every accumulator and every FP16 output
+    256 x 256 tiles, then the rest with its own kernel; the last cases rests of several row tiles, on
+    256 x 128 tiles with a ragged one and on 64-row tiles with K slices): every accumulator and every FP16 output
     against the exact float64 product, through both public entry points."""
     import torch
 
