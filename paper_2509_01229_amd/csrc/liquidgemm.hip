@@ -670,7 +670,7 @@ static int find_variant(const char *name)
     return -1;
 }
 
-// The 256-row tiles with one wave per SIMD (solo_pt_m256: 256 x 256; solo_g2_m256: 256 x 128
+// The 256-row tiles with one wave per SIMD (solo16_pt_m256: 256 x 256; solo16_g2_m256: 256 x 128
 // with two k groups per block) against the 128 x 256 tiles with two waves per SIMD.  Half the
 // dequantisation per MFMA makes their stage loop shorter -- per 128 x 256 of output and 1024 k,
 // 6.0 us (256 x 256) and 7.0 us (256 x 128) against 7.1 to 7.4 us measured on N = K = 8192 --
