@@ -167,7 +167,8 @@ const char *w4a8_variant_name(int variant);            /* NULL if out of range  
 int w4a8_variant_supports(int variant, int M, int N, int K, int group); /* 1 if it can run the shape */
 int w4a8_select_variant(int M, int N, int K, int group); /* the dispatcher's choice, <0 on error */
 /* What w4a8_gemm / w4a8_gemm_i32 launch for a shape.  A batch whose 256 x 256 tiles make whole
- * rounds of the chip plus a rest of at most 256 rows runs as two launches over consecutive rows: returns the variant
+ * rounds of the chip plus a rest that a kernel of its own serves better (a few rows, or several
+ * hundred on smaller tiles) runs as two launches over consecutive rows: returns the variant
  * of the first, writes its rows to *rows_first (= M when there is one launch only) and the
  * variant of the launch over the remaining rows to *variant_rest (-1 when there is none).
  * <0 on error. */
