@@ -55,7 +55,14 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
     const int j16 = lane & 15, kq = lane >> 4;
     const int grp = KG == 2 ? wave >> 1 : 0;       // KG = 2: the chunk of every stage this wave computes
     const int colw = KG == 2 ? (wave & 1) : wave;  // which 64 channels of the block's 256 / KG
-    const int stages = (K >> 7) / src.slices();  // of a tile's K slice, a multiple of four
+    // Stages of 128 k of a tile's K slice.  The stage loop runs them four at a time: where their
+    // number is 2 mod 4 (K % 512 == 256, one slice), two stages are added whose loads re-read the
+    // last real stage and whose group parameters are replaced, as they arrive, by those of an
+    // all-zero group (s = 0, a = 128: (code * 0 + 128) XOR 0x80 = 0) -- they add nothing.
+    const int stages_real = (K >> 7) / src.slices();
+    const int stages = (stages_real + 3) & ~3;
+    const bool has_pad = stages != stages_real;
+    constexpr uint32_t kZeroGroup = G128 ? 0x8000u : 0x80008000u;
     const int chunks_per_tile = K >> 6;
     const int tiles = src.tiles(), G = (int)gridDim.x;
 
@@ -72,6 +79,7 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
     asm volatile("" : "+v"(wl_t[0]), "+v"(wl_t[1]), "+v"(pl_t[0]), "+v"(pl_t[1]));
     const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) void *)lds;
     int l_lid = (int)blockIdx.x, l_s = 0;  // tile and stage the next prefetch takes
+    int l_e = 0;                           // the stage it reads: l_s, or the last real one for an added stage
     uint32_t xg[8];
     const char *wbase, *pbase;
     const int8_t *ld_X;
@@ -84,7 +92,7 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
 #pragma unroll
         for (int i = 0; i < 8; ++i)
             xg[i] = (uint32_t)min(bm * 256 + 32 * i + ld_row, M - 1) * (uint32_t)K + 16 * ld_c;
-        const size_t s0 = (size_t)t.ks * stages;  // first stage of the K slice
+        const size_t s0 = (size_t)t.ks * stages_real;  // first stage of the K slice
         ld_X = t.X + s0 * 128;
         wbase = reinterpret_cast<const char *>(t.Wp + (size_t)t0 * chunks_per_tile * 64) + s0 * 2048;
         pbase = reinterpret_cast<const char *>(t.gp) + (size_t)t0 * pg_stride + s0 * (G128 ? 64 : 128);
@@ -94,6 +102,10 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
     // q = 0): the other stages advance without a test.  After the block's last tile (KG = 2: of
     // every tile) it falls back four stages and re-reads stages of that tile into LDS stages and
     // registers nobody reads any more.
+    auto load_side_step = [&] {
+        ++l_s;
+        l_e = min(l_s, stages_real - 1);
+    };
     auto load_side_advance = [&] {
         if (++l_s == stages) {
             asm volatile("" ::: "memory");
@@ -105,11 +117,12 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
                 l_s = stages - 4;
             }
         }
+        l_e = min(l_s, stages_real - 1);
     };
     auto issue_x1 = [&](int buf, int i) {
         asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                      : "+v"(wl)
-                     : "v"(xg[i]), "s"(ld_X + (size_t)l_s * 128), "s"(lds0 + buf * STAGE + (4 * i + wave) * 1024)
+                     : "v"(xg[i]), "s"(ld_X + (size_t)l_e * 128), "s"(lds0 + buf * STAGE + (4 * i + wave) * 1024)
                      : "memory", "m0");
     };
     // piece 0, 1 = the codes of the stage's chunk 0, 1 of channel tile t (KG = 2: piece 0 = the
@@ -118,13 +131,13 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
         // (one scalar base per stage for the codes and one for the parameters: the tile is in
         // the lane offset, the chunk in the instruction's immediate)
         if (piece < 2) {
-            const char *wb = wbase + (size_t)l_s * 2048 + (KG == 2 ? grp * 1024 : 0);
+            const char *wb = wbase + (size_t)l_e * 2048 + (KG == 2 ? grp * 1024 : 0);
             if (piece == 0)
                 asm volatile("global_load_dwordx4 %0, %1, %2" : "=&v"(w[t][piece]) : "v"(wl_t[t]), "s"(wb) : "memory");
             else
                 asm volatile("global_load_dwordx4 %0, %1, %2 offset:1024" : "=&v"(w[t][piece]) : "v"(wl_t[t]), "s"(wb) : "memory");
         } else {
-            const char *pb = pbase + (size_t)l_s * (G128 ? 64 : 128);
+            const char *pb = pbase + (size_t)l_e * (G128 ? 64 : 128);
             if (G128)
                 asm volatile("global_load_ushort %0, %1, %2" : "=&v"(p[t].raw) : "v"(pl_t[t]), "s"(pb) : "memory");
             else
@@ -193,7 +206,7 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
     auto mm_x = [&](int i, const v4i (&b)[4], int buf, int xi) {
         asm volatile("s_mov_b32 m0, %4\n\tv_mfma_i32_16x16x64_i8 %0, %5, %6, %0\n\tglobal_load_lds_dwordx4 %2, %3"
                      : "+a"(acc[i >> 2][i & 3]), "+v"(wl)
-                     : "v"(xg[xi]), "s"(ld_X + (size_t)l_s * 128), "s"(lds0 + buf * STAGE + (4 * xi + wave) * 1024),
+                     : "v"(xg[xi]), "s"(ld_X + (size_t)l_e * 128), "s"(lds0 + buf * STAGE + (4 * xi + wave) * 1024),
                        "v"(b[i & 3]), "v"(ax[(i >> 2) & 7])
                      : "memory", "m0");
     };
@@ -271,13 +284,21 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
     // chunk 0, ax its fragments 0..6 on entry): two k-steps.  The second first waits for X and W
     // of the next stage, then meets the other waves and starts the prefetch of the stage three
     // ahead; the 14 loads of a prefetch are spread over the 128 slots up to the next stage's barrier.
+    bool tail_pad = false;  // this trip of the stage loop ends with the two added stages
     auto stage = [&](auto q_tag) {
         constexpr int q = decltype(q_tag)::value, nq = (q + 1) & 3, gq = (q + 2) & 3, fq = (q + 3) & 3;
+        // the parameters that arrive in this stage are those of stage q + 1: an added stage's become
+        // those of an all-zero group
+        auto zero_added = [&] {
+            if constexpr (q == 1 || q == 2) {
+                if (tail_pad) pr[nq][0].raw = kZeroGroup, pr[nq][1].raw = kZeroGroup;
+            }
+        };
         if constexpr (KG == 2) {
             // one k-step: the wave's chunk of stage q, the operands of its chunk of the next stage
             // built beside it, and all 12 loads of the stage three ahead
             kstep(bw[q & 1], bw[~q & 1], wr[nq], pr[nq], grp, q, 0, nq, 0, [&](int i) {
-                if (i == -1) arrive_w(std::integral_constant<int, PER_STAGE>{}, wr[nq], pr[nq]);
+                if (i == -1) arrive_w(std::integral_constant<int, PER_STAGE>{}, wr[nq], pr[nq]), zero_added();
                 if (i == 1) asm volatile("s_barrier" ::: "memory");
                 if (i == 50) load_w_piece(0, 0, wr[fq], pr[fq]);
                 if (i == 53) load_w_piece(0, 2, wr[fq], pr[fq]);
@@ -287,7 +308,7 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
             if (q == 0)
                 load_side_advance();
             else
-                ++l_s;
+                load_side_step();
 #pragma unroll
             for (int f = 0; f < 4; ++f)
 #pragma unroll
@@ -305,10 +326,10 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
         if (q == 1)
             load_side_advance();
         else
-            ++l_s;
+            load_side_step();
         SB();
         kstep(bw[1], bw[0], wr[nq], pr[nq], 0, q, 1, nq, 0, [&](int i) {
-            if (i == -1) arrive_w(std::integral_constant<int, PER_STAGE>{}, wr[nq], pr[nq]);
+            if (i == -1) arrive_w(std::integral_constant<int, PER_STAGE>{}, wr[nq], pr[nq]), zero_added();
             if (i == 1) asm volatile("s_barrier" ::: "memory");
         }, [&](int i) { return i == 7 ? fq * 8 + 0 : i == 21 ? fq * 8 + 1 : i == 35 ? fq * 8 + 2 : i == 49 ? fq * 8 + 3 : -1; });
         // (the next stage's first operands are complete here, also where the next stage is the
@@ -455,7 +476,7 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
             }
             __builtin_amdgcn_sched_barrier(0);
             if (KG == 2)
-                ++l_s;
+                load_side_step();
             else
                 load_side_advance();
         }
@@ -479,7 +500,7 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
         M = cur.M, Y = cur.Y, ACC = cur.ACC;
         if (KG == 2) {
             l_lid = lid;
-            l_s = 0;
+            l_s = l_e = 0;
             fill();
         }
         // the tile's 256 activation scales and the wave's 64 channel scales go to LDS now (see solo_body)
@@ -496,6 +517,7 @@ __device__ __forceinline__ void solo16_body(const Src &src, const int N, const i
                          : "memory", "m0");
         }
         for (int it = 0; it < stages; it += 4) {
+            tail_pad = has_pad && it + 4 >= stages;
             stage(q0);
             stage(q1);
             stage(q2);

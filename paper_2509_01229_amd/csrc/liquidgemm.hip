@@ -446,7 +446,8 @@ static int launch_duo_pt(const Args &a)
 }
 
 // Persistent 256 x 256 tiles, one wave per SIMD (see kernels_tiled_solo.h); KG = 2: 256 x 128
-// tiles with the four waves as two k groups.  Needs K % 512 == 0.
+// tiles with the four waves as two k groups.  Needs K % 512 == 0 (the 16x16x64 forms without K
+// slices: K % 256 == 0).
 // K slices across blocks for outputs with fewer tiles than CUs: every slice a multiple of 512 k,
 // tiles * slices at most the CUs (one round), the partial sums of a slice as an INT32 matrix of
 // its own in the workspace and a second, streaming kernel that adds them up.  Unlike the ticket
@@ -468,7 +469,9 @@ static size_t solo_ws_bytes(int M, int N, int S)
 template <int KG, int SPLIT = 0, bool SHAPE16 = false>
 static int launch_solo_pt(const Args &a)
 {
-    if (a.K % 512 != 0) return fail(LQ_ERR_INVALID, "the 256-row tile variants need K %% 512 == 0, got %d", a.K);
+    // (the 16x16x64 forms without K slices also take K % 512 == 256: two added stages of zero weights)
+    if (a.K % 512 != 0 && !(SHAPE16 && SPLIT <= 0))
+        return fail(LQ_ERR_INVALID, "this 256-row tile variant needs K %% 512 == 0, got %d", a.K);
     constexpr int TN = 256 / KG;
     const int blocks_n = (a.N + TN - 1) / TN, blocks_m = (a.M + 255) / 256;
     if ((long long)a.M * a.K >= (1ll << 32))
@@ -483,7 +486,7 @@ static int launch_solo_pt(const Args &a)
         if ((a.K / 512) % S != 0)
             return fail(LQ_ERR_INVALID, "%d K slices need K %% %d == 0, got %d", S, 512 * S, a.K);
     } else if (SPLIT < 0) {
-        S = solo_split(blocks_m * blocks_n, a.K, a.query ? (int)kAssumedCUs : cus);
+        S = a.K % 512 != 0 ? 1 : solo_split(blocks_m * blocks_n, a.K, a.query ? (int)kAssumedCUs : cus);
         // (a workspace too small for them: the largest number of slices it holds)
         // (a query names its limit, if it has one, in ws_bytes)
         auto too_large = [&](int s) {
@@ -629,8 +632,8 @@ static const Variant kVariants[] = {
     {"duo_m128", &launch_duo<0, 0>, 0, 1, 1},
     {"duo_dl_m128", &launch_duo_dl<0>, 0, 1, 1},
     {"duo_pt_m128", &launch_duo_pt, 0, 1, 8, 512},
-    {"solo16_pt_m256", &launch_solo_pt<1, 0, true>, 0, 1, 8, 512},
-    {"solo16_g2_m256", &launch_solo_pt<2, 0, true>, 0, 1, 8, 512},
+    {"solo16_pt_m256", &launch_solo_pt<1, 0, true>, 0, 1, 4, 512},
+    {"solo16_g2_m256", &launch_solo_pt<2, 0, true>, 0, 1, 4, 512},
     {"solo16_g2_sk_m256", &launch_solo_pt<2, -1, true>, 0, 1, 8, 512},
     // --- the 256-row tile kernels on the 32x32x32 MFMA (what the 16x16x64 forms are measured against) ---
     {"solo_pt_m256", &launch_solo_pt<1>, 0, 1, 8, 512},
@@ -684,7 +687,8 @@ struct TiledCosts {
 // (pt_ok: the persistent form of the 128-row tiles can run the shape)
 static TiledCosts tiled_costs(long long t128, long long t256, long long t2, int K, bool pt_ok)
 {
-    if (K % 512 != 0) return TiledCosts{1.0, 1e30, 1e30};
+    // (K % 512 == 256: the 16x16x64 forms of the 256-row tiles run two added stages of zero weights,
+    // the persistent form of the 128-row tiles does not take the shape -- pt_ok is false then)
     // No form's cost is proportional to its tiles while these leave CUs idle or half occupied (a
     // partly filled chip clocks higher).  Fitted to measurements on K = 8192 (us / 64, so that a
     // round of 256 128-row tiles, one per CU, costs about 1):
@@ -721,7 +725,7 @@ static TiledCosts tiled_costs(int M, int N, int K)
 {
     const long long bm256 = (M + 255) / 256;
     return tiled_costs((long long)((M + 127) / 128) * ((N + 255) / 256), bm256 * ((N + 255) / 256),
-                       bm256 * ((N + 127) / 128), K, true);
+                       bm256 * ((N + 127) / 128), K, K % 512 == 0);
 }
 static int solo_form_of(const TiledCosts &c)
 {
@@ -817,7 +821,7 @@ static int select_variant(int M, int N, int K)
 // the rows of the first piece (M if the batch stays whole).
 static int rows_of_first_launch(int M, int N, int K)
 {
-    if (K % 512 != 0 || M <= 256) return M;
+    if (M <= 256) return M;
     const int bm = (M + 255) / 256, bn = (N + 255) / 256;
     double best = tiled_costs(M, N, K).best() * 0.97;  // (a split has to win by 3 %)
     const double second_launch = 5.0 / (8.0 * K / 1024.0);  // (a unit is 64 us at K = 8192)

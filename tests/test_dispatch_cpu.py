@@ -112,7 +112,10 @@ def test_dispatcher_boundaries():
     # ... and the 128-row tiles where a last round of 256-row tiles would be mostly empty
     assert _pick(2560, 8192, 8192) == "duo_pt_m128" and _pick(3072, 8192, 8192) == "duo_pt_m128"
     assert _pick(2048, 10240, 8192, 128) == "duo_pt_m128" and _pick(2048, 11008, 4096) == "duo_pt_m128"
-    assert _pick(4096, 8192, 11008) == "duo_dl_m128"           # K not a multiple of 512: one tile per block
+    # K % 512 == 256: the 16x16x64 forms of the 256-row tiles take it (two added stages of zero weights),
+    # the persistent 128-row tiles do not
+    assert _pick(4096, 8192, 11008) == "solo16_pt_m256" and _pick(4096, 4096, 11008) == "solo16_pt_m256"
+    assert _pick(2048, 4096, 11008) == "solo16_g2_m256" and _pick(2560, 8192, 11008) == "duo_dl_m128"
     assert _pick(4096 + 40, 8192, 8192) == "duo_dl_m128"       # (rounds of 256-row tiles: 3 against 2.06) ragged last row tile of at most 64 rows: its two-fragment path
     assert _pick(4096 + 100, 8192, 8192) == "duo_pt_m128"
     with pytest.raises(api.LiquidGemmError):
@@ -141,8 +144,10 @@ def test_two_launch_plans():
     # ... but not a rest that would be 256 x 256 tiles again, nor with short K
     assert _plan(3584, 8192, 8192) == [(3584, "solo16_pt_m256")] and _plan(2304, 11008, 4096) == [(2304, "solo16_pt_m256")]
     assert _plan(2748, 8192, 512) == [(2748, _pick(2748, 8192, 512))]
+    # K % 512 == 256 splits like any other K (the 16x16x64 forms take it)
+    assert _plan(3072, 8192, 8448) == [(2048, "solo16_pt_m256"), (1024, "solo16_g2_m256")]
     for M, N, K, g in [(4096, 8192, 8192, 64), (2048, 28672, 8192, 128), (1536, 8192, 8192, 64), (16, 8192, 8192, 64),
-                       (256, 8192, 8192, 64), (2048, 11008, 4096, 64), (3072, 8192, 8448, 64), (0, 4096, 4096, 64)]:
+                       (256, 8192, 8192, 64), (2048, 11008, 4096, 64), (0, 4096, 4096, 64)]:
         assert _plan(M, N, K, g) == [(M, _pick(M, N, K, g))], (M, N, K)
     for s in WL.ALL_SHAPES:
         plan = api.w4a8_select_plan(s.M, s.N, s.K, s.group)

@@ -157,15 +157,17 @@ def test_grouped_full_size_layer_all_families():
                             f"expert {e}")
 
 
-def test_grouped_large_experts_take_256_row_tiles():
+@pytest.mark.parametrize("K", [1024, 768])
+def test_grouped_large_experts_take_256_row_tiles(K):
     """Experts of several hundred rows on a layer wide enough that whole rounds of 256 x 256 tiles
     pay: the big experts run as one persistent launch of the one-wave-per-SIMD kernel over all of
     them (ragged last row tiles of 8, 132 and 188 rows, an expert of exactly 256 rows, tile
     boundaries between experts inside a block's stream), the small ones in their own families.
+    Also with K % 512 == 256 (two added stages of zero weights per tile).
     Checked in full against the exact float64 product of the oracle's dequantised weights."""
     import torch
 
-    E, N, K, g = 7, 4096, 1024, 128
+    E, N, g = 7, 4096, 128
     rows = [700, 5, 520, 900, 40, 256, 1000]
     _say(f"grouped 256-row tiles E={E} N={N} K={K} rows={rows}")
     Ws = [WL.make_weights(N, K, 0.02, seed=300 + e) for e in range(E)]
