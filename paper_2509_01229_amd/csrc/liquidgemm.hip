@@ -632,8 +632,8 @@ static const Variant kVariants[] = {
     {"duo_m128", &launch_duo<0, 0>, 0, 1, 1},
     {"duo_dl_m128", &launch_duo_dl<0>, 0, 1, 1},
     {"duo_pt_m128", &launch_duo_pt, 0, 1, 8, 512},
-    {"solo16_pt_m256", &launch_solo_pt<1, 0, true>, 0, 1, 4, 512},
-    {"solo16_g2_m256", &launch_solo_pt<2, 0, true>, 0, 1, 4, 512},
+    {"solo16_pt_m256", &launch_solo_pt<1, 0, true>, 0, 1, 4},
+    {"solo16_g2_m256", &launch_solo_pt<2, 0, true>, 0, 1, 4},
     {"solo16_g2_sk_m256", &launch_solo_pt<2, -1, true>, 0, 1, 8, 512},
     // --- the 256-row tile kernels on the 32x32x32 MFMA (what the 16x16x64 forms are measured against) ---
     {"solo_pt_m256", &launch_solo_pt<1>, 0, 1, 8, 512},

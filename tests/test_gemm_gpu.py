@@ -266,8 +266,9 @@ def test_random_shapes_through_the_dispatcher():
 def test_random_large_grids_through_the_dispatcher():
     """Seeded shapes with more than 256 tiles of 128 x 256 (the direct-to-LDS tiled kernels and the
     256-row tiles with one wave per SIMD: ragged
-    last row tiles, N tails, 2 to 24 stages so that every remainder of its three-stage loop
-    occurs) and a few just below; the accumulators are compared with the exact float64
+    last row tiles, N tails, 2 to 24 stages so that every remainder of the three-stage loop of the
+    former occurs, and the added stages of the latter for K % 512 == 256, K = 256 included) and a few
+    just below; the accumulators are compared with the exact float64
     product on the oracle's dequantised weights, the FP16 output with the epilogue definition."""
     import torch
 
@@ -292,7 +293,7 @@ def test_random_large_grids_through_the_dispatcher():
         assert np.array_equal(ACC.cpu().numpy().astype(np.float64), ref), f"case {case}: accumulators differ"
         H.assert_fp16_close(Y.cpu().numpy(), O.scale_epilogue_f64(ref, s_x, s_w), f"case {case}")
         del P, dX, ACC, Y
-    assert {"duo_dl_m128", "duo_pt_m128", "solo16_pt_m256"} <= seen and seen & {"duo_m128", "duo_m64"}
+    assert {"duo_dl_m128", "duo_pt_m128", "solo16_pt_m256", "solo16_g2_m256"} <= seen
 
 
 def test_random_small_batches_through_the_dispatcher():
@@ -495,7 +496,7 @@ def test_batch_beyond_32_bit_offsets_of_x():
 
 @pytest.mark.parametrize("kernel", ["duo_pt_m128", "solo_pt_m256", "solo_g2_m256", "solo16_pt_m256", "solo16_g2_m256"])
 @pytest.mark.parametrize("M,N,K,g", [(1541, 12352, 512, 64), (2048, 10240, 1024, 128), (700, 2048, 1536, 64),
-                                     (1100, 4160, 768, 64), (600, 5120, 1280, 128)])
+                                     (1100, 4160, 768, 64), (600, 5120, 1280, 128), (520, 2048, 256, 64)])
 def test_persistent_tile_kernel(M, N, K, g, kernel):
     """The persistent forms of the tiled kernel (blocks walk several tiles as one stream of
     stages; 128-row tiles with two waves per SIMD, 256-row tiles with one, also in its form of
